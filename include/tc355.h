@@ -1,0 +1,144 @@
+/*
+ * tc355.h -- C ABI of libtc355: evaluation of tensor comprehensions on one
+ * AMD MI355X (gfx950).
+ *
+ * A tensor comprehension (arXiv 1802.04730, Section 3) is an index-notation
+ * statement: every output element is a sum, over the indices that appear only
+ * on the right-hand side, of a product of tensor accesses, optionally followed
+ * by a pointwise epilogue.  This library evaluates four fixed comprehensions.
+ *
+ * Conventions common to every entry point
+ *  - Every tensor pointer is a DEVICE pointer to a dense row-major array (last
+ *    index fastest, Section 5 "row-major arrays"), fp32 storage, base address
+ *    a multiple of 16 bytes.  The caller owns all tensors, outputs included
+ *    (Section 3.1: memory management is left to the calling framework), and
+ *    keeps them alive until the stream has run the work.
+ *  - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
+ *    the default stream).  Calls are asynchronous: the library never
+ *    synchronises, allocates or frees device memory.
+ *  - Outputs need not be zeroed: a "+=!" reduction starts from 0 (Section 3).
+ *  - Outputs must not overlap inputs.  Equal base pointers are rejected with
+ *    TC_ERR_ALIAS; other overlap is undefined.
+ *  - Arithmetic: inputs are widened exactly to fp64, products and sums are
+ *    taken in fp64 (fp64 matrix-core instructions), and each declared output
+ *    is rounded once to fp32.  Values handed from one stage of a chain to the
+ *    next stay in fp64.
+ *  - Validation precedes any launch: on a non-zero status nothing was written.
+ *    A batch extent of 0 returns TC_OK without launching.
+ *  - Thread safety: the library keeps no mutable global state apart from a
+ *    per-process cache of device properties; concurrent calls from several
+ *    host threads are allowed.
+ */
+#ifndef TC355_H
+#define TC355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  TC_OK = 0,
+  TC_ERR_NULL = 1,      /* a required pointer is NULL                          */
+  TC_ERR_SHAPE = 2,     /* an extent is <= 0, or an inferred extent is <= 0    */
+  TC_ERR_ALIAS = 3,     /* an output base pointer equals an input base pointer */
+  TC_ERR_ALIGN = 4,     /* a base pointer is not 16-byte aligned               */
+  TC_ERR_WORKSPACE = 5, /* workspace missing, misaligned or too small          */
+  TC_ERR_LAUNCH = 6,    /* the HIP runtime refused the launch                  */
+  TC_ERR_UNSUPPORTED = 7 /* extents beyond what the kernels index (>= 2^31 elements per tensor) */
+} tc_status;
+
+/* Human-readable name of a status; static storage, never freed. */
+const char *tc_status_string(tc_status s);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int tc355_version(void);
+
+/*
+ * Transposed batched matmul (Section 7, "Transposed Batched Matrix
+ * Multiplication", listing tbmm; index names as in the benchmark
+ * configurations):
+ *     Z(b,n,m) +=! X(b,n,k) * Y(b,m,k)
+ * X: [B,N,K]   Y: [B,M,K]   Z: [B,N,M]  (all device, fp32).
+ * The reduction index is the fastest index of both operands.  B = 1 gives the
+ * transposed matmul of Section 7 (listing tmm).
+ */
+tc_status tc_tbmm(const float *X, const float *Y, float *Z, int64_t B,
+                  int64_t N, int64_t M, int64_t K, void *hip_stream);
+
+/*
+ * Chain of n_layers fully connected + bias + ReLU layers, evaluated by one
+ * call (Section 3, listing fcrelu; appendix "Production Models", listings
+ * MLP1 (n_layers = 1) and MLP3 (n_layers = 3)).  For layer l = 0..n_layers-1
+ *     O_l(b,n)  = bias_l(n)
+ *     O_l(b,n) += In_l(b,m) * W_l(n,m)
+ *     O_l(b,n)  = fmaxf(O_l(b,n), 0)
+ * with In_0 = I and In_{l+1} = O_l.
+ *   I        device [batch, dims[0]]
+ *   dims     HOST array of n_layers+1 extents: dims[0] input width,
+ *            dims[l+1] width of layer l
+ *   W        HOST array of n_layers device pointers, W[l]: [dims[l+1], dims[l]]
+ *   bias     HOST array of n_layers device pointers, bias[l]: [dims[l+1]]
+ *   O        HOST array of n_layers device pointers, O[l]: [batch, dims[l+1]];
+ *            O[n_layers-1] is required, O[l] for earlier layers may be NULL
+ *            (that intermediate is then not written as fp32 at all)
+ *   workspace  device scratch of at least tc_mlp_fcrelu_workspace_bytes(...)
+ *            bytes, 256-byte aligned; it carries the fp64 activations from
+ *            one layer to the next and the inter-layer synchronisation
+ *            counters.  Contents on entry are irrelevant; calls that share a
+ *            workspace must be ordered on one stream.  May be NULL when the
+ *            required size is 0 (n_layers == 1).
+ * The host arrays are read before the call returns.  1 <= n_layers <= 8.
+ * The clamp maps NaN and -0 to +0, like fmaxf(x, 0).
+ */
+tc_status tc_mlp_fcrelu(const float *I, int64_t batch, int32_t n_layers,
+                        const int64_t *dims, const float *const *W,
+                        const float *const *bias, float *const *O,
+                        void *workspace, size_t workspace_bytes,
+                        void *hip_stream);
+
+/* Bytes of workspace tc_mlp_fcrelu needs for these extents (0 on bad input). */
+size_t tc_mlp_fcrelu_workspace_bytes(int64_t batch, int32_t n_layers,
+                                     const int64_t *dims);
+
+/*
+ * Grouped 2-D convolution, stride 1, no padding, plus per-output-channel bias
+ * (Section 7, "Grouped Convolutions", listing gconv):
+ *     O(n,g,o,h,w) +=! I(n,g,i,h+kh,w+kw) * W1(g,o,i,kh,kw)
+ *     O(n,g,o,h,w)  =  O(n,g,o,h,w) + bias(g*F+o)
+ * I: [N,G,C,H,W] (= NCHW with G*C channels)   W1: [G,F,C,KH,KW]
+ * bias: [G*F] or NULL (no bias statement)      O: [N,G,F,H-KH+1,W-KW+1].
+ * Output extents follow range inference (Section 3.1); H < KH or W < KW gives
+ * TC_ERR_SHAPE.
+ */
+tc_status tc_group_conv(const float *I, const float *W1, const float *bias,
+                        float *O, int64_t N, int64_t G, int64_t C, int64_t F,
+                        int64_t H, int64_t W, int64_t KH, int64_t KW,
+                        void *hip_stream);
+
+/*
+ * Output extents of tc_group_conv by range inference (Section 3.1: the output
+ * index h keeps h+kh inside the input for every kh, hence H-KH+1 values).
+ * Host only; touches no GPU.  OH, OW: host pointers.
+ */
+tc_status tc_group_conv_infer(int64_t H, int64_t W, int64_t KH, int64_t KW,
+                              int64_t *OH, int64_t *OW);
+
+/*
+ * Kronecker-factored linear layer (benchmark configuration 5; semantics of
+ * Section 3):
+ *     Y(b,i,j) +=! W1(i,k) * W2(j,l) * X(b,k,l)
+ * W1: [I,K]   W2: [J,L]   X: [B,K,L]   Y: [B,I,J].
+ * Evaluated as two chained contractions, T(b,i,l) = sum_k W1(i,k) X(b,k,l)
+ * then Y(b,i,j) = sum_l T(b,i,l) W2(j,l); T stays on chip in fp64.
+ */
+tc_status tc_kron(const float *W1, const float *W2, const float *X, float *Y,
+                  int64_t B, int64_t I, int64_t K, int64_t J, int64_t L,
+                  void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TC355_H */

@@ -1,0 +1,228 @@
+// Host side of libtc355: argument validation, kernel selection and launches
+// for the four entry points declared in include/tc355.h.
+#include "../../include/tc355.h"
+
+#include <hip/hip_runtime.h>
+
+#include "gconv_wave.hpp"
+#include "gemm_wave.hpp"
+#include "kron_wave.hpp"
+
+using namespace tc355;
+
+namespace {
+
+constexpr int64_t kMaxElems = (int64_t)1 << 31;  // per-tensor element limit of the 32-bit in-tile indexing
+constexpr int64_t kMaxGrid = 2147483647;
+
+inline bool misaligned(const void* p, size_t a = 16) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+inline tc_status launch_status() { return hipGetLastError() == hipSuccess ? TC_OK : TC_ERR_LAUNCH; }
+
+// ---- generic wave-level contraction launcher --------------------------------
+template <typename TA, int VEC, int EPI>
+tc_status launch_gemm_tm(GemmArgs a, int64_t batch, int tm, hipStream_t s) {
+  a.tiles_n = (int)ceil_div(a.N, 16);
+  a.strips_m = (int)ceil_div(a.M, 16 * tm);
+  a.jobs = batch * a.tiles_n * a.strips_m;
+  const int64_t grid = ceil_div(a.jobs, WAVES_PER_WG);
+  if (grid > kMaxGrid) return TC_ERR_UNSUPPORTED;
+  const dim3 g((unsigned)grid), b(WG_THREADS);
+  switch (tm) {
+    case 1: gemm_nt_wave_kernel<TA, VEC, 1, EPI><<<g, b, 0, s>>>(a); break;
+    case 2: gemm_nt_wave_kernel<TA, VEC, 2, EPI><<<g, b, 0, s>>>(a); break;
+    case 3: gemm_nt_wave_kernel<TA, VEC, 3, EPI><<<g, b, 0, s>>>(a); break;
+    case 4: gemm_nt_wave_kernel<TA, VEC, 4, EPI><<<g, b, 0, s>>>(a); break;
+    default: gemm_nt_wave_kernel<TA, VEC, 5, EPI><<<g, b, 0, s>>>(a); break;
+  }
+  return launch_status();
+}
+
+template <typename TA, int EPI>
+tc_status launch_gemm(const GemmArgs& a, int64_t batch, int tm, hipStream_t s) {
+  // widest per-lane load that keeps every row start aligned
+  if (a.K % 4 == 0) return launch_gemm_tm<TA, 4, EPI>(a, batch, tm, s);
+  if (a.K % 2 == 0) return launch_gemm_tm<TA, 2, EPI>(a, batch, tm, s);
+  return launch_gemm_tm<TA, 1, EPI>(a, batch, tm, s);
+}
+
+// Strip width (in 16-column tiles) that wastes the fewest padded columns; ties go to the wider strip.
+int pick_strip(int64_t M, int64_t waves_if_one) {
+  const int64_t tiles = ceil_div(M, 16);
+  if (tiles <= 5) return (int)tiles;
+  if (waves_if_one < 4096) return 1;  // few jobs: favour parallelism over operand reuse
+  int best = 1;
+  int64_t best_pad = -1;
+  for (int tm = 5; tm >= 2; tm--) {
+    const int64_t pad = ceil_div(tiles, tm) * tm - tiles;
+    if (best_pad < 0 || pad < best_pad) { best = tm; best_pad = pad; }
+  }
+  return best;
+}
+
+size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+}  // namespace
+
+extern "C" {
+
+const char* tc_status_string(tc_status s) {
+  switch (s) {
+    case TC_OK: return "TC_OK";
+    case TC_ERR_NULL: return "TC_ERR_NULL: a required pointer is NULL";
+    case TC_ERR_SHAPE: return "TC_ERR_SHAPE: an extent or an inferred extent is <= 0";
+    case TC_ERR_ALIAS: return "TC_ERR_ALIAS: an output aliases an input";
+    case TC_ERR_ALIGN: return "TC_ERR_ALIGN: a base pointer is not 16-byte aligned";
+    case TC_ERR_WORKSPACE: return "TC_ERR_WORKSPACE: workspace missing, misaligned or too small";
+    case TC_ERR_LAUNCH: return "TC_ERR_LAUNCH: the HIP runtime refused the launch";
+    case TC_ERR_UNSUPPORTED: return "TC_ERR_UNSUPPORTED: extents exceed the kernels' index range";
+  }
+  return "unknown tc_status";
+}
+
+int tc355_version(void) { return 100; }
+
+tc_status tc_tbmm(const float* X, const float* Y, float* Z, int64_t B, int64_t N, int64_t M, int64_t K,
+                  void* hip_stream) {
+  if (!X || !Y || !Z) return TC_ERR_NULL;
+  if (B < 0 || N <= 0 || M <= 0 || K <= 0) return TC_ERR_SHAPE;
+  if (Z == X || Z == Y) return TC_ERR_ALIAS;
+  if (misaligned(X) || misaligned(Y) || misaligned(Z)) return TC_ERR_ALIGN;
+  if (N >= kMaxElems || M >= kMaxElems || K >= kMaxElems || N * K >= kMaxElems || M * K >= kMaxElems ||
+      N * M >= kMaxElems)
+    return TC_ERR_UNSUPPORTED;
+  if (B == 0) return TC_OK;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+  GemmArgs a{};
+  a.A = X; a.Bm = Y; a.bias = nullptr; a.C = Z; a.C64 = nullptr;
+  a.strideA = N * K; a.strideB = M * K; a.strideC = N * M;
+  a.N = (int)N; a.M = (int)M; a.K = (int)K;
+  const int tm = pick_strip(M, B * ceil_div(N, 16) * ceil_div(M, 16));
+  return launch_gemm<float, EPI_NONE>(a, B, tm, s);
+}
+
+size_t tc_mlp_fcrelu_workspace_bytes(int64_t batch, int32_t n_layers, const int64_t* dims) {
+  if (!dims || batch < 0 || n_layers <= 0 || n_layers > 8) return 0;
+  size_t total = 0;
+  for (int l = 0; l + 1 < n_layers; l++) {
+    if (dims[l + 1] <= 0) return 0;
+    total += round256((size_t)batch * (size_t)dims[l + 1] * sizeof(double));
+  }
+  return total;
+}
+
+tc_status tc_mlp_fcrelu(const float* I, int64_t batch, int32_t n_layers, const int64_t* dims,
+                        const float* const* W, const float* const* bias, float* const* O, void* workspace,
+                        size_t workspace_bytes, void* hip_stream) {
+  if (!I || !dims || !W || !bias || !O) return TC_ERR_NULL;
+  if (batch < 0 || n_layers <= 0 || n_layers > 8) return TC_ERR_SHAPE;
+  for (int l = 0; l <= n_layers; l++)
+    if (dims[l] <= 0) return TC_ERR_SHAPE;
+  for (int l = 0; l < n_layers; l++)
+    if (!W[l] || !bias[l]) return TC_ERR_NULL;
+  if (!O[n_layers - 1]) return TC_ERR_NULL;
+  if (misaligned(I)) return TC_ERR_ALIGN;
+  for (int l = 0; l < n_layers; l++) {
+    if (misaligned(W[l]) || misaligned(bias[l]) || (O[l] && misaligned(O[l]))) return TC_ERR_ALIGN;
+    if (O[l] && (O[l] == I)) return TC_ERR_ALIAS;
+    for (int m = 0; m < n_layers; m++) {
+      if (O[l] && (O[l] == W[m] || O[l] == bias[m])) return TC_ERR_ALIAS;
+      if (O[l] && m != l && O[l] == O[m]) return TC_ERR_ALIAS;
+    }
+    if (dims[l] >= kMaxElems || dims[l + 1] >= kMaxElems || dims[l] * dims[l + 1] >= kMaxElems ||
+        batch * dims[l] >= kMaxElems || batch * dims[l + 1] >= kMaxElems)
+      return TC_ERR_UNSUPPORTED;
+  }
+  const size_t need = tc_mlp_fcrelu_workspace_bytes(batch, n_layers, dims);
+  if (need > 0 && (!workspace || misaligned(workspace, 256) || workspace_bytes < need)) return TC_ERR_WORKSPACE;
+  if (batch == 0) return TC_OK;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+  // fp64 activations of layer l live at act[l] inside the workspace
+  char* ws = static_cast<char*>(workspace);
+  const void* in = I;
+  for (int l = 0; l < n_layers; l++) {
+    double* out64 = nullptr;
+    if (l + 1 < n_layers) {
+      out64 = reinterpret_cast<double*>(ws);
+      ws += round256((size_t)batch * (size_t)dims[l + 1] * sizeof(double));
+    }
+    GemmArgs a{};
+    a.A = in; a.Bm = W[l]; a.bias = bias[l]; a.C = O[l]; a.C64 = out64;
+    a.strideA = 0; a.strideB = 0; a.strideC = 0;
+    a.N = (int)batch; a.M = (int)dims[l + 1]; a.K = (int)dims[l];
+    const int tm = pick_strip(dims[l + 1], ceil_div(batch, 16) * ceil_div(dims[l + 1], 16));
+    const tc_status st = (l == 0) ? launch_gemm<float, EPI_BIAS_RELU>(a, 1, tm, s)
+                                  : launch_gemm<double, EPI_BIAS_RELU>(a, 1, tm, s);
+    if (st != TC_OK) return st;
+    in = out64;
+  }
+  return TC_OK;
+}
+
+tc_status tc_group_conv_infer(int64_t H, int64_t W, int64_t KH, int64_t KW, int64_t* OH, int64_t* OW) {
+  if (!OH || !OW) return TC_ERR_NULL;
+  if (H <= 0 || W <= 0 || KH <= 0 || KW <= 0) return TC_ERR_SHAPE;
+  if (H - KH + 1 <= 0 || W - KW + 1 <= 0) return TC_ERR_SHAPE;
+  *OH = H - KH + 1;
+  *OW = W - KW + 1;
+  return TC_OK;
+}
+
+tc_status tc_group_conv(const float* I, const float* W1, const float* bias, float* O, int64_t N, int64_t G,
+                        int64_t C, int64_t F, int64_t H, int64_t W, int64_t KH, int64_t KW, void* hip_stream) {
+  if (!I || !W1 || !O) return TC_ERR_NULL;
+  if (N < 0 || G <= 0 || C <= 0 || F <= 0) return TC_ERR_SHAPE;
+  int64_t OH, OW;
+  const tc_status inf = tc_group_conv_infer(H, W, KH, KW, &OH, &OW);
+  if (inf != TC_OK) return inf;
+  if (O == I || O == W1 || (bias && O == bias)) return TC_ERR_ALIAS;
+  if (misaligned(I) || misaligned(W1) || misaligned(O) || (bias && misaligned(bias))) return TC_ERR_ALIGN;
+  if (C * H * W >= kMaxElems || F * OH * OW >= kMaxElems || C * KH * KW >= kMaxElems ||
+      G * F * C * KH * KW >= kMaxElems || G >= kMaxElems / 16 || F >= kMaxElems / 16)
+    return TC_ERR_UNSUPPORTED;
+  if (N == 0) return TC_OK;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+  GconvArgs a{};
+  a.I = I; a.W1 = W1; a.bias = bias; a.O = O;
+  a.N = (int)N; a.G = (int)G; a.C = (int)C; a.F = (int)F; a.H = (int)H; a.W = (int)W;
+  a.KH = (int)KH; a.KW = (int)KW; a.OH = (int)OH; a.OW = (int)OW;
+  constexpr int TP = 4;
+  a.tiles_f = (int)ceil_div(F, 16);
+  a.strips_p = (int)ceil_div(OH * OW, 16 * TP);
+  a.jobs = N * G * a.tiles_f * a.strips_p;
+  const int64_t grid = ceil_div(a.jobs, WAVES_PER_WG);
+  if (grid > kMaxGrid) return TC_ERR_UNSUPPORTED;
+  gconv_wave_kernel<TP><<<dim3((unsigned)grid), dim3(WG_THREADS), 0, s>>>(a);
+  return launch_status();
+}
+
+tc_status tc_kron(const float* W1, const float* W2, const float* X, float* Y, int64_t B, int64_t I, int64_t K,
+                  int64_t J, int64_t L, void* hip_stream) {
+  if (!W1 || !W2 || !X || !Y) return TC_ERR_NULL;
+  if (B < 0 || I <= 0 || K <= 0 || J <= 0 || L <= 0) return TC_ERR_SHAPE;
+  if (Y == W1 || Y == W2 || Y == X) return TC_ERR_ALIAS;
+  if (misaligned(W1) || misaligned(W2) || misaligned(X) || misaligned(Y)) return TC_ERR_ALIGN;
+  if (I * K >= kMaxElems || J * L >= kMaxElems || K * L >= kMaxElems || I * J >= kMaxElems)
+    return TC_ERR_UNSUPPORTED;
+  if (B == 0) return TC_OK;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+  KronArgs a{};
+  a.W1 = W1; a.W2 = W2; a.X = X; a.Y = Y;
+  a.I = (int)I; a.K = (int)K; a.J = (int)J; a.L = (int)L;
+  constexpr int TJ = 4;
+  a.tiles_i = (int)ceil_div(I, 16);
+  a.blocks_j = (int)ceil_div(J, 16 * TJ);
+  a.jobs = B * a.tiles_i * a.blocks_j;
+  const int64_t grid = ceil_div(a.jobs, WAVES_PER_WG);
+  if (grid > kMaxGrid) return TC_ERR_UNSUPPORTED;
+  kron_wave_kernel<TJ><<<dim3((unsigned)grid), dim3(WG_THREADS), 0, s>>>(a);
+  return launch_status();
+}
+
+}  // extern "C"

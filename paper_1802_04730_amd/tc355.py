@@ -1,0 +1,167 @@
+"""Thin ctypes binding of libtc355.so: argument marshalling only.
+
+Every function has the name and argument order of the C entry point in
+include/tc355.h.  Tensors are torch CUDA tensors (device memory owned by the
+caller); extents are read from their shapes; work is enqueued on torch's
+current stream unless ``stream`` (a raw hipStream_t value) is given.  A non-zero
+status raises ``TcError``.  There is no CPU fallback: if the library cannot be
+loaded the import of this module's functions fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+from . import build as _build
+
+_LIB = None
+
+TC_OK = 0
+STATUS_NAMES = {0: "TC_OK", 1: "TC_ERR_NULL", 2: "TC_ERR_SHAPE", 3: "TC_ERR_ALIAS", 4: "TC_ERR_ALIGN",
+                5: "TC_ERR_WORKSPACE", 6: "TC_ERR_LAUNCH", 7: "TC_ERR_UNSUPPORTED"}
+
+EXPORTS = ["tc_status_string", "tc355_version", "tc_tbmm", "tc_mlp_fcrelu", "tc_mlp_fcrelu_workspace_bytes",
+           "tc_group_conv", "tc_group_conv_infer", "tc_kron"]
+
+
+class TcError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s" % (where, status_string(status)))
+
+
+def lib() -> ctypes.CDLL:
+    """Load libtc355.so (building it first only if no built library exists)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = _build.LIB
+    if not os.path.exists(path):
+        _build.build(force=True)
+    L = ctypes.CDLL(path)
+    i64, i32, vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p
+    L.tc_status_string.argtypes = [ctypes.c_int]
+    L.tc_status_string.restype = ctypes.c_char_p
+    L.tc355_version.restype = ctypes.c_int
+    L.tc_tbmm.argtypes = [vp, vp, vp, i64, i64, i64, i64, vp]
+    L.tc_tbmm.restype = ctypes.c_int
+    L.tc_mlp_fcrelu.argtypes = [vp, i64, i32, ctypes.POINTER(i64), ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                ctypes.POINTER(vp), vp, ctypes.c_size_t, vp]
+    L.tc_mlp_fcrelu.restype = ctypes.c_int
+    L.tc_mlp_fcrelu_workspace_bytes.argtypes = [i64, i32, ctypes.POINTER(i64)]
+    L.tc_mlp_fcrelu_workspace_bytes.restype = ctypes.c_size_t
+    L.tc_group_conv.argtypes = [vp, vp, vp, vp] + [i64] * 8 + [vp]
+    L.tc_group_conv.restype = ctypes.c_int
+    L.tc_group_conv_infer.argtypes = [i64, i64, i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    L.tc_group_conv_infer.restype = ctypes.c_int
+    L.tc_kron.argtypes = [vp, vp, vp, vp] + [i64] * 5 + [vp]
+    L.tc_kron.restype = ctypes.c_int
+    _LIB = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return lib().tc_status_string(int(status)).decode()
+
+
+def tc355_version() -> int:
+    return int(lib().tc355_version())
+
+
+def _ptr(t, name: str) -> int:
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a torch CUDA tensor" % name)
+    if t.dtype != torch.float32:
+        raise TypeError("%s must be float32, got %s" % (name, t.dtype))
+    if not t.is_contiguous():
+        raise ValueError("%s must be dense row-major (contiguous)" % name)
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return int(stream)
+
+
+def _check(status: int, where: str) -> None:
+    if status != TC_OK:
+        raise TcError(status, where)
+
+
+def tc_tbmm(X, Y, Z, stream=None) -> None:
+    """Z[B,N,M] = sum_k X[B,N,K] * Y[B,M,K]; Z is written in place."""
+    B, N, K = X.shape
+    B2, M, K2 = Y.shape
+    if (B, K) != (B2, K2) or tuple(Z.shape) != (B, N, M):
+        raise ValueError("tc_tbmm: shapes X %s Y %s Z %s do not fit" % (tuple(X.shape), tuple(Y.shape), tuple(Z.shape)))
+    _check(lib().tc_tbmm(_ptr(X, "X"), _ptr(Y, "Y"), _ptr(Z, "Z"), B, N, M, K, _stream(stream)), "tc_tbmm")
+
+
+def tc_mlp_fcrelu_workspace_bytes(batch: int, dims) -> int:
+    n = len(dims) - 1
+    arr = (ctypes.c_int64 * (n + 1))(*[int(d) for d in dims])
+    return int(lib().tc_mlp_fcrelu_workspace_bytes(int(batch), n, arr))
+
+
+def tc_mlp_fcrelu(I, W, bias, O, workspace=None, stream=None) -> None:
+    """Chained fcrelu layers.  W, bias, O are lists (O[l] may be None for l < last).
+
+    ``workspace`` is a torch CUDA uint8 tensor of at least
+    tc_mlp_fcrelu_workspace_bytes(batch, dims) bytes (None only when that is 0).
+    """
+    n = len(W)
+    batch, d0 = I.shape
+    dims = [d0] + [int(w.shape[0]) for w in W]
+    for l in range(n):
+        if tuple(W[l].shape) != (dims[l + 1], dims[l]) or tuple(bias[l].shape) != (dims[l + 1],):
+            raise ValueError("tc_mlp_fcrelu: layer %d shapes do not chain" % l)
+        if O[l] is not None and tuple(O[l].shape) != (batch, dims[l + 1]):
+            raise ValueError("tc_mlp_fcrelu: O[%d] has the wrong shape" % l)
+    vp = ctypes.c_void_p
+    Wp = (vp * n)(*[_ptr(w, "W[%d]" % l) for l, w in enumerate(W)])
+    bp = (vp * n)(*[_ptr(b, "bias[%d]" % l) for l, b in enumerate(bias)])
+    Op = (vp * n)(*[_ptr(o, "O[%d]" % l) for l, o in enumerate(O)])
+    dm = (ctypes.c_int64 * (n + 1))(*dims)
+    ws_ptr, ws_bytes = None, 0
+    if workspace is not None:
+        if not workspace.is_cuda or not workspace.is_contiguous():
+            raise TypeError("workspace must be a contiguous CUDA tensor")
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    _check(lib().tc_mlp_fcrelu(_ptr(I, "I"), batch, n, dm, Wp, bp, Op, ws_ptr, ws_bytes, _stream(stream)),
+           "tc_mlp_fcrelu")
+
+
+def tc_group_conv_infer(H: int, W: int, KH: int, KW: int):
+    oh, ow = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().tc_group_conv_infer(H, W, KH, KW, ctypes.byref(oh), ctypes.byref(ow)), "tc_group_conv_infer")
+    return int(oh.value), int(ow.value)
+
+
+def tc_group_conv(I, W1, bias, O, stream=None) -> None:
+    """O[N,G,F,OH,OW] = grouped conv of I[N,G,C,H,W] with W1[G,F,C,KH,KW] plus bias[G*F] (or None)."""
+    N, G, C, H, W = I.shape
+    G2, F, C2, KH, KW = W1.shape
+    if (G, C) != (G2, C2):
+        raise ValueError("tc_group_conv: I and W1 disagree on G or C")
+    if bias is not None and tuple(bias.shape) != (G * F,):
+        raise ValueError("tc_group_conv: bias must be [G*F]")
+    if tuple(O.shape) != (N, G, F, H - KH + 1, W - KW + 1):
+        raise ValueError("tc_group_conv: O has the wrong shape")
+    _check(lib().tc_group_conv(_ptr(I, "I"), _ptr(W1, "W1"), _ptr(bias, "bias"), _ptr(O, "O"),
+                               N, G, C, F, H, W, KH, KW, _stream(stream)), "tc_group_conv")
+
+
+def tc_kron(W1, W2, X, Y, stream=None) -> None:
+    """Y[B,I,J] = sum_{k,l} W1[I,K] * W2[J,L] * X[B,K,L]."""
+    I, K = W1.shape
+    J, L = W2.shape
+    B, K2, L2 = X.shape
+    if (K, L) != (K2, L2) or tuple(Y.shape) != (B, I, J):
+        raise ValueError("tc_kron: shapes do not fit")
+    _check(lib().tc_kron(_ptr(W1, "W1"), _ptr(W2, "W2"), _ptr(X, "X"), _ptr(Y, "Y"), B, I, K, J, L,
+                         _stream(stream)), "tc_kron")

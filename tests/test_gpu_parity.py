@@ -1,0 +1,215 @@
+"""GPU parity: libtc355 (through its C ABI) against the float64 oracle, element by element.
+
+Bar: max |gpu - ref| / (|ref| + 1e-3 max|ref|) <= 2e-5 on the same seeded inputs.
+The library accumulates exact fp32 x fp32 products in fp64 and rounds each output
+once, so the error it can actually show is one fp32 rounding (2^-24 ~ 6e-8 relative);
+TIGHT asserts that as well, to catch a silent loss of precision long before the bar.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1802_04730_amd import inputs
+from paper_1802_04730_amd.metric import PARITY_BAR, parity_error
+
+pytestmark = pytest.mark.gpu
+
+TIGHT = 2.5e-7
+
+
+@pytest.fixture(scope="module")
+def tc():
+    from paper_1802_04730_amd import tc355
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    tc355.lib()
+    return tc355
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def check(gpu_tensor, ref, what):
+    torch.cuda.synchronize()
+    got = gpu_tensor.cpu().numpy().astype(np.float64)
+    err = parity_error(got, ref)
+    print("%s: parity error %.3e" % (what, err), flush=True)
+    assert err <= PARITY_BAR, "%s: %.3e exceeds the parity bar" % (what, err)
+    assert err <= TIGHT, "%s: %.3e exceeds one fp32 rounding" % (what, err)
+
+
+# ---------------------------------------------------------------- tbmm
+TBMM_SHAPES = [
+    (8, 26, 72, 26),      # configuration 1
+    (500, 26, 72, 26),    # configuration 2
+    (500, 26, 26, 72),    # the paper's own naming: output 26 x 26, reduction 72
+    (1, 1, 1, 1),
+    (3, 17, 33, 7),       # odd K: scalar loads, ragged tiles
+    (2, 16, 16, 4),       # exact tiles
+    (5, 40, 200, 30),     # several strips per row tile, K even but not a multiple of 4
+    (1, 128, 256, 32),    # transposed matmul of Section 7 (B = 1)
+    (7, 5, 81, 64),
+]
+
+
+@pytest.mark.parametrize("shape", TBMM_SHAPES)
+def test_tbmm(tc, shape, oracle_threads):
+    B, N, M, K = shape
+    X, Y = inputs.make_tbmm(B, N, M, K, seed=inputs.SEED_BASE + (1 if B == 8 else 2))
+    ref = oracle.tbmm(X, Y)
+    Z = torch.full((B, N, M), float("nan"), device="cuda")
+    tc.tc_tbmm(dev(X), dev(Y), Z)
+    check(Z, ref, "tbmm %s" % (shape,))
+
+
+def test_tbmm_empty_batch_and_guard_band(tc):
+    X = torch.zeros((0, 4, 5), device="cuda")
+    Y = torch.zeros((0, 6, 5), device="cuda")
+    Z = torch.zeros((0, 4, 6), device="cuda")
+    # an empty batch has no storage; pass valid aligned dummies through the raw ABI
+    d = torch.zeros(16, device="cuda")
+    e = torch.zeros(16, device="cuda")
+    f = torch.zeros(16, device="cuda")
+    assert tc.lib().tc_tbmm(d.data_ptr(), e.data_ptr(), f.data_ptr(), 0, 4, 6, 5, None) == 0
+    # writes stay inside Z: canaries on both sides of the output survive
+    B, N, M, K = 3, 26, 72, 26
+    Xh, Yh = inputs.make_tbmm(B, N, M, K, seed=5)
+    buf = torch.full((B * N * M + 512,), 777.0, device="cuda")
+    Zv = buf[256:256 + B * N * M].view(B, N, M)
+    tc.tc_tbmm(dev(Xh), dev(Yh), Zv)
+    torch.cuda.synchronize()
+    assert torch.all(buf[:256] == 777.0) and torch.all(buf[256 + B * N * M:] == 777.0)
+    check(Zv, oracle.tbmm(Xh, Yh), "tbmm guard band")
+
+
+def test_tbmm_runs_on_a_side_stream(tc):
+    X, Y = inputs.make_tbmm(8, 26, 72, 26, seed=9)
+    Xd, Yd = dev(X), dev(Y)
+    Z = torch.empty((8, 26, 72), device="cuda")
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    tc.tc_tbmm(Xd, Yd, Z, stream=s.cuda_stream)
+    s.synchronize()
+    check(Z, oracle.tbmm(X, Y), "tbmm side stream")
+
+
+# ---------------------------------------------------------------- mlp
+def run_mlp(tc, I, Ws, bs, keep=None):
+    batch = I.shape[0]
+    dims = [I.shape[1]] + [w.shape[0] for w in Ws]
+    n = len(Ws)
+    keep = keep if keep is not None else [True] * n
+    O = [torch.full((batch, dims[l + 1]), float("nan"), device="cuda") if keep[l] else None for l in range(n)]
+    nbytes = tc.tc_mlp_fcrelu_workspace_bytes(batch, dims)
+    ws = torch.empty(max(nbytes, 1), dtype=torch.uint8, device="cuda") if nbytes else None
+    tc.tc_mlp_fcrelu(dev(I), [dev(w) for w in Ws], [dev(b) for b in bs], O, ws)
+    return O
+
+
+MLP_SHAPES = [
+    (128, (1024, 1024, 512, 256)),  # configuration 3
+    (5, (7, 9, 3)),
+    (1, (33, 17)),                  # one layer = fcrelu / MLP1, odd widths
+    (16, (64, 48, 32, 16)),
+    (37, (130, 70, 50, 10, 4)),
+    (128, (1024, 1000)),            # odd output extent 1000 (the C3 weight of Section 7)
+]
+
+
+@pytest.mark.parametrize("shape", MLP_SHAPES)
+def test_mlp(tc, shape, oracle_threads):
+    batch, dims = shape
+    I, Ws, bs = inputs.make_mlp(batch, dims, seed=inputs.SEED_BASE + 3)
+    ref = oracle.mlp_fcrelu(I, Ws, bs)
+    O = run_mlp(tc, I, Ws, bs)
+    for l in range(len(Ws)):
+        check(O[l], ref[l], "mlp %s layer %d" % (shape, l))
+        assert float(O[l].min()) >= 0.0
+
+
+def test_mlp_intermediates_may_be_skipped(tc, oracle_threads):
+    I, Ws, bs = inputs.make_mlp(24, (96, 80, 40, 24), seed=4, w_std=0.1, b_std=0.1)
+    ref = oracle.mlp_fcrelu(I, Ws, bs)
+    O = run_mlp(tc, I, Ws, bs, keep=[False, False, True])
+    check(O[2], ref[2], "mlp last layer only")
+
+
+def test_mlp_large_weights_exercise_the_clamp(tc, oracle_threads):
+    I, Ws, bs = inputs.make_mlp(20, (50, 60, 30), seed=8, w_std=1.0, b_std=1.0)
+    ref = oracle.mlp_fcrelu(I, Ws, bs)
+    O = run_mlp(tc, I, Ws, bs)
+    for l in range(2):
+        check(O[l], ref[l], "mlp big weights layer %d" % l)
+        assert np.array_equal(O[l].cpu().numpy() == 0.0, ref[l] == 0.0) or parity_error(O[l].cpu().numpy(), ref[l]) <= TIGHT
+
+
+# ---------------------------------------------------------------- gconv
+GCONV_SHAPES = [
+    (2, 4, 16, 16, 58, 58, 3, 3),   # configuration 4 geometry, fewer images/groups
+    (1, 2, 2, 3, 5, 6, 3, 2),       # ragged everything
+    (2, 1, 3, 4, 8, 7, 3, 3),       # G = 1: ordinary convolution
+    (2, 3, 4, 5, 6, 7, 1, 1),       # pointwise filter
+    (1, 2, 4, 4, 3, 3, 3, 3),       # a single output pixel
+    (2, 4, 32, 32, 7, 7, 3, 3),     # paper table shape (32,32,32,32,7,7), fewer images/groups
+    (2, 4, 4, 4, 56, 56, 3, 3),     # paper table shape (32,32,4,4,56,56), fewer images/groups
+    (1, 2, 5, 20, 9, 11, 2, 4),     # two channel tiles, odd reduction length
+]
+
+
+@pytest.mark.parametrize("shape", GCONV_SHAPES)
+def test_gconv(tc, shape, oracle_threads):
+    N, G, C, F, H, W, KH, KW = shape
+    I, W1, bias = inputs.make_gconv(*shape, seed=inputs.SEED_BASE + 4)
+    ref = oracle.group_conv(I, W1, bias)
+    O = torch.full(ref.shape, float("nan"), device="cuda")
+    tc.tc_group_conv(dev(I), dev(W1), dev(bias), O)
+    check(O, ref, "gconv %s" % (shape,))
+
+
+def test_gconv_without_bias(tc, oracle_threads):
+    I, W1, _ = inputs.make_gconv(1, 3, 4, 6, 10, 9, 3, 3, seed=2)
+    ref = oracle.group_conv(I, W1, None)
+    O = torch.full(ref.shape, float("nan"), device="cuda")
+    tc.tc_group_conv(dev(I), dev(W1), None, O)
+    check(O, ref, "gconv no bias")
+
+
+def test_gconv_full_configuration_4(tc, oracle_threads):
+    _, (I, W1, bias) = inputs.make_config(4)
+    O = torch.full((32, 32, 16, 56, 56), float("nan"), device="cuda")
+    tc.tc_group_conv(dev(I), dev(W1), dev(bias), O)
+    torch.cuda.synchronize()
+    ref = oracle.group_conv(I, W1, bias)
+    check(O, ref, "gconv configuration 4")
+
+
+# ---------------------------------------------------------------- kron
+KRON_SHAPES = [
+    (256, 64, 64, 64, 64),  # configuration 5
+    (1, 2, 3, 2, 3),
+    (3, 5, 7, 3, 9),        # ragged
+    (2, 20, 6, 70, 33),     # two column blocks, ragged l blocks
+    (4, 16, 16, 16, 16),
+    (2, 64, 32, 128, 48),
+]
+
+
+@pytest.mark.parametrize("shape", KRON_SHAPES)
+def test_kron(tc, shape, oracle_threads):
+    B, I, K, J, L = shape
+    W1, W2, X = inputs.make_kron(B, I, K, J, L, seed=inputs.SEED_BASE + 5)
+    ref = oracle.kron(W1, W2, X)
+    Y = torch.full((B, I, J), float("nan"), device="cuda")
+    tc.tc_kron(dev(W1), dev(W2), dev(X), Y)
+    check(Y, ref, "kron %s" % (shape,))
+
+
+def test_outputs_need_no_zeroing_and_calls_repeat(tc, oracle_threads):
+    W1, W2, X = inputs.make_kron(4, 16, 16, 16, 16, seed=1)
+    ref = oracle.kron(W1, W2, X)
+    Y = torch.full((4, 16, 16), 1e30, device="cuda")
+    a, b, c = dev(W1), dev(W2), dev(X)
+    for _ in range(3):
+        tc.tc_kron(a, b, c, Y)
+    check(Y, ref, "kron repeated")
