@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the tc355 hot path on one MI355X.
+
+One "step" = one pass over all four operators at the benchmark configurations
+2-5 (tbmm B=500, 3-layer MLP batch 128, grouped convolution 32x512x58x58,
+Kronecker layer B=256) with inputs resident in HBM.  Prints ONE JSON line:
+whole-step throughput in GFLOP/s (algorithmic flops of the four comprehensions
+per step / wall time per step), a per-operator table (kernel time from HIP
+events on the launch stream, GFLOP/s, fraction of the roofline that bounds the
+operator), the roofline of the dominant kernel (grouped convolution), and the
+float64 CPU oracle timed on the host cores on a bounded sample of the same
+workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published peaks
+PEAK_HBM_GBS = 8000.0
+PEAK_F64_MFMA_TFLOPS = 78.6
+PEAK_F32_MFMA_TFLOPS = 157.3
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--op-reps", type=int, default=200, help="launches per operator in the per-operator timing loops")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def read_traffic(name):
+    """HBM bytes per launch from a committed rocprofv3 --pmc summary, or None."""
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
+    return float(m.group(1)) if m else None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_1802_04730_amd import inputs, tc355
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    tc355.lib()
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    cfg = {c: {k: v for k, v in inputs.CONFIGS[c].items() if k != "op"} for c in (2, 3, 4, 5)}
+
+    # ---- inputs, resident in HBM before anything is timed
+    X, Y = (dev(a) for a in inputs.make_config(2)[1])
+    Z = torch.empty((500, 26, 72), device="cuda")
+    Ih, Wsh, bsh = inputs.make_config(3)[1]
+    I, Ws, bs = dev(Ih), [dev(w) for w in Wsh], [dev(b) for b in bsh]
+    dims = cfg[3]["dims"]
+    O = [torch.empty((128, d), device="cuda") for d in dims[1:]]
+    ws = torch.empty(max(1, tc355.tc_mlp_fcrelu_workspace_bytes(128, dims)), dtype=torch.uint8, device="cuda")
+    Ig, W1g, bg = (dev(a) for a in inputs.make_config(4)[1])
+    Og = torch.empty((32, 32, 16, 56, 56), device="cuda")
+    K1, K2, Xk = (dev(a) for a in inputs.make_config(5)[1])
+    Yk = torch.empty((256, 64, 64), device="cuda")
+
+    ops = {
+        "tbmm": (lambda: tc355.tc_tbmm(X, Y, Z), inputs.flops_tbmm(**cfg[2]), inputs.bytes_tbmm(**cfg[2])),
+        "mlp": (lambda: tc355.tc_mlp_fcrelu(I, Ws, bs, O, ws), inputs.flops_mlp(**cfg[3]), inputs.bytes_mlp(**cfg[3])),
+        "gconv": (lambda: tc355.tc_group_conv(Ig, W1g, bg, Og), inputs.flops_gconv(**cfg[4]),
+                  inputs.bytes_gconv(**cfg[4])),
+        "kron": (lambda: tc355.tc_kron(K1, K2, Xk, Yk), inputs.flops_kron(**cfg[5]), inputs.bytes_kron(**cfg[5])),
+    }
+    step_flops = sum(v[1] for v in ops.values())
+
+    def step(ev=None):
+        ops["tbmm"][0]()
+        ops["mlp"][0]()
+        if ev is not None:
+            ev[0].record()
+        ops["gconv"][0]()
+        if ev is not None:
+            ev[1].record()
+        ops["kron"][0]()
+
+    # ---- whole-step throughput; the dominant kernel is bracketed by HIP events on the launch stream
+    for _ in range(args.warmup):
+        step()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(evs[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    gconv_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+
+    # ---- per-operator kernel time: back-to-back launches between two events
+    per_op = {}
+    for name, (fn, flops, nbytes) in ops.items():
+        for _ in range(10):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.op_reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / args.op_reps
+        t_mfma = flops / (PEAK_F64_MFMA_TFLOPS * 1e12)
+        t_hbm = nbytes / (PEAK_HBM_GBS * 1e9)
+        bound = "mfma" if t_mfma >= t_hbm else "hbm"
+        per_op[name] = {
+            "us": round(us, 3),
+            "gflops": round(flops / us * 1e-3, 1),
+            "gbs": round(nbytes / us * 1e-3, 1),
+            "bound": bound,
+            "roofline_us": round(max(t_mfma, t_hbm) * 1e6, 3),
+            "frac": round(max(t_mfma, t_hbm) * 1e6 / us, 4),
+            "frac_vs_f32_mfma_or_hbm": round(max(flops / (PEAK_F32_MFMA_TFLOPS * 1e12), t_hbm) * 1e6 / us, 4),
+        }
+
+    g_flops = ops["gconv"][1]
+    achieved = g_flops / (gconv_ms * 1e-3) / 1e12
+    roofline = {
+        "kernel": "grouped convolution (configuration 4)",
+        "bound": "mfma",
+        "achieved": round(achieved, 3),
+        "peak": PEAK_F64_MFMA_TFLOPS,
+        "unit": "TFLOP/s",
+        "frac": round(achieved / PEAK_F64_MFMA_TFLOPS, 4),
+        "traffic": read_traffic("gconv_cfg4_hbm_traffic.txt"),
+        "avg_launch_us": round(gconv_ms * 1e3, 2),
+        "flops_per_launch": g_flops,
+        "note": "fp64 MFMA accumulation of fp32 inputs; peak is the dense fp64 matrix rate",
+    }
+
+    out = {
+        "metric": "GFLOP/s and % of fp32-MFMA/HBM roofline per op (TBMM, MLP, group conv)",
+        "value": round(step_flops / (ms_per_step * 1e-3) / 1e9, 1),
+        "unit": "GFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f64",
+        "data": "synthetic",
+        "config": {"workload": "configs 2-5 per step: tbmm B=500 N=26 M=72 K=26; MLP 128x1024->1024->512->256; "
+                               "gconv N=32 G=32 C=F=16 58x58 3x3; kron B=256 64^4",
+                   "flops_per_step": step_flops},
+        "ops": per_op,
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(inputs, Ih, Wsh, bsh)
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(inputs, Ih, Wsh, bsh):
+    """The float64 oracle, as it stands, on the host cores, on a bounded sample of the step's workload."""
+    import oracle
+
+    threads = oracle.max_threads()
+    oracle.set_threads(threads)
+    Xh, Yh = inputs.make_config(2)[1]
+    c4 = {k: v for k, v in inputs.CONFIGS[4].items() if k != "op"}
+    c4["N"] = 4
+    Igh, W1h, bh = inputs.make_gconv(seed=inputs.SEED_BASE + 4, **c4)
+    c5 = {k: v for k, v in inputs.CONFIGS[5].items() if k != "op"}
+    c5["B"] = 32
+    K1h, K2h, Xkh = inputs.make_kron(seed=inputs.SEED_BASE + 5, **c5)
+    flops = (inputs.flops_tbmm(500, 26, 72, 26) + inputs.flops_mlp(128, inputs.CONFIGS[3]["dims"])
+             + inputs.flops_gconv(**c4) + inputs.flops_kron(**c5))
+    t0 = time.perf_counter()
+    oracle.tbmm(Xh, Yh)
+    oracle.mlp_fcrelu(Ih, Wsh, bsh)
+    oracle.group_conv(Igh, W1h, bh)
+    oracle.kron(K1h, K2h, Xkh)
+    dt = time.perf_counter() - t0
+    return {
+        "value": round(flops / dt / 1e9, 3),
+        "unit": "GFLOP/s",
+        "cores": threads,
+        "kind": "oracle",
+        "seconds": round(dt, 2),
+        "sample": "tbmm and MLP configurations in full, grouped convolution with N=4 of 32 images, Kronecker layer "
+                  "with B=32 of 256 (single 5-index comprehension); algorithmic flops of the sample / wall time",
+    }
+
+
+if __name__ == "__main__":
+    main()

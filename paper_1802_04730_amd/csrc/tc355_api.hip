@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include "gconv_lds.hpp"
 #include "gconv_wave.hpp"
 #include "gemm_wave.hpp"
 #include "kron_wave.hpp"
@@ -63,6 +64,28 @@ int pick_strip(int64_t M, int64_t waves_if_one) {
 }
 
 size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// ---- tuned grouped convolution: returns false if this instance does not apply -----
+template <int C, int F, int KH, int KW, int TP>
+bool try_gconv_lds(const GconvArgs& g, hipStream_t s, tc_status* st) {
+  if (g.C != C || g.F != F || g.KH != KH || g.KW != KW) return false;
+  const int npix = g.OH * g.OW;
+  const int rows = gconv_band_rows(64 * TP, g.OW, KH);
+  const int PS = gconv_plane_stride(rows * g.W);
+  const size_t lds = (size_t)C * PS * sizeof(float);
+  if (lds > 64 * 1024) return false;
+  GconvLdsArgs a{};
+  a.I = g.I; a.W1 = g.W1; a.bias = g.bias; a.O = g.O;
+  a.G = g.G; a.H = g.H; a.W = g.W; a.OH = g.OH; a.OW = g.OW;
+  a.PS = PS;
+  a.pblocks = (int)ceil_div(npix, 64 * TP);
+  a.ngs = (int64_t)g.N * g.G;
+  const int64_t grid = a.ngs * a.pblocks;
+  if (grid > kMaxGrid) return false;
+  gconv_lds_kernel<C, F, KH, KW, TP><<<dim3((unsigned)grid), dim3(WG_THREADS), lds, s>>>(a);
+  *st = launch_status();
+  return true;
+}
 
 }  // namespace
 
@@ -191,6 +214,8 @@ tc_status tc_group_conv(const float* I, const float* W1, const float* bias, floa
   a.I = I; a.W1 = W1; a.bias = bias; a.O = O;
   a.N = (int)N; a.G = (int)G; a.C = (int)C; a.F = (int)F; a.H = (int)H; a.W = (int)W;
   a.KH = (int)KH; a.KW = (int)KW; a.OH = (int)OH; a.OW = (int)OW;
+  tc_status st = TC_OK;
+  if (try_gconv_lds<16, 16, 3, 3, 7>(a, s, &st)) return st;
   constexpr int TP = 4;
   a.tiles_f = (int)ceil_div(F, 16);
   a.strips_p = (int)ceil_div(OH * OW, 16 * TP);
