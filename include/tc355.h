@@ -25,9 +25,12 @@
  *    next stay in fp64.
  *  - Validation precedes any launch: on a non-zero status nothing was written.
  *    A batch extent of 0 returns TC_OK without launching.
- *  - Thread safety: the library keeps no mutable global state apart from a
- *    per-process cache of device properties; concurrent calls from several
- *    host threads are allowed.
+ *  - Thread safety: the only mutable global state is a per-process cache of
+ *    device properties and an atomic call counter; concurrent calls from
+ *    several host threads are allowed.
+ *  - Environment (read at every call, meant for tests): TC355_MLP_FUSED=0
+ *    forces one launch per MLP layer; TC355_MLP_SPIN_LIMIT=<n> bounds the
+ *    polls of a device-wide wait.
  */
 #ifndef TC355_H
 #define TC355_H
@@ -85,11 +88,17 @@ tc_status tc_tbmm(const float *X, const float *Y, float *Z, int64_t B,
  *            O[n_layers-1] is required, O[l] for earlier layers may be NULL
  *            (that intermediate is then not written as fp32 at all)
  *   workspace  device scratch of at least tc_mlp_fcrelu_workspace_bytes(...)
- *            bytes, 256-byte aligned; it carries the fp64 activations from
- *            one layer to the next and the inter-layer synchronisation
- *            counters.  Contents on entry are irrelevant; calls that share a
- *            workspace must be ordered on one stream.  May be NULL when the
- *            required size is 0 (n_layers == 1).
+ *            bytes, 256-byte aligned.  Its head holds the counters of the
+ *            device-wide synchronisation between layers; the rest carries
+ *            the fp64 activations from one layer to the next.  Contents on
+ *            entry are irrelevant (the kernel initialises what it needs);
+ *            calls that share a workspace must be ordered on one stream.  May
+ *            be NULL when the required size is 0 (n_layers == 1).  After the
+ *            call has run, 32-bit word 33 of the workspace is 1 if a
+ *            device-wide wait gave up (workgroups could not all be resident
+ *            at once; outputs are then unspecified) and 0 otherwise.
+ * When every reduction extent dims[l] is a multiple of 4 the whole chain runs
+ * as one persistent kernel; otherwise one kernel per layer is launched.
  * The host arrays are read before the call returns.  1 <= n_layers <= 8.
  * The clamp maps NaN and -0 to +0, like fmaxf(x, 0).
  */

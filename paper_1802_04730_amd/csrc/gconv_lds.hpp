@@ -9,9 +9,10 @@
 //   LDS        -> the band of input rows those pixels touch, all C channels,
 //                 fp32, plane stride PS chosen = 16 (mod 64) words so that the
 //                 four k slots of a wavefront read disjoint banks;
-//   registers  -> the whole filter bank of the group as fp64 MFMA A operands
-//                 (KH*KW*C/4 values per lane and 16 output channels), loaded
-//                 once; TP accumulator tiles per wavefront.
+//                 The filter bank of the group sits behind it, fp32, already
+//                 permuted into MFMA A-operand order (one word per lane and
+//                 step), so it costs no registers;
+//   registers  -> TP accumulator tiles per wavefront.
 // The reduction is consumed in the order (kh, kw, c/4) with k slot q carrying
 // channel 4*(c/4)+q, so that every LDS read of a step is "lane base + constant".
 // Each 16x16x4 fp64 MFMA needs one 4-byte LDS read and one widening, far below
@@ -47,7 +48,7 @@ inline int gconv_band_rows(int pixels, int OW, int KH) {
 }
 
 template <int C, int F, int KH, int KW, int TP>
-__global__ __launch_bounds__(WG_THREADS, 2) void gconv_lds_kernel(GconvLdsArgs p) {
+__global__ __launch_bounds__(WG_THREADS, 3) void gconv_lds_kernel(GconvLdsArgs p) {
   static_assert(C % 4 == 0 && F % 16 == 0, "channel counts must fit the 16x16x4 tile");
   constexpr int NS = KH * KW * (C / 4);  // MFMA steps per output tile
   constexpr int FT = F / 16;
@@ -73,18 +74,15 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_lds_kernel(GconvLdsArgs p
   const int plast = min(P0 + 64 * TP, npix) - 1;
   const int rows = plast / OW - h_first + KH;
 
-  // ---- filter bank of this group -> registers (fp64)
-  double a[FT][NS];
-#pragma unroll
-  for (int ft = 0; ft < FT; ft++) {
-    const float* wp = p.W1 + ((int64_t)(g * F + ft * 16 + r16) * C + q) * (KH * KW);
-#pragma unroll
-    for (int kh = 0; kh < KH; kh++)
-#pragma unroll
-      for (int kw = 0; kw < KW; kw++)
-#pragma unroll
-        for (int c4 = 0; c4 < C / 4; c4++)
-          a[ft][(kh * KW + kw) * (C / 4) + c4] = (double)wp[(4 * c4) * (KH * KW) + kh * KW + kw];
+  // ---- filter bank of this group -> LDS, already in MFMA A-operand order:
+  //      wl[(ft*NS + s)*64 + lane] = W1[g][ft*16 + r16][4*c4 + q][kh][kw],  s = (kh*KW + kw)*(C/4) + c4
+  float* wl = lds + C * PS;
+  for (int idx = tid; idx < FT * NS * WAVE; idx += WG_THREADS) {
+    const int ln = idx & (WAVE - 1), fs = idx / WAVE;
+    const int ft = fs / NS, st = fs - ft * NS;
+    const int c4 = st % (C / 4), kk = st / (C / 4);  // kk = kh*KW + kw
+    const int f = ft * 16 + (ln & 15), c = 4 * c4 + (ln >> 4);
+    wl[idx] = p.W1[((int64_t)(g * F + f) * C + c) * (KH * KW) + kk];
   }
 
   // ---- input band -> LDS
@@ -128,11 +126,14 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_lds_kernel(GconvLdsArgs p
       for (int c4 = 0; c4 < C / 4; c4++) {
         const int s = (kh * KW + kw) * (C / 4) + c4;
         const int off = 4 * c4 * PS + kh * W + kw;
+        double a[FT];
+#pragma unroll
+        for (int ft = 0; ft < FT; ft++) a[ft] = (double)wl[(ft * NS + s) * WAVE + lane];
 #pragma unroll
         for (int t = 0; t < TP; t++) {
           const double b = (double)lds[base[t] + off];
 #pragma unroll
-          for (int ft = 0; ft < FT; ft++) acc[ft][t] = mfma_f64(a[ft][s], b, acc[ft][t]);
+          for (int ft = 0; ft < FT; ft++) acc[ft][t] = mfma_f64(a[ft], b, acc[ft][t]);
         }
       }
 

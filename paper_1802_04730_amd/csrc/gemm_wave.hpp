@@ -59,22 +59,49 @@ __global__ __launch_bounds__(WG_THREADS) void gemm_nt_wave_kernel(GemmArgs p) {
     acc[t] = (EPI == EPI_BIAS_RELU) ? d4_splat((double)p.bias[bcol]) : d4_zero();
   }
 
-  for (int k0 = 0; k0 < K; k0 += 4 * VEC) {
+  // The reduction is walked in chunks of 4*VEC elements; GC chunks form a group and
+  // the loads of group g+1 are issued before the MFMAs of group g, so several
+  // memory round trips are in flight per wavefront at any time.
+  constexpr int GC = 4;
+  constexpr int CH = 4 * VEC;
+  struct Chunk {
+    Vec<TA, VEC> a;
+    Vec<float, VEC> b[TM];
+  };
+  auto load_chunk = [&](int k0, Chunk& c) {
     const int kk = k0 + VEC * q;
-    const bool in = kk < K;
-    const int kc = in ? kk : 0;
-    const Vec<TA, VEC> av = load_vec<TA, VEC>(ap + kc);
-    Vec<float, VEC> bv[TM];
+    const int kc = kk < K ? kk : 0;
+    c.a = load_vec<TA, VEC>(ap + kc);
 #pragma unroll
-    for (int t = 0; t < TM; t++) bv[t] = load_vec<float, VEC>(bp[t] + kc);
+    for (int t = 0; t < TM; t++) c.b[t] = load_vec<float, VEC>(bp[t] + kc);
+  };
+  auto compute_chunk = [&](int k0, const Chunk& c) {
+    if (k0 >= K) return;  // uniform over the wavefront
+    const bool in = k0 + VEC * q < K;
 #pragma unroll
     for (int e = 0; e < VEC; e++) {
-      const double a = in ? (double)av.e[e] : 0.0;
+      const double a = in ? (double)c.a.e[e] : 0.0;
 #pragma unroll
       for (int t = 0; t < TM; t++) {
-        const double bb = in ? (double)bv[t].e[e] : 0.0;
+        const double bb = in ? (double)c.b[t].e[e] : 0.0;
         acc[t] = mfma_f64(a, bb, acc[t]);
       }
+    }
+  };
+  Chunk cur[GC], nxt[GC];
+#pragma unroll
+  for (int i = 0; i < GC; i++) load_chunk(i * CH, cur[i]);
+  for (int k0 = 0; k0 < K; k0 += GC * CH) {
+    const bool more = k0 + GC * CH < K;
+    if (more) {
+#pragma unroll
+      for (int i = 0; i < GC; i++) load_chunk(k0 + (GC + i) * CH, nxt[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < GC; i++) compute_chunk(k0 + i * CH, cur[i]);
+    if (more) {
+#pragma unroll
+      for (int i = 0; i < GC; i++) cur[i] = nxt[i];
     }
   }
 

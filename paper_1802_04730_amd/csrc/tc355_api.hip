@@ -4,10 +4,18 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <atomic>
+#include <chrono>
+#include <cstdlib>
+#include <random>
+
 #include "gconv_lds.hpp"
 #include "gconv_wave.hpp"
 #include "gemm_wave.hpp"
+#include "kron_lds.hpp"
 #include "kron_wave.hpp"
+#include "mlp_fused.hpp"
 
 using namespace tc355;
 
@@ -72,7 +80,7 @@ bool try_gconv_lds(const GconvArgs& g, hipStream_t s, tc_status* st) {
   const int npix = g.OH * g.OW;
   const int rows = gconv_band_rows(64 * TP, g.OW, KH);
   const int PS = gconv_plane_stride(rows * g.W);
-  const size_t lds = (size_t)C * PS * sizeof(float);
+  const size_t lds = ((size_t)C * PS + (size_t)(F / 16) * (KH * KW * C / 4) * WAVE) * sizeof(float);
   if (lds > 64 * 1024) return false;
   GconvLdsArgs a{};
   a.I = g.I; a.W1 = g.W1; a.bias = g.bias; a.O = g.O;
@@ -86,6 +94,43 @@ bool try_gconv_lds(const GconvArgs& g, hipStream_t s, tc_status* st) {
   *st = launch_status();
   return true;
 }
+
+// Number of compute units of the current device (cached per device index).
+int device_cus() {
+  static std::atomic<int> cache[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+  int cus = cache[dev].load(std::memory_order_relaxed);
+  if (cus == 0) {
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    cache[dev].store(cus, std::memory_order_relaxed);
+  }
+  return cus;
+}
+
+// A fresh 64-bit token per fused-MLP call (never 0): random start, then counting.
+unsigned long long next_token() {
+  static std::atomic<unsigned long long> tok{[] {
+    std::random_device rd;
+    unsigned long long t = ((unsigned long long)rd() << 32) ^ rd();
+    t ^= (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count();
+    return t | 1ull;
+  }()};
+  unsigned long long t = tok.fetch_add(1, std::memory_order_relaxed);
+  return t ? t : tok.fetch_add(1, std::memory_order_relaxed);
+}
+
+long env_long(const char* name, long dflt) {
+  const char* v = std::getenv(name);
+  if (!v || !*v) return dflt;
+  char* end = nullptr;
+  const long x = std::strtol(v, &end, 10);
+  return (end && *end == 0) ? x : dflt;
+}
+
+size_t mlp_sync_bytes() { return round256((MLP_SYNC_WORDS + (size_t)(MLP_MAX_LAYERS - 1) * MLP_BAR_WORDS) * sizeof(unsigned)); }
+
+size_t mlp_act_bytes(int64_t batch, int64_t width) { return round256((size_t)batch * (size_t)width * sizeof(double)); }
 
 }  // namespace
 
@@ -128,11 +173,12 @@ tc_status tc_tbmm(const float* X, const float* Y, float* Z, int64_t B, int64_t N
 }
 
 size_t tc_mlp_fcrelu_workspace_bytes(int64_t batch, int32_t n_layers, const int64_t* dims) {
-  if (!dims || batch < 0 || n_layers <= 0 || n_layers > 8) return 0;
-  size_t total = 0;
+  if (!dims || batch < 0 || n_layers <= 0 || n_layers > MLP_MAX_LAYERS) return 0;
+  if (n_layers == 1) return 0;
+  size_t total = mlp_sync_bytes();  // synchronisation words first
   for (int l = 0; l + 1 < n_layers; l++) {
     if (dims[l + 1] <= 0) return 0;
-    total += round256((size_t)batch * (size_t)dims[l + 1] * sizeof(double));
+    total += mlp_act_bytes(batch, dims[l + 1]);
   }
   return total;
 }
@@ -141,7 +187,7 @@ tc_status tc_mlp_fcrelu(const float* I, int64_t batch, int32_t n_layers, const i
                         const float* const* W, const float* const* bias, float* const* O, void* workspace,
                         size_t workspace_bytes, void* hip_stream) {
   if (!I || !dims || !W || !bias || !O) return TC_ERR_NULL;
-  if (batch < 0 || n_layers <= 0 || n_layers > 8) return TC_ERR_SHAPE;
+  if (batch < 0 || n_layers <= 0 || n_layers > MLP_MAX_LAYERS) return TC_ERR_SHAPE;
   for (int l = 0; l <= n_layers; l++)
     if (dims[l] <= 0) return TC_ERR_SHAPE;
   for (int l = 0; l < n_layers; l++)
@@ -164,24 +210,58 @@ tc_status tc_mlp_fcrelu(const float* I, int64_t batch, int32_t n_layers, const i
   if (batch == 0) return TC_OK;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
-  // fp64 activations of layer l live at act[l] inside the workspace
+  // workspace: [synchronisation words | fp64 activations of layer 0 | layer 1 | ...]
   char* ws = static_cast<char*>(workspace);
+  double* act[MLP_MAX_LAYERS] = {};
+  {
+    char* pws = ws + mlp_sync_bytes();
+    for (int l = 0; l + 1 < n_layers; l++) {
+      act[l] = reinterpret_cast<double*>(pws);
+      pws += mlp_act_bytes(batch, dims[l + 1]);
+    }
+  }
+
+  // One persistent kernel for the whole chain when every reduction extent allows 16-byte loads.
+  bool fused = env_long("TC355_MLP_FUSED", 1) != 0;
+  for (int l = 0; l < n_layers; l++) fused = fused && (dims[l] % 4 == 0);
+  const int cus = device_cus();
+  if (fused && cus > 0) {
+    MlpArgs a{};
+    a.I = I;
+    int64_t max_jobs = 1;
+    for (int l = 0; l < n_layers; l++) {
+      a.W[l] = W[l]; a.bias[l] = bias[l]; a.O[l] = O[l]; a.act[l] = act[l];
+      max_jobs = std::max<int64_t>(max_jobs, ceil_div(batch, 16) * ceil_div(dims[l + 1], 16));
+    }
+    for (int l = 0; l <= n_layers; l++) a.dims[l] = (int)dims[l];
+    a.batch = (int)batch; a.n_layers = n_layers;
+    a.sync = reinterpret_cast<unsigned*>(ws);
+    a.token = next_token();
+    a.spin_limit = (unsigned)std::max<long>(1, env_long("TC355_MLP_SPIN_LIMIT", 4000000));
+    const unsigned nwg = (unsigned)std::min<int64_t>(std::min(2 * cus, MLP_FANIN * MLP_GROUPS), max_jobs);  // all resident: two per compute unit
+    static std::atomic<int> lds_ok{0};  // the kernel stages more than the default 64 KiB of LDS
+    if (!lds_ok.load(std::memory_order_acquire)) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_fused_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, MLP_LDS_BYTES) != hipSuccess)
+        return TC_ERR_LAUNCH;
+      lds_ok.store(1, std::memory_order_release);
+    }
+    mlp_fused_kernel<<<dim3(nwg), dim3(WG_THREADS), MLP_LDS_BYTES, s>>>(a);
+    return launch_status();
+  }
+
+  // Otherwise one launch per layer through the shape-generic contraction.
   const void* in = I;
   for (int l = 0; l < n_layers; l++) {
-    double* out64 = nullptr;
-    if (l + 1 < n_layers) {
-      out64 = reinterpret_cast<double*>(ws);
-      ws += round256((size_t)batch * (size_t)dims[l + 1] * sizeof(double));
-    }
     GemmArgs a{};
-    a.A = in; a.Bm = W[l]; a.bias = bias[l]; a.C = O[l]; a.C64 = out64;
+    a.A = in; a.Bm = W[l]; a.bias = bias[l]; a.C = O[l]; a.C64 = act[l];
     a.strideA = 0; a.strideB = 0; a.strideC = 0;
     a.N = (int)batch; a.M = (int)dims[l + 1]; a.K = (int)dims[l];
     const int tm = pick_strip(dims[l + 1], ceil_div(batch, 16) * ceil_div(dims[l + 1], 16));
     const tc_status st = (l == 0) ? launch_gemm<float, EPI_BIAS_RELU>(a, 1, tm, s)
                                   : launch_gemm<double, EPI_BIAS_RELU>(a, 1, tm, s);
     if (st != TC_OK) return st;
-    in = out64;
+    in = act[l];
   }
   return TC_OK;
 }
@@ -240,6 +320,17 @@ tc_status tc_kron(const float* W1, const float* W2, const float* X, float* Y, in
   KronArgs a{};
   a.W1 = W1; a.W2 = W2; a.X = X; a.Y = Y;
   a.I = (int)I; a.K = (int)K; a.J = (int)J; a.L = (int)L;
+  if (K == 64 && L == 64 && J == 64) {
+    KronLdsArgs f{};
+    f.W1 = W1; f.W2 = W2; f.X = X; f.Y = Y;
+    f.I = (int)I;
+    f.iblocks = (int)ceil_div(I, 64);
+    const int64_t fgrid = B * f.iblocks;
+    if (fgrid <= kMaxGrid) {
+      kron_lds_kernel<64, 64, 64><<<dim3((unsigned)fgrid), dim3(WG_THREADS), 0, s>>>(f);
+      return launch_status();
+    }
+  }
   constexpr int TJ = 4;
   a.tiles_i = (int)ceil_div(I, 16);
   a.blocks_j = (int)ceil_div(J, 16 * TJ);

@@ -128,6 +128,51 @@ def test_mlp(tc, shape, oracle_threads):
         assert float(O[l].min()) >= 0.0
 
 
+def test_mlp_per_layer_launch_path(tc, oracle_threads, monkeypatch):
+    # the same chain through one launch per layer (the path taken when a width is not a multiple of 4)
+    monkeypatch.setenv("TC355_MLP_FUSED", "0")
+    batch, dims = 128, (1024, 1024, 512, 256)
+    I, Ws, bs = inputs.make_mlp(batch, dims, seed=inputs.SEED_BASE + 3)
+    ref = oracle.mlp_fcrelu(I, Ws, bs)
+    O = run_mlp(tc, I, Ws, bs)
+    for l in range(3):
+        check(O[l], ref[l], "mlp per-layer launches, layer %d" % l)
+
+
+def test_mlp_bounded_wait_gives_up_and_recovers(tc, oracle_threads, monkeypatch):
+    # A spin limit of 1 makes the device-wide wait give up at once: the kernel must still
+    # drain, flag the workspace, and the next ordinary call must be correct again.
+    batch, dims = 128, (1024, 1024, 512, 256)
+    I, Ws, bs = inputs.make_mlp(batch, dims, seed=inputs.SEED_BASE + 3)
+    Id, Wd, bd = dev(I), [dev(w) for w in Ws], [dev(b) for b in bs]
+    O = [torch.empty((batch, d), device="cuda") for d in dims[1:]]
+    ws = torch.zeros(tc.tc_mlp_fcrelu_workspace_bytes(batch, dims), dtype=torch.uint8, device="cuda")
+    monkeypatch.setenv("TC355_MLP_SPIN_LIMIT", "1")
+    tc.tc_mlp_fcrelu(Id, Wd, bd, O, ws)
+    torch.cuda.synchronize()
+    assert int(ws[:256].view(torch.int32)[33]) == 1
+    monkeypatch.delenv("TC355_MLP_SPIN_LIMIT")
+    tc.tc_mlp_fcrelu(Id, Wd, bd, O, ws)
+    torch.cuda.synchronize()
+    assert int(ws[:256].view(torch.int32)[33]) == 0
+    ref = oracle.mlp_fcrelu(I, Ws, bs)
+    for l in range(3):
+        check(O[l], ref[l], "mlp after a timed-out call, layer %d" % l)
+
+
+def test_mlp_workspace_may_hold_garbage(tc, oracle_threads):
+    batch, dims = 64, (256, 128, 64)
+    I, Ws, bs = inputs.make_mlp(batch, dims, seed=12, w_std=0.05)
+    ref = oracle.mlp_fcrelu(I, Ws, bs)
+    O = [torch.empty((batch, d), device="cuda") for d in dims[1:]]
+    ws = torch.full((tc.tc_mlp_fcrelu_workspace_bytes(batch, dims),), 0xAB, dtype=torch.uint8, device="cuda")
+    Id, Wd, bd = dev(I), [dev(w) for w in Ws], [dev(b) for b in bs]
+    for _ in range(3):
+        tc.tc_mlp_fcrelu(Id, Wd, bd, O, ws)
+    for l in range(2):
+        check(O[l], ref[l], "mlp garbage workspace, layer %d" % l)
+
+
 def test_mlp_intermediates_may_be_skipped(tc, oracle_threads):
     I, Ws, bs = inputs.make_mlp(24, (96, 80, 40, 24), seed=4, w_std=0.1, b_std=0.1)
     ref = oracle.mlp_fcrelu(I, Ws, bs)
