@@ -180,20 +180,17 @@ def main():
 
 
 def cpu_baseline(inputs, Ih, Wsh, bsh):
-    """The float64 oracle, as it stands, on the host cores, on a bounded sample of the step's workload."""
+    """The float64 oracle, as it stands, on the host cores, over one full step's workload (configurations 2-5)."""
     import oracle
 
     threads = oracle.max_threads()
     oracle.set_threads(threads)
     Xh, Yh = inputs.make_config(2)[1]
-    c4 = {k: v for k, v in inputs.CONFIGS[4].items() if k != "op"}
-    c4["N"] = 4
-    Igh, W1h, bh = inputs.make_gconv(seed=inputs.SEED_BASE + 4, **c4)
-    c5 = {k: v for k, v in inputs.CONFIGS[5].items() if k != "op"}
-    c5["B"] = 32
-    K1h, K2h, Xkh = inputs.make_kron(seed=inputs.SEED_BASE + 5, **c5)
-    flops = (inputs.flops_tbmm(500, 26, 72, 26) + inputs.flops_mlp(128, inputs.CONFIGS[3]["dims"])
-             + inputs.flops_gconv(**c4) + inputs.flops_kron(**c5))
+    Igh, W1h, bh = inputs.make_config(4)[1]
+    K1h, K2h, Xkh = inputs.make_config(5)[1]
+    cfg = {c: {k: v for k, v in inputs.CONFIGS[c].items() if k != "op"} for c in (2, 3, 4, 5)}
+    flops = (inputs.flops_tbmm(**cfg[2]) + inputs.flops_mlp(**cfg[3]) + inputs.flops_gconv(**cfg[4])
+             + inputs.flops_kron(**cfg[5]))
     t0 = time.perf_counter()
     oracle.tbmm(Xh, Yh)
     oracle.mlp_fcrelu(Ih, Wsh, bsh)
@@ -206,8 +203,8 @@ def cpu_baseline(inputs, Ih, Wsh, bsh):
         "cores": threads,
         "kind": "oracle",
         "seconds": round(dt, 2),
-        "sample": "tbmm and MLP configurations in full, grouped convolution with N=4 of 32 images, Kronecker layer "
-                  "with B=32 of 256 (single 5-index comprehension); algorithmic flops of the sample / wall time",
+        "sample": "one full step (configurations 2-5 once; the Kronecker layer as the single 5-index comprehension, "
+                  "counted at the flops of the two-stage evaluation); algorithmic flops of the step / wall time",
     }
 
 

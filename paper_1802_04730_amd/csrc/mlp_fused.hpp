@@ -34,23 +34,6 @@
 
 namespace tc355 {
 
-// Optional in-kernel timeline (development aid, compiled in only with -DTC355_MLP_TRACE):
-// thread 0 of every workgroup appends (tag, 100 MHz timestamp) pairs to a caller buffer.
-#ifdef TC355_MLP_TRACE
-#define TC355_TRACE_FIELD unsigned long long* trace;
-#define TC355_TRACE(p_, tag_)                                                                  \
-  do {                                                                                         \
-    if ((p_) && threadIdx.x == 0) {                                                            \
-      unsigned long long* t_ = (p_) + (size_t)blockIdx.x * 256;                                \
-      const unsigned long long n_ = t_[0];                                                     \
-      if (n_ < 126) { t_[1 + 2 * n_] = (tag_); t_[2 + 2 * n_] = __builtin_amdgcn_s_memrealtime(); t_[0] = n_ + 1; } \
-    }                                                                                          \
-  } while (0)
-#else
-#define TC355_TRACE_FIELD
-#define TC355_TRACE(p_, tag_) do { } while (0)
-#endif
-
 constexpr int MLP_MAX_LAYERS = 8;
 constexpr int MLP_SYNC_WORDS = 64;  // header of the sync area: token, error word
 constexpr int MLP_SYNC_TOKEN = 16;  // words 16,17: token of the call that owns the counters
@@ -329,7 +312,7 @@ __device__ __forceinline__ void mlp_layer(const TA* __restrict__ A, const float*
 
 __global__ __launch_bounds__(WG_THREADS, 2) void mlp_fused_kernel(MlpArgs p) {
   extern __shared__ __attribute__((aligned(32))) char smem[];
-#ifdef TC355_MLP_TRACE
+#ifdef TC355_TRACE_ENABLE
   unsigned long long* trace = p.trace;
 #else
   unsigned long long* trace = nullptr;

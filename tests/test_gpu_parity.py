@@ -199,6 +199,10 @@ GCONV_SHAPES = [
     (2, 4, 32, 32, 7, 7, 3, 3),     # paper table shape (32,32,32,32,7,7), fewer images/groups
     (2, 4, 4, 4, 56, 56, 3, 3),     # paper table shape (32,32,4,4,56,56), fewer images/groups
     (1, 2, 5, 20, 9, 11, 2, 4),     # two channel tiles, odd reduction length
+    (1, 2, 16, 16, 21, 58, 3, 3),   # width-58 band kernel: odd height (unaligned planes), ragged last band
+    (2, 1, 16, 16, 12, 58, 3, 3),   # width-58 band kernel: two bands, second one partial
+    (1, 1, 16, 16, 3, 58, 3, 3),    # width-58 band kernel: a single output row
+    (1, 3, 16, 16, 20, 30, 3, 3),   # 16x16 channels, other width: runtime-width LDS kernel
 ]
 
 
