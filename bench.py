@@ -39,6 +39,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--op-reps", type=int, default=200, help="launches per operator in the per-operator timing loops")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="only launch the grouped convolution and a plain 512 MiB device copy a few times (for "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs; the copy calibrates the counters)")
     return ap.parse_args()
 
 
@@ -89,6 +92,17 @@ def main():
         "kron": (lambda: tc355.tc_kron(K1, K2, Xk, Yk), inputs.flops_kron(**cfg[5]), inputs.bytes_kron(**cfg[5])),
     }
     step_flops = sum(v[1] for v in ops.values())
+
+    if args.traffic_probe:
+        src = torch.ones(128 * 1024 * 1024, dtype=torch.float32, device="cuda")  # 512 MiB read + 512 MiB written
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            ops["gconv"][0]()
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"traffic_probe": True, "copy_bytes_each_way": src.numel() * 4,
+                          "gconv_algorithmic_bytes": ops["gconv"][2]}), flush=True)
+        return
 
     def step(ev=None):
         ops["tbmm"][0]()
