@@ -26,7 +26,7 @@
 //     current one is contracted, one 16-byte load every few MFMA steps: issued
 //     as one burst, the loads of all workgroups pile up in the memory pipeline
 //     and block the issuing wavefronts for ~10 us per band (measured).
-// Two workgroups fit per compute unit (2 x 74 KiB of LDS).  Bias is added in fp64 before the single rounding.
+// Two workgroups fit per compute unit (2 x 74 KiB of LDS).  The accumulators start from the bias (fp64), so the epilogue is the single rounding.
 #pragma once
 #include "tc355_device.hpp"
 
@@ -180,7 +180,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_band_kernel(GconvBandArgs
       double bcur[TG], bnxt[TG];
 #pragma unroll
       for (int t = 0; t < TG; t++) {
-        acc[t] = d4_zero();
+        acc[t] = d4{bz[0], bz[1], bz[2], bz[3]};  // start from the bias: one add less per output
         if (t < tn) bcur[t] = bp[t0 + t][0];
       }
 #pragma unroll
@@ -198,6 +198,9 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_band_kernel(GconvBandArgs
           for (int t = 0; t < TG; t++)
             if (t < tn) bnxt[t] = bp[t0 + t][off];
         }
+        // pin the order "reads of step s+1, then MFMAs of step s": left alone, the compiler sinks
+        // the reads below the MFMAs to save registers and the LDS latency lands on the matrix pipe
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int t = 0; t < TG; t++)
           if (t < tn) acc[t] = mfma_f64(a[s], bcur[t], acc[t]);
@@ -213,7 +216,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_band_kernel(GconvBandArgs
           const int pl = (wave * TP + t0 + t) * 16 + r16;
           if (live[t0 + t] && pl < ROWS * OW && P0 + pl < npix) {
 #pragma unroll
-            for (int v = 0; v < 4; v++) dst[(int64_t)d_row(q, v) * npix + P0 + pl] = (float)(acc[t][v] + bz[v]);
+            for (int v = 0; v < 4; v++) dst[(int64_t)d_row(q, v) * npix + P0 + pl] = (float)acc[t][v];
           }
         }
       }
