@@ -13,6 +13,7 @@
 #include "gconv_band.hpp"
 #include "gconv_lds.hpp"
 #include "gconv_wave.hpp"
+#include "gemm_tile.hpp"
 #include "gemm_wave.hpp"
 #include "kron_lds.hpp"
 #include "kron_wave.hpp"
@@ -50,8 +51,31 @@ tc_status launch_gemm_tm(GemmArgs a, int64_t batch, int tm, hipStream_t s) {
   return launch_status();
 }
 
+// LDS-tiled kernel for big blocks (64 x 64 output tiles); returns false if it does not apply.
+template <typename TA, int EPI>
+bool try_gemm_tile(const GemmArgs& a, int64_t batch, hipStream_t s, tc_status* st) {
+  if (a.K % 4 != 0 || a.N < 48 || a.M < 48) return false;
+  const int64_t tiles = ceil_div(a.N, GT_BM) * ceil_div(a.M, GT_BN);
+  if (tiles > kMaxGrid || batch > 65535) return false;
+  if (tiles * batch < 128) return false;  // too few blocks to fill the chip: the wave-level kernel spreads wider
+  static std::atomic<int> lds_ok{0};  // needs more than the default 64 KiB of dynamic LDS
+  if (!lds_ok.load(std::memory_order_acquire)) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_nt_tile_kernel<TA, EPI>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, GT_LDS_BYTES) != hipSuccess) {
+      *st = TC_ERR_LAUNCH;
+      return true;
+    }
+    lds_ok.store(1, std::memory_order_release);
+  }
+  gemm_nt_tile_kernel<TA, EPI><<<dim3((unsigned)tiles, (unsigned)batch), dim3(WG_THREADS), GT_LDS_BYTES, s>>>(a);
+  *st = launch_status();
+  return true;
+}
+
 template <typename TA, int EPI>
 tc_status launch_gemm(const GemmArgs& a, int64_t batch, int tm, hipStream_t s) {
+  tc_status st = TC_OK;
+  if (try_gemm_tile<TA, EPI>(a, batch, s, &st)) return st;
   // widest per-lane load that keeps every row start aligned
   if (a.K % 4 == 0) return launch_gemm_tm<TA, 4, EPI>(a, batch, tm, s);
   if (a.K % 2 == 0) return launch_gemm_tm<TA, 2, EPI>(a, batch, tm, s);

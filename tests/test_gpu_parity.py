@@ -50,6 +50,10 @@ TBMM_SHAPES = [
     (5, 40, 200, 30),     # several strips per row tile, K even but not a multiple of 4
     (1, 128, 256, 32),    # transposed matmul of Section 7 (B = 1)
     (7, 5, 81, 64),
+    (40, 100, 130, 68),   # LDS-tiled kernel (>= 128 blocks): ragged 64x64 blocks, reduction not a multiple of the chunk
+    (1, 128, 1024, 1024), # the paper's medium transposed matmul (M,K,N) = (128,1024,1024)
+    (1, 128, 4096, 96),   # LDS-tiled kernel, one batch element, three chunks
+    (130, 64, 64, 4),     # LDS-tiled kernel: a single short chunk
 ]
 
 
