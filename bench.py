@@ -153,6 +153,27 @@ def main():
             "frac_vs_f32_mfma_or_hbm": round(max(flops / (PEAK_F32_MFMA_TFLOPS * 1e12), t_hbm) * 1e6 / us, 4),
         }
 
+    # ---- beyond the step: the paper's largest transposed matmul (Section 7, tmm (M,K,N) = (128,4096,16384)),
+    # the one shape of the paper that is bound by the matrix pipe alone; runs through tc_tbmm with B = 1
+    Xt = torch.randn((1, 128, 4096), device="cuda")
+    Yt = torch.randn((1, 16384, 4096), device="cuda")
+    Zt = torch.empty((1, 128, 16384), device="cuda")
+    for _ in range(3):
+        tc355.tc_tbmm(Xt, Yt, Zt)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(20):
+        tc355.tc_tbmm(Xt, Yt, Zt)
+    e1.record()
+    torch.cuda.synchronize()
+    tmm_us = e0.elapsed_time(e1) * 1e3 / 20
+    tmm_flops = inputs.flops_tbmm(1, 128, 16384, 4096)
+    extra = {"tmm_128x4096x16384": {"us": round(tmm_us, 1), "gflops": round(tmm_flops / tmm_us * 1e-3, 1),
+                                    "bound": "mfma",
+                                    "frac": round(tmm_flops / (PEAK_F64_MFMA_TFLOPS * 1e12) * 1e6 / tmm_us, 4)}}
+    del Xt, Yt, Zt
+
     g_flops = ops["gconv"][1]
     achieved = g_flops / (gconv_ms * 1e-3) / 1e12
     roofline = {
@@ -185,6 +206,7 @@ def main():
                                "gconv N=32 G=32 C=F=16 58x58 3x3; kron B=256 64^4",
                    "flops_per_step": step_flops},
         "ops": per_op,
+        "ops_beyond_step": extra,
         "roofline": roofline,
     }
 

@@ -28,6 +28,8 @@
 //     and block the issuing wavefronts for ~10 us per band (measured).
 // Two workgroups fit per compute unit (2 x 74 KiB of LDS).  The accumulators start from the bias (fp64), so the epilogue is the single rounding.
 #pragma once
+#include <type_traits>
+
 #include "tc355_device.hpp"
 
 namespace tc355 {
@@ -58,11 +60,10 @@ struct GconvBandGeom {
   static_assert((4 * (C / 4 - 1) * PS + (KH - 1) * W + KW - 1) * 8 < 65536, "LDS immediates out of range");
 };
 
-template <int C, int KH, int KW, int W, int ROWS>
-__global__ __launch_bounds__(WG_THREADS, 2) void gconv_band_kernel(GconvBandArgs p) {
+template <int C, int KH, int KW, int W, int ROWS, int MINW>
+__global__ __launch_bounds__(WG_THREADS, MINW) void gconv_band_kernel(GconvBandArgs p) {
   using Gm = GconvBandGeom<C, KH, KW, W, ROWS>;
-  constexpr int F = Gm::F, OW = Gm::OW, PS = Gm::PS, TP = Gm::TP, NS = Gm::NS, LEN = Gm::LEN, LEN4 = Gm::LEN4,
-                NLD = Gm::NLD;
+  constexpr int F = Gm::F, OW = Gm::OW, PS = Gm::PS, NS = Gm::NS, LEN = Gm::LEN, LEN4 = Gm::LEN4, NLD = Gm::NLD;
   extern __shared__ __attribute__((aligned(16))) double band[];  // [C][PS]
 
 #ifdef TC355_TRACE_ENABLE
@@ -158,77 +159,72 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_band_kernel(GconvBandArgs
     TC355_TRACE_R(trace, 4);
 
     const int P0 = b * ROWS * OW;
-    // All TP tiles of this wavefront advance together, one reduction step at a time, and the
-    // LDS reads of step s+1 are issued before the MFMAs of step s: every accumulator chain
-    // then has TP MFMA slots between dependent instructions, which covers the LDS latency.
-    const double* bp[TP];
-    bool live[TP];
+    // Tiles of the band are dealt to the wavefronts round-robin: tile id = 4*t + wr.  Every wavefront
+    // gets FULL = TILES/4 of them; the first TILES%4 ranks get one more.  The rank wr of a wavefront
+    // rotates with the band number, so over four bands every SIMD does the same amount of work.
+    constexpr int TILES = Gm::TILES, FULL = TILES / WAVES_PER_WG, REM = TILES % WAVES_PER_WG;
+    const int wr = (wave + b) & (WAVES_PER_WG - 1);
+    auto tile_ptr = [&](int tile) {
+      const int px = min(min(P0 + tile * 16 + r16, npix - 1) - P0, ROWS * OW - 1);  // clamp a ragged last band
+      return band + q * PS + (px / OW) * W + (px % OW);
+    };
+    // TN tiles advance together, one reduction step at a time; the LDS reads of step s+1 are issued
+    // before the MFMAs of step s.  FETCH: units [j0, j0+NJ) of the next band are fetched between steps.
+    auto group = [&](auto tn_c, int t_first, auto j0_c, auto nj_c) {
+      constexpr int TN = decltype(tn_c)::value, J0 = decltype(j0_c)::value, NJ = decltype(nj_c)::value;
+      constexpr int EVERY = NJ > 0 ? (NS / NJ > 0 ? NS / NJ : 1) : NS + 1;
+      const double* bp[TN];
+      d4 acc[TN];
+      double bcur[TN], bnxt[TN];
 #pragma unroll
-    for (int t = 0; t < TP; t++) {
-      const int pl = (wave * TP + t) * 16 + r16;                       // pixel within the band
-      live[t] = (wave * TP + t) * 16 < ROWS * OW;                      // uniform
-      const int px = min(min(P0 + pl, npix - 1) - P0, ROWS * OW - 1);  // clamp ragged bands / tiles
-      const int hl = px / OW, wl = px - hl * OW;
-      bp[t] = band + q * PS + hl * W + wl;
-    }
-    // tiles are processed in groups of at most TG to bound the live registers
-    constexpr int TG = 4;
-#pragma unroll
-    for (int t0 = 0; t0 < TP; t0 += TG) {
-      const int tn = (TP - t0 < TG) ? TP - t0 : TG;
-      d4 acc[TG];
-      double bcur[TG], bnxt[TG];
-#pragma unroll
-      for (int t = 0; t < TG; t++) {
+      for (int t = 0; t < TN; t++) {
+        bp[t] = tile_ptr(4 * (t_first + t) + wr);
         acc[t] = d4{bz[0], bz[1], bz[2], bz[3]};  // start from the bias: one add less per output
-        if (t < tn) bcur[t] = bp[t0 + t][0];
+        bcur[t] = bp[t][0];
       }
 #pragma unroll
       for (int s = 0; s < NS; s++) {
-        {
-          constexpr int SLOTS = ((TP + TG - 1) / TG) * NS;        // MFMA steps per band and wavefront
-          constexpr int EVERY = SLOTS / NLD > 0 ? SLOTS / NLD : 1;  // one fetch every EVERY steps, spread over the whole band
-          const int slot = (t0 / TG) * NS + s;
-          if (slot % EVERY == EVERY / 2 && slot / EVERY < NLD && more) fetch_one(b + 1, slot / EVERY);
-        }
+        if (NJ > 0 && s % EVERY == EVERY / 2 && s / EVERY < NJ && more) fetch_one(b + 1, J0 + s / EVERY);
         if (s + 1 < NS) {
           const int kk = (s + 1) / (C / 4), c4 = (s + 1) % (C / 4);
           const int off = 4 * c4 * PS + (kk / KW) * W + (kk % KW);
 #pragma unroll
-          for (int t = 0; t < TG; t++)
-            if (t < tn) bnxt[t] = bp[t0 + t][off];
+          for (int t = 0; t < TN; t++) bnxt[t] = bp[t][off];
         }
         // pin the order "reads of step s+1, then MFMAs of step s": left alone, the compiler sinks
         // the reads below the MFMAs to save registers and the LDS latency lands on the matrix pipe
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int t = 0; t < TG; t++)
-          if (t < tn) acc[t] = mfma_f64(a[s], bcur[t], acc[t]);
+        for (int t = 0; t < TN; t++) acc[t] = mfma_f64(a[s], bcur[t], acc[t]);
 #pragma unroll
-        for (int t = 0; t < TG; t++)
-          if (t < tn) bcur[t] = bnxt[t];
-        // keep the compiler from hoisting every LDS read of the tile to the top (register spills)
+        for (int t = 0; t < TN; t++) bcur[t] = bnxt[t];
+        // keep the compiler from hoisting every LDS read of the group to the top (register spills)
         __builtin_amdgcn_sched_barrier(0);
       }
+      if (NJ > 0 && more) {  // units the loop had no step for
 #pragma unroll
-      for (int t = 0; t < TG; t++) {
-        if (t < tn) {
-          const int pl = (wave * TP + t0 + t) * 16 + r16;
-          if (live[t0 + t] && pl < ROWS * OW && P0 + pl < npix) {
+        for (int j = (NS - 1 - EVERY / 2) / EVERY + 1; j < NJ; j++) fetch_one(b + 1, J0 + j);
+      }
 #pragma unroll
-            for (int v = 0; v < 4; v++) dst[(int64_t)d_row(q, v) * npix + P0 + pl] = (float)acc[t][v];
-          }
+      for (int t = 0; t < TN; t++) {
+        const int pl = (4 * (t_first + t) + wr) * 16 + r16;  // pixel within the band
+        if (pl < ROWS * OW && P0 + pl < npix) {
+#pragma unroll
+          for (int v = 0; v < 4; v++) dst[(int64_t)d_row(q, v) * npix + P0 + pl] = (float)acc[t][v];
         }
       }
-    }
-    {
-      constexpr int SLOTS = ((TP + TG - 1) / TG) * NS;
-      constexpr int EVERY = SLOTS / NLD > 0 ? SLOTS / NLD : 1;
-      constexpr int DONE = (SLOTS - 1 - EVERY / 2) / EVERY + 1 < NLD ? (SLOTS - 1 - EVERY / 2) / EVERY + 1 : NLD;  // units already fetched inside the loop
-      if (more) {
-#pragma unroll
-        for (int j = DONE; j < NLD; j++) fetch_one(b + 1, j);
-      }
+    };
+    using std::integral_constant;
+    // FULL tiles in groups of at most 4 (bounds the live registers); the next band's NLD fetch units
+    // are spread over the groups in proportion
+    constexpr int G1 = FULL < 4 ? FULL : 4, G2 = FULL - G1 < 4 ? FULL - G1 : 4;
+    static_assert(FULL >= 1 && FULL <= 8, "1..8 whole tiles per wavefront and band");
+    constexpr int NJ1 = G2 > 0 ? (NLD * G1 + FULL - 1) / FULL : NLD;
+    group(integral_constant<int, G1>{}, 0, integral_constant<int, 0>{}, integral_constant<int, NJ1>{});
+    if constexpr (G2 > 0)
+      group(integral_constant<int, G2>{}, G1, integral_constant<int, NJ1>{}, integral_constant<int, NLD - NJ1>{});
+    if constexpr (REM > 0) {
+      if (wr < REM) group(integral_constant<int, 1>{}, FULL, integral_constant<int, 0>{}, integral_constant<int, 0>{});
     }
     TC355_TRACE_R(trace, 5);
   }

@@ -59,37 +59,59 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gemm_nt_tile_kernel(GemmArgs p)
     Vec<TA, AV> a[A_LD];
     Vec<float, 4> b[B_LD];
   };
-  // No branch around the loads: a unit past K re-reads the start of its row and is staged as zeros.
+  // Loads are never skipped per lane: a unit past K re-reads the start of its row and is staged as zeros.
   auto fetch = [&](Regs& r, int ck) {
     const int k0 = min(ck, nck - 1) * GT_KC;
-    const bool ain = k0 + a_k < K, bin = k0 + b_k < K;
+    if (k0 + GT_KC <= K) {  // whole chunk inside the reduction (uniform): lane offset + scalar base, no ALU work
+      const TA* Ak = A + k0;
+      const float* Bk = Bm + k0;
 #pragma unroll
-    for (int i = 0; i < A_LD; i++) r.a[i] = load_vec<TA, AV>(A + aoff[i] + (ain ? k0 : -a_k));
+      for (int i = 0; i < A_LD; i++) r.a[i] = load_vec<TA, AV>(Ak + aoff[i]);
 #pragma unroll
-    for (int i = 0; i < B_LD; i++) r.b[i] = load_vec<float, 4>(Bm + boff[i] + (bin ? k0 : -b_k));
+      for (int i = 0; i < B_LD; i++) r.b[i] = load_vec<float, 4>(Bk + boff[i]);
+    } else {
+      const bool ain = k0 + a_k < K, bin = k0 + b_k < K;
+#pragma unroll
+      for (int i = 0; i < A_LD; i++) r.a[i] = load_vec<TA, AV>(A + aoff[i] + (ain ? k0 : -a_k));
+#pragma unroll
+      for (int i = 0; i < B_LD; i++) r.b[i] = load_vec<float, 4>(Bm + boff[i] + (bin ? k0 : -b_k));
+    }
   };
   auto stage = [&](const Regs& r, int ck, double* buf) {
     const int k0 = ck * GT_KC;
-    const bool ain = k0 + a_k < K, bin = k0 + b_k < K;
     double* As = buf + a_row0 * GT_RS + a_k;
     double* Bs = buf + GT_BM * GT_RS + b_row0 * GT_RS + b_k;
+    if (k0 + GT_KC <= K) {  // whole chunk inside the reduction (uniform): widen and store, nothing else
 #pragma unroll
-    for (int i = 0; i < A_LD; i++) {
-      double* d = As + i * (WG_THREADS / A_UPR) * GT_RS;
+      for (int i = 0; i < A_LD; i++)
 #pragma unroll
-      for (int e = 0; e < AV; e += 2) {
-        dbl2 v = {ain ? (double)r.a[i].e[e] : 0.0, ain ? (double)r.a[i].e[e + 1] : 0.0};
-        *reinterpret_cast<dbl2*>(d + e) = v;
-      }
-    }
+        for (int e = 0; e < AV; e += 2) {
+          dbl2 v = {(double)r.a[i].e[e], (double)r.a[i].e[e + 1]};
+          *reinterpret_cast<dbl2*>(As + i * (WG_THREADS / A_UPR) * GT_RS + e) = v;
+        }
 #pragma unroll
-    for (int i = 0; i < B_LD; i++) {
-      double* d = Bs + i * (WG_THREADS / B_UPR) * GT_RS;
+      for (int i = 0; i < B_LD; i++)
 #pragma unroll
-      for (int e = 0; e < 4; e += 2) {
-        dbl2 v = {bin ? (double)r.b[i].e[e] : 0.0, bin ? (double)r.b[i].e[e + 1] : 0.0};
-        *reinterpret_cast<dbl2*>(d + e) = v;
-      }
+        for (int e = 0; e < 4; e += 2) {
+          dbl2 v = {(double)r.b[i].e[e], (double)r.b[i].e[e + 1]};
+          *reinterpret_cast<dbl2*>(Bs + i * (WG_THREADS / B_UPR) * GT_RS + e) = v;
+        }
+    } else {  // ragged last chunk: what lies past K is staged as zeros
+      const bool ain = k0 + a_k < K, bin = k0 + b_k < K;
+#pragma unroll
+      for (int i = 0; i < A_LD; i++)
+#pragma unroll
+        for (int e = 0; e < AV; e += 2) {
+          dbl2 v = {ain ? (double)r.a[i].e[e] : 0.0, ain ? (double)r.a[i].e[e + 1] : 0.0};
+          *reinterpret_cast<dbl2*>(As + i * (WG_THREADS / A_UPR) * GT_RS + e) = v;
+        }
+#pragma unroll
+      for (int i = 0; i < B_LD; i++)
+#pragma unroll
+        for (int e = 0; e < 4; e += 2) {
+          dbl2 v = {bin ? (double)r.b[i].e[e] : 0.0, bin ? (double)r.b[i].e[e + 1] : 0.0};
+          *reinterpret_cast<dbl2*>(Bs + i * (WG_THREADS / B_UPR) * GT_RS + e) = v;
+        }
     }
   };
 
@@ -122,14 +144,23 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gemm_nt_tile_kernel(GemmArgs p)
         fetch(ring[(i + 1) & 1], c + 3);
         const double* As = gt_lds + (i & 1) * GT_BUF + (32 * wr + r16) * GT_RS + q;
         const double* Bs = gt_lds + (i & 1) * GT_BUF + GT_BM * GT_RS + (32 * wc + r16) * GT_RS + q;
+        // LDS reads of step s+1 are issued before the MFMAs of step s (the barriers pin that order;
+        // left alone, the compiler reads right before use and the LDS latency lands on the matrix pipe)
+        double a0 = As[0], a1 = As[16 * GT_RS], b0 = Bs[0], b1 = Bs[16 * GT_RS];
 #pragma unroll
         for (int s = 0; s < GT_KC / 4; s++) {
-          const double a0 = As[4 * s], a1 = As[16 * GT_RS + 4 * s];
-          const double b0 = Bs[4 * s], b1 = Bs[16 * GT_RS + 4 * s];
+          double na0 = 0, na1 = 0, nb0 = 0, nb1 = 0;
+          if (s + 1 < GT_KC / 4) {
+            na0 = As[4 * s + 4]; na1 = As[16 * GT_RS + 4 * s + 4];
+            nb0 = Bs[4 * s + 4]; nb1 = Bs[16 * GT_RS + 4 * s + 4];
+          }
+          __builtin_amdgcn_sched_barrier(0);
           acc[0][0] = mfma_f64(a0, b0, acc[0][0]);
           acc[0][1] = mfma_f64(a0, b1, acc[0][1]);
           acc[1][0] = mfma_f64(a1, b0, acc[1][0]);
           acc[1][1] = mfma_f64(a1, b1, acc[1][1]);
+          __builtin_amdgcn_sched_barrier(0);
+          a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
         }
         __syncthreads();
       }

@@ -158,7 +158,7 @@ size_t mlp_sync_bytes() { return round256((MLP_SYNC_WORDS + (size_t)(MLP_MAX_LAY
 size_t mlp_act_bytes(int64_t batch, int64_t width) { return round256((size_t)batch * (size_t)width * sizeof(double)); }
 
 // ---- fastest grouped convolution: compile-time width, one workgroup per (image, group) -----
-template <int C, int KH, int KW, int W, int ROWS>
+template <int C, int KH, int KW, int W, int ROWS, int MINW>
 bool try_gconv_band(const GconvArgs& g, hipStream_t s, tc_status* st) {
   using Gm = GconvBandGeom<C, KH, KW, W, ROWS>;
   if (g.C != C || g.F != Gm::F || g.KH != KH || g.KW != KW || g.W != W) return false;
@@ -166,7 +166,7 @@ bool try_gconv_band(const GconvArgs& g, hipStream_t s, tc_status* st) {
   if (grid > kMaxGrid) return false;
   static std::atomic<int> lds_ok{0};  // more than the default 64 KiB of dynamic LDS
   if (!lds_ok.load(std::memory_order_acquire)) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gconv_band_kernel<C, KH, KW, W, ROWS>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gconv_band_kernel<C, KH, KW, W, ROWS, MINW>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, Gm::LDS_BYTES) != hipSuccess) {
       *st = TC_ERR_LAUNCH;
       return true;
@@ -176,7 +176,7 @@ bool try_gconv_band(const GconvArgs& g, hipStream_t s, tc_status* st) {
   GconvBandArgs a{};
   a.I = g.I; a.W1 = g.W1; a.bias = g.bias; a.O = g.O;
   a.G = g.G; a.H = g.H;
-  gconv_band_kernel<C, KH, KW, W, ROWS><<<dim3((unsigned)grid), dim3(WG_THREADS), Gm::LDS_BYTES, s>>>(a);
+  gconv_band_kernel<C, KH, KW, W, ROWS, MINW><<<dim3((unsigned)grid), dim3(WG_THREADS), Gm::LDS_BYTES, s>>>(a);
   *st = launch_status();
   return true;
 }
@@ -344,7 +344,7 @@ tc_status tc_group_conv(const float* I, const float* W1, const float* bias, floa
   a.N = (int)N; a.G = (int)G; a.C = (int)C; a.F = (int)F; a.H = (int)H; a.W = (int)W;
   a.KH = (int)KH; a.KW = (int)KW; a.OH = (int)OH; a.OW = (int)OW;
   tc_status st = TC_OK;
-  if (try_gconv_band<16, 3, 3, 58, 8>(a, s, &st)) return st;
+  if (try_gconv_band<16, 3, 3, 58, 8, 2>(a, s, &st)) return st;
   if (try_gconv_lds<16, 16, 3, 3, 7>(a, s, &st)) return st;
   constexpr int TP = 4;
   a.tiles_f = (int)ceil_div(F, 16);
