@@ -25,7 +25,9 @@
 // kernel starts and then publishes the call's 64-bit token (unique per call,
 // chosen by the host); a workgroup adds itself to a counter only after it has
 // seen that token, which by the time a layer is finished is long there; release
-// words are compared with the token, so stale ones never match.  Every
+// words are compared with the token, so stale ones never match; the last
+// workgroup to leave withdraws the token, which makes replays of a captured graph
+// (same token every time) safe.  Every
 // spin is bounded: if a wait does not end (workgroups not co-resident), the
 // waiting workgroup raises the error word and goes on, so the grid always
 // drains.
@@ -37,6 +39,7 @@ namespace tc355 {
 constexpr int MLP_MAX_LAYERS = 8;
 constexpr int MLP_SYNC_WORDS = 64;  // header of the sync area: token, error word
 constexpr int MLP_SYNC_TOKEN = 16;  // words 16,17: token of the call that owns the counters
+constexpr int MLP_SYNC_EXIT = 32;   // workgroups that have left the kernel
 constexpr int MLP_SYNC_ERROR = 33;  // 1 if a device-wide wait of the last call gave up
 
 struct MlpArgs {
@@ -323,9 +326,13 @@ __global__ __launch_bounds__(WG_THREADS, 2) void mlp_fused_kernel(MlpArgs p) {
     for (int l = 0; l + 1 < p.n_layers; l++) {
       unsigned* bar = p.sync + MLP_SYNC_WORDS + l * MLP_BAR_WORDS;
       __hip_atomic_store(bar, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      for (unsigned g = 0; g < ngroups; g++)
+      for (unsigned g = 0; g < ngroups; g++) {
         __hip_atomic_store(bar + 16 + 16 * g, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // release words too: a graph replay carries the same token, so last time's would still match
+        __hip_atomic_store(bar + 16 + 16 * MLP_GROUPS + 16 * g, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
     }
+    __hip_atomic_store(p.sync + MLP_SYNC_EXIT, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __hip_atomic_store(p.sync + MLP_SYNC_ERROR, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __hip_atomic_store(reinterpret_cast<unsigned long long*>(p.sync + MLP_SYNC_TOKEN), p.token, __ATOMIC_RELEASE,
                        __HIP_MEMORY_SCOPE_AGENT);
@@ -340,6 +347,15 @@ __global__ __launch_bounds__(WG_THREADS, 2) void mlp_fused_kernel(MlpArgs p) {
     TC355_TRACE(trace, 6);
     if (l + 1 < p.n_layers) mlp_grid_barrier(p.sync, l, p.token, gridDim.x, p.spin_limit);
     TC355_TRACE(trace, 7);
+  }
+  // The last workgroup out withdraws the token.  A replay of a captured HIP graph launches this
+  // kernel again with the SAME token; with the token withdrawn, the other workgroups again wait
+  // until workgroup 0 has zeroed the counters before they count themselves in.
+  if (p.n_layers > 1 && threadIdx.x == 0) {
+    const unsigned old = __hip_atomic_fetch_add(p.sync + MLP_SYNC_EXIT, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (old == gridDim.x - 1)
+      __hip_atomic_store(reinterpret_cast<unsigned long long*>(p.sync + MLP_SYNC_TOKEN), 0ull, __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
   }
 }
 

@@ -133,7 +133,7 @@ int device_cus() {
   return cus;
 }
 
-// A fresh 64-bit token per fused-MLP call (never 0): random start, then counting.
+// A fresh 64-bit token per fused-MLP call (low 32 bits never 0): random start, then counting.
 unsigned long long next_token() {
   static std::atomic<unsigned long long> tok{[] {
     std::random_device rd;
@@ -142,7 +142,8 @@ unsigned long long next_token() {
     return t | 1ull;
   }()};
   unsigned long long t = tok.fetch_add(1, std::memory_order_relaxed);
-  return t ? t : tok.fetch_add(1, std::memory_order_relaxed);
+  while ((t & 0xffffffffull) == 0) t = tok.fetch_add(1, std::memory_order_relaxed);  // low word is what release words carry
+  return t;
 }
 
 long env_long(const char* name, long dflt) {

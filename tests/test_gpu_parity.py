@@ -266,3 +266,81 @@ def test_outputs_need_no_zeroing_and_calls_repeat(tc, oracle_threads):
     for _ in range(3):
         tc.tc_kron(a, b, c, Y)
     check(Y, ref, "kron repeated")
+
+
+# ---------------------------------------------------------------- HIP graph capture
+def test_all_entry_points_replay_from_a_hip_graph(tc, oracle_threads):
+    # The library enqueues kernels only (no memset, no allocation), so a step can be captured once and
+    # replayed.  Replays are interleaved with eager work and synchronisations, and every replay is
+    # checked (the fused MLP re-runs with the same barrier token on every replay).
+    X, Y = inputs.make_tbmm(64, 26, 72, 26, seed=21)
+    I, Ws, bs = inputs.make_mlp(128, (256, 256, 128, 64), seed=22, w_std=0.05)
+    Ig, W1, bias = inputs.make_gconv(2, 4, 16, 16, 58, 58, 3, 3, seed=23)
+    K1, K2, Xk = inputs.make_kron(16, 64, 64, 64, 64, seed=24)
+    ref = {"tbmm": oracle.tbmm(X, Y), "mlp": oracle.mlp_fcrelu(I, Ws, bs),
+           "gconv": oracle.group_conv(Ig, W1, bias), "kron": oracle.kron(K1, K2, Xk)}
+    Xd, Yd, Id, Wd, bd = dev(X), dev(Y), dev(I), [dev(w) for w in Ws], [dev(b) for b in bs]
+    Igd, W1d, biasd, K1d, K2d, Xkd = dev(Ig), dev(W1), dev(bias), dev(K1), dev(K2), dev(Xk)
+    Z = torch.empty((64, 26, 72), device="cuda")
+    O = [torch.empty((128, w.shape[0]), device="cuda") for w in Ws]
+    ws = torch.empty(tc.tc_mlp_fcrelu_workspace_bytes(128, (256, 256, 128, 64)), dtype=torch.uint8, device="cuda")
+    Og = torch.empty(ref["gconv"].shape, device="cuda")
+    Yk = torch.empty((16, 64, 64), device="cuda")
+
+    def step():
+        tc.tc_tbmm(Xd, Yd, Z)
+        tc.tc_mlp_fcrelu(Id, Wd, bd, O, ws)
+        tc.tc_group_conv(Igd, W1d, biasd, Og)
+        tc.tc_kron(K1d, K2d, Xkd, Yk)
+
+    step()  # eager once: first-call set-up (LDS limits) happens outside the capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for rep in range(3):
+        for t in [Z, Og, Yk] + O:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        scratch = torch.randn(1 << 20, device="cuda").sum()  # eager work between replays
+        torch.cuda.synchronize()
+        check(Z, ref["tbmm"], "graph replay %d tbmm" % rep)
+        for l in range(3):
+            check(O[l], ref["mlp"][l], "graph replay %d mlp layer %d" % (rep, l))
+        check(Og, ref["gconv"], "graph replay %d gconv" % rep)
+        check(Yk, ref["kron"], "graph replay %d kron" % rep)
+        assert int(ws[:256].view(torch.int32)[33]) == 0
+        del scratch
+
+
+# ---------------------------------------------------------------- large sizes, sampled
+def test_tbmm_large_batch_sampled(tc, oracle_threads):
+    # 40x the benchmark batch; the oracle evaluates a sample of batch elements
+    B, N, M, K = 20000, 26, 72, 26
+    X, Y = inputs.make_tbmm(B, N, M, K, seed=31)
+    Z = torch.full((B, N, M), float("nan"), device="cuda")
+    tc.tc_tbmm(dev(X), dev(Y), Z)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(Z).all())
+    pick = np.random.default_rng(0).choice(B, size=64, replace=False)
+    pick = np.concatenate([pick, [0, B - 1]])
+    check(Z[torch.from_numpy(pick).cuda()], oracle.tbmm(X[pick], Y[pick]), "tbmm B=20000, sampled batches")
+
+
+def test_kron_and_gconv_stay_inside_their_outputs(tc, oracle_threads):
+    # canaries on both sides of the outputs survive
+    W1, W2, X = inputs.make_kron(5, 40, 64, 64, 64, seed=32)  # 40 rows: the tuned kernel with a ragged row block
+    buf = torch.full((5 * 40 * 64 + 512,), 777.0, device="cuda")
+    Yv = buf[256:256 + 5 * 40 * 64].view(5, 40, 64)
+    tc.tc_kron(dev(W1), dev(W2), dev(X), Yv)
+    check(Yv, oracle.kron(W1, W2, X), "kron guard band")
+    assert torch.all(buf[:256] == 777.0) and torch.all(buf[256 + 5 * 40 * 64:] == 777.0)
+
+    Ig, Wg, bias = inputs.make_gconv(1, 2, 16, 16, 21, 58, 3, 3, seed=33)  # band kernel, ragged last band
+    n = 1 * 2 * 16 * 19 * 56
+    buf = torch.full((n + 512,), 777.0, device="cuda")
+    Ov = buf[256:256 + n].view(1, 2, 16, 19, 56)
+    tc.tc_group_conv(dev(Ig), dev(Wg), dev(bias), Ov)
+    check(Ov, oracle.group_conv(Ig, Wg, bias), "gconv guard band")
+    assert torch.all(buf[:256] == 777.0) and torch.all(buf[256 + n:] == 777.0)
