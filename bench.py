@@ -39,6 +39,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--op-reps", type=int, default=200, help="launches per operator in the per-operator timing loops")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--scaling", action="store_true",
+                    help="supplementary: time tbmm, the MLP and the Kronecker layer at 1x, 8x and 64x the benchmark "
+                         "batch (one JSON line per point), to separate launch/latency floors from kernel throughput")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="only launch the grouped convolution and a plain 512 MiB device copy a few times (for "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs; the copy calibrates the counters)")
@@ -92,6 +95,10 @@ def main():
         "kron": (lambda: tc355.tc_kron(K1, K2, Xk, Yk), inputs.flops_kron(**cfg[5]), inputs.bytes_kron(**cfg[5])),
     }
     step_flops = sum(v[1] for v in ops.values())
+
+    if args.scaling:
+        scaling_study(torch, tc355, inputs)
+        return
 
     if args.traffic_probe:
         src = torch.ones(128 * 1024 * 1024, dtype=torch.float32, device="cuda")  # 512 MiB read + 512 MiB written
@@ -213,6 +220,56 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inputs, Ih, Wsh, bsh)
     print(json.dumps(out), flush=True)
+
+
+def scaling_study(torch, tc355, inputs):
+    """Batch-scaled versions of the three latency-bound operators (supplementary, not the headline metric)."""
+    def timed(fn, reps):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps
+
+    def report(op, scale, us, flops, nbytes):
+        t_mfma, t_hbm = flops / (PEAK_F64_MFMA_TFLOPS * 1e12), nbytes / (PEAK_HBM_GBS * 1e9)
+        print(json.dumps({"op": op, "batch_scale": scale, "us": round(us, 2), "gflops": round(flops / us * 1e-3, 1),
+                          "gbs": round(nbytes / us * 1e-3, 1), "bound": "mfma" if t_mfma >= t_hbm else "hbm",
+                          "frac": round(max(t_mfma, t_hbm) * 1e6 / us, 4)}), flush=True)
+
+    for scale in (1, 8, 64):
+        B = 500 * scale
+        X = torch.rand((B, 26, 26), device="cuda") * 2 - 1
+        Y = torch.rand((B, 72, 26), device="cuda") * 2 - 1
+        Z = torch.empty((B, 26, 72), device="cuda")
+        us = timed(lambda: tc355.tc_tbmm(X, Y, Z), 100 if scale < 64 else 30)
+        report("tbmm", scale, us, inputs.flops_tbmm(B, 26, 72, 26), inputs.bytes_tbmm(B, 26, 72, 26))
+        del X, Y, Z
+    dims = inputs.CONFIGS[3]["dims"]
+    Ws = [torch.randn((dims[l + 1], dims[l]), device="cuda") * 0.02 for l in range(3)]
+    bs = [torch.randn((dims[l + 1],), device="cuda") * 0.01 for l in range(3)]
+    for scale in (1, 8, 64):
+        batch = 128 * scale
+        I = torch.randn((batch, dims[0]), device="cuda")
+        O = [torch.empty((batch, d), device="cuda") for d in dims[1:]]
+        ws = torch.empty(tc355.tc_mlp_fcrelu_workspace_bytes(batch, dims), dtype=torch.uint8, device="cuda")
+        us = timed(lambda: tc355.tc_mlp_fcrelu(I, Ws, bs, O, ws), 100 if scale < 64 else 20)
+        report("mlp", scale, us, inputs.flops_mlp(batch, dims), inputs.bytes_mlp(batch, dims))
+        del I, O, ws
+    W1 = torch.randn((64, 64), device="cuda") / 8
+    W2 = torch.randn((64, 64), device="cuda") / 8
+    for scale in (1, 8, 64):
+        B = 256 * scale
+        X = torch.randn((B, 64, 64), device="cuda") / 8
+        Y = torch.empty((B, 64, 64), device="cuda")
+        us = timed(lambda: tc355.tc_kron(W1, W2, X, Y), 100 if scale < 64 else 30)
+        report("kron", scale, us, inputs.flops_kron(B, 64, 64, 64, 64), inputs.bytes_kron(B, 64, 64, 64, 64))
+        del X, Y
 
 
 def cpu_baseline(inputs, Ih, Wsh, bsh):
