@@ -1,0 +1,361 @@
+// Grouped convolution (Section 7, listing gconv) on the int8 matrix core, for
+// C = F = 16 channels per group, a 3 x 3 filter and a compile-time image width:
+//
+//   O(n,g,o,h,w) = sum_{i,kh,kw} I(n,g,i,h+kh,w+kw) * W1(g,o,i,kh,kw) + bias(g*F+o)
+//
+// The fp64 matrix instruction delivers 16 multiply-adds per clock and SIMD, the
+// int8 one 1024.  This kernel therefore evaluates the contraction in exact
+// integer arithmetic on slices of the operands:
+//   * every fp32 operand x of a block (one filter row of W1; one band of input
+//     rows) is written as a 31-bit fixed-point number relative to the block's
+//     largest magnitude, v = rint(x * 2^(30-e)) with max|x| < 2^e, and v is split
+//     into four signed 8-bit digits, v = sum_k d_k 256^k.  Elements within 2^-7
+//     of the block maximum are represented exactly, smaller ones to 2^-31 of it;
+//   * a product of two operands is sum_{k,l} a_k b_l 256^(k+l); the 13 digit
+//     pairs with k + l >= 2 are kept (the dropped ones are below 2^-38 of the
+//     block maxima' product).  Each pair is one int8 MFMA accumulation in int32,
+//     which is exact (no rounding, any order), one accumulator per diagonal k + l;
+//   * the five diagonals are combined exactly (int32 shifts, then fp64), scaled
+//     by 2^(ea+eb-36), the bias is added in fp64, and the sum is rounded to fp32
+//     once.
+// Against the float64 definition the result differs by the input quantisation
+// only: measured 4e-7 on the parity metric at the benchmark's distribution (the
+// bar is 2e-5), ~1e-9 relative on outputs of typical magnitude.  A band whose
+// inputs contain Inf/NaN yields NaN for all of that band's outputs.
+//
+// MFMA v_mfma_i32_16x16x64_i8, lane = (r16 = lane % 16, q = lane / 16), measured:
+//   A (16 x 64): lane supplies A[row r16][k = 16q .. 16q+15]  (16 bytes)
+//   B (64 x 16): lane supplies B[k = 16q .. 16q+15][col r16]
+//   D (16 x 16): lane holds D[row 4q + v][col r16], v = 0..3
+// Here rows are the 16 filters, columns are 16 output pixels of one image row,
+// and the 64 reduction slots of one instruction are (kw = q, channel = byte):
+// slot group q = 3 is padding (A holds zeros there).  One "group" of 13 MFMAs
+// therefore covers one filter row kh for a 16-pixel tile, and the B operand of
+// input row r is shared by the output rows r, r-1 and r-2.
+//
+// Work split: persistent workgroups, each taking (image, group) pairs round-robin; bands of 8 output rows; the
+// band's 10 input rows sit in LDS as four digit planes [pixel][16 channels]
+// (double-buffered); wavefront w owns output rows 2w and 2w+1 of the band: three
+// full 16-pixel columns swept over 4 input rows each, and the last 8 columns of
+// both rows packed into one tile (lanes 0-7: row 2w, lanes 8-15: row 2w+1).
+// Every wavefront executes the same 21 groups per band.  The next band (of this
+// or of the next image) is fetched into registers piecemeal between the groups.
+// A band costs a staging phase (vector ALU: slicing) and a contraction phase
+// (matrix pipe).  Two workgroups share a compute unit; started together they
+// stay in lockstep and leave the matrix pipe idle while both are staging, so
+// the workgroup in the upper half of the unit's LDS starts a fraction of a band
+// later: then one contracts while the other stages.
+#pragma once
+#include <type_traits>
+
+#include "tc355_device.hpp"
+
+namespace tc355 {
+
+typedef int i4 __attribute__((ext_vector_type(4)));
+
+struct GconvI8Args {
+  const float* I;
+  const float* W1;
+  const float* bias;  // or nullptr
+  float* O;
+  int G, H;
+  int total;  // N*G (image, group) pairs
+  int delay;  // start offset of every second workgroup of a compute unit, in 10 ns ticks
+  TC355_TRACE_FIELD
+};
+
+template <int W, int ROWS>
+struct GconvI8Geom {
+  static constexpr int C = 16, F = 16, KH = 3, KW = 3;
+  static constexpr int OW = W - KW + 1;
+  static constexpr int IN_ROWS = ROWS + KH - 1;
+  static constexpr int NPX = IN_ROWS * W;                               // pixels of a band
+  static constexpr int PLANE = NPX * 16;                                // bytes of one digit plane
+  static constexpr int BUF = 4 * PLANE;                                 // bytes of one band buffer
+  static constexpr int NU = (NPX + WG_THREADS - 1) / WG_THREADS;        // pixels per thread and band
+  static constexpr int MISC = 2 * BUF;                                  // byte offset of the small arrays
+  static constexpr int LDS_BYTES = 2 * BUF + 128;
+  static constexpr int NFC = OW / 16;                                   // full 16-pixel columns
+  static_assert(ROWS == 2 * WAVES_PER_WG, "two output rows per wavefront");
+  static_assert(OW % 16 == 8, "the last 8 columns of two rows share one tile");
+  static_assert(3 * PLANE + 3 * W * 16 < 65536, "LDS immediates out of range");
+  static_assert(F * C * KH * KW * 4 <= BUF, "filter bank scratch must fit one band buffer");
+};
+
+// x -> four signed digits of rint(x * 2^sh), one per byte (byte k = digit of weight 256^k).
+__device__ __forceinline__ int i8_digits(float x, int sh) {
+  int v;  // floor(x * 2^sh + 0.5), exact for |.| <= 2^30
+  asm("v_cvt_rpi_i32_f32 %0, %1" : "=v"(v) : "v"(ldexpf(x, sh)));
+  return (v + 0x00808080) ^ 0x00808080;
+}
+
+// 4 x 4 byte transpose: x[c] holds the 4 digits of channel c; y[k] receives digit k of the 4 channels.
+__device__ __forceinline__ void i8_transpose4(const int (&x)[4], int (&y)[4]) {
+  const unsigned lo01 = __builtin_amdgcn_perm(x[1], x[0], 0x05010400u);  // x0.0 x1.0 x0.1 x1.1
+  const unsigned hi01 = __builtin_amdgcn_perm(x[1], x[0], 0x07030602u);  // x0.2 x1.2 x0.3 x1.3
+  const unsigned lo23 = __builtin_amdgcn_perm(x[3], x[2], 0x05010400u);
+  const unsigned hi23 = __builtin_amdgcn_perm(x[3], x[2], 0x07030602u);
+  y[0] = (int)__builtin_amdgcn_perm(lo23, lo01, 0x05040100u);
+  y[1] = (int)__builtin_amdgcn_perm(lo23, lo01, 0x07060302u);
+  y[2] = (int)__builtin_amdgcn_perm(hi23, hi01, 0x05040100u);
+  y[3] = (int)__builtin_amdgcn_perm(hi23, hi01, 0x07060302u);
+}
+
+// 16 channels of one pixel / one filter tap -> one 16-byte record per digit.
+__device__ __forceinline__ void i8_slice16(const float (&x)[16], int sh, i4 (&rec)[4]) {
+#pragma unroll
+  for (int m = 0; m < 4; m++) {
+    int d[4], y[4];
+#pragma unroll
+    for (int e = 0; e < 4; e++) d[e] = i8_digits(x[4 * m + e], sh);
+    i8_transpose4(d, y);
+#pragma unroll
+    for (int k = 0; k < 4; k++) rec[k][m] = y[k];
+  }
+}
+
+__device__ __forceinline__ i4 mfma_i8(i4 a, i4 b, i4 c) { return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0); }
+
+template <int W, int ROWS, int MINW>
+__global__ __launch_bounds__(WG_THREADS, MINW) void gconv_i8_kernel(GconvI8Args p) {
+  using Gm = GconvI8Geom<W, ROWS>;
+  constexpr int C = Gm::C, F = Gm::F, KH = Gm::KH, KW = Gm::KW, OW = Gm::OW, NPX = Gm::NPX, PLANE = Gm::PLANE,
+                BUF = Gm::BUF, NU = Gm::NU, NFC = Gm::NFC;
+  constexpr int WN = F * C * KH * KW, WPT = WN / WG_THREADS;  // filter bank of a group; floats per thread
+  static_assert(WN % WG_THREADS == 0, "whole filter-bank floats per thread");
+  extern __shared__ __attribute__((aligned(16))) char gi8_lds[];
+  unsigned* maxw = reinterpret_cast<unsigned*>(gi8_lds + Gm::MISC);     // [2][4] band maxima per wavefront
+
+#ifdef TC355_TRACE_ENABLE
+  unsigned long long* trace = p.trace;
+#else
+  unsigned long long* trace = nullptr;
+#endif
+  (void)trace;
+  TC355_TRACE_DECL
+  TC355_TRACE_R(trace, 1);
+  const int tid = threadIdx.x;
+  const int lane = tid & (WAVE - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
+  const int r16 = lane & 15, q = lane >> 4;
+  const int kwq = q < KW ? q : KW - 1;  // slot group 3 is padding: it re-reads kw = 2 against zero weights
+  const int H = p.H, OH = H - KH + 1;
+  const int npix = OH * OW;
+  const int nbands = (OH + ROWS - 1) / ROWS;
+  const int plane = H * W;
+  const int stride = gridDim.x;
+  int img = blockIdx.x;  // n*G + g
+  if (img >= p.total) return;
+
+  // ---- this thread's pixels of a band: pi = tid + 256 u (clamped; the clamped duplicates are never written to LDS)
+  float pre[NU][C];     // the band being fetched: 16 channels of up to three pixels
+  const float* fsrc;    // image block the band is fetched from
+  unsigned offn[NU];    // byte offsets of this thread's pixels inside a channel plane of that band
+  auto set_fetch = [&](int im, int b) {
+    fsrc = p.I + (int64_t)im * C * plane;
+#pragma unroll
+    for (int u = 0; u < NU; u++) {  // recomputed per band: cheaper than holding row and column in registers
+      const int pi = min(tid + u * WG_THREADS, NPX - 1);
+      const int prow = pi / W, pcol = pi - prow * W;
+      offn[u] = 4u * (unsigned)(min(b * ROWS + prow, H - 1) * W + pcol);  // rows past the image: last row
+    }
+  };
+  // piece (u, cq): channels 4cq..4cq+3 of pixel u.  Skipped by whole wavefronts only (uniform), never per lane.
+  auto fetch_piece = [&](auto u_c, auto cq_c) {
+    constexpr int u = decltype(u_c)::value, cq = decltype(cq_c)::value;
+    if (wave * WAVE + u * WG_THREADS < NPX) {
+#pragma unroll
+      for (int e = 0; e < 4; e++) {  // uniform image base + 32-bit byte offset (the host checks 64*H*W < 2^32)
+        const unsigned off = offn[u] + 4u * (unsigned)((4 * cq + e) * plane);
+        pre[u][4 * cq + e] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(fsrc) + off);
+      }
+    }
+  };
+  using std::integral_constant;
+  auto fetch_pixel = [&](auto u_c) {
+    fetch_piece(u_c, integral_constant<int, 0>{});
+    fetch_piece(u_c, integral_constant<int, 1>{});
+    fetch_piece(u_c, integral_constant<int, 2>{});
+    fetch_piece(u_c, integral_constant<int, 3>{});
+  };
+  set_fetch(img, 0);
+  fetch_pixel(integral_constant<int, 0>{});
+  fetch_pixel(integral_constant<int, 1>{});
+  fetch_pixel(integral_constant<int, 2>{});
+  static_assert(NU == 3, "the fetch schedule is written for three pixels per thread");
+
+  // ---- phase offset between the two workgroups of a compute unit (the first loads are already in flight)
+  if (p.delay > 0 && (__builtin_amdgcn_s_getreg(6 | (7 << 11)) & 0xff) != 0) {  // HW_REG_LDS_ALLOC, LDS_BASE != 0
+    const unsigned long long t0 = __builtin_amdgcn_s_memrealtime();
+    while (__builtin_amdgcn_s_memrealtime() - t0 < (unsigned long long)p.delay) __builtin_amdgcn_s_sleep(8);
+  }
+
+  i4 a[KH][4];     // a[kh][k]: digit k of W1[g][r16][c = byte][kh][kw = q], zeros for q = 3
+  int ea_v[4];     // exponent of filter row 4q + v
+  float bz[4];     // bias of filter row 4q + v
+  int it = 0;      // bands staged so far by this workgroup: LDS buffer parity
+  for (;;) {
+    const int g = img % p.G;
+    float* dst = p.O + (int64_t)img * F * npix;
+    // ---- filter bank -> A operands, through the band buffer that is staged next (free: it was last read two bands ago)
+    {
+      float* wl = reinterpret_cast<float*>(gi8_lds + (it & 1) * BUF);
+      const float* wg = p.W1 + (int64_t)g * WN;
+#pragma unroll
+      for (int j = 0; j < WPT; j++) wl[tid + j * WG_THREADS] = wg[tid + j * WG_THREADS];
+      __syncthreads();
+      const float* wp = wl + r16 * (C * KH * KW) + kwq;
+      unsigned m = 0;  // two passes over the LDS copy (maximum, then slicing) keep the live registers low
+#pragma unroll
+      for (int kh = 0; kh < KH; kh++)
+#pragma unroll
+        for (int c = 0; c < C; c++) m = max(m, __float_as_uint(wp[c * (KH * KW) + kh * KW]) & 0x7fffffffu);
+      m = max(m, (unsigned)__shfl_xor((int)m, 16));
+      m = max(m, (unsigned)__shfl_xor((int)m, 32));
+      const int ea = (int)(m >> 23) - 126;  // max|w| < 2^ea over the filter row (255-126 marks Inf/NaN)
+#pragma unroll
+      for (int kh = 0; kh < KH; kh++) {
+        float wv[C];
+#pragma unroll
+        for (int c = 0; c < C; c++) wv[c] = wp[c * (KH * KW) + kh * KW];
+        i8_slice16(wv, 30 - ea, a[kh]);
+        if (q >= KW) {
+#pragma unroll
+          for (int k = 0; k < 4; k++) a[kh][k] = i4{0, 0, 0, 0};
+        }
+      }
+#pragma unroll
+      for (int v = 0; v < 4; v++) {
+        ea_v[v] = __shfl(ea, 4 * q + v);  // lane 4q+v holds filter row 4q+v
+        bz[v] = p.bias ? p.bias[g * F + 4 * q + v] : 0.f;
+      }
+      // the staging below overwrites wl only after the next barrier, which every wavefront reaches after these reads
+    }
+    TC355_TRACE_R(trace, 2);
+
+    for (int b = 0; b < nbands; b++, it++) {
+      char* buf = gi8_lds + (it & 1) * BUF;
+      // ---- largest magnitude of the band (bit patterns order like magnitudes; NaN sorts above Inf)
+      unsigned m = 0;
+#pragma unroll
+      for (int u = 0; u < NU; u++)
+        if (wave * WAVE + u * WG_THREADS < NPX) {
+#pragma unroll
+          for (int c = 0; c < C; c++) m = max(m, __float_as_uint(pre[u][c]) & 0x7fffffffu);
+        }
+#pragma unroll
+      for (int o = 1; o < WAVE; o <<= 1) m = max(m, (unsigned)__shfl_xor((int)m, o));
+      if (lane == 0) maxw[(it & 1) * 4 + wave] = m;
+      __syncthreads();
+      TC355_TRACE_R(trace, 3);
+      m = max(max(maxw[(it & 1) * 4 + 0], maxw[(it & 1) * 4 + 1]), max(maxw[(it & 1) * 4 + 2], maxw[(it & 1) * 4 + 3]));
+      const int mexp = __builtin_amdgcn_readfirstlane((int)(m >> 23));
+      const int eb = mexp - 126;  // max|x| < 2^eb
+
+      // ---- slice and stage: digit plane k, record of pixel pi at byte k*PLANE + 16*pi
+#pragma unroll
+      for (int u = 0; u < NU; u++)
+        if (wave * WAVE + u * WG_THREADS < NPX) {
+          i4 rec[4];
+          i8_slice16(pre[u], 30 - eb, rec);
+          if (tid + u * WG_THREADS < NPX) {
+#pragma unroll
+            for (int k = 0; k < 4; k++) *reinterpret_cast<i4*>(buf + k * PLANE + 16 * (tid + u * WG_THREADS)) = rec[k];
+          }
+        }
+      __syncthreads();
+      TC355_TRACE_R(trace, 4);
+
+      // ---- what to fetch while this band is contracted: the next band, or the next image's first band and filters
+      const bool last = b + 1 == nbands;
+      const bool more = !last || img + stride < p.total;
+      if (!last) set_fetch(img, b + 1);
+      else if (more) set_fetch(img + stride, 0);
+      // 2^(ea+eb-36) per filter row of this lane: high word of the fp64 bit pattern; NaN if the band or the row holds Inf/NaN
+      int scale_hi[4];
+#pragma unroll
+      for (int v = 0; v < 4; v++) {
+        const bool bad = mexp == 255 || ea_v[v] == 255 - 126;
+        scale_hi[v] = bad ? 0x7ff80000 : (1023 + ea_v[v] + eb - 36) << 20;
+      }
+
+      const int h0 = b * ROWS + 2 * wave;  // first output row of this wavefront in this band
+      // One sweep: NR output rows per lane, NR + 2 input rows starting at the lane's LDS pointer `base`
+      // (input row of its first output row, column of its pixel + kw).  orow/ocol: the lane's first output
+      // row and its column.  PIECE0: first of the next band's fetch pieces to issue, one per input row.
+      auto sweep = [&](auto nr_c, auto piece0_c, const char* base, int orow, int ocol) {
+        constexpr int NR = decltype(nr_c)::value, PIECE0 = decltype(piece0_c)::value;
+        i4 acc[NR][5];
+#pragma unroll
+        for (int hl = 0; hl < NR; hl++)
+#pragma unroll
+          for (int d = 0; d < 5; d++) acc[hl][d] = i4{0, 0, 0, 0};
+        i4 bc[4], bn[4];
+#pragma unroll
+        for (int l = 0; l < 4; l++) bc[l] = *reinterpret_cast<const i4*>(base + l * PLANE);
+        auto row = [&](auto r_c) {
+          constexpr int r = decltype(r_c)::value;
+          if constexpr (r + 1 < NR + 2) {
+#pragma unroll
+            for (int l = 0; l < 4; l++) bn[l] = *reinterpret_cast<const i4*>(base + l * PLANE + (r + 1) * W * 16);
+          }
+          if constexpr (PIECE0 >= 0 && PIECE0 + r < 4 * NU) {
+            constexpr int pc = PIECE0 + r;
+            if (more) fetch_piece(integral_constant<int, pc / 4>{}, integral_constant<int, pc % 4>{});
+          }
+          // pin "reads of row r+1, then MFMAs of row r"
+          __builtin_amdgcn_sched_barrier(0);
+          // digit pairs (k of the weights, l of the input), ordered so that consecutive MFMAs hit different diagonals
+          constexpr int PK[13] = {3, 3, 3, 3, 2, 2, 2, 2, 1, 1, 1, 0, 0};
+          constexpr int PL[13] = {3, 2, 1, 0, 0, 3, 2, 1, 1, 3, 2, 2, 3};
+#pragma unroll
+          for (int i = 0; i < 13; i++)
+#pragma unroll
+            for (int hl = 0; hl < NR; hl++) {
+              const int kh = r - hl;
+              if (kh >= 0 && kh < KH) acc[hl][PK[i] + PL[i] - 2] = mfma_i8(a[kh][PK[i]], bc[PL[i]], acc[hl][PK[i] + PL[i] - 2]);
+            }
+#pragma unroll
+          for (int l = 0; l < 4; l++) bc[l] = bn[l];
+          __builtin_amdgcn_sched_barrier(0);
+        };
+        row(integral_constant<int, 0>{});
+        row(integral_constant<int, 1>{});
+        row(integral_constant<int, 2>{});
+        if constexpr (NR == 2) row(integral_constant<int, 3>{});
+        static_assert(NR == 1 || NR == 2, "one or two output rows per sweep");
+        // ---- exact recombination of the diagonals, scaling, bias, single rounding
+#pragma unroll
+        for (int hl = 0; hl < NR; hl++) {
+          const int h = orow + hl;
+          if (h < OH) {
+#pragma unroll
+            for (int v = 0; v < 4; v++) {
+              const int hi = acc[hl][4][v] * 256 + acc[hl][3][v];  // |.| < 2^28
+              const int lo = acc[hl][2][v] * 256 + acc[hl][1][v];  // |.| < 2^31
+              double rr = __builtin_fma((double)hi, 65536.0, (double)lo);
+              rr = __builtin_fma((double)acc[hl][0][v], 0.00390625, rr);
+              dst[(int64_t)(4 * q + v) * npix + h * OW + ocol] = (float)__builtin_fma(rr, __hiloint2double(scale_hi[v], 0), (double)bz[v]);
+            }
+          }
+        }
+      };
+      const char* lbase = buf + ((2 * wave) * W + r16 + kwq) * 16;
+      sweep(integral_constant<int, 2>{}, integral_constant<int, 0>{}, lbase, h0, r16);
+      sweep(integral_constant<int, 2>{}, integral_constant<int, 4>{}, lbase + 256, h0, 16 + r16);
+      sweep(integral_constant<int, 2>{}, integral_constant<int, 8>{}, lbase + 512, h0, 32 + r16);
+      static_assert(NFC == 3, "three full columns are written out above");
+      // last 8 columns of both rows in one tile
+      const int hr = r16 >> 3;
+      sweep(integral_constant<int, 1>{}, integral_constant<int, -1>{},
+            buf + ((2 * wave + hr) * W + 16 * NFC + (r16 & 7) + kwq) * 16, h0 + hr, 16 * NFC + (r16 & 7));
+      TC355_TRACE_R(trace, 5);
+    }
+    img += stride;
+    if (img >= p.total) break;
+  }
+  TC355_TRACE_FLUSH(trace);
+}
+
+}  // namespace tc355

@@ -1,9 +1,11 @@
 """GPU parity: libtc355 (through its C ABI) against the float64 oracle, element by element.
 
 Bar: max |gpu - ref| / (|ref| + 1e-3 max|ref|) <= 2e-5 on the same seeded inputs.
-The library accumulates exact fp32 x fp32 products in fp64 and rounds each output
-once, so the error it can actually show is one fp32 rounding (2^-24 ~ 6e-8 relative);
+The fp64 kernels accumulate exact fp32 x fp32 products in fp64 and round each output
+once, so the error they can actually show is one fp32 rounding (2^-24 ~ 6e-8 relative);
 TIGHT asserts that as well, to catch a silent loss of precision long before the bar.
+The int8 grouped convolution (width 58, 16 channels, 3 x 3) sums exactly but quantises
+its operands to 2^-31 of their block maximum: TIGHT_I8 bounds that (measured 4e-7).
 """
 import numpy as np
 import pytest
@@ -16,6 +18,7 @@ from paper_1802_04730_amd.metric import PARITY_BAR, parity_error
 pytestmark = pytest.mark.gpu
 
 TIGHT = 2.5e-7
+TIGHT_I8 = 2e-6
 
 
 @pytest.fixture(scope="module")
@@ -30,13 +33,18 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def check(gpu_tensor, ref, what):
+def check(gpu_tensor, ref, what, tight=TIGHT):
     torch.cuda.synchronize()
     got = gpu_tensor.cpu().numpy().astype(np.float64)
     err = parity_error(got, ref)
     print("%s: parity error %.3e" % (what, err), flush=True)
     assert err <= PARITY_BAR, "%s: %.3e exceeds the parity bar" % (what, err)
-    assert err <= TIGHT, "%s: %.3e exceeds one fp32 rounding" % (what, err)
+    assert err <= tight, "%s: %.3e exceeds the error this kernel's arithmetic allows (%.1e)" % (what, err, tight)
+
+
+def takes_i8_path(shape):
+    N, G, C, F, H, W, KH, KW = shape
+    return (C, F, W, KH, KW) == (16, 16, 58, 3, 3)
 
 
 # ---------------------------------------------------------------- tbmm
@@ -203,9 +211,10 @@ GCONV_SHAPES = [
     (2, 4, 32, 32, 7, 7, 3, 3),     # paper table shape (32,32,32,32,7,7), fewer images/groups
     (2, 4, 4, 4, 56, 56, 3, 3),     # paper table shape (32,32,4,4,56,56), fewer images/groups
     (1, 2, 5, 20, 9, 11, 2, 4),     # two channel tiles, odd reduction length
-    (1, 2, 16, 16, 21, 58, 3, 3),   # width-58 band kernel: odd height (unaligned planes), ragged last band
-    (2, 1, 16, 16, 12, 58, 3, 3),   # width-58 band kernel: two bands, second one partial
-    (1, 1, 16, 16, 3, 58, 3, 3),    # width-58 band kernel: a single output row
+    (1, 2, 16, 16, 21, 58, 3, 3),   # width-58 kernels: odd height (unaligned planes), ragged last band
+    (2, 1, 16, 16, 12, 58, 3, 3),   # width-58 kernels: two bands, second one partial
+    (1, 1, 16, 16, 3, 58, 3, 3),    # width-58 kernels: a single output row
+    (3, 5, 16, 16, 11, 58, 3, 3),   # width-58 kernels: 15 (image, group) pairs, two bands
     (1, 3, 16, 16, 20, 30, 3, 3),   # 16x16 channels, other width: runtime-width LDS kernel
 ]
 
@@ -217,7 +226,48 @@ def test_gconv(tc, shape, oracle_threads):
     ref = oracle.group_conv(I, W1, bias)
     O = torch.full(ref.shape, float("nan"), device="cuda")
     tc.tc_group_conv(dev(I), dev(W1), dev(bias), O)
-    check(O, ref, "gconv %s" % (shape,))
+    check(O, ref, "gconv %s" % (shape,), TIGHT_I8 if takes_i8_path(shape) else TIGHT)
+
+
+@pytest.mark.parametrize("shape", [sh for sh in GCONV_SHAPES if takes_i8_path(sh)])
+def test_gconv_width_58_on_the_fp64_path(tc, shape, oracle_threads, monkeypatch):
+    monkeypatch.setenv("TC355_GCONV_ARITH", "f64")
+    I, W1, bias = inputs.make_gconv(*shape, seed=inputs.SEED_BASE + 4)
+    ref = oracle.group_conv(I, W1, bias)
+    O = torch.full(ref.shape, float("nan"), device="cuda")
+    tc.tc_group_conv(dev(I), dev(W1), dev(bias), O)
+    check(O, ref, "gconv fp64 path %s" % (shape,))
+
+
+def test_gconv_i8_wide_dynamic_range_and_nonfinite(tc, oracle_threads):
+    """Per-band / per-filter scaling: magnitudes spread over many binades, an all-zero band, and Inf/NaN poisoning a band."""
+    shape = (1, 2, 16, 16, 26, 58, 3, 3)   # three bands
+    I, W1, bias = inputs.make_gconv(*shape, seed=77)
+    rng = np.random.default_rng(5)
+    I = (I * np.exp2(rng.integers(-12, 12, size=I.shape))).astype(np.float32)      # 24 binades inside every band
+    I[0, 0, :, 8:18, :] = 0.0                                                      # image 0, group 0: band 1 is all zeros
+    W1 = (W1 * np.exp2(rng.integers(-20, 20, size=(2, 16, 1, 1, 1)))).astype(np.float32)  # filter rows of very different scale
+    ref = oracle.group_conv(I, W1, bias)
+    O = torch.full(ref.shape, float("nan"), device="cuda")
+    tc.tc_group_conv(dev(I), dev(W1), dev(bias), O)
+    torch.cuda.synchronize()
+    got = O.cpu().numpy().astype(np.float64)
+    # filter rows differ by 2^40 in scale: compare every filter's plane on its own scale
+    for g in range(2):
+        for f in range(16):
+            err = parity_error(got[:, g, f], ref[:, g, f])
+            # the quantisation step is 2^-31 of the band maximum whatever the spread inside the band;
+            # with 24 binades of spread most terms sit far below it: a quarter of the bar is the limit here
+            assert err <= PARITY_BAR / 4, "group %d filter %d: %.3e" % (g, f, err)
+    Ibad = I.copy()
+    Ibad[0, 1, 3, 20, 7] = np.inf                                                   # rows 16..25 are band 2 (+ halo of band 1)
+    O2 = torch.zeros(ref.shape, device="cuda")
+    tc.tc_group_conv(dev(Ibad), dev(W1), dev(bias), O2)
+    torch.cuda.synchronize()
+    got2 = O2.cpu().numpy()
+    assert np.isnan(got2[0, 1, :, 18:21, 5:8]).all(), "outputs that read the Inf must not be finite"
+    assert np.array_equal(got2[0, 0], got[0, 0].astype(np.float32)), "the other group is untouched by it"
+    assert np.isfinite(got2[0, 1, :, 0:8]).all(), "bands that never read the Inf stay finite"
 
 
 def test_gconv_without_bias(tc, oracle_threads):
@@ -234,7 +284,7 @@ def test_gconv_full_configuration_4(tc, oracle_threads):
     tc.tc_group_conv(dev(I), dev(W1), dev(bias), O)
     torch.cuda.synchronize()
     ref = oracle.group_conv(I, W1, bias)
-    check(O, ref, "gconv configuration 4")
+    check(O, ref, "gconv configuration 4", TIGHT_I8)
 
 
 # ---------------------------------------------------------------- kron
@@ -308,7 +358,7 @@ def test_all_entry_points_replay_from_a_hip_graph(tc, oracle_threads):
         check(Z, ref["tbmm"], "graph replay %d tbmm" % rep)
         for l in range(3):
             check(O[l], ref["mlp"][l], "graph replay %d mlp layer %d" % (rep, l))
-        check(Og, ref["gconv"], "graph replay %d gconv" % rep)
+        check(Og, ref["gconv"], "graph replay %d gconv" % rep, TIGHT_I8)
         check(Yk, ref["kron"], "graph replay %d kron" % rep)
         assert int(ws[:256].view(torch.int32)[33]) == 0
         del scratch
@@ -342,5 +392,5 @@ def test_kron_and_gconv_stay_inside_their_outputs(tc, oracle_threads):
     buf = torch.full((n + 512,), 777.0, device="cuda")
     Ov = buf[256:256 + n].view(1, 2, 16, 19, 56)
     tc.tc_group_conv(dev(Ig), dev(Wg), dev(bias), Ov)
-    check(Ov, oracle.group_conv(Ig, Wg, bias), "gconv guard band")
+    check(Ov, oracle.group_conv(Ig, Wg, bias), "gconv guard band", TIGHT_I8)
     assert torch.all(buf[:256] == 777.0) and torch.all(buf[256 + n:] == 777.0)
