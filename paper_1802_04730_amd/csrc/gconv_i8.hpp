@@ -33,18 +33,17 @@
 // therefore covers one filter row kh for a 16-pixel tile, and the B operand of
 // input row r is shared by the output rows r, r-1 and r-2.
 //
-// Work split: persistent workgroups, each taking (image, group) pairs round-robin; bands of 8 output rows; the
-// band's 10 input rows sit in LDS as four digit planes [pixel][16 channels]
-// (double-buffered); wavefront w owns output rows 2w and 2w+1 of the band: three
+// Work split: persistent workgroups (two per compute unit), each taking (image,
+// group) pairs round-robin; bands of 8 output rows; the band's 10 input rows sit
+// in LDS as four digit planes [pixel][16 channels] (double-buffered);
+// wavefront w owns output rows 2w and 2w+1 of the band: three
 // full 16-pixel columns swept over 4 input rows each, and the last 8 columns of
 // both rows packed into one tile (lanes 0-7: row 2w, lanes 8-15: row 2w+1).
 // Every wavefront executes the same 21 groups per band.  The next band (of this
-// or of the next image) is fetched into registers piecemeal between the groups.
-// A band costs a staging phase (vector ALU: slicing) and a contraction phase
-// (matrix pipe).  Two workgroups share a compute unit; started together they
-// stay in lockstep and leave the matrix pipe idle while both are staging, so
-// the workgroup in the upper half of the unit's LDS starts a fraction of a band
-// later: then one contracts while the other stages.
+// or of the next image) is fetched into registers piecemeal between the groups,
+// with 16-byte loads: the kernel takes only heights whose bands are whole and
+// 16-byte aligned (H even, H - 2 a multiple of 8); a band's rows are then one
+// contiguous run of every channel plane.
 #pragma once
 #include <type_traits>
 
@@ -61,7 +60,6 @@ struct GconvI8Args {
   float* O;
   int G, H;
   int total;  // N*G (image, group) pairs
-  int delay;  // start offset of every second workgroup of a compute unit, in 10 ns ticks
   TC355_TRACE_FIELD
 };
 
@@ -73,7 +71,11 @@ struct GconvI8Geom {
   static constexpr int NPX = IN_ROWS * W;                               // pixels of a band
   static constexpr int PLANE = NPX * 16;                                // bytes of one digit plane
   static constexpr int BUF = 4 * PLANE;                                 // bytes of one band buffer
-  static constexpr int NU = (NPX + WG_THREADS - 1) / WG_THREADS;        // pixels per thread and band
+  // staging units: 4 channels (group cg) x 4 consecutive pixels (quad px4), unit = 4*px4 + cg, so that four
+  // neighbouring lanes fill one 16-byte record; a thread takes units tid and tid + 256, and what is left is dealt
+  // out as half units of 4 channels x 2 pixels, so that no thread slices much more than its share
+  static constexpr int NQ = NPX / 4, NUNIT = 4 * NQ, NHALF = 2 * (NUNIT - 2 * WG_THREADS);
+  static_assert(NPX % 4 == 0 && NUNIT > 2 * WG_THREADS && NHALF <= WG_THREADS, "two rounds of units and one of half units");
   static constexpr int MISC = 2 * BUF;                                  // byte offset of the small arrays
   static constexpr int LDS_BYTES = 2 * BUF + 128;
   static constexpr int NFC = OW / 16;                                   // full 16-pixel columns
@@ -102,26 +104,13 @@ __device__ __forceinline__ void i8_transpose4(const int (&x)[4], int (&y)[4]) {
   y[3] = (int)__builtin_amdgcn_perm(hi23, hi01, 0x07060302u);
 }
 
-// 16 channels of one pixel / one filter tap -> one 16-byte record per digit.
-__device__ __forceinline__ void i8_slice16(const float (&x)[16], int sh, i4 (&rec)[4]) {
-#pragma unroll
-  for (int m = 0; m < 4; m++) {
-    int d[4], y[4];
-#pragma unroll
-    for (int e = 0; e < 4; e++) d[e] = i8_digits(x[4 * m + e], sh);
-    i8_transpose4(d, y);
-#pragma unroll
-    for (int k = 0; k < 4; k++) rec[k][m] = y[k];
-  }
-}
-
 __device__ __forceinline__ i4 mfma_i8(i4 a, i4 b, i4 c) { return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0); }
 
-template <int W, int ROWS, int MINW>
-__global__ __launch_bounds__(WG_THREADS, MINW) void gconv_i8_kernel(GconvI8Args p) {
+template <int W, int ROWS>
+__global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) {
   using Gm = GconvI8Geom<W, ROWS>;
-  constexpr int C = Gm::C, F = Gm::F, KH = Gm::KH, KW = Gm::KW, OW = Gm::OW, NPX = Gm::NPX, PLANE = Gm::PLANE,
-                BUF = Gm::BUF, NU = Gm::NU, NFC = Gm::NFC;
+  constexpr int C = Gm::C, F = Gm::F, KH = Gm::KH, KW = Gm::KW, OW = Gm::OW, PLANE = Gm::PLANE, BUF = Gm::BUF,
+                NFC = Gm::NFC, NHALF = Gm::NHALF;
   constexpr int WN = F * C * KH * KW, WPT = WN / WG_THREADS;  // filter bank of a group; floats per thread
   static_assert(WN % WG_THREADS == 0, "whole filter-bank floats per thread");
   extern __shared__ __attribute__((aligned(16))) char gi8_lds[];
@@ -142,54 +131,43 @@ __global__ __launch_bounds__(WG_THREADS, MINW) void gconv_i8_kernel(GconvI8Args 
   const int kwq = q < KW ? q : KW - 1;  // slot group 3 is padding: it re-reads kw = 2 against zero weights
   const int H = p.H, OH = H - KH + 1;
   const int npix = OH * OW;
-  const int nbands = (OH + ROWS - 1) / ROWS;
+  const int nbands = OH / ROWS;
   const int plane = H * W;
   const int stride = gridDim.x;
   int img = blockIdx.x;  // n*G + g
   if (img >= p.total) return;
 
-  // ---- this thread's pixels of a band: pi = tid + 256 u (clamped; the clamped duplicates are never written to LDS)
-  float pre[NU][C];     // the band being fetched: 16 channels of up to three pixels
-  const float* fsrc;    // image block the band is fetched from
-  unsigned offn[NU];    // byte offsets of this thread's pixels inside a channel plane of that band
+  // ---- the band being fetched: two units and (first NHALF threads) one half unit per thread
+  const bool has_half = wave * WAVE < NHALF;  // whole wavefronts only
+  const int hunit = 2 * WG_THREADS + min(tid, NHALF - 1) / 2, hhalf = tid & 1;
+  f4 pre[2][4];   // [round][channel of the group], 4 pixels each
+  f2 preh[4];
+  const char* fimg;   // image block the band is fetched from
+  unsigned foff;      // byte offset of the band inside a channel plane
   auto set_fetch = [&](int im, int b) {
-    fsrc = p.I + (int64_t)im * C * plane;
-#pragma unroll
-    for (int u = 0; u < NU; u++) {  // recomputed per band: cheaper than holding row and column in registers
-      const int pi = min(tid + u * WG_THREADS, NPX - 1);
-      const int prow = pi / W, pcol = pi - prow * W;
-      offn[u] = 4u * (unsigned)(min(b * ROWS + prow, H - 1) * W + pcol);  // rows past the image: last row
-    }
+    fimg = reinterpret_cast<const char*>(p.I + (int64_t)im * C * plane);
+    foff = 4u * (unsigned)(b * ROWS * W);
   };
-  // piece (u, cq): channels 4cq..4cq+3 of pixel u.  Skipped by whole wavefronts only (uniform), never per lane.
-  auto fetch_piece = [&](auto u_c, auto cq_c) {
-    constexpr int u = decltype(u_c)::value, cq = decltype(cq_c)::value;
-    if (wave * WAVE + u * WG_THREADS < NPX) {
+  // piece 0, 1: the two units; piece 2: the half unit.  Uniform base + 32-bit byte offset (the host checks 64*H*W < 2^32).
+  auto fetch_piece = [&](auto pc_c) {
+    constexpr int pc = decltype(pc_c)::value;
+    if constexpr (pc < 2) {
+      const int unit = tid + pc * WG_THREADS, cg = unit & 3, px4 = unit >> 2;
+      const unsigned off = foff + 4u * (unsigned)((4 * cg) * plane + 4 * px4);
 #pragma unroll
-      for (int e = 0; e < 4; e++) {  // uniform image base + 32-bit byte offset (the host checks 64*H*W < 2^32)
-        const unsigned off = offn[u] + 4u * (unsigned)((4 * cq + e) * plane);
-        pre[u][4 * cq + e] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(fsrc) + off);
-      }
+      for (int c = 0; c < 4; c++) pre[pc][c] = *reinterpret_cast<const f4*>(fimg + (off + 4u * (unsigned)(c * plane)));
+    } else if (has_half) {
+      const int cg = hunit & 3, px4 = hunit >> 2;
+      const unsigned off = foff + 4u * (unsigned)((4 * cg) * plane + 4 * px4 + 2 * hhalf);
+#pragma unroll
+      for (int c = 0; c < 4; c++) preh[c] = *reinterpret_cast<const f2*>(fimg + (off + 4u * (unsigned)(c * plane)));
     }
   };
   using std::integral_constant;
-  auto fetch_pixel = [&](auto u_c) {
-    fetch_piece(u_c, integral_constant<int, 0>{});
-    fetch_piece(u_c, integral_constant<int, 1>{});
-    fetch_piece(u_c, integral_constant<int, 2>{});
-    fetch_piece(u_c, integral_constant<int, 3>{});
-  };
   set_fetch(img, 0);
-  fetch_pixel(integral_constant<int, 0>{});
-  fetch_pixel(integral_constant<int, 1>{});
-  fetch_pixel(integral_constant<int, 2>{});
-  static_assert(NU == 3, "the fetch schedule is written for three pixels per thread");
-
-  // ---- phase offset between the two workgroups of a compute unit (the first loads are already in flight)
-  if (p.delay > 0 && (__builtin_amdgcn_s_getreg(6 | (7 << 11)) & 0xff) != 0) {  // HW_REG_LDS_ALLOC, LDS_BASE != 0
-    const unsigned long long t0 = __builtin_amdgcn_s_memrealtime();
-    while (__builtin_amdgcn_s_memrealtime() - t0 < (unsigned long long)p.delay) __builtin_amdgcn_s_sleep(8);
-  }
+  fetch_piece(integral_constant<int, 0>{});
+  fetch_piece(integral_constant<int, 1>{});
+  fetch_piece(integral_constant<int, 2>{});
 
   i4 a[KH][4];     // a[kh][k]: digit k of W1[g][r16][c = byte][kh][kw = q], zeros for q = 3
   int ea_v[4];     // exponent of filter row 4q + v
@@ -197,16 +175,21 @@ __global__ __launch_bounds__(WG_THREADS, MINW) void gconv_i8_kernel(GconvI8Args 
   int it = 0;      // bands staged so far by this workgroup: LDS buffer parity
   for (;;) {
     const int g = img % p.G;
-    float* dst = p.O + (int64_t)img * F * npix;
-    // ---- filter bank -> A operands, through the band buffer that is staged next (free: it was last read two bands ago)
+    char* dst = reinterpret_cast<char*>(p.O + (int64_t)img * F * npix);
+    // ---- filter bank -> A operands, through the band buffer that is staged next (free: it was last read two bands ago).
+    // Every lane needs digit records of all 16 channels of its (filter row, kw) for the 3 kh; wavefront w slices
+    // channels 4w..4w+3 and the four share their dwords through LDS: record (kh, k) of a lane at
+    // arec + ((kh*4 + k)*64 + lane)*16, dword w.
     {
       float* wl = reinterpret_cast<float*>(gi8_lds + (it & 1) * BUF);
+      char* arec = reinterpret_cast<char*>(wl) + 16384;
+      static_assert(WN * 4 <= 16384 && 16384 + KH * 4 * WAVE * 16 <= BUF, "scratch must fit one band buffer");
       const float* wg = p.W1 + (int64_t)g * WN;
 #pragma unroll
       for (int j = 0; j < WPT; j++) wl[tid + j * WG_THREADS] = wg[tid + j * WG_THREADS];
       __syncthreads();
       const float* wp = wl + r16 * (C * KH * KW) + kwq;
-      unsigned m = 0;  // two passes over the LDS copy (maximum, then slicing) keep the live registers low
+      unsigned m = 0;
 #pragma unroll
       for (int kh = 0; kh < KH; kh++)
 #pragma unroll
@@ -216,34 +199,50 @@ __global__ __launch_bounds__(WG_THREADS, MINW) void gconv_i8_kernel(GconvI8Args 
       const int ea = (int)(m >> 23) - 126;  // max|w| < 2^ea over the filter row (255-126 marks Inf/NaN)
 #pragma unroll
       for (int kh = 0; kh < KH; kh++) {
-        float wv[C];
+        int d[4], y[4];
 #pragma unroll
-        for (int c = 0; c < C; c++) wv[c] = wp[c * (KH * KW) + kh * KW];
-        i8_slice16(wv, 30 - ea, a[kh]);
-        if (q >= KW) {
+        for (int c = 0; c < 4; c++) d[c] = i8_digits(wp[(4 * wave + c) * (KH * KW) + kh * KW], 30 - ea);
+        i8_transpose4(d, y);
 #pragma unroll
-          for (int k = 0; k < 4; k++) a[kh][k] = i4{0, 0, 0, 0};
-        }
+        for (int k = 0; k < 4; k++)
+          *reinterpret_cast<int*>(arec + ((kh * 4 + k) * WAVE + lane) * 16 + 4 * wave) = q < KW ? y[k] : 0;
       }
+      __syncthreads();
+#pragma unroll
+      for (int kh = 0; kh < KH; kh++)
+#pragma unroll
+        for (int k = 0; k < 4; k++) a[kh][k] = *reinterpret_cast<const i4*>(arec + ((kh * 4 + k) * WAVE + lane) * 16);
 #pragma unroll
       for (int v = 0; v < 4; v++) {
         ea_v[v] = __shfl(ea, 4 * q + v);  // lane 4q+v holds filter row 4q+v
         bz[v] = p.bias ? p.bias[g * F + 4 * q + v] : 0.f;
       }
-      // the staging below overwrites wl only after the next barrier, which every wavefront reaches after these reads
+      // the staging below overwrites this scratch only after the next barrier, which every wavefront reaches after these reads
     }
     TC355_TRACE_R(trace, 2);
 
     for (int b = 0; b < nbands; b++, it++) {
       char* buf = gi8_lds + (it & 1) * BUF;
-      // ---- largest magnitude of the band (bit patterns order like magnitudes; NaN sorts above Inf)
-      unsigned m = 0;
+      // ---- largest magnitude of the band: bit patterns order like magnitudes.  Positive values (and NaNs) win a
+      // signed maximum, negative ones an unsigned maximum: one instruction per two elements each.
+      int mp = 0;
+      unsigned mn = 0;
+      auto take = [&](float x, float y) {
+        mp = max(mp, max(__float_as_int(x), __float_as_int(y)));
+        mn = max(mn, max(__float_as_uint(x), __float_as_uint(y)));
+      };
 #pragma unroll
-      for (int u = 0; u < NU; u++)
-        if (wave * WAVE + u * WG_THREADS < NPX) {
+      for (int j = 0; j < 2; j++)
 #pragma unroll
-          for (int c = 0; c < C; c++) m = max(m, __float_as_uint(pre[u][c]) & 0x7fffffffu);
+        for (int c = 0; c < 4; c++) {
+          take(pre[j][c][0], pre[j][c][1]);
+          take(pre[j][c][2], pre[j][c][3]);
         }
+      if (has_half) {
+#pragma unroll
+        for (int c = 0; c < 4; c++) take(preh[c][0], preh[c][1]);
+      }
+      unsigned m = max((unsigned)mp, mn & 0x7fffffffu);
 #pragma unroll
       for (int o = 1; o < WAVE; o <<= 1) m = max(m, (unsigned)__shfl_xor((int)m, o));
       if (lane == 0) maxw[(it & 1) * 4 + wave] = m;
@@ -253,21 +252,33 @@ __global__ __launch_bounds__(WG_THREADS, MINW) void gconv_i8_kernel(GconvI8Args 
       const int mexp = __builtin_amdgcn_readfirstlane((int)(m >> 23));
       const int eb = mexp - 126;  // max|x| < 2^eb
 
-      // ---- slice and stage: digit plane k, record of pixel pi at byte k*PLANE + 16*pi
+      // ---- slice and stage: digit plane k, record of pixel pi at byte k*PLANE + 16*pi, channels 4cg.. at +4cg
+      {
+        const int sh = 30 - eb;
+        auto put = [&](float x0, float x1, float x2, float x3, int cg, int pixel) {  // 4 channels of one pixel
+          int d[4] = {i8_digits(x0, sh), i8_digits(x1, sh), i8_digits(x2, sh), i8_digits(x3, sh)}, y[4];
+          i8_transpose4(d, y);
 #pragma unroll
-      for (int u = 0; u < NU; u++)
-        if (wave * WAVE + u * WG_THREADS < NPX) {
-          i4 rec[4];
-          i8_slice16(pre[u], 30 - eb, rec);
-          if (tid + u * WG_THREADS < NPX) {
+          for (int k = 0; k < 4; k++) *reinterpret_cast<int*>(buf + k * PLANE + 16 * pixel + 4 * cg) = y[k];
+        };
 #pragma unroll
-            for (int k = 0; k < 4; k++) *reinterpret_cast<i4*>(buf + k * PLANE + 16 * (tid + u * WG_THREADS)) = rec[k];
+        for (int j = 0; j < 2; j++) {
+          const int unit = tid + j * WG_THREADS, cg = unit & 3, px4 = unit >> 2;
+#pragma unroll
+          for (int e = 0; e < 4; e++) put(pre[j][0][e], pre[j][1][e], pre[j][2][e], pre[j][3][e], cg, 4 * px4 + e);
+        }
+        if (has_half) {
+          const int cg = hunit & 3, px4 = hunit >> 2;
+          if (tid < NHALF) {
+#pragma unroll
+            for (int e = 0; e < 2; e++) put(preh[0][e], preh[1][e], preh[2][e], preh[3][e], cg, 4 * px4 + 2 * hhalf + e);
           }
         }
+      }
       __syncthreads();
       TC355_TRACE_R(trace, 4);
 
-      // ---- what to fetch while this band is contracted: the next band, or the next image's first band and filters
+      // ---- what to fetch while this band is contracted: the next band, or the next image's first band
       const bool last = b + 1 == nbands;
       const bool more = !last || img + stride < p.total;
       if (!last) set_fetch(img, b + 1);
@@ -283,9 +294,9 @@ __global__ __launch_bounds__(WG_THREADS, MINW) void gconv_i8_kernel(GconvI8Args 
       const int h0 = b * ROWS + 2 * wave;  // first output row of this wavefront in this band
       // One sweep: NR output rows per lane, NR + 2 input rows starting at the lane's LDS pointer `base`
       // (input row of its first output row, column of its pixel + kw).  orow/ocol: the lane's first output
-      // row and its column.  PIECE0: first of the next band's fetch pieces to issue, one per input row.
-      auto sweep = [&](auto nr_c, auto piece0_c, const char* base, int orow, int ocol) {
-        constexpr int NR = decltype(nr_c)::value, PIECE0 = decltype(piece0_c)::value;
+      // row and its column.  PIECE: the fetch piece of the next band to issue during this sweep, or -1.
+      auto sweep = [&](auto nr_c, auto piece_c, const char* base, int orow, int ocol) {
+        constexpr int NR = decltype(nr_c)::value, PIECE = decltype(piece_c)::value;
         i4 acc[NR][5];
 #pragma unroll
         for (int hl = 0; hl < NR; hl++)
@@ -300,9 +311,8 @@ __global__ __launch_bounds__(WG_THREADS, MINW) void gconv_i8_kernel(GconvI8Args 
 #pragma unroll
             for (int l = 0; l < 4; l++) bn[l] = *reinterpret_cast<const i4*>(base + l * PLANE + (r + 1) * W * 16);
           }
-          if constexpr (PIECE0 >= 0 && PIECE0 + r < 4 * NU) {
-            constexpr int pc = PIECE0 + r;
-            if (more) fetch_piece(integral_constant<int, pc / 4>{}, integral_constant<int, pc % 4>{});
+          if constexpr (PIECE >= 0 && r == 1) {
+            if (more) fetch_piece(integral_constant<int, PIECE >= 0 ? PIECE : 0>{});
           }
           // pin "reads of row r+1, then MFMAs of row r"
           __builtin_amdgcn_sched_barrier(0);
@@ -329,22 +339,21 @@ __global__ __launch_bounds__(WG_THREADS, MINW) void gconv_i8_kernel(GconvI8Args 
 #pragma unroll
         for (int hl = 0; hl < NR; hl++) {
           const int h = orow + hl;
-          if (h < OH) {
 #pragma unroll
-            for (int v = 0; v < 4; v++) {
-              const int hi = acc[hl][4][v] * 256 + acc[hl][3][v];  // |.| < 2^28
-              const int lo = acc[hl][2][v] * 256 + acc[hl][1][v];  // |.| < 2^31
-              double rr = __builtin_fma((double)hi, 65536.0, (double)lo);
-              rr = __builtin_fma((double)acc[hl][0][v], 0.00390625, rr);
-              dst[(int64_t)(4 * q + v) * npix + h * OW + ocol] = (float)__builtin_fma(rr, __hiloint2double(scale_hi[v], 0), (double)bz[v]);
-            }
+          for (int v = 0; v < 4; v++) {
+            const int hi = acc[hl][4][v] * 256 + acc[hl][3][v];  // |.| < 2^28
+            const int lo = acc[hl][2][v] * 256 + acc[hl][1][v];  // |.| < 2^31
+            const unsigned off = 4u * (unsigned)((4 * q + v) * npix + h * OW + ocol);
+            double rr = __builtin_fma((double)hi, 65536.0, (double)lo);  // sum_d P_d 256^(d-3), exact
+            rr = __builtin_fma((double)acc[hl][0][v], 0.00390625, rr);
+            *reinterpret_cast<float*>(dst + off) = (float)__builtin_fma(rr, __hiloint2double(scale_hi[v], 0), (double)bz[v]);
           }
         }
       };
       const char* lbase = buf + ((2 * wave) * W + r16 + kwq) * 16;
       sweep(integral_constant<int, 2>{}, integral_constant<int, 0>{}, lbase, h0, r16);
-      sweep(integral_constant<int, 2>{}, integral_constant<int, 4>{}, lbase + 256, h0, 16 + r16);
-      sweep(integral_constant<int, 2>{}, integral_constant<int, 8>{}, lbase + 512, h0, 32 + r16);
+      sweep(integral_constant<int, 2>{}, integral_constant<int, 1>{}, lbase + 256, h0, 16 + r16);
+      sweep(integral_constant<int, 2>{}, integral_constant<int, 2>{}, lbase + 512, h0, 32 + r16);
       static_assert(NFC == 3, "three full columns are written out above");
       // last 8 columns of both rows in one tile
       const int hr = r16 >> 3;

@@ -184,17 +184,18 @@ bool try_gconv_band(const GconvArgs& g, hipStream_t s, tc_status* st) {
 }
 
 // ---- grouped convolution on the int8 matrix core (sliced fixed-point operands, exact int32 sums) ----
-template <int W, int ROWS, int MINW>
+template <int W, int ROWS>
 bool try_gconv_i8(const GconvArgs& g, hipStream_t s, tc_status* st) {
   using Gm = GconvI8Geom<W, ROWS>;
   if (g.C != Gm::C || g.F != Gm::F || g.KH != Gm::KH || g.KW != Gm::KW || g.W != W) return false;
   if ((int64_t)g.H * W >= (1 << 24)) return false;  // 32-bit byte offsets inside one (image, group) block of 16 planes
+  if ((g.H & 1) || (g.H - (Gm::KH - 1)) % ROWS != 0) return false;  // whole, 16-byte aligned bands only
   const int64_t total = (int64_t)g.N * g.G;
   if (total >= (1ll << 31)) return false;
   const int64_t grid = std::min<int64_t>(total, 2 * (int64_t)device_cus());  // persistent: two workgroups per compute unit
   static std::atomic<int> lds_ok{0};  // more than the default 64 KiB of dynamic LDS
   if (!lds_ok.load(std::memory_order_acquire)) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gconv_i8_kernel<W, ROWS, MINW>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gconv_i8_kernel<W, ROWS>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, Gm::LDS_BYTES) != hipSuccess) {
       *st = TC_ERR_LAUNCH;
       return true;
@@ -205,8 +206,7 @@ bool try_gconv_i8(const GconvArgs& g, hipStream_t s, tc_status* st) {
   a.I = g.I; a.W1 = g.W1; a.bias = g.bias; a.O = g.O;
   a.G = g.G; a.H = g.H;
   a.total = (int)total;
-  a.delay = (int)std::min<long>(2000, std::max<long>(0, env_long("TC355_GCONV_I8_DELAY", 250)));
-  gconv_i8_kernel<W, ROWS, MINW><<<dim3((unsigned)grid), dim3(WG_THREADS), Gm::LDS_BYTES, s>>>(a);
+  gconv_i8_kernel<W, ROWS><<<dim3((unsigned)grid), dim3(WG_THREADS), Gm::LDS_BYTES, s>>>(a);
   *st = launch_status();
   return true;
 }
@@ -377,7 +377,7 @@ tc_status tc_group_conv(const float* I, const float* W1, const float* bias, floa
   // TC355_GCONV_ARITH=f64 keeps the fp64 matrix path for every shape
   const char* arith = std::getenv("TC355_GCONV_ARITH");
   const bool i8 = !(arith && arith[0] == 'f');
-  if (i8 && try_gconv_i8<58, 8, 2>(a, s, &st)) return st;
+  if (i8 && try_gconv_i8<58, 8>(a, s, &st)) return st;
   if (try_gconv_band<16, 3, 3, 58, 8, 2>(a, s, &st)) return st;
   if (try_gconv_lds<16, 16, 3, 3, 7>(a, s, &st)) return st;
   constexpr int TP = 4;

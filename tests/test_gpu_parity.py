@@ -44,7 +44,7 @@ def check(gpu_tensor, ref, what, tight=TIGHT):
 
 def takes_i8_path(shape):
     N, G, C, F, H, W, KH, KW = shape
-    return (C, F, W, KH, KW) == (16, 16, 58, 3, 3)
+    return (C, F, W, KH, KW) == (16, 16, 58, 3, 3) and H % 2 == 0 and (H - 2) % 8 == 0
 
 
 # ---------------------------------------------------------------- tbmm
@@ -214,7 +214,9 @@ GCONV_SHAPES = [
     (1, 2, 16, 16, 21, 58, 3, 3),   # width-58 kernels: odd height (unaligned planes), ragged last band
     (2, 1, 16, 16, 12, 58, 3, 3),   # width-58 kernels: two bands, second one partial
     (1, 1, 16, 16, 3, 58, 3, 3),    # width-58 kernels: a single output row
-    (3, 5, 16, 16, 11, 58, 3, 3),   # width-58 kernels: 15 (image, group) pairs, two bands
+    (3, 5, 16, 16, 18, 58, 3, 3),   # int8 kernel: 15 (image, group) pairs, two bands
+    (1, 3, 16, 16, 10, 58, 3, 3),   # int8 kernel: a single band
+    (37, 29, 16, 16, 26, 58, 3, 3), # int8 kernel: 1073 pairs on 512 persistent workgroups (2 or 3 images each)
     (1, 3, 16, 16, 20, 30, 3, 3),   # 16x16 channels, other width: runtime-width LDS kernel
 ]
 
@@ -241,7 +243,7 @@ def test_gconv_width_58_on_the_fp64_path(tc, shape, oracle_threads, monkeypatch)
 
 def test_gconv_i8_wide_dynamic_range_and_nonfinite(tc, oracle_threads):
     """Per-band / per-filter scaling: magnitudes spread over many binades, an all-zero band, and Inf/NaN poisoning a band."""
-    shape = (1, 2, 16, 16, 26, 58, 3, 3)   # three bands
+    shape = (1, 2, 16, 16, 26, 58, 3, 3)   # three bands of the int8 kernel
     I, W1, bias = inputs.make_gconv(*shape, seed=77)
     rng = np.random.default_rng(5)
     I = (I * np.exp2(rng.integers(-12, 12, size=I.shape))).astype(np.float32)      # 24 binades inside every band
@@ -387,10 +389,11 @@ def test_kron_and_gconv_stay_inside_their_outputs(tc, oracle_threads):
     check(Yv, oracle.kron(W1, W2, X), "kron guard band")
     assert torch.all(buf[:256] == 777.0) and torch.all(buf[256 + 5 * 40 * 64:] == 777.0)
 
-    Ig, Wg, bias = inputs.make_gconv(1, 2, 16, 16, 21, 58, 3, 3, seed=33)  # band kernel, ragged last band
-    n = 1 * 2 * 16 * 19 * 56
-    buf = torch.full((n + 512,), 777.0, device="cuda")
-    Ov = buf[256:256 + n].view(1, 2, 16, 19, 56)
-    tc.tc_group_conv(dev(Ig), dev(Wg), dev(bias), Ov)
-    check(Ov, oracle.group_conv(Ig, Wg, bias), "gconv guard band", TIGHT_I8)
-    assert torch.all(buf[:256] == 777.0) and torch.all(buf[256 + n:] == 777.0)
+    for H in (21, 26):  # fp64 band kernel with a ragged last band; int8 kernel, three whole bands
+        Ig, Wg, bias = inputs.make_gconv(1, 2, 16, 16, H, 58, 3, 3, seed=33)
+        n = 1 * 2 * 16 * (H - 2) * 56
+        buf = torch.full((n + 512,), 777.0, device="cuda")
+        Ov = buf[256:256 + n].view(1, 2, 16, H - 2, 56)
+        tc.tc_group_conv(dev(Ig), dev(Wg), dev(bias), Ov)
+        check(Ov, oracle.group_conv(Ig, Wg, bias), "gconv guard band H=%d" % H, TIGHT_I8)
+        assert torch.all(buf[:256] == 777.0) and torch.all(buf[256 + n:] == 777.0)
