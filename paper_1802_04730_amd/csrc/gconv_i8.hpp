@@ -9,11 +9,11 @@
 //   * every fp32 operand x of a block (one filter row of W1; one band of input
 //     rows) is written as a 31-bit fixed-point number relative to the block's
 //     largest magnitude, v = rint(x * 2^(30-e)) with max|x| < 2^e, and v is split
-//     into four signed 8-bit digits, v = sum_k d_k 256^k.  Elements within 2^-7
-//     of the block maximum are represented exactly, smaller ones to 2^-31 of it;
+//     into four signed 8-bit digits, v = sum_k d_k 256^k.  Elements within 2^-6
+//     of the block maximum are represented exactly, smaller ones to 2^-30 of it;
 //   * a product of two operands is sum_{k,l} a_k b_l 256^(k+l); the 13 digit
-//     pairs with k + l >= 2 are kept (the dropped ones are below 2^-38 of the
-//     block maxima' product).  Each pair is one int8 MFMA accumulation in int32,
+//     pairs with k + l >= 2 are kept (the dropped ones are below 2^-35 of the
+//     product of the block maxima).  Each pair is one int8 MFMA accumulation in int32,
 //     which is exact (no rounding, any order), one accumulator per diagonal k + l;
 //   * the five diagonals are combined exactly (int32 shifts, then fp64), scaled
 //     by 2^(ea+eb-36), the bias is added in fp64, and the sum is rounded to fp32

@@ -1,6 +1,7 @@
 // Device-side building blocks shared by the tc355 kernels (gfx950 only).
 //
-// Arithmetic model of the whole library: fp32 inputs are widened exactly to
+// Arithmetic model of the library (the int8 grouped convolution in gconv_i8.hpp
+// states its own): fp32 inputs are widened exactly to
 // fp64, multiplied and summed by the fp64 matrix-core instruction
 // v_mfma_f64_16x16x4_f64, and rounded to fp32 once when a declared output is
 // written.  An fp32 accumulator (vector or matrix) cannot meet the parity bar
