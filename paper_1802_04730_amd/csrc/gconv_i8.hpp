@@ -87,9 +87,17 @@ struct GconvI8Geom {
 
 // x -> four signed digits of rint(x * 2^sh), one per byte (byte k = digit of weight 256^k).
 __device__ __forceinline__ int i8_digits(float x, int sh) {
-  int v;  // floor(x * 2^sh + 0.5), exact for |.| <= 2^30
-  asm("v_cvt_rpi_i32_f32 %0, %1" : "=v"(v) : "v"(ldexpf(x, sh)));
+  const int v = (int)__builtin_rintf(ldexpf(x, sh));  // exact: |.| <= 2^30
   return (v + 0x00808080) ^ 0x00808080;
+}
+
+// Exponent e with m < 2^e for the magnitude whose bit pattern is mbits (sign cleared), denormals included; 129 for
+// Inf/NaN.  A block scaled by it fills bit 29 of the fixed-point numbers, so that the digit pairs that are dropped
+// stay 2^-35 below the leading ones.
+constexpr int I8_NONFINITE = 129;
+__device__ __forceinline__ int i8_exponent(unsigned mbits) {
+  const int biased = (int)(mbits >> 23);
+  return biased ? biased - 126 : (32 - __clz((int)mbits)) - 149;
 }
 
 // 4 x 4 byte transpose: x[c] holds the 4 digits of channel c; y[k] receives digit k of the 4 channels.
@@ -196,7 +204,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
         for (int c = 0; c < C; c++) m = max(m, __float_as_uint(wp[c * (KH * KW) + kh * KW]) & 0x7fffffffu);
       m = max(m, (unsigned)__shfl_xor((int)m, 16));
       m = max(m, (unsigned)__shfl_xor((int)m, 32));
-      const int ea = (int)(m >> 23) - 126;  // max|w| < 2^ea over the filter row (255-126 marks Inf/NaN)
+      const int ea = i8_exponent(m);  // max|w| < 2^ea over the filter row
 #pragma unroll
       for (int kh = 0; kh < KH; kh++) {
         int d[4], y[4];
@@ -249,8 +257,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
       __syncthreads();
       TC355_TRACE_R(trace, 3);
       m = max(max(maxw[(it & 1) * 4 + 0], maxw[(it & 1) * 4 + 1]), max(maxw[(it & 1) * 4 + 2], maxw[(it & 1) * 4 + 3]));
-      const int mexp = __builtin_amdgcn_readfirstlane((int)(m >> 23));
-      const int eb = mexp - 126;  // max|x| < 2^eb
+      const int eb = __builtin_amdgcn_readfirstlane(i8_exponent(m));  // max|x| < 2^eb over the band
 
       // ---- slice and stage: digit plane k, record of pixel pi at byte k*PLANE + 16*pi, channels 4cg.. at +4cg
       {
@@ -287,7 +294,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
       int scale_hi[4];
 #pragma unroll
       for (int v = 0; v < 4; v++) {
-        const bool bad = mexp == 255 || ea_v[v] == 255 - 126;
+        const bool bad = eb == I8_NONFINITE || ea_v[v] == I8_NONFINITE;
         scale_hi[v] = bad ? 0x7ff80000 : (1023 + ea_v[v] + eb - 36) << 20;
       }
 

@@ -272,6 +272,25 @@ def test_gconv_i8_wide_dynamic_range_and_nonfinite(tc, oracle_threads):
     assert np.isfinite(got2[0, 1, :, 0:8]).all(), "bands that never read the Inf stay finite"
 
 
+@pytest.mark.parametrize("in_exp,w_exp", [(-100, 60), (100, 20), (-140, 100), (0, -120)])
+def test_gconv_i8_extreme_magnitudes(tc, oracle_threads, in_exp, w_exp):
+    """Block scaling must follow the operands through the whole fp32 exponent range (denormal inputs included)."""
+    shape = (1, 2, 16, 16, 18, 58, 3, 3)
+    I, W1, _ = inputs.make_gconv(*shape, seed=91)
+    I = np.ldexp(I, in_exp).astype(np.float32)
+    W1 = np.ldexp(W1, w_exp).astype(np.float32)
+    ref = oracle.group_conv(I, W1, None)
+    assert np.isfinite(ref).all() and np.abs(ref).max() > 0
+    O = torch.full(ref.shape, float("nan"), device="cuda")
+    tc.tc_group_conv(dev(I), dev(W1), None, O)
+    torch.cuda.synchronize()
+    got = O.cpu().numpy().astype(np.float64)
+    small = np.abs(ref) < 2.0 ** -120   # outputs in the denormal range of fp32 round on a coarser grid
+    err = parity_error(np.where(small, ref, got), ref)
+    print("gconv extreme 2^%d x 2^%d: parity error %.3e" % (in_exp, w_exp, err), flush=True)
+    assert err <= TIGHT_I8 * (4 if in_exp < -126 else 1)   # denormal inputs carry fewer bits themselves
+
+
 def test_gconv_without_bias(tc, oracle_threads):
     I, W1, _ = inputs.make_gconv(1, 3, 4, 6, 10, 9, 3, 3, seed=2)
     ref = oracle.group_conv(I, W1, None)
