@@ -32,6 +32,7 @@
 // waiting workgroup raises the error word and goes on, so the grid always
 // drains.
 #pragma once
+#include "gemm_wave.hpp"
 #include "tc355_device.hpp"
 
 namespace tc355 {
@@ -139,7 +140,9 @@ constexpr int MLP_LDS_BYTES = 2 * MLP_BUF_BYTES + 2 * WAVES_PER_WG * WAVE * 32; 
 // NR chunks ahead of the MFMAs through a register ring, also across tile
 // boundaries, and pass through a double-buffered LDS stage from which the four
 // wavefronts read their quarter of the chunk as MFMA operands.
-template <typename TA>
+// FC: the fcrelu epilogue (sum started from the bias, clamp); without it the body is a plain contraction
+// C = A * Wl^T (the transposed matmul of Section 7 at sizes too small for the 64 x 64 block kernel).
+template <typename TA, bool FC = true>
 __device__ __forceinline__ void mlp_layer(const TA* __restrict__ A, const float* __restrict__ Wl,
                                           const float* __restrict__ bias, float* __restrict__ O,
                                           double* __restrict__ act, int batch, int K, int M, char* smem,
@@ -242,7 +245,7 @@ __device__ __forceinline__ void mlp_layer(const TA* __restrict__ A, const float*
   const int total = my_jobs * nck;  // chunks in this workgroup's stream
   int job = blockIdx.x, ck = 0;
   d4 acc = d4_zero();
-  double bz = (job < njobs) ? (double)bias[min((job % tiles_m) * 16 + r16, M - 1)] : 0.0;
+  double bz = (FC && job < njobs) ? (double)bias[min((job % tiles_m) * 16 + r16, M - 1)] : 0.0;
   if (total > 0) {
     stage(ring[0], smem);
     load_next(ring[0]);
@@ -292,7 +295,7 @@ __device__ __forceinline__ void mlp_layer(const TA* __restrict__ A, const float*
           x += part[1 * WAVE + lane][v];
           x += part[2 * WAVE + lane][v];
           x += part[3 * WAVE + lane][v];
-          x = relu64(x);
+          if (FC) x = relu64(x);
           const int ct = job % tiles_m, rt = job / tiles_m;
           const int row = rt * 16 + d_row(q, v), col = ct * 16 + r16;
           if (row < batch && col < M) {
@@ -305,7 +308,7 @@ __device__ __forceinline__ void mlp_layer(const TA* __restrict__ A, const float*
           parity ^= 1;
           job += step;
           acc = d4_zero();
-          if (job < njobs) bz = (double)bias[min((job % tiles_m) * 16 + r16, M - 1)];
+          if (FC && job < njobs) bz = (double)bias[min((job % tiles_m) * 16 + r16, M - 1)];
         }
       }
     }
@@ -357,6 +360,14 @@ __global__ __launch_bounds__(WG_THREADS, 2) void mlp_fused_kernel(MlpArgs p) {
       __hip_atomic_store(reinterpret_cast<unsigned long long*>(p.sync + MLP_SYNC_TOKEN), 0ull, __ATOMIC_RELAXED,
                          __HIP_MEMORY_SCOPE_AGENT);
   }
+}
+
+// One contraction C[N][M] = sum_k A[N][k] * Bm[M][k] with the layer body above: 16 x 16 output tiles dealt to
+// persistent workgroups whose four wavefronts split every chunk of the reduction.  For one matrix pair (no batch
+// stride) with a long reduction and too few 64 x 64 blocks to fill the chip.
+__global__ __launch_bounds__(WG_THREADS, 2) void gemm_nt_splitk_kernel(GemmArgs p) {
+  extern __shared__ __attribute__((aligned(32))) char smem[];
+  mlp_layer<float, false>(static_cast<const float*>(p.A), p.Bm, nullptr, p.C, nullptr, p.N, p.K, p.M, smem, nullptr);
 }
 
 }  // namespace tc355

@@ -9,6 +9,7 @@
 #include <chrono>
 #include <cstdlib>
 #include <random>
+#include <type_traits>
 
 #include "gconv_band.hpp"
 #include "gconv_i8.hpp"
@@ -73,10 +74,37 @@ bool try_gemm_tile(const GemmArgs& a, int64_t batch, hipStream_t s, tc_status* s
   return true;
 }
 
+int device_cus();
+
+// Split-reduction kernel (the MLP layer body without its epilogue) for one fp32 matrix pair with a long reduction
+// and too few 64 x 64 blocks for the kernel above; returns false if it does not apply.
+bool try_gemm_splitk(const GemmArgs& a, int64_t batch, hipStream_t s, tc_status* st) {
+  if (batch != 1 || a.K % 4 != 0 || a.K < 2 * MLP_KC || !a.C || a.C64) return false;
+  const int64_t jobs = ceil_div(a.N, 16) * ceil_div(a.M, 16);
+  const int cus = device_cus();
+  if (jobs < 64 || cus <= 0) return false;
+  static std::atomic<int> lds_ok{0};  // needs more than the default 64 KiB of dynamic LDS
+  if (!lds_ok.load(std::memory_order_acquire)) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_nt_splitk_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, MLP_LDS_BYTES) != hipSuccess) {
+      *st = TC_ERR_LAUNCH;
+      return true;
+    }
+    lds_ok.store(1, std::memory_order_release);
+  }
+  const unsigned nwg = (unsigned)std::min<int64_t>(2 * cus, jobs);
+  gemm_nt_splitk_kernel<<<dim3(nwg), dim3(WG_THREADS), MLP_LDS_BYTES, s>>>(a);
+  *st = launch_status();
+  return true;
+}
+
 template <typename TA, int EPI>
 tc_status launch_gemm(const GemmArgs& a, int64_t batch, int tm, hipStream_t s) {
   tc_status st = TC_OK;
   if (try_gemm_tile<TA, EPI>(a, batch, s, &st)) return st;
+  if constexpr (std::is_same<TA, float>::value && EPI == EPI_NONE) {
+    if (try_gemm_splitk(a, batch, s, &st)) return st;
+  }
   // widest per-lane load that keeps every row start aligned
   if (a.K % 4 == 0) return launch_gemm_tm<TA, 4, EPI>(a, batch, tm, s);
   if (a.K % 2 == 0) return launch_gemm_tm<TA, 2, EPI>(a, batch, tm, s);

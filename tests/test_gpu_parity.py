@@ -59,7 +59,8 @@ TBMM_SHAPES = [
     (1, 128, 256, 32),    # transposed matmul of Section 7 (B = 1)
     (7, 5, 81, 64),
     (40, 100, 130, 68),   # LDS-tiled kernel (>= 128 blocks): ragged 64x64 blocks, reduction not a multiple of the chunk
-    (1, 128, 1024, 1024), # the paper's medium transposed matmul (M,K,N) = (128,1024,1024)
+    (1, 128, 1024, 1024), # the paper's medium transposed matmul (M,K,N) = (128,1024,1024): split-reduction kernel
+    (1, 100, 200, 260),   # split-reduction kernel: ragged 16x16 tiles, reduction tail of 4 past two chunks
     (1, 128, 4096, 96),   # LDS-tiled kernel, one batch element, three chunks
     (130, 64, 64, 4),     # LDS-tiled kernel: a single short chunk
 ]
@@ -397,6 +398,40 @@ def test_tbmm_large_batch_sampled(tc, oracle_threads):
     pick = np.random.default_rng(0).choice(B, size=64, replace=False)
     pick = np.concatenate([pick, [0, B - 1]])
     check(Z[torch.from_numpy(pick).cuda()], oracle.tbmm(X[pick], Y[pick]), "tbmm B=20000, sampled batches")
+
+
+def test_tmm_largest_paper_shape_sampled(tc, oracle_threads):
+    """Section 7, tmm (M,K,N) = (128,4096,16384) through tc_tbmm with B = 1: full size on the GPU, sampled columns in the oracle."""
+    rng = np.random.default_rng(77)
+    X = rng.standard_normal((1, 128, 4096)).astype(np.float32)
+    Y = rng.standard_normal((1, 16384, 4096)).astype(np.float32)
+    Z = torch.full((1, 128, 16384), float("nan"), device="cuda")
+    tc.tc_tbmm(dev(X), dev(Y), Z)
+    torch.cuda.synchronize()
+    assert not torch.isnan(Z).any()
+    pick = np.sort(rng.choice(16384, size=96, replace=False))
+    pick[:4] = [0, 63, 64, 16383]
+    ref = oracle.tbmm(X, np.ascontiguousarray(Y[:, pick]))
+    check(Z[:, :, torch.from_numpy(pick).cuda()], ref, "tmm 128x4096x16384, 96 sampled columns")
+
+
+@pytest.mark.parametrize("shape", [
+    (32, 32, 16, 16, 14, 14, 3, 3),
+    (32, 32, 32, 32, 7, 7, 3, 3),
+    (32, 32, 4, 4, 56, 56, 3, 3),
+    (32, 32, 8, 8, 28, 28, 3, 3),
+])
+def test_gconv_paper_table_shapes_full_size_sampled(tc, oracle_threads, shape):
+    """Section 7, grouped-convolution table: full size on the GPU, four sampled images in the oracle."""
+    N, G, C, F, H, W, KH, KW = shape
+    I, W1, bias = inputs.make_gconv(*shape, seed=55)
+    O = torch.full((N, G, F, H - KH + 1, W - KW + 1), float("nan"), device="cuda")
+    tc.tc_group_conv(dev(I), dev(W1), dev(bias), O)
+    torch.cuda.synchronize()
+    assert not torch.isnan(O).any()
+    pick = np.array([0, 13, 14, 31])
+    ref = oracle.group_conv(np.ascontiguousarray(I[pick]), W1, bias)
+    check(O[torch.from_numpy(pick).cuda()], ref, "gconv %s, images %s" % (shape, pick.tolist()))
 
 
 def test_kron_and_gconv_stay_inside_their_outputs(tc, oracle_threads):
