@@ -172,7 +172,8 @@ __global__ __launch_bounds__(WG_THREADS, MINW) void gconv_band_kernel(GconvBandA
     // before the MFMAs of step s.  FETCH: units [j0, j0+NJ) of the next band are fetched between steps.
     auto group = [&](auto tn_c, int t_first, auto j0_c, auto nj_c) {
       constexpr int TN = decltype(tn_c)::value, J0 = decltype(j0_c)::value, NJ = decltype(nj_c)::value;
-      constexpr int EVERY = NJ > 0 ? (NS / NJ > 0 ? NS / NJ : 1) : NS + 1;
+      constexpr int NJD = NJ > 0 ? NJ : 1;  // (keeps the unused branch free of a division by zero)
+      constexpr int EVERY = NJ > 0 ? (NS / NJD > 0 ? NS / NJD : 1) : NS + 1;
       const double* bp[TN];
       d4 acc[TN];
       double bcur[TN], bnxt[TN];

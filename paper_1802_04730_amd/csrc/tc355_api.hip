@@ -14,6 +14,7 @@
 #include "gconv_band.hpp"
 #include "gconv_i8.hpp"
 #include "gconv_lds.hpp"
+#include "gconv_quad.hpp"
 #include "gconv_wave.hpp"
 #include "gemm_tile.hpp"
 #include "gemm_wave.hpp"
@@ -75,6 +76,30 @@ bool try_gemm_tile(const GemmArgs& a, int64_t batch, hipStream_t s, tc_status* s
 }
 
 int device_cus();
+
+// ---- grouped convolution with 4 or 8 channels per group (4x4x4 MFMA blocks), compile-time width --------
+template <int C, int F, int KH, int KW, int W, int ROWS, int MINW>
+bool try_gconv_quad(const GconvArgs& g, hipStream_t s, tc_status* st) {
+  using Gm = GconvQuadGeom<C, F, KH, KW, W, ROWS>;
+  if (g.C != C || g.F != F || g.KH != KH || g.KW != KW || g.W != W) return false;
+  const int64_t grid = (int64_t)g.N * g.G;
+  if (grid > kMaxGrid) return false;
+  static std::atomic<int> lds_ok{0};
+  if (!lds_ok.load(std::memory_order_acquire)) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gconv_quad_kernel<C, F, KH, KW, W, ROWS, MINW>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, Gm::LDS_BYTES) != hipSuccess) {
+      *st = TC_ERR_LAUNCH;
+      return true;
+    }
+    lds_ok.store(1, std::memory_order_release);
+  }
+  GconvQuadArgs a{};
+  a.I = g.I; a.W1 = g.W1; a.bias = g.bias; a.O = g.O;
+  a.G = g.G; a.H = g.H;
+  gconv_quad_kernel<C, F, KH, KW, W, ROWS, MINW><<<dim3((unsigned)grid), dim3(WG_THREADS), Gm::LDS_BYTES, s>>>(a);
+  *st = launch_status();
+  return true;
+}
 
 // Split-reduction kernel (the MLP layer body without its epilogue) for one fp32 matrix pair with a long reduction
 // and too few 64 x 64 blocks for the kernel above; returns false if it does not apply.
@@ -407,6 +432,9 @@ tc_status tc_group_conv(const float* I, const float* W1, const float* bias, floa
   const bool i8 = !(arith && arith[0] == 'f');
   if (i8 && try_gconv_i8<58, 8>(a, s, &st)) return st;
   if (try_gconv_band<16, 3, 3, 58, 8, 2>(a, s, &st)) return st;
+  if (try_gconv_band<16, 3, 3, 14, 12, 2>(a, s, &st)) return st;  // the paper's (32,32,16,16,14,14): the whole image is one band
+  if (try_gconv_quad<4, 4, 3, 3, 56, 16, 4>(a, s, &st)) return st;    // the paper's (32,32,4,4,56,56)
+  if (try_gconv_quad<8, 8, 3, 3, 28, 26, 3>(a, s, &st)) return st;    // the paper's (32,32,8,8,28,28): one band
   if (try_gconv_lds<16, 16, 3, 3, 7>(a, s, &st)) return st;
   constexpr int TP = 4;
   a.tiles_f = (int)ceil_div(F, 16);

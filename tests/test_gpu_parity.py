@@ -219,6 +219,12 @@ GCONV_SHAPES = [
     (1, 3, 16, 16, 10, 58, 3, 3),   # int8 kernel: a single band
     (37, 29, 16, 16, 26, 58, 3, 3), # int8 kernel: 1073 pairs on 512 persistent workgroups (2 or 3 images each)
     (1, 3, 16, 16, 20, 30, 3, 3),   # 16x16 channels, other width: runtime-width LDS kernel
+    (2, 3, 16, 16, 14, 14, 3, 3),   # width-14 band kernel (paper table shape), whole image = one band
+    (1, 2, 16, 16, 17, 14, 3, 3),   # width-14 band kernel: odd height, two bands, unaligned planes
+    (2, 3, 4, 4, 56, 56, 3, 3),     # 4x4x4-block kernel (paper table shape): four bands, last one ragged
+    (1, 2, 4, 4, 5, 56, 3, 3),      # 4x4x4-block kernel: one short band
+    (2, 3, 8, 8, 28, 28, 3, 3),     # 4x4x4-block kernel, 8 channels (paper table shape)
+    (1, 2, 8, 8, 31, 28, 3, 3),     # 4x4x4-block kernel, 8 channels: two bands, ragged tiles
 ]
 
 
