@@ -187,7 +187,47 @@ def main():
     extra = {"tmm_128x4096x16384": {"us": round(tmm_us, 1), "gflops": round(tmm_flops / tmm_us * 1e-3, 1),
                                     "bound": "mfma",
                                     "frac": round(tmm_flops / (PEAK_F64_MFMA_TFLOPS * 1e12) * 1e6 / tmm_us, 4)}}
-    del Xt, Yt, Zt
+    # the other workloads of the paper's Section 7 tables, through the same entry points (fp64 matrix path)
+    def timed(fn, reps=20):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps
+
+    def entry(us, flops, nbytes):
+        t_mfma, t_hbm = flops / (PEAK_F64_MFMA_TFLOPS * 1e12), nbytes / (PEAK_HBM_GBS * 1e9)
+        return {"us": round(us, 1), "gflops": round(flops / us * 1e-3, 1), "bound": "mfma" if t_mfma >= t_hbm else "hbm",
+                "frac": round(max(t_mfma, t_hbm) * 1e6 / us, 4)}
+
+    for (M_, K_, N_) in [(128, 32, 256), (128, 1024, 1024)]:
+        Xt = torch.randn((1, M_, K_), device="cuda")
+        Yt = torch.randn((1, N_, K_), device="cuda")
+        Zt = torch.empty((1, M_, N_), device="cuda")
+        extra["tmm_%dx%dx%d" % (M_, K_, N_)] = entry(timed(lambda: tc355.tc_tbmm(Xt, Yt, Zt)), inputs.flops_tbmm(1, M_, N_, K_),
+                                                     4 * (M_ * K_ + N_ * K_ + M_ * N_))
+    for name, width in (("mlp1_128x1024x1024", 1024), ("c3_128x1024x1000", 1000)):
+        Im = torch.randn((128, 1024), device="cuda")
+        Wm = [torch.randn((width, 1024), device="cuda") * 0.02]
+        bm = [torch.randn((width,), device="cuda") * 0.01]
+        Om = [torch.empty((128, width), device="cuda")]
+        extra[name] = entry(timed(lambda: tc355.tc_mlp_fcrelu(Im, Wm, bm, Om, None)), 2 * 128 * 1024 * width,
+                            4 * (128 * 1024 + width * 1024 + width + 128 * width))
+    for (C_, F_, HW) in [(16, 16, 14), (32, 32, 7), (4, 4, 56), (8, 8, 28)]:
+        It = torch.randn((32, 32, C_, HW, HW), device="cuda")
+        Wt = torch.randn((32, F_, C_, 3, 3), device="cuda") * 0.05
+        bt = torch.randn((32 * F_,), device="cuda") * 0.05
+        Ot = torch.empty((32, 32, F_, HW - 2, HW - 2), device="cuda")
+        extra["gconv_32x32x%dx%dx%dx%d" % (F_, C_, HW, HW)] = entry(
+            timed(lambda: tc355.tc_group_conv(It, Wt, bt, Ot)), inputs.flops_gconv(32, 32, C_, F_, HW, HW, 3, 3),
+            4 * (It.numel() + Wt.numel() + bt.numel() + Ot.numel()))
+    del Xt, Yt, Zt, Im, Wm, bm, Om, It, Wt, bt, Ot
+
     # the grouped convolution on the fp64 matrix path (what every other shape of the operator takes), for comparison
     os.environ["TC355_GCONV_ARITH"] = "f64"
     for _ in range(3):

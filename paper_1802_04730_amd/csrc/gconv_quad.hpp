@@ -48,6 +48,7 @@ struct GconvQuadGeom {
   static constexpr int CQ = C / 4, FQ = F / 4;
   static constexpr int NS = KH * KW * CQ;                          // reduction steps per tile
   static_assert(C % 4 == 0 && F % 4 == 0 && C <= 8 && F <= 8, "4 or 8 channels and filters per group");
+  static_assert(W % 4 == 0, "16-byte loads: every row starts 16-byte aligned");
   static_assert(PS >= LEN, "plane stride too small");
   static_assert((4 * (CQ - 1) * PS + (KH - 1) * W + KW - 1) * 8 < 65536, "LDS immediates out of range");
   static_assert(F * C * KH * KW * 4 <= LDS_BYTES, "the filter bank is parked in the band area first");
@@ -96,12 +97,31 @@ __global__ __launch_bounds__(WG_THREADS, MINW) void gconv_quad_kernel(GconvQuadA
 
   for (int b = 0; b < nbands; b++) {
     __syncthreads();  // the previous band (or the parked filter bank) has been read by everyone
-    // ---- stage the band: rows b*ROWS .. of every channel, widened to fp64; rows past the image are skipped
+    // ---- stage the band: rows b*ROWS .. of every channel, widened to fp64; rows past the image are skipped.
+    // W is a multiple of 4, so planes, band starts and row ends are 16-byte aligned.  All loads are issued
+    // before the first conversion (one at a time, every load would wait for the previous one's round trip).
     const int h0 = b * ROWS;
-    const int avail = min((H - h0) * W, LEN);  // floats of each plane that belong to this band
-    for (int idx = tid; idx < C * LEN; idx += WG_THREADS) {
-      const int c = idx / LEN, i = idx - c * LEN;
-      if (i < avail) gq_band[c * PS + i] = (double)src[c * plane + (int64_t)h0 * W + i];
+    const int avail = min((H - h0) * W, LEN);  // floats of each plane that belong to this band (a multiple of 4)
+    {
+      constexpr int LEN4 = LEN / 4, NLD = (C * LEN4 + WG_THREADS - 1) / WG_THREADS;
+      f4 v[NLD];
+#pragma unroll
+      for (int j = 0; j < NLD; j++) {
+        const int u = min(tid + j * WG_THREADS, C * LEN4 - 1);
+        const int c = u / LEN4, i = min(4 * (u - c * LEN4), avail - 4);  // clamped, never skipped per lane
+        v[j] = *reinterpret_cast<const f4*>(src + c * plane + (int64_t)h0 * W + i);
+      }
+#pragma unroll
+      for (int j = 0; j < NLD; j++) {
+        const int u = tid + j * WG_THREADS;
+        const int c = u / LEN4, i = 4 * (u - c * LEN4);
+        if (u < C * LEN4 && i < avail) {
+          double* d = gq_band + c * PS + i;  // PS and i are even: 16-byte aligned pairs
+          const dbl2 lo = {(double)v[j][0], (double)v[j][1]}, hi = {(double)v[j][2], (double)v[j][3]};
+          *reinterpret_cast<dbl2*>(d) = lo;
+          *reinterpret_cast<dbl2*>(d + 2) = hi;
+        }
+      }
     }
     __syncthreads();
 
