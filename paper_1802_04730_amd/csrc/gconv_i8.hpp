@@ -112,6 +112,19 @@ __device__ __forceinline__ void i8_transpose4(const int (&x)[4], int (&y)[4]) {
   y[3] = (int)__builtin_amdgcn_perm(hi23, hi01, 0x07060302u);
 }
 
+// Maximum over the wavefront, returned in every lane: four cross-lane steps inside each row of 16 lanes (data
+// parallel primitives: no LDS round trips), then the four rows through scalar registers.
+__device__ __forceinline__ unsigned i8_wave_max(unsigned m) {
+  int v = (int)m;  // bit patterns with the sign cleared: signed and unsigned order agree
+  v = max(v, __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+  v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+  v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x141, 0xF, 0xF, false));  // row_half_mirror
+  v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x140, 0xF, 0xF, false));  // row_mirror
+  const int r0 = __builtin_amdgcn_readlane(v, 0), r1 = __builtin_amdgcn_readlane(v, 16);
+  const int r2 = __builtin_amdgcn_readlane(v, 32), r3 = __builtin_amdgcn_readlane(v, 48);
+  return (unsigned)max(max(r0, r1), max(r2, r3));
+}
+
 __device__ __forceinline__ i4 mfma_i8(i4 a, i4 b, i4 c) { return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0); }
 
 template <int W, int ROWS>
@@ -251,8 +264,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
         for (int c = 0; c < 4; c++) take(preh[c][0], preh[c][1]);
       }
       unsigned m = max((unsigned)mp, mn & 0x7fffffffu);
-#pragma unroll
-      for (int o = 1; o < WAVE; o <<= 1) m = max(m, (unsigned)__shfl_xor((int)m, o));
+      m = i8_wave_max(m);
       if (lane == 0) maxw[(it & 1) * 4 + wave] = m;
       __syncthreads();
       TC355_TRACE_R(trace, 3);
