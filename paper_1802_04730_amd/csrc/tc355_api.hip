@@ -436,13 +436,18 @@ tc_status tc_group_conv(const float* I, const float* W1, const float* bias, floa
   if (try_gconv_quad<4, 4, 3, 3, 56, 16, 4>(a, s, &st)) return st;    // the paper's (32,32,4,4,56,56)
   if (try_gconv_quad<8, 8, 3, 3, 28, 26, 3>(a, s, &st)) return st;    // the paper's (32,32,8,8,28,28): one band
   if (try_gconv_lds<16, 16, 3, 3, 7>(a, s, &st)) return st;
-  constexpr int TP = 4;
+  // generic kernel: a wavefront takes 16 filters x a strip of 16*TP pixels; small images take a narrower strip
+  const int64_t tiles_p = ceil_div(OH * OW, 16);
+  const int tp = tiles_p >= 4 ? 4 : (tiles_p >= 2 ? 2 : 1);
   a.tiles_f = (int)ceil_div(F, 16);
-  a.strips_p = (int)ceil_div(OH * OW, 16 * TP);
+  a.strips_p = (int)ceil_div(OH * OW, 16 * tp);
   a.jobs = N * G * a.tiles_f * a.strips_p;
   const int64_t grid = ceil_div(a.jobs, WAVES_PER_WG);
   if (grid > kMaxGrid) return TC_ERR_UNSUPPORTED;
-  gconv_wave_kernel<TP><<<dim3((unsigned)grid), dim3(WG_THREADS), 0, s>>>(a);
+  const dim3 gd((unsigned)grid), bd(WG_THREADS);
+  if (tp == 4) gconv_wave_kernel<4><<<gd, bd, 0, s>>>(a);
+  else if (tp == 2) gconv_wave_kernel<2><<<gd, bd, 0, s>>>(a);
+  else gconv_wave_kernel<1><<<gd, bd, 0, s>>>(a);
   return launch_status();
 }
 
