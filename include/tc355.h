@@ -31,7 +31,8 @@
  *    device properties and an atomic call counter; concurrent calls from
  *    several host threads are allowed.
  *  - Environment (read at every call, meant for tests): TC355_MLP_FUSED=0
- *    forces one launch per MLP layer; TC355_MLP_SPIN_LIMIT=<n> bounds the
+ *    forces one launch per MLP layer, =1 the single fused kernel (by default
+ *    very large batches take one launch per layer); TC355_MLP_SPIN_LIMIT=<n> bounds the
  *    polls of a device-wide wait; TC355_GCONV_ARITH=f64 keeps every grouped
  *    convolution on the fp64 path.
  */

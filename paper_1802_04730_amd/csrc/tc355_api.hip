@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <atomic>
 #include <chrono>
+#include <cstdint>
 #include <cstdlib>
 #include <random>
 #include <type_traits>
@@ -356,6 +357,13 @@ tc_status tc_mlp_fcrelu(const float* I, int64_t batch, int32_t n_layers, const i
   // One persistent kernel for the whole chain when every reduction extent allows 16-byte loads.
   bool fused = env_long("TC355_MLP_FUSED", 1) != 0;
   for (int l = 0; l < n_layers; l++) fused = fused && (dims[l] % 4 == 0);
+  // Large batches: when every layer fills the chip with 64 x 64 blocks, one LDS-tiled launch per layer (70 % of the
+  // fp64 matrix peak) beats the fused kernel's 16 x 16 tiles (43 %), and the launches no longer matter.
+  if (n_layers > 1 && env_long("TC355_MLP_FUSED", -1) != 1) {
+    int64_t min_blocks = INT64_MAX;
+    for (int l = 0; l < n_layers; l++) min_blocks = std::min(min_blocks, ceil_div(batch, GT_BM) * ceil_div(dims[l + 1], GT_BN));
+    if (min_blocks >= 256) fused = false;
+  }
   const int cus = device_cus();
   if (fused && cus > 0) {
     MlpArgs a{};

@@ -406,6 +406,26 @@ def test_tbmm_large_batch_sampled(tc, oracle_threads):
     check(Z[torch.from_numpy(pick).cuda()], oracle.tbmm(X[pick], Y[pick]), "tbmm B=20000, sampled batches")
 
 
+@pytest.mark.parametrize("fused", ["default", "1"])
+def test_mlp_large_batch_sampled(tc, oracle_threads, monkeypatch, fused):
+    """Batch 8192: by default one LDS-tiled launch per layer, with TC355_MLP_FUSED=1 the fused kernel; sampled rows in the oracle."""
+    if fused != "default":
+        monkeypatch.setenv("TC355_MLP_FUSED", fused)
+    batch, dims = 8192, (1024, 1024, 512, 256)
+    I, Ws, bs = inputs.make_mlp(batch, dims, seed=71)
+    O = run_mlp(tc, I, Ws, bs)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(3)
+    pick = np.sort(rng.choice(batch, size=48, replace=False))
+    pick[:3] = [0, 63, 64]
+    pick[-1] = batch - 1
+    ref = oracle.mlp_fcrelu(np.ascontiguousarray(I[pick]), Ws, bs)
+    sel = torch.from_numpy(pick).cuda()
+    for l in range(3):
+        assert not torch.isnan(O[l]).any()
+        check(O[l][sel], ref[l], "mlp batch 8192 (fused=%s), layer %d, sampled rows" % (fused, l))
+
+
 def test_tmm_largest_paper_shape_sampled(tc, oracle_threads):
     """Section 7, tmm (M,K,N) = (128,4096,16384) through tc_tbmm with B = 1: full size on the GPU, sampled columns in the oracle."""
     rng = np.random.default_rng(77)
