@@ -35,8 +35,9 @@
 //
 // Work split: persistent workgroups (two per compute unit), each taking (image,
 // group) pairs round-robin; bands of 8 output rows; the band's 10 input rows sit
-// in LDS as four digit planes [pixel][16 channels] (double-buffered);
-// wavefront w owns output rows 2w and 2w+1 of the band: three
+// in LDS as four digit planes [pixel][16 channels] (two buffers, used in turn:
+// the idle one is the scratch through which the next image's filter bank is set
+// up while slower wavefronts still read the other); wavefront w owns output rows 2w and 2w+1 of the band: three
 // full 16-pixel columns swept over 4 input rows each, and the last 8 columns of
 // both rows packed into one tile (lanes 0-7: row 2w, lanes 8-15: row 2w+1).
 // Every wavefront executes the same 21 groups per band.  The next band (of this
