@@ -16,6 +16,7 @@
 #include "gconv_i8.hpp"
 #include "gconv_lds.hpp"
 #include "gconv_quad.hpp"
+#include "gconv_tiny.hpp"
 #include "gconv_wave.hpp"
 #include "gemm_tile.hpp"
 #include "gemm_wave.hpp"
@@ -98,6 +99,28 @@ bool try_gconv_quad(const GconvArgs& g, hipStream_t s, tc_status* st) {
   a.I = g.I; a.W1 = g.W1; a.bias = g.bias; a.O = g.O;
   a.G = g.G; a.H = g.H;
   gconv_quad_kernel<C, F, KH, KW, W, ROWS, MINW><<<dim3((unsigned)grid), dim3(WG_THREADS), Gm::LDS_BYTES, s>>>(a);
+  *st = launch_status();
+  return true;
+}
+
+// ---- grouped convolution with a large filter bank on tiny images: the bank stays in registers, images stream ----
+template <int C, int F, int KH, int KW, int H, int W>
+bool try_gconv_tiny(const GconvArgs& g, hipStream_t s, tc_status* st) {
+  using Gm = GconvTinyGeom<C, F, KH, KW, H, W>;
+  if (g.C != C || g.F != F || g.KH != KH || g.KW != KW || g.H != H || g.W != W) return false;
+  const int cus = device_cus();
+  if (cus <= 0) return false;
+  // about two workgroups per compute unit: each owns one group and a run of images
+  const int64_t nchunks = std::min<int64_t>(g.N, std::max<int64_t>(1, 2 * (int64_t)cus / g.G));
+  const int64_t chunk = ceil_div(g.N, nchunks);
+  GconvTinyArgs a{};
+  a.I = g.I; a.W1 = g.W1; a.bias = g.bias; a.O = g.O;
+  a.N = g.N; a.G = g.G;
+  a.chunk = (int)chunk;
+  a.nchunks = (int)ceil_div(g.N, chunk);
+  const int64_t grid = (int64_t)g.G * a.nchunks;
+  if (grid > kMaxGrid) return false;
+  gconv_tiny_kernel<C, F, KH, KW, H, W><<<dim3((unsigned)grid), dim3(WG_THREADS), Gm::LDS_BYTES, s>>>(a);
   *st = launch_status();
   return true;
 }
@@ -443,6 +466,7 @@ tc_status tc_group_conv(const float* I, const float* W1, const float* bias, floa
   if (try_gconv_band<16, 3, 3, 14, 12, 2>(a, s, &st)) return st;  // the paper's (32,32,16,16,14,14): the whole image is one band
   if (try_gconv_quad<4, 4, 3, 3, 56, 16, 4>(a, s, &st)) return st;    // the paper's (32,32,4,4,56,56)
   if (try_gconv_quad<8, 8, 3, 3, 28, 26, 3>(a, s, &st)) return st;    // the paper's (32,32,8,8,28,28): one band
+  if (try_gconv_tiny<32, 32, 3, 3, 7, 7>(a, s, &st)) return st;       // the paper's (32,32,32,32,7,7)
   if (try_gconv_lds<16, 16, 3, 3, 7>(a, s, &st)) return st;
   // generic kernel: a wavefront takes 16 filters x a strip of 16*TP pixels; small images take a narrower strip
   const int64_t tiles_p = ceil_div(OH * OW, 16);

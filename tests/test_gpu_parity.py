@@ -209,7 +209,9 @@ GCONV_SHAPES = [
     (2, 1, 3, 4, 8, 7, 3, 3),       # G = 1: ordinary convolution
     (2, 3, 4, 5, 6, 7, 1, 1),       # pointwise filter
     (1, 2, 4, 4, 3, 3, 3, 3),       # a single output pixel
-    (2, 4, 32, 32, 7, 7, 3, 3),     # paper table shape (32,32,32,32,7,7), fewer images/groups
+    (2, 4, 32, 32, 7, 7, 3, 3),     # paper table shape (32,32,32,32,7,7), fewer images/groups (bank-stationary kernel)
+    (5, 3, 32, 32, 7, 7, 3, 3),     # bank-stationary kernel: odd image count, ragged last chunk
+    (1, 2, 32, 32, 7, 7, 3, 3),     # bank-stationary kernel: a single image per group
     (2, 4, 4, 4, 56, 56, 3, 3),     # paper table shape (32,32,4,4,56,56), fewer images/groups
     (1, 2, 5, 20, 9, 11, 2, 4),     # two channel tiles, odd reduction length
     (1, 2, 16, 16, 21, 58, 3, 3),   # width-58 kernels: odd height (unaligned planes), ragged last band
