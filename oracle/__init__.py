@@ -10,6 +10,9 @@ from .tc_oracle import (  # noqa: F401
     group_conv,
     group_conv_infer,
     kron,
+    sconv2d,
+    sconv2d_infer,
+    lut,
     set_threads,
     get_threads,
     max_threads,

@@ -1,8 +1,9 @@
 /*
  * tc_oracle.c -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
  *
- * A plain, slow, float64 CPU evaluator of the four tensor comprehensions the
- * GPU library implements.  Every function is the loop nest that the paper's
+ * A plain, slow, float64 CPU evaluator of the tensor comprehensions the GPU
+ * library implements (transposed batched matmul, fcrelu chain, grouped
+ * convolution, Kronecker layer, strided convolution, lookup-table sum).  Every function is the loop nest that the paper's
  * Section 3 ("Tensor Comprehensions") gives as the meaning of a
  * comprehension: one "parallel for" per left-hand-side index, one
  * "reduction for" per index that appears on the right only, the body being
@@ -30,7 +31,14 @@
  * vec identities) and planted-mistake checks.  The paper prints no numeric
  * input->output example, so there is no printed value to match.
  *
- * Return value of every evaluator: 0 on success, 1 null pointer, 2 bad shape.
+ * The strided convolution is pinned against torch's conv2d with a stride, the
+ * stride-1 case, subsampling of the stride-1 result, delta filters and loops;
+ * the lookup-table sum against a one-hot matrix product, plain fancy indexing,
+ * a closed form on an affine table and loops; the inferred extents of the
+ * strided convolution against a count over the quantified definition.
+ *
+ * Return value of every evaluator: 0 on success, 1 null pointer, 2 bad shape
+ * (tc_oracle_lut: 3 if an index lies outside the table).
  */
 #include <stddef.h>
 #include <stdint.h>
@@ -209,5 +217,83 @@ int tc_oracle_kron(const float *W1, const float *W2, const float *X, double *Y,
                  (double)X[(b * K + k) * L + l];
         Y[(b * I + i) * J + j] = y;
       }
+  return 0;
+}
+
+/*
+ * Output extents of the strided convolution by range inference (Section 3.1
+ * "Range Inference"): kh and kw take the full filter extent from W; the
+ * output index h may take every value for which sh*h + kh stays inside
+ * [0, H) for ALL kh < KH, i.e. sh*h <= H - KH: floor((H-KH)/sh) + 1 values
+ * (likewise for w).  Returns 2 if an extent, a stride or a range is empty.
+ */
+int tc_oracle_sconv2d_infer(int64_t H, int64_t W, int64_t KH, int64_t KW,
+                            int64_t sh, int64_t sw, int64_t *OH, int64_t *OW) {
+  if (!OH || !OW) return 1;
+  if (H <= 0 || W <= 0 || KH <= 0 || KW <= 0 || sh <= 0 || sw <= 0) return 2;
+  if (H < KH || W < KW) return 2;
+  *OH = (H - KH) / sh + 1;
+  *OW = (W - KW) / sw + 1;
+  return 0;
+}
+
+/*
+ * Strided convolution (Section 3, listing sconv2d):
+ *     O(n,f,h,w)  = B(f)
+ *     O(n,f,h,w) += I(n,c, sh*h + kh, sw*w + kw) * W(f,c,kh,kw)
+ * I is [N,C,H,W], Wt is [F,C,KH,KW], Bv is [F] (may be NULL: the first
+ * statement then assigns 0), O is [N,F,OH,OW] with the inferred extents.
+ * The bias is assigned first and the products accumulate onto it, in the
+ * order of the listing.
+ */
+int tc_oracle_sconv2d(const float *I, const float *Wt, const float *Bv,
+                      double *O, int64_t N, int64_t C, int64_t F, int64_t H,
+                      int64_t W, int64_t KH, int64_t KW, int64_t sh,
+                      int64_t sw) {
+  int64_t OH, OW;
+  if (!I || !Wt || !O) return 1;
+  if (N < 0 || C <= 0 || F <= 0) return 2;
+  if (tc_oracle_sconv2d_infer(H, W, KH, KW, sh, sw, &OH, &OW)) return 2;
+#pragma omp parallel for num_threads(g_threads) schedule(static) collapse(2)
+  for (int64_t n = 0; n < N; n++)
+    for (int64_t f = 0; f < F; f++)
+      for (int64_t h = 0; h < OH; h++)
+        for (int64_t w = 0; w < OW; w++) {
+          double o = Bv ? (double)Bv[f] : 0.0;
+          for (int64_t c = 0; c < C; c++)
+            for (int64_t kh = 0; kh < KH; kh++)
+              for (int64_t kw = 0; kw < KW; kw++)
+                o += (double)I[((n * C + c) * H + (sh * h + kh)) * W +
+                               (sw * w + kw)] *
+                     (double)Wt[((f * C + c) * KH + kh) * KW + kw];
+          O[((n * F + f) * OH + h) * OW + w] = o;
+        }
+  return 0;
+}
+
+/*
+ * Lookup-table sum (Section 7, production model; appendix listing 2LUT, one
+ * of its two statements):
+ *     O(i,j) +=! LUT(Idx(i,k), j)
+ * LUT is [E,D] fp32, Idx is [B,L] int32, O is [B,D].  i and j range over the
+ * rows of Idx and the columns of LUT, k over the columns of Idx; an index
+ * that occurs several times in a row counts as often.  The comprehension
+ * gives no meaning to an index outside [0,E): the evaluator checks all of
+ * them first and returns 3 without writing anything.
+ */
+int tc_oracle_lut(const float *LUT, const int32_t *Idx, double *O, int64_t E,
+                  int64_t D, int64_t B, int64_t L) {
+  if (!LUT || !Idx || !O) return 1;
+  if (E <= 0 || D <= 0 || B < 0 || L <= 0) return 2;
+  for (int64_t t = 0; t < B * L; t++)
+    if (Idx[t] < 0 || (int64_t)Idx[t] >= E) return 3;
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+  for (int64_t i = 0; i < B; i++)
+    for (int64_t j = 0; j < D; j++) {
+      double o = 0.0; /* "+=!" */
+      for (int64_t k = 0; k < L; k++)
+        o += (double)LUT[(int64_t)Idx[i * L + k] * D + j];
+      O[i * D + j] = o;
+    }
   return 0;
 }

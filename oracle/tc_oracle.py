@@ -51,6 +51,12 @@ def _load():
     lib.tc_oracle_group_conv.restype = ctypes.c_int
     lib.tc_oracle_kron.argtypes = [fp, fp, fp, dp] + [i64] * 5
     lib.tc_oracle_kron.restype = ctypes.c_int
+    lib.tc_oracle_sconv2d_infer.argtypes = [i64] * 6 + [ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    lib.tc_oracle_sconv2d_infer.restype = ctypes.c_int
+    lib.tc_oracle_sconv2d.argtypes = [fp, fp, fp, dp] + [i64] * 9
+    lib.tc_oracle_sconv2d.restype = ctypes.c_int
+    lib.tc_oracle_lut.argtypes = [fp, ctypes.POINTER(ctypes.c_int32), dp] + [i64] * 4
+    lib.tc_oracle_lut.restype = ctypes.c_int
     lib.tc_oracle_set_threads.argtypes = [ctypes.c_int]
     lib.tc_oracle_get_threads.restype = ctypes.c_int
     lib.tc_oracle_max_threads.restype = ctypes.c_int
@@ -87,7 +93,8 @@ def _dp(a: np.ndarray):
 
 def _check(rc: int, what: str) -> None:
     if rc != 0:
-        raise ValueError("%s: oracle status %d (1 = null pointer, 2 = bad shape)" % (what, rc))
+        raise ValueError("%s: oracle status %d (1 = null pointer, 2 = bad shape, 3 = index outside the table)"
+                         % (what, rc))
 
 
 def tbmm(X, Y) -> np.ndarray:
@@ -166,3 +173,43 @@ def kron(W1, W2, X) -> np.ndarray:
     Y = np.empty((B, I, J), dtype=np.float64)
     _check(_load().tc_oracle_kron(_fp(W1), _fp(W2), _fp(X), _dp(Y), B, I, K, J, L), "kron")
     return Y
+
+
+def sconv2d_infer(H: int, W: int, KH: int, KW: int, sh: int, sw: int):
+    oh, ow = ctypes.c_int64(), ctypes.c_int64()
+    _check(_load().tc_oracle_sconv2d_infer(H, W, KH, KW, sh, sw, ctypes.byref(oh), ctypes.byref(ow)),
+           "sconv2d_infer")
+    return int(oh.value), int(ow.value)
+
+
+def sconv2d(I, Wt, bias, sh: int, sw: int) -> np.ndarray:
+    """O[n,f,h,w] = bias[f] + sum_{c,kh,kw} I[n,c,sh*h+kh,sw*w+kw] * Wt[f,c,kh,kw]."""
+    I, Wt = _f32(I), _f32(Wt)
+    N, C, H, W = I.shape
+    F, C2, KH, KW = Wt.shape
+    if C != C2:
+        raise ValueError("sconv2d: I %s and W %s disagree on C" % (I.shape, Wt.shape))
+    OH, OW = sconv2d_infer(H, W, KH, KW, sh, sw)
+    bp = None
+    if bias is not None:
+        bias = _f32(bias)
+        if bias.shape != (F,):
+            raise ValueError("sconv2d: bias must be [F]")
+        bp = _fp(bias)
+    O = np.empty((N, F, OH, OW), dtype=np.float64)
+    _check(_load().tc_oracle_sconv2d(_fp(I), _fp(Wt), bp, _dp(O), N, C, F, H, W, KH, KW, sh, sw), "sconv2d")
+    return O
+
+
+def lut(LUT, Idx) -> np.ndarray:
+    """O[i,j] = sum_k LUT[Idx[i,k], j] in float64; raises if an index lies outside the table."""
+    LUT = _f32(LUT)
+    Idx = np.ascontiguousarray(Idx)
+    if Idx.dtype != np.int32:
+        raise TypeError("lut: indices are int32, got %s" % Idx.dtype)
+    E, D = LUT.shape
+    B, L = Idx.shape
+    O = np.empty((B, D), dtype=np.float64)
+    _check(_load().tc_oracle_lut(_fp(LUT), Idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), _dp(O),
+                                 E, D, B, L), "lut")
+    return O

@@ -77,6 +77,26 @@ def make_kron(B, I, K, J, L, seed=SEED_BASE + 5, std=0.125):
     return W1, W2, X
 
 
+def make_sconv2d(N, C, F, H, W, KH, KW, seed=SEED_BASE + 6, w_std=0.05, b_std=0.05):
+    """I [N,C,H,W] ~ N(0,1); W [F,C,KH,KW] ~ N(0,w_std); bias [F] ~ N(0,b_std) (Section 3, listing sconv2d; the
+    paper states no sizes or distributions for it: those of the grouped convolution are reused)."""
+    r = _rng(seed)
+    I = _f32(r.standard_normal(size=(N, C, H, W)))
+    Wt = _f32(r.normal(0.0, w_std, size=(F, C, KH, KW)))
+    bias = _f32(r.normal(0.0, b_std, size=(F,)))
+    return I, Wt, bias
+
+
+def make_lut(E, D, B, L, seed=SEED_BASE + 7):
+    """LUT [E,D] ~ N(0,1), drawn directly in float32 (at the paper's E = 10^7 a float64 draw would need 5 GB);
+    Idx [B,L] int32, uniform over [0,E) with repetitions allowed.  The paper's production indices are not
+    published (Section 7, production models); uniform random rows stand in for them."""
+    r = _rng(seed)
+    LUT = r.standard_normal(size=(E, D), dtype=np.float32)
+    Idx = r.integers(0, E, size=(B, L), dtype=np.int32)
+    return LUT, Idx
+
+
 def make_config(c):
     """Inputs of benchmark configuration c (1..5) with its default seed."""
     cfg = dict(CONFIGS[c])
@@ -130,3 +150,20 @@ def flops_kron(B, I, K, J, L):
 
 def bytes_kron(B, I, K, J, L):
     return 4 * (I * K + J * L + B * K * L + B * I * J)
+
+
+def flops_sconv2d(N, C, F, H, W, KH, KW, sh, sw):
+    return 2 * N * F * ((H - KH) // sh + 1) * ((W - KW) // sw + 1) * C * KH * KW
+
+
+def bytes_sconv2d(N, C, F, H, W, KH, KW, sh, sw):
+    return 4 * (N * C * H * W + F * C * KH * KW + F + N * F * ((H - KH) // sh + 1) * ((W - KW) // sw + 1))
+
+
+def flops_lut(E, D, B, L):
+    return B * D * L  # one addition per gathered element
+
+
+def bytes_lut(E, D, B, L):
+    # the gathered rows, the indices, the output; the table as a whole is never read
+    return 4 * (B * L * D + B * L + B * D)
