@@ -5,7 +5,7 @@
  * A tensor comprehension (arXiv 1802.04730, Section 3) is an index-notation
  * statement: every output element is a sum, over the indices that appear only
  * on the right-hand side, of a product of tensor accesses, optionally followed
- * by a pointwise epilogue.  This library evaluates four fixed comprehensions.
+ * by a pointwise epilogue.  This library evaluates six fixed comprehensions.
  *
  * Conventions common to every entry point
  *  - Every tensor pointer is a DEVICE pointer to a dense row-major array (last
@@ -162,6 +162,50 @@ tc_status tc_group_conv_infer(int64_t H, int64_t W, int64_t KH, int64_t KW,
 tc_status tc_kron(const float *W1, const float *W2, const float *X, float *Y,
                   int64_t B, int64_t I, int64_t K, int64_t J, int64_t L,
                   void *hip_stream);
+
+/*
+ * Strided 2-D convolution, no padding, per-output-channel bias (Section 3,
+ * listing sconv2d):
+ *     O(n,f,h,w)  = B(f)
+ *     O(n,f,h,w) += I(n,c, sh*h + kh, sw*w + kw) * W(f,c,kh,kw)
+ * I: [N,C,H,W]   Wt: [F,C,KH,KW]   bias: [F] or NULL (the first statement
+ * then assigns 0)   O: [N,F,OH,OW] with OH = (H-KH)/sh + 1, OW = (W-KW)/sw + 1
+ * (integer division; see tc_sconv2d_infer).  sh, sw >= 1; sh = sw = 1 is the
+ * plain convolution.  H < KH or W < KW gives TC_ERR_SHAPE.  Arithmetic: fp64,
+ * one rounding per output.
+ */
+tc_status tc_sconv2d(const float *I, const float *Wt, const float *bias,
+                     float *O, int64_t N, int64_t C, int64_t F, int64_t H,
+                     int64_t W, int64_t KH, int64_t KW, int64_t sh, int64_t sw,
+                     void *hip_stream);
+
+/*
+ * Output extents of tc_sconv2d by range inference (Section 3.1): h takes every
+ * value for which sh*h + kh is a row of I for all kh < KH, i.e. sh*h <= H-KH.
+ * Host only; touches no GPU.  OH, OW: host pointers.
+ */
+tc_status tc_sconv2d_infer(int64_t H, int64_t W, int64_t KH, int64_t KW,
+                           int64_t sh, int64_t sw, int64_t *OH, int64_t *OW);
+
+/*
+ * Lookup-table sums, n_tables of them in one launch (Section 7, production
+ * model; appendix listing 2LUT, which is n_tables = 2; its single-table form
+ * 1LUT is n_tables = 1).  For every table t:
+ *     O_t(i,j) +=! LUT_t(Idx_t(i,k), j)        i < B, j < D, k < L[t]
+ *   LUT   HOST array of n_tables device pointers, LUT[t]: [E[t], D] fp32
+ *   Idx   HOST array of n_tables device pointers, Idx[t]: [B, L[t]] int32
+ *   O     HOST array of n_tables device pointers, O[t]: [B, D] fp32
+ *   E, L  HOST arrays of n_tables extents; D and B are common to all tables
+ * 1 <= n_tables <= 8; E[t] <= 2^31.  The host arrays are read before the call
+ * returns.  An index that occurs several times in a row of Idx counts as
+ * often.  The comprehension gives no meaning to an index outside [0, E[t]):
+ * the kernel reads nothing for it and writes NaN to the whole output row i of
+ * that table (indices live on the device, so the host cannot reject them).
+ * Arithmetic: the gathered values are summed in fp64 and rounded to fp32 once.
+ */
+tc_status tc_lut(int32_t n_tables, const float *const *LUT,
+                 const int32_t *const *Idx, float *const *O, const int64_t *E,
+                 const int64_t *L, int64_t D, int64_t B, void *hip_stream);
 
 #ifdef __cplusplus
 }

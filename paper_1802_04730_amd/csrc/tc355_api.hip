@@ -1,5 +1,5 @@
 // Host side of libtc355: argument validation, kernel selection and launches
-// for the four entry points declared in include/tc355.h.
+// for the entry points declared in include/tc355.h.
 #include "../../include/tc355.h"
 
 #include <hip/hip_runtime.h>
@@ -22,7 +22,9 @@
 #include "gemm_wave.hpp"
 #include "kron_lds.hpp"
 #include "kron_wave.hpp"
+#include "lut_sum.hpp"
 #include "mlp_fused.hpp"
+#include "sconv_tile.hpp"
 
 using namespace tc355;
 
@@ -515,6 +517,93 @@ tc_status tc_kron(const float* W1, const float* W2, const float* X, float* Y, in
   const int64_t grid = ceil_div(a.jobs, WAVES_PER_WG);
   if (grid > kMaxGrid) return TC_ERR_UNSUPPORTED;
   kron_wave_kernel<TJ><<<dim3((unsigned)grid), dim3(WG_THREADS), 0, s>>>(a);
+  return launch_status();
+}
+
+tc_status tc_sconv2d_infer(int64_t H, int64_t W, int64_t KH, int64_t KW, int64_t sh, int64_t sw, int64_t* OH,
+                           int64_t* OW) {
+  if (!OH || !OW) return TC_ERR_NULL;
+  if (H <= 0 || W <= 0 || KH <= 0 || KW <= 0 || sh <= 0 || sw <= 0) return TC_ERR_SHAPE;
+  if (H < KH || W < KW) return TC_ERR_SHAPE;
+  *OH = (H - KH) / sh + 1;
+  *OW = (W - KW) / sw + 1;
+  return TC_OK;
+}
+
+tc_status tc_sconv2d(const float* I, const float* Wt, const float* bias, float* O, int64_t N, int64_t C, int64_t F,
+                     int64_t H, int64_t W, int64_t KH, int64_t KW, int64_t sh, int64_t sw, void* hip_stream) {
+  if (!I || !Wt || !O) return TC_ERR_NULL;
+  if (N < 0 || C <= 0 || F <= 0) return TC_ERR_SHAPE;
+  int64_t OH, OW;
+  const tc_status inf = tc_sconv2d_infer(H, W, KH, KW, sh, sw, &OH, &OW);
+  if (inf != TC_OK) return inf;
+  if (O == I || O == Wt || (bias && O == bias)) return TC_ERR_ALIAS;
+  if (misaligned(I) || misaligned(Wt) || misaligned(O) || (bias && misaligned(bias))) return TC_ERR_ALIGN;
+  const int64_t K = C * KH * KW;
+  if (C * H * W >= kMaxElems || N * C * H * W >= kMaxElems || K >= kMaxElems || F * K >= kMaxElems ||
+      N * OH * OW >= kMaxElems || F * OH * OW >= kMaxElems || sh >= kMaxElems || sw >= kMaxElems)
+    return TC_ERR_UNSUPPORTED;
+  if (N == 0) return TC_OK;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+  SconvArgs a{};
+  a.I = I; a.Wt = Wt; a.bias = bias; a.O = O;
+  a.N = (int)N; a.C = (int)C; a.F = (int)F; a.H = (int)H; a.W = (int)W; a.KH = (int)KH; a.KW = (int)KW;
+  a.sh = (int)sh; a.sw = (int)sw; a.OH = (int)OH; a.OW = (int)OW;
+  a.K = (int)K; a.P = (int)(N * OH * OW);
+  a.tiles_f = (int)ceil_div(F, SC_BF);
+  const int64_t grid = (int64_t)a.tiles_f * ceil_div(a.P, SC_BP);
+  if (grid > kMaxGrid) return TC_ERR_UNSUPPORTED;
+  static std::atomic<int> lds_ok{0};  // the kernels stage more than the default 64 KiB of LDS
+  if (!lds_ok.load(std::memory_order_acquire)) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(sconv_tile_kernel<4>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, SC_LDS_BYTES) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void*>(sconv_tile_kernel<1>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, SC_LDS_BYTES) != hipSuccess)
+      return TC_ERR_LAUNCH;
+    lds_ok.store(1, std::memory_order_release);
+  }
+  const dim3 gd((unsigned)grid), bd(WG_THREADS);
+  if (K % 4 == 0) sconv_tile_kernel<4><<<gd, bd, SC_LDS_BYTES, s>>>(a);
+  else sconv_tile_kernel<1><<<gd, bd, SC_LDS_BYTES, s>>>(a);
+  return launch_status();
+}
+
+tc_status tc_lut(int32_t n_tables, const float* const* LUT, const int32_t* const* Idx, float* const* O,
+                 const int64_t* E, const int64_t* L, int64_t D, int64_t B, void* hip_stream) {
+  if (!LUT || !Idx || !O || !E || !L) return TC_ERR_NULL;
+  if (n_tables <= 0 || n_tables > LUT_MAX_TABLES || D <= 0 || B < 0) return TC_ERR_SHAPE;
+  for (int t = 0; t < n_tables; t++) {
+    if (!LUT[t] || !Idx[t] || !O[t]) return TC_ERR_NULL;
+    if (E[t] <= 0 || L[t] <= 0) return TC_ERR_SHAPE;
+  }
+  for (int t = 0; t < n_tables; t++) {
+    if (misaligned(LUT[t]) || misaligned(Idx[t]) || misaligned(O[t])) return TC_ERR_ALIGN;
+    for (int m = 0; m < n_tables; m++) {
+      if (static_cast<const void*>(O[t]) == LUT[m] || static_cast<const void*>(O[t]) == Idx[m]) return TC_ERR_ALIAS;
+      if (m != t && O[t] == O[m]) return TC_ERR_ALIAS;
+    }
+    if (L[t] >= kMaxElems || B * L[t] >= kMaxElems || E[t] > (int64_t)INT32_MAX + 1) return TC_ERR_UNSUPPORTED;
+  }
+  if (D >= kMaxElems || B * D >= kMaxElems) return TC_ERR_UNSUPPORTED;
+  if (B == 0) return TC_OK;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+  LutArgs a{};
+  for (int t = 0; t < n_tables; t++) {
+    a.LUT[t] = LUT[t]; a.Idx[t] = Idx[t]; a.O[t] = O[t]; a.E[t] = E[t]; a.L[t] = (int)L[t];
+  }
+  a.D = (int)D; a.B = (int)B;
+  const int v = (D % 4 == 0) ? 4 : 1;
+  const int64_t units = D / v;
+  int cpw = 1;
+  while (cpw < units && cpw < WG_THREADS) cpw *= 2;
+  a.cpw = cpw;
+  a.blocks = (int)ceil_div(units, cpw);
+  const int64_t grid = (int64_t)n_tables * B * a.blocks;
+  if (grid > kMaxGrid) return TC_ERR_UNSUPPORTED;
+  if (v == 4) lut_sum_kernel<4><<<dim3((unsigned)grid), dim3(WG_THREADS), 0, s>>>(a);
+  else lut_sum_kernel<1><<<dim3((unsigned)grid), dim3(WG_THREADS), 0, s>>>(a);
   return launch_status();
 }
 

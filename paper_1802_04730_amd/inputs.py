@@ -97,6 +97,11 @@ def make_lut(E, D, B, L, seed=SEED_BASE + 7):
     return LUT, Idx
 
 
+def make_lut_indices(E, B, L, seed):
+    """Idx [B,L] int32 alone, uniform over [0,E) (a second table's lookups without a second table draw)."""
+    return _rng(seed).integers(0, E, size=(B, L), dtype=np.int32)
+
+
 def make_config(c):
     """Inputs of benchmark configuration c (1..5) with its default seed."""
     cfg = dict(CONFIGS[c])

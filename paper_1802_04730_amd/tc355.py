@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "TC_OK", 1: "TC_ERR_NULL", 2: "TC_ERR_SHAPE", 3: "TC_ERR_ALIA
                 5: "TC_ERR_WORKSPACE", 6: "TC_ERR_LAUNCH", 7: "TC_ERR_UNSUPPORTED"}
 
 EXPORTS = ["tc_status_string", "tc355_version", "tc_tbmm", "tc_mlp_fcrelu", "tc_mlp_fcrelu_workspace_bytes",
-           "tc_group_conv", "tc_group_conv_infer", "tc_kron"]
+           "tc_group_conv", "tc_group_conv_infer", "tc_kron", "tc_sconv2d", "tc_sconv2d_infer", "tc_lut"]
 
 
 class TcError(RuntimeError):
@@ -58,6 +58,13 @@ def lib() -> ctypes.CDLL:
     L.tc_group_conv_infer.restype = ctypes.c_int
     L.tc_kron.argtypes = [vp, vp, vp, vp] + [i64] * 5 + [vp]
     L.tc_kron.restype = ctypes.c_int
+    L.tc_sconv2d.argtypes = [vp, vp, vp, vp] + [i64] * 9 + [vp]
+    L.tc_sconv2d.restype = ctypes.c_int
+    L.tc_sconv2d_infer.argtypes = [i64] * 6 + [ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    L.tc_sconv2d_infer.restype = ctypes.c_int
+    L.tc_lut.argtypes = [i32, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(i64),
+                         ctypes.POINTER(i64), i64, i64, vp]
+    L.tc_lut.restype = ctypes.c_int
     _LIB = L
     return L
 
@@ -165,3 +172,43 @@ def tc_kron(W1, W2, X, Y, stream=None) -> None:
         raise ValueError("tc_kron: shapes do not fit")
     _check(lib().tc_kron(_ptr(W1, "W1"), _ptr(W2, "W2"), _ptr(X, "X"), _ptr(Y, "Y"), B, I, K, J, L,
                          _stream(stream)), "tc_kron")
+
+
+def tc_sconv2d_infer(H: int, W: int, KH: int, KW: int, sh: int, sw: int):
+    oh, ow = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().tc_sconv2d_infer(H, W, KH, KW, sh, sw, ctypes.byref(oh), ctypes.byref(ow)), "tc_sconv2d_infer")
+    return int(oh.value), int(ow.value)
+
+
+def tc_sconv2d(I, Wt, bias, O, sh: int, sw: int, stream=None) -> None:
+    """O[N,F,OH,OW] = bias[F] + convolution of I[N,C,H,W] with Wt[F,C,KH,KW], strides (sh, sw), no padding."""
+    N, C, H, W = I.shape
+    F, C2, KH, KW = Wt.shape
+    if C != C2:
+        raise ValueError("tc_sconv2d: I and Wt disagree on C")
+    if bias is not None and tuple(bias.shape) != (F,):
+        raise ValueError("tc_sconv2d: bias must be [F]")
+    if tuple(O.shape) != (N, F) + tc_sconv2d_infer(H, W, KH, KW, sh, sw):
+        raise ValueError("tc_sconv2d: O has the wrong shape")
+    _check(lib().tc_sconv2d(_ptr(I, "I"), _ptr(Wt, "Wt"), _ptr(bias, "bias"), _ptr(O, "O"),
+                            N, C, F, H, W, KH, KW, sh, sw, _stream(stream)), "tc_sconv2d")
+
+
+def tc_lut(LUT, Idx, O, stream=None) -> None:
+    """O[t][B,D] = sum_k LUT[t][Idx[t][B,k], :] for every table t; LUT, Idx, O are lists of equal length."""
+    n = len(LUT)
+    if n == 0 or len(Idx) != n or len(O) != n:
+        raise ValueError("tc_lut: LUT, Idx and O must be lists of the same, non-zero length")
+    B, D = O[0].shape
+    for t in range(n):
+        if Idx[t].dtype != torch.int32 or not Idx[t].is_cuda or not Idx[t].is_contiguous():
+            raise TypeError("tc_lut: Idx[%d] must be a contiguous int32 CUDA tensor" % t)
+        if LUT[t].shape[1] != D or Idx[t].shape[0] != B or tuple(O[t].shape) != (B, D):
+            raise ValueError("tc_lut: table %d shapes do not fit" % t)
+    vp = ctypes.c_void_p
+    Lp = (vp * n)(*[_ptr(x, "LUT[%d]" % t) for t, x in enumerate(LUT)])
+    Ip = (vp * n)(*[x.data_ptr() for x in Idx])
+    Op = (vp * n)(*[_ptr(x, "O[%d]" % t) for t, x in enumerate(O)])
+    Ev = (ctypes.c_int64 * n)(*[int(x.shape[0]) for x in LUT])
+    Lv = (ctypes.c_int64 * n)(*[int(x.shape[1]) for x in Idx])
+    _check(lib().tc_lut(n, Lp, Ip, Op, Ev, Lv, D, B, _stream(stream)), "tc_lut")

@@ -84,6 +84,48 @@ def test_kron_and_gconv_validation(L):
     assert L.tc_group_conv(A, B_, None, C_, 0, 1, 1, 1, 5, 5, 3, 3, None) == 0
 
 
+def test_sconv2d_validation_and_infer(L):
+    oh, ow = ctypes.c_int64(), ctypes.c_int64()
+    assert L.tc_sconv2d_infer(56, 56, 3, 3, 2, 2, ctypes.byref(oh), ctypes.byref(ow)) == 0
+    assert (oh.value, ow.value) == (27, 27)
+    assert L.tc_sconv2d_infer(10, 9, 3, 2, 2, 3, ctypes.byref(oh), ctypes.byref(ow)) == 0
+    assert (oh.value, ow.value) == (4, 3)
+    assert L.tc_sconv2d_infer(3, 3, 3, 3, 5, 5, ctypes.byref(oh), ctypes.byref(ow)) == 0
+    assert (oh.value, ow.value) == (1, 1)
+    assert L.tc_sconv2d_infer(2, 7, 3, 3, 1, 1, ctypes.byref(oh), ctypes.byref(ow)) == 2
+    assert L.tc_sconv2d_infer(7, 7, 3, 3, 0, 1, ctypes.byref(oh), ctypes.byref(ow)) == 2
+    assert L.tc_sconv2d_infer(7, 7, 3, 3, 1, 1, None, ctypes.byref(ow)) == 1
+    assert L.tc_sconv2d(A, B_, None, None, 1, 1, 1, 5, 5, 3, 3, 2, 2, None) == 1
+    assert L.tc_sconv2d(A, B_, None, C_, 1, 1, 1, 2, 5, 3, 3, 2, 2, None) == 2
+    assert L.tc_sconv2d(A, B_, None, C_, 1, 0, 1, 5, 5, 3, 3, 2, 2, None) == 2
+    assert L.tc_sconv2d(A, B_, None, C_, 1, 1, 1, 5, 5, 3, 3, 2, -1, None) == 2
+    assert L.tc_sconv2d(A, B_, C_, C_, 1, 1, 1, 5, 5, 3, 3, 2, 2, None) == 3
+    assert L.tc_sconv2d(A, B_ + 8, None, C_, 1, 1, 1, 5, 5, 3, 3, 2, 2, None) == 4
+    assert L.tc_sconv2d(A, B_, None, C_, 1 << 12, 1 << 10, 1, 1 << 5, 1 << 5, 3, 3, 2, 2, None) == 7
+    assert L.tc_sconv2d(A, B_, None, C_, 0, 1, 1, 5, 5, 3, 3, 2, 2, None) == 0
+
+
+def test_lut_validation(L):
+    i64, vp = ctypes.c_int64, ctypes.c_void_p
+    T = (vp * 2)(0x50000, 0x60000)
+    I = (vp * 2)(0x70000, 0x80000)
+    O = (vp * 2)(0x90000, 0xA0000)
+    E = (i64 * 2)(1000, 2000)
+    Ls = (i64 * 2)(50, 7)
+    assert L.tc_lut(2, T, I, O, E, Ls, 64, 0, None) == 0  # empty batch: nothing to do
+    assert L.tc_lut(2, None, I, O, E, Ls, 64, 4, None) == 1
+    assert L.tc_lut(2, T, (vp * 2)(0x70000, None), O, E, Ls, 64, 4, None) == 1
+    assert L.tc_lut(0, T, I, O, E, Ls, 64, 4, None) == 2
+    assert L.tc_lut(9, T, I, O, E, Ls, 64, 4, None) == 2
+    assert L.tc_lut(2, T, I, O, E, Ls, 0, 4, None) == 2
+    assert L.tc_lut(2, T, I, O, (i64 * 2)(1000, 0), Ls, 64, 4, None) == 2
+    assert L.tc_lut(2, T, I, O, E, (i64 * 2)(50, -1), 64, 4, None) == 2
+    assert L.tc_lut(2, T, I, (vp * 2)(0x90000, 0x50000), E, Ls, 64, 4, None) == 3
+    assert L.tc_lut(2, T, I, (vp * 2)(0x90000, 0x90000), E, Ls, 64, 4, None) == 3
+    assert L.tc_lut(2, T, I, (vp * 2)(0x90000, 0xA0004), E, Ls, 64, 4, None) == 4
+    assert L.tc_lut(2, T, I, O, (i64 * 2)(1000, 1 << 40), Ls, 64, 4, None) == 7
+
+
 def test_mlp_validation(L):
     i64, vp = ctypes.c_int64, ctypes.c_void_p
     dims = (i64 * 3)(8, 6, 4)

@@ -1,0 +1,172 @@
+"""GPU parity of the strided convolution and the lookup-table sums (through the C ABI) against the float64 oracle.
+
+Same bar and same tight bound as the other fp64 kernels: one fp32 rounding of the exact result.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1802_04730_amd import inputs
+from paper_1802_04730_amd.metric import PARITY_BAR, parity_error
+
+pytestmark = pytest.mark.gpu
+
+TIGHT = 2.5e-7
+
+
+@pytest.fixture(scope="module")
+def tc():
+    from paper_1802_04730_amd import tc355
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    tc355.lib()
+    return tc355
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def check(gpu_tensor, ref, what, tight=TIGHT):
+    torch.cuda.synchronize()
+    got = gpu_tensor.cpu().numpy().astype(np.float64)
+    err = parity_error(got, ref)
+    print("%s: parity error %.3e" % (what, err), flush=True)
+    assert err <= PARITY_BAR, "%s: %.3e exceeds the parity bar" % (what, err)
+    assert err <= tight, "%s: %.3e exceeds the error this kernel's arithmetic allows (%.1e)" % (what, err, tight)
+
+
+# ---------------------------------------------------------------- sconv2d
+# (N, C, F, H, W, KH, KW, sh, sw)
+SCONV_SHAPES = [
+    (2, 16, 24, 23, 21, 3, 3, 2, 2),     # reduction 144: four whole chunks and a half; ragged filter and pixel tiles
+    (1, 5, 7, 19, 30, 4, 2, 3, 2),       # reduction 40: one whole chunk and a ragged one of 8 taps
+    (3, 3, 70, 12, 13, 3, 3, 1, 1),      # reduction 27: scalar filter loads; two filter tiles, the second ragged
+    (2, 8, 8, 15, 15, 1, 1, 2, 2),       # 1 x 1 filter: pure subsampling plus channel mixing, one short chunk
+    (1, 3, 4, 12, 12, 7, 7, 2, 2),       # 7 x 7 stride 2 (the first layer of residual networks), reduction 147
+    (1, 1, 1, 3, 3, 3, 3, 5, 5),         # a single output element
+    (4, 64, 128, 20, 20, 3, 3, 2, 2),    # many chunks (reduction 576), 64 x 64 blocks all full in the filter dimension
+    (2, 6, 10, 9, 40, 2, 5, 1, 4),       # wide stride along w only
+]
+
+
+@pytest.mark.parametrize("shape", SCONV_SHAPES)
+def test_sconv2d(tc, shape, oracle_threads):
+    N, C, F, H, W, KH, KW, sh, sw = shape
+    I, Wt, bias = inputs.make_sconv2d(N, C, F, H, W, KH, KW)
+    ref = oracle.sconv2d(I, Wt, bias, sh, sw)
+    O = torch.full(ref.shape, float("nan"), device="cuda")
+    tc.tc_sconv2d(dev(I), dev(Wt), dev(bias), O, sh, sw)
+    check(O, ref, "sconv2d %s" % (shape,))
+
+
+def test_sconv2d_without_bias_and_unit_strides_match_group_conv(tc, oracle_threads):
+    I, Wt, _ = inputs.make_sconv2d(2, 16, 16, 18, 20, 3, 3)
+    ref = oracle.sconv2d(I, Wt, None, 1, 1)
+    O = torch.full(ref.shape, float("nan"), device="cuda")
+    tc.tc_sconv2d(dev(I), dev(Wt), None, O, 1, 1)
+    check(O, ref, "sconv2d no bias, unit strides")
+    O2 = torch.full((2, 1, 16, 16, 18), float("nan"), device="cuda")
+    tc.tc_group_conv(dev(I[:, None]), dev(Wt[None]), None, O2)
+    torch.cuda.synchronize()
+    assert torch.equal(O2[:, 0], O)  # both round the exact fp64 sum once
+
+
+def test_sconv2d_resnext_like_full_size_sampled(tc, oracle_threads):
+    # a down-sampling layer of the size class the paper's grouped convolutions come from: 64 -> 128 channels,
+    # 56 x 56 -> 27 x 27, batch 32; the oracle evaluates two images
+    N, C, F, H, W = 32, 64, 128, 56, 56
+    I, Wt, bias = inputs.make_sconv2d(N, C, F, H, W, 3, 3)
+    O = torch.full((N, F, 27, 27), float("nan"), device="cuda")
+    tc.tc_sconv2d(dev(I), dev(Wt), dev(bias), O, 2, 2)
+    torch.cuda.synchronize()
+    assert not torch.isnan(O).any()
+    for n in (0, 31):
+        check(O[n:n + 1], oracle.sconv2d(I[n:n + 1], Wt, bias, 2, 2), "sconv2d full size, image %d" % n)
+
+
+def test_sconv2d_stays_inside_its_output(tc, oracle_threads):
+    N, C, F, H, W = 3, 5, 9, 11, 13
+    I, Wt, bias = inputs.make_sconv2d(N, C, F, H, W, 3, 3)
+    ref = oracle.sconv2d(I, Wt, bias, 2, 3)
+    n = ref.size
+    buf = torch.full((n + 512,), 7.0, device="cuda")
+    O = buf[256:256 + n].view(ref.shape)
+    tc.tc_sconv2d(dev(I), dev(Wt), dev(bias), O, 2, 3)
+    check(O, ref, "sconv2d guard band")
+    assert torch.all(buf[:256] == 7.0) and torch.all(buf[256 + n:] == 7.0)
+
+
+# ---------------------------------------------------------------- lookup tables
+# (E, D, B, L)
+LUT_SHAPES = [
+    (1000, 64, 128, 50),     # the paper's D, B, L on a small table: many repeated rows
+    (5000, 64, 3, 1),        # one lookup per row: a gather
+    (777, 20, 9, 13),        # D = 20: five 16-byte units, slots beyond the lookups
+    (300, 7, 11, 70),        # D not a multiple of 4: scalar loads; more lookups than one round holds
+    (50, 1, 5, 3),           # a single column
+    (4000, 1100, 4, 9),      # D beyond one block of 256 units: two column blocks per row
+    (100000, 256, 17, 129),  # several rounds per thread
+]
+
+
+@pytest.mark.parametrize("shape", LUT_SHAPES)
+def test_lut_one_table(tc, shape, oracle_threads):
+    E, D, B, L = shape
+    LUT, Idx = inputs.make_lut(E, D, B, L)
+    ref = oracle.lut(LUT, Idx)
+    O = torch.full((B, D), float("nan"), device="cuda")
+    tc.tc_lut([dev(LUT)], [dev(Idx)], [O])
+    check(O, ref, "lut %s" % (shape,))
+
+
+def test_lut_two_tables_one_launch(tc, oracle_threads):
+    # listing 2LUT: two tables of different heights and lookup counts, one output width and batch
+    LUT1, Idx1 = inputs.make_lut(30000, 64, 128, 50, seed=inputs.SEED_BASE + 7)
+    LUT2, Idx2 = inputs.make_lut(1234, 64, 128, 31, seed=inputs.SEED_BASE + 8)
+    O1 = torch.full((128, 64), float("nan"), device="cuda")
+    O2 = torch.full((128, 64), float("nan"), device="cuda")
+    tc.tc_lut([dev(LUT1), dev(LUT2)], [dev(Idx1), dev(Idx2)], [O1, O2])
+    check(O1, oracle.lut(LUT1, Idx1), "2LUT first table")
+    check(O2, oracle.lut(LUT2, Idx2), "2LUT second table")
+
+
+def test_lut_paper_size(tc, oracle_threads):
+    # (E, D, L) = (10^7, 64, 50), B = 128 (Section 7, production models): a 2.56 GB table.  The second table is the
+    # negated first one (a second 2.56 GB draw would only cost host time); its indices are drawn separately.
+    E, D, B, L = 10**7, 64, 128, 50
+    LUT, Idx1 = inputs.make_lut(E, D, B, L)
+    Idx2 = inputs.make_lut_indices(E, B, L, seed=inputs.SEED_BASE + 8)
+    T1 = dev(LUT)
+    T2 = -T1
+    O1 = torch.full((B, D), float("nan"), device="cuda")
+    O2 = torch.full((B, D), float("nan"), device="cuda")
+    tc.tc_lut([T1, T2], [dev(Idx1), dev(Idx2)], [O1, O2])
+    check(O1, oracle.lut(LUT, Idx1), "2LUT paper size, first table")
+    check(O2, -oracle.lut(LUT, Idx2), "2LUT paper size, second table")
+
+
+def test_lut_index_outside_the_table_gives_nan_rows_only(tc, oracle_threads):
+    E, D, B, L = 500, 64, 6, 10
+    LUT, Idx = inputs.make_lut(E, D, B, L)
+    ref = oracle.lut(LUT, Idx)
+    bad = Idx.copy()
+    bad[1, 3] = E          # one past the end
+    bad[4, 0] = -1
+    O = torch.full((B, D), 3.0, device="cuda")
+    tc.tc_lut([dev(LUT)], [dev(bad)], [O])
+    torch.cuda.synchronize()
+    got = O.cpu().numpy()
+    assert np.all(np.isnan(got[[1, 4]]))
+    keep = [0, 2, 3, 5]
+    assert parity_error(got[keep].astype(np.float64), ref[keep]) <= TIGHT
+
+
+def test_lut_stays_inside_its_output(tc, oracle_threads):
+    E, D, B, L = 300, 12, 7, 5
+    LUT, Idx = inputs.make_lut(E, D, B, L)
+    buf = torch.full((B * D + 512,), 7.0, device="cuda")
+    O = buf[256:256 + B * D].view(B, D)
+    tc.tc_lut([dev(LUT)], [dev(Idx)], [O])
+    check(O, oracle.lut(LUT, Idx), "lut guard band")
+    assert torch.all(buf[:256] == 7.0) and torch.all(buf[256 + B * D:] == 7.0)
