@@ -226,7 +226,38 @@ def main():
         extra["gconv_32x32x%dx%dx%dx%d" % (F_, C_, HW, HW)] = entry(
             timed(lambda: tc355.tc_group_conv(It, Wt, bt, Ot)), inputs.flops_gconv(32, 32, C_, F_, HW, HW, 3, 3),
             4 * (It.numel() + Wt.numel() + bt.numel() + Ot.numel()))
-    del Xt, Yt, Zt, Im, Wm, bm, Om, It, Wt, bt, Ot
+    # strided convolution (Section 3, listing sconv2d; the paper states no size: a ResNeXt-like down-sampling layer)
+    Is_ = torch.randn((32, 64, 56, 56), device="cuda")
+    Ws_ = torch.randn((128, 64, 3, 3), device="cuda") * 0.05
+    bs_ = torch.randn((128,), device="cuda") * 0.05
+    Os_ = torch.empty((32, 128, 27, 27), device="cuda")
+    extra["sconv2d_32x64x128x56x56_3x3_s2"] = entry(timed(lambda: tc355.tc_sconv2d(Is_, Ws_, bs_, Os_, 2, 2)),
+                                                    inputs.flops_sconv2d(32, 64, 128, 56, 56, 3, 3, 2, 2),
+                                                    inputs.bytes_sconv2d(32, 64, 128, 56, 56, 3, 3, 2, 2))
+    # lookup-table sums at the paper's size (Section 7, production models: (E,D,L) = (10^7,64,50), batch 128);
+    # fresh random indices every call, so that no gathered row is still in a cache from the call before
+    E_, D_, B_, L_ = 10**7, 64, 128, 50
+    T1 = torch.randn((E_, D_), device="cuda")
+    T2 = torch.randn((E_, D_), device="cuda")
+    idx = [torch.randint(0, E_, (B_, L_), device="cuda", dtype=torch.int32) for _ in range(46)]
+    O1, O2 = torch.empty((B_, D_), device="cuda"), torch.empty((B_, D_), device="cuda")
+    turn = [0]
+
+    def lut_call(n_tables):
+        turn[0] = (turn[0] + 1) % 23
+        a, b = idx[turn[0]], idx[23 + turn[0]]
+        if n_tables == 1:
+            tc355.tc_lut([T1], [a], [O1])
+        else:
+            tc355.tc_lut([T1, T2], [a, b], [O1, O2])
+
+    for n_tables in (1, 2):
+        us = timed(lambda: lut_call(n_tables))
+        nbytes = n_tables * inputs.bytes_lut(E_, D_, B_, L_)
+        extra["%dlut_1e7x64_l50_b128" % n_tables] = {
+            "us": round(us, 2), "gbs": round(nbytes / us * 1e-3, 1), "bound": "hbm",
+            "frac": round(nbytes / (PEAK_HBM_GBS * 1e9) * 1e6 / us, 4)}
+    del Xt, Yt, Zt, Im, Wm, bm, Om, It, Wt, bt, Ot, Is_, Ws_, bs_, Os_, T1, T2, idx, O1, O2
 
     # the grouped convolution on the fp64 matrix path (what every other shape of the operator takes), for comparison
     os.environ["TC355_GCONV_ARITH"] = "f64"
