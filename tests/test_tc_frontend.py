@@ -1,0 +1,309 @@
+"""The TC front-end (parser, range inference in rounds, float64 evaluation) against what the paper fixes, and the
+hand-written oracle loop nests against the front-end's evaluation of the same comprehensions from their text.
+
+The comprehension texts below restate the paper's listings (Section 3, Section 7, appendix) with the argument
+shapes made consistent where the printed ones are not.
+"""
+import ctypes
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import tc_frontend as fe
+from paper_1802_04730_amd import inputs
+
+MV = """
+def mv(float(M,K) A, float(K) x) -> (C) {
+  C(i)  = 0
+  C(i) += A(i,k) * x(k)
+}"""
+MV_INIT = """
+def mv(float(M,K) A, float(K) x) -> (C) {
+  C(i) +=! A(i,k) * x(k)
+}"""
+CONV1D = """
+def conv1d(float(M) I, float(N) K) -> (O) {
+  O(i) +=! K(x) * I(i + x)
+}"""
+CONV2D = """
+def conv2d(float(B,IP,H,W) in, float(OP,IP,KH,KW) weight) -> (out) {
+  out(b,op,h,w) +=! in(b,ip, h + kh, w + kw) * weight(op,ip,kh,kw)
+}"""
+MAXPOOL = """
+def maxpool2x2(float(B,C,H,W) in) -> (out) {
+  out(b,c,i,j) max=! in(b,c, 2 * i + kw, 2 * j + kh)
+    where kw in 0:2, kh in 0:2
+}"""
+GATHER = """
+def gather(float(N) X, int(A,B) I) -> (Z) {
+  Z(i,j) = X(I(i,j))
+}"""
+TBMM = """
+def tbmm(float(B,N,K) X, float(B,M,K) Y) -> (Z) {
+  Z(b,n,m) +=! X(b,n,k) * Y(b,m,k)
+}"""
+MLP3 = """
+def MLP3(float(B,M) I, float(N,M) W1, float(N) B1, float(O,N) W2, float(O) B2, float(P,O) W3, float(P) B3)
+    -> (O1, O2, O3) {
+  O1(b,n)  = B1(n)
+  O1(b,n) += I(b,m) * W1(n,m)
+  O1(b,n)  = fmaxf(O1(b,n), 0)
+  O2(b,o)  = B2(o)
+  O2(b,o) += O1(b,n) * W2(o,n)
+  O2(b,o)  = fmaxf(O2(b,o), 0)
+  O3(b,p)  = B3(p)
+  O3(b,p) += O2(b,o) * W3(p,o)
+  O3(b,p)  = fmaxf(O3(b,p), 0)
+}"""
+GCONV = """
+def gconv(float(N,G,C,H,W) I, float(G,F,C,KH,KW) W1, float(M) B) -> (O) {
+  O(n,g,o,h,w) +=! I(n,g,i, h + kh, w + kw) * W1(g,o,i,kh,kw)
+  O(n,g,o,h,w)  = O(n,g,o,h,w) + B(g * F + o)
+}"""
+KRON = """
+def kron(float(I,K) W1, float(J,L) W2, float(B,K,L) X) -> (Y) {
+  Y(b,i,j) +=! W1(i,k) * W2(j,l) * X(b,k,l)
+}"""
+SCONV2D = """
+def sconv2d(int sh, int sw, float(N,C,H,W) I, float(F,C,KH,KW) W, float(F) B) -> (O) {
+  O(n,f,h,w)  = B(f)
+  O(n,f,h,w) += I(n,c, sh * h + kh, sw * w + kw) * W(f,c,kh,kw)
+}"""
+LUT2 = """
+def 2LUT(float(E1,D) LUT1, int(B,L1) I1, float(E2,D) LUT2, int(B,L2) I2) -> (O1, O2) {
+  O1(i,j) +=! LUT1(I1(i,k),j)
+  O2(i,j) +=! LUT2(I2(i,k),j)
+}"""
+
+
+# ---------------------------------------------------------------------------------------------- parsing
+def test_parse_structure_of_a_function():
+    f = fe.parse(LUT2)
+    assert f.name == "2LUT"  # identifiers may start with digits (appendix, grammar of core TC)
+    assert [(a.name, a.scalar_type, a.shape) for a in f.args] == [
+        ("LUT1", "float", ["E1", "D"]), ("I1", "int", ["B", "L1"]), ("LUT2", "float", ["E2", "D"]),
+        ("I2", "int", ["B", "L2"])]
+    assert f.returns == ["O1", "O2"]
+    assert [(s.lhs, s.lhs_idx, s.op) for s in f.stmts] == [("O1", ["i", "j"], "+=!"), ("O2", ["i", "j"], "+=!")]
+    inner = f.stmts[0].rhs
+    assert isinstance(inner, fe.Call) and inner.name == "LUT1" and isinstance(inner.args[0], fe.Call)
+
+
+def test_parse_operators_numbers_and_where():
+    f = fe.parse("""
+    def t(float a, float(N) X) -> (Y, Z) {   # a comment
+      Y(i) = -X(i) * 2.5e-1f + (X(i) > 0 ? a : 1) / 4 - 0x10 % 3
+      Z(i) min=! X(i + k) where k in 0:3
+    }""")
+    assert [s.op for s in f.stmts] == ["=", "min=!"]
+    assert set(f.stmts[1].where) == {"k"}
+    nums = [n.value for n in fe._walk(f.stmts[0].rhs) if isinstance(n, fe.Num)]
+    assert nums == [0.25, 0, 1, 4, 16, 3]
+    X = np.array([1.0, -2.0, 3.0, 0.5, -1.0], np.float32)
+    got = fe.run(f, {"X": X}, {"a": 8.0})
+    want_y = -X.astype(np.float64) * 0.25 + np.where(X > 0, 8.0, 1.0) / 4 - 1
+    assert np.array_equal(got["Y"], want_y)
+    assert np.array_equal(got["Z"], [-2.0, -2.0, -1.0])
+
+
+@pytest.mark.parametrize("text", [
+    "def f(float(N) X) -> (Y) { Y(i) = X(i) ",          # missing brace
+    "def f(floaty(N) X) -> (Y) { Y(i) = X(i) }",        # unknown scalar type
+    "def f(float(N) X) -> (Y) { Y(i) := X(i) }",        # not an assignment operator
+    "def f(float(N) X) -> (Y) { Y(i+1) = X(i) }",       # the left-hand side lists plain indices
+    "fun f(float(N) X) -> (Y) { Y(i) = X(i) }",
+])
+def test_syntax_errors(text):
+    with pytest.raises(fe.TcError):
+        fe.parse(text)
+
+
+# ---------------------------------------------------------------------------------------------- range inference
+def test_matrix_vector_ranges():
+    # Section 3: i = [0,M), k = [0,K)
+    plan = fe.infer(fe.parse(MV_INIT), {"A": (5, 7), "x": (7,)})
+    assert plan.ranges[0] == {"i": (0, 5), "k": (0, 7)} and plan.shapes["C"] == (5,)
+    with pytest.raises(fe.TcError):  # K is one size: the signature makes the two extents equal
+        fe.infer(fe.parse(MV_INIT), {"A": (5, 7), "x": (6,)})
+
+
+def test_conv1d_rounds():
+    # Section 3.1: x is resolved first from K(x) alone, then i from I(i+x) for ALL x: 0..M-N
+    plan = fe.infer(fe.parse(CONV1D), {"I": (10,), "K": (3,)})
+    assert plan.ranges[0] == {"i": (0, 8), "x": (0, 3)}
+
+
+def test_extents_the_paper_states():
+    path = os.path.join(os.path.dirname(__file__), "golden", "range_inference.txt")
+    seen = 0
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        case, n_in, n_f, n_out = line.split('"')[0].split()
+        n_in, n_f, n_out = int(n_in), int(n_f), int(n_out)
+        if case == "conv1d_rule":
+            assert fe.output_shapes(CONV1D, {"I": (n_in,), "K": (n_f,)}) == {"O": (n_out,)}
+        else:
+            got = fe.output_shapes(GCONV, {"I": (2, 3, 4, n_in, n_in), "W1": (3, 5, 4, n_f, n_f), "B": (15,)})
+            assert got == {"O": (2, 3, 5, n_out, n_out)}
+        seen += 1
+    assert seen >= 5
+
+
+def test_max_pooling_needs_its_where_clause():
+    assert fe.output_shapes(MAXPOOL, {"in": (2, 3, 9, 8)}) == {"out": (2, 3, 4, 4)}
+    with pytest.raises(fe.TcError):
+        fe.output_shapes(MAXPOOL.split("where")[0] + "}", {"in": (2, 3, 9, 8)})
+
+
+def test_a_data_dependent_subscript_constrains_nothing_but_its_own_subscripts():
+    assert fe.output_shapes(GATHER, {"X": (100,), "I": (4, 6)}) == {"Z": (4, 6)}
+    assert fe.output_shapes(LUT2, {"LUT1": (50, 8), "I1": (3, 5), "LUT2": (70, 8), "I2": (3, 9)}) == {
+        "O1": (3, 8), "O2": (3, 8)}
+
+
+def test_fcrelu_takes_the_batch_range_from_the_accumulating_statement():
+    plan = fe.infer(fe.parse(MLP3), {"I": (4, 6), "W1": (5, 6), "B1": (5,), "W2": (3, 5), "B2": (3,),
+                                     "W3": (2, 3), "B3": (2,)})
+    assert plan.shapes["O1"] == (4, 5) and plan.shapes["O2"] == (4, 3) and plan.shapes["O3"] == (4, 2)
+    assert plan.ranges[0] == {"b": (0, 4), "n": (0, 5)}
+
+
+def test_intersection_of_constraints_on_one_variable():
+    # k is constrained by both accesses in the same round: the smaller extent wins (Section 3.1, sgemm example)
+    f = fe.parse("def f(float(M,K1) A, float(K2,N) B) -> (C) { C(i,j) +=! A(i,k) * B(k,j) }")
+    assert fe.infer(f, {"A": (3, 7), "B": (5, 4)}).ranges[0]["k"] == (0, 5)
+
+
+def test_transposition_into_another_tensor_and_temporaries():
+    text = "def f(float(N,M) a) -> (b) { t(i,j) = a(j,i)\n b(i,j) = t(i,j) * 2 }"  # t is a temporary, not an output
+    assert fe.output_shapes(text, {"a": (3, 4)}) == {"b": (4, 3)}
+    a = np.arange(12, dtype=np.float32).reshape(3, 4)
+    assert np.array_equal(fe.evaluate(text, {"a": a})["b"], 2.0 * a.T)
+
+
+@pytest.mark.parametrize("text,shapes", [
+    ("def f(float(N,N) X) -> (a) { a(i,j) = X(i,j)\n a(i,j) = a(j,i) }", {"X": (3, 3)}),   # in-place transposition
+    ("def f(float(N) X) -> (Y) { Y(i) = X(i + k) }", {"X": (5,)}),                          # k is under-constrained
+    ("def f(float(N) X, float(N) K) -> (Y) { Y(i) = K(x) * X(i + x) }", {"X": (5,), "K": (5,)}),  # '=' with a reduction index
+    ("def f(float(N) X) -> (Y) { Y(i) = X(i - 1) }", {"X": (5,)}),                          # 0 is not admissible for i
+    ("def f(float(N) X) -> (Y) { Z(i) = X(i) }", {"X": (5,)}),                              # Y is never defined
+    ("def f(float(N) X) -> (Y) { Y(i,i) = X(i) }", {"X": (5,)}),
+    ("def f(float(N) X) -> (Y) { X(i) = 1 \n Y(i) = X(i) }", {"X": (5,)}),                  # an input is assigned
+])
+def test_rejected_functions(text, shapes):
+    with pytest.raises(fe.TcError):
+        fe.output_shapes(text, shapes)
+
+
+def test_strided_convolution_extents_by_three_routes():
+    # the front-end's inference, the oracle's closed form and the library's host function agree
+    from paper_1802_04730_amd import tc355
+    L = tc355.lib()
+    oh, ow = ctypes.c_int64(), ctypes.c_int64()
+    for H, KH, sh in itertools.product((1, 2, 5, 9, 14, 23), (1, 2, 3, 7), (1, 2, 3, 4)):
+        W, KW, sw = H + 3, max(1, KH - 1), (sh % 3) + 1
+        if H < KH:
+            assert L.tc_sconv2d_infer(H, W, KH, KW, sh, sw, ctypes.byref(oh), ctypes.byref(ow)) == 2
+            continue
+        got = fe.output_shapes(SCONV2D, {"I": (2, 3, H, W), "W": (4, 3, KH, KW), "B": (4,)}, {"sh": sh, "sw": sw})["O"]
+        assert got[:2] == (2, 4)
+        assert got[2:] == oracle.sconv2d_infer(H, W, KH, KW, sh, sw)
+        assert L.tc_sconv2d_infer(H, W, KH, KW, sh, sw, ctypes.byref(oh), ctypes.byref(ow)) == 0
+        assert got[2:] == (oh.value, ow.value)
+        if sh == 1 and sw == 1:
+            assert L.tc_group_conv_infer(H, W, KH, KW, ctypes.byref(oh), ctypes.byref(ow)) == 0
+            assert got[2:] == (oh.value, ow.value) == oracle.group_conv_infer(H, W, KH, KW)
+
+
+# ---------------------------------------------------------------------------------------------- evaluation
+def test_mv_both_spellings_and_numpy():
+    r = np.random.default_rng(0)
+    A, x = r.standard_normal((6, 9)).astype(np.float32), r.standard_normal(9).astype(np.float32)
+    want = A.astype(np.float64) @ x.astype(np.float64)
+    a, b = fe.evaluate(MV, {"A": A, "x": x})["C"], fe.evaluate(MV_INIT, {"A": A, "x": x})["C"]
+    np.testing.assert_allclose(a, want, rtol=1e-14, atol=1e-15)
+    assert np.array_equal(a, b)
+
+
+def test_reductions_other_than_sum():
+    r = np.random.default_rng(1)
+    X = r.standard_normal((2, 3, 9, 8)).astype(np.float32)
+    got = fe.evaluate(MAXPOOL, {"in": X})["out"]
+    want = X[:, :, :8, :8].reshape(2, 3, 4, 2, 4, 2).max(axis=(3, 5)).astype(np.float64)
+    assert np.array_equal(got, want)
+    prod = fe.evaluate("def p(float(N,M) X) -> (Y) { Y(i) *=! X(i,j) }", {"X": X[0, 0]})["Y"]
+    np.testing.assert_allclose(prod, np.prod(X[0, 0].astype(np.float64), axis=1), rtol=1e-14)
+
+
+def test_accumulating_onto_nothing_is_rejected_and_gather_checks_bounds():
+    with pytest.raises(fe.TcError):
+        fe.evaluate("def f(float(N,M) X) -> (Y) { Y(i) += X(i,j) }", {"X": np.ones((2, 3), np.float32)})
+    X = np.arange(10, dtype=np.float32)
+    I = np.array([[0, 9], [3, 3]], np.int32)
+    assert np.array_equal(fe.evaluate(GATHER, {"X": X, "I": I})["Z"], [[0.0, 9.0], [3.0, 3.0]])
+    with pytest.raises(fe.TcError):
+        fe.evaluate(GATHER, {"X": X, "I": np.array([[0, 10]], np.int32)})
+    with pytest.raises(fe.TcError):
+        fe.evaluate(GATHER, {"X": X, "I": np.array([[-1, 2]], np.int32)})
+    with pytest.raises(fe.TcError):
+        fe.evaluate(GATHER, {"X": X, "I": np.array([[1.0, 2.0]], np.float32)})
+
+
+def test_large_iteration_spaces_are_evaluated_in_slabs(monkeypatch):
+    X, Y = inputs.make_tbmm(3, 7, 5, 6, seed=4)
+    whole = fe.evaluate(TBMM, {"X": X, "Y": Y})["Z"]
+    monkeypatch.setattr(fe, "_SLAB_ELEMS", 64)
+    assert np.array_equal(fe.evaluate(TBMM, {"X": X, "Y": Y})["Z"], whole)
+
+
+# ------------------------------------------------------- the library's comprehensions: text vs hand-written loop nests
+def close(a, b):
+    np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-13)
+
+
+def test_tbmm_text_matches_the_oracle():
+    X, Y = inputs.make_tbmm(4, 26, 72, 26, seed=11)
+    close(fe.evaluate(TBMM, {"X": X, "Y": Y})["Z"], oracle.tbmm(X, Y))
+
+
+def test_mlp3_text_matches_the_oracle():
+    I, Ws, bs = inputs.make_mlp(16, (48, 40, 24, 12), seed=12, w_std=0.2, b_std=0.1)
+    got = fe.evaluate(MLP3, {"I": I, "W1": Ws[0], "B1": bs[0], "W2": Ws[1], "B2": bs[1], "W3": Ws[2], "B3": bs[2]})
+    want = oracle.mlp_fcrelu(I, Ws, bs)
+    for name, w in zip(("O1", "O2", "O3"), want):
+        close(got[name], w)
+        assert (got[name] >= 0).all() and (got[name] == 0).any()  # the clamp acts
+
+
+def test_gconv_text_matches_the_oracle():
+    I, W1, bias = inputs.make_gconv(2, 3, 4, 5, 9, 8, 3, 3, seed=13)
+    close(fe.evaluate(GCONV, {"I": I, "W1": W1, "B": bias})["O"], oracle.group_conv(I, W1, bias))
+
+
+def test_conv2d_text_is_the_one_group_convolution_without_bias():
+    I, W1, _ = inputs.make_gconv(2, 1, 3, 4, 8, 7, 3, 2, seed=18)
+    close(fe.evaluate(CONV2D, {"in": I[:, 0], "weight": W1[0]})["out"], oracle.group_conv(I, W1, None)[:, 0])
+
+
+def test_kron_text_matches_the_oracle():
+    W1, W2, X = inputs.make_kron(3, 6, 5, 7, 4, seed=14)
+    close(fe.evaluate(KRON, {"W1": W1, "W2": W2, "X": X})["Y"], oracle.kron(W1, W2, X))
+
+
+def test_sconv2d_text_matches_the_oracle():
+    I, Wt, bias = inputs.make_sconv2d(2, 3, 4, 11, 13, 3, 2, seed=15)
+    for sh, sw in ((2, 3), (1, 1), (3, 2)):
+        close(fe.evaluate(SCONV2D, {"I": I, "W": Wt, "B": bias}, {"sh": sh, "sw": sw})["O"],
+              oracle.sconv2d(I, Wt, bias, sh, sw))
+
+
+def test_2lut_text_matches_the_oracle():
+    LUT1, I1 = inputs.make_lut(200, 16, 9, 12, seed=16)
+    T2, I2 = inputs.make_lut(70, 16, 9, 5, seed=17)
+    got = fe.evaluate(LUT2, {"LUT1": LUT1, "I1": I1, "LUT2": T2, "I2": I2})
+    close(got["O1"], oracle.lut(LUT1, I1))
+    close(got["O2"], oracle.lut(T2, I2))
