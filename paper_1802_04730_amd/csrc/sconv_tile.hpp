@@ -8,28 +8,37 @@
 // gathered from I on the fly: element (tap k, pixel p) lives at
 //   pixbase(p) + tapoff(k),  pixbase = (n*C*H + sh*oh)*W + sw*ow,  tapoff = (c*H + kh)*W + kw.
 //
-// One workgroup = 64 filters x 64 pixels, four wavefronts of 32 x 32 (2 x 2
-// fp64 MFMA tiles), the reduction walked in chunks of 32 taps.  Per chunk a
-// thread gathers 8 input elements (one pixel, 8 taps: consecutive lanes take
-// consecutive pixels, so a wavefront's load covers a run of one input row) and
-// one or two 16-byte pieces of filter rows, two chunks ahead of the MFMAs; the
-// values are widened once to fp64 and staged in double-buffered LDS, filters as
-// [filter][tap] (row stride 34 doubles), pixels as [tap][pixel] (row stride 80
-// doubles: both the 64-lane writes and the MFMA operand reads are free of bank
-// conflicts).  The (c, kh, kw) of a thread's taps advance by 32 taps per chunk
-// with carries instead of divisions.  Accumulators start from the bias, as the
+// One workgroup = 64 filters x 64 (or 32) pixels, four wavefronts of 32 x 32
+// (32 x 16): 2 x 2 (2 x 1) fp64 MFMA tiles; the reduction is walked in chunks of
+// 16 taps.  Per chunk a thread gathers 4 (2) input elements (one pixel, taps 4
+// (8) apart: consecutive lanes take consecutive pixels, so a wavefront's load
+// covers a run of one input row) and one 16-byte piece of a filter row, two
+// chunks ahead of the MFMAs; the values are widened once to fp64 and staged in
+// double-buffered LDS, filters as [filter][tap] (row stride 18 doubles), pixels
+// as [tap][pixel] (row stride 80 (48) doubles: both the 64-lane writes and the
+// MFMA operand reads are free of bank conflicts).  Short chunks keep the LDS
+// stage under 40 KB, so that three to four workgroups share a compute unit and
+// cover each other's gathers (chunks of 32 taps at two workgroups per unit were
+// 12-20 % slower).  The (c, kh, kw) of a thread's taps advance by 16 taps per
+// chunk with carries instead of divisions.  Accumulators start from the bias, as the
 // listing's first statement says.  One barrier per chunk.
 #pragma once
 #include "tc355_device.hpp"
 
 namespace tc355 {
 
-constexpr int SC_BF = 64, SC_BP = 64, SC_KC = 32;
+constexpr int SC_BF = 64, SC_KC = 16;
 constexpr int SC_RSA = SC_KC + 2;                       // filter stage: row stride in doubles
-constexpr int SC_RSB = SC_BP + 16;                      // pixel stage: row stride in doubles, = 16 (mod 32)
-constexpr int SC_BUF = SC_BF * SC_RSA + SC_KC * SC_RSB;  // doubles per stage
-constexpr int SC_LDS_BYTES = 2 * SC_BUF * 8;            // 75,776 bytes: two workgroups per compute unit
-constexpr int SC_TAPS = SC_KC * SC_BP / WG_THREADS;     // gathered elements per thread and chunk: 8
+// BP pixels per block: 64, or 32 when 64 would leave the chip short of blocks
+template <int BP>
+struct SconvGeom {
+  static constexpr int RSB = BP + 16;                          // pixel stage: row stride in doubles, = 16 (mod 32)
+  static constexpr int BUF = SC_BF * SC_RSA + SC_KC * RSB;      // doubles per stage
+  static constexpr int LDS_BYTES = 2 * BUF * 8;                // 38,912 / 30,720 bytes: four workgroups per compute unit
+  static constexpr int TAPS = SC_KC * BP / WG_THREADS;         // gathered elements per thread and chunk: 4 / 2
+  static constexpr int KSTEP = WG_THREADS / BP;                // a thread's taps are KSTEP apart: 4 / 8
+  static_assert(BP == 64 || BP == 32, "two pixel tiles per wavefront, or one");
+};
 
 struct SconvArgs {
   const float* I;     // [N][C][H][W]
@@ -42,12 +51,15 @@ struct SconvArgs {
   int tiles_f;  // ceil(F / 64)
 };
 
-// AV: floats per load of a filter row (4 needs K % 4 == 0)
-template <int AV>
-__global__ __launch_bounds__(WG_THREADS, 2) void sconv_tile_kernel(SconvArgs p) {
+// AV: floats per load of a filter row (4 needs K % 4 == 0); BP: pixels per block
+template <int AV, int BP>
+__global__ __launch_bounds__(WG_THREADS, 3) void sconv_tile_kernel(SconvArgs p) {
+  using Gm = SconvGeom<BP>;
+  constexpr int SC_BP = BP, SC_RSB = Gm::RSB, SC_BUF = Gm::BUF, SC_TAPS = Gm::TAPS, KSTEP = Gm::KSTEP, TJ = BP / 32;
   constexpr int A_LD = SC_BF * SC_KC / AV / WG_THREADS;  // loads per thread and chunk: 2 or 8
   constexpr int A_UPR = SC_KC / AV;                      // units per filter row and chunk
   extern __shared__ __attribute__((aligned(16))) double sc_lds[];
+  static_assert(SC_KC % 4 == 0 && SC_KC * BP % WG_THREADS == 0 && SC_BF * SC_KC / AV % WG_THREADS == 0, "whole loads per thread");
 
   const int tid = threadIdx.x;
   const int lane = tid & (WAVE - 1);
@@ -65,7 +77,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void sconv_tile_kernel(SconvArgs p) 
 #pragma unroll
   for (int i = 0; i < A_LD; i++) aoff[i] = min(f0 + a_row0 + i * (WG_THREADS / A_UPR), F - 1) * K + a_k;
 
-  // ---- gathered pixels: this thread's pixel, and its taps b_k0 + 4*j of every chunk
+  // ---- gathered pixels: this thread's pixel, and its taps b_k0 + KSTEP*j of every chunk
   const int b_p = tid & (SC_BP - 1), b_k0 = tid / SC_BP;
   int pixbase;
   {
@@ -78,7 +90,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void sconv_tile_kernel(SconvArgs p) 
   int tc[SC_TAPS], tkh[SC_TAPS], tkw[SC_TAPS];
 #pragma unroll
   for (int j = 0; j < SC_TAPS; j++) {
-    const int k = b_k0 + 4 * j;
+    const int k = b_k0 + KSTEP * j;
     tkw[j] = k % KW;
     tkh[j] = (k / KW) % KH;
     tc[j] = k / (KW * KH);
@@ -98,7 +110,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void sconv_tile_kernel(SconvArgs p) 
     for (int i = 0; i < A_LD; i++) r.a[i] = load_vec<float, AV>(p.Wt + aoff[i] + ((whole || k0 + a_k < K) ? k0 : -a_k));
 #pragma unroll
     for (int j = 0; j < SC_TAPS; j++) {
-      const bool in = whole || k0 + b_k0 + 4 * j < K;
+      const bool in = whole || k0 + b_k0 + KSTEP * j < K;
       r.b[j] = p.I[pixbase + (in ? (tc[j] * H + tkh[j]) * W + tkw[j] : 0)];  // a tap past K reads a valid element, staged as 0
     }
     if (fck + 1 < nck) {
@@ -133,14 +145,14 @@ __global__ __launch_bounds__(WG_THREADS, 2) void sconv_tile_kernel(SconvArgs p) 
     }
 #pragma unroll
     for (int j = 0; j < SC_TAPS; j++) {
-      const bool in = whole || k0 + b_k0 + 4 * j < K;
-      Bs[4 * j * SC_RSB] = in ? (double)r.b[j] : 0.0;
+      const bool in = whole || k0 + b_k0 + KSTEP * j < K;
+      Bs[KSTEP * j * SC_RSB] = in ? (double)r.b[j] : 0.0;
     }
   };
 
-  // wavefront (wr, wc) owns filters 32*wr.., pixels 32*wc.. of the block
+  // wavefront (wr, wc) owns filters 32*wr.., pixels 16*TJ*wc.. of the block
   const int wr = wave >> 1, wc = wave & 1;
-  d4 acc[2][2];
+  d4 acc[2][TJ];
 #pragma unroll
   for (int i = 0; i < 2; i++) {
     d4 bz;
@@ -149,8 +161,8 @@ __global__ __launch_bounds__(WG_THREADS, 2) void sconv_tile_kernel(SconvArgs p) 
       const int f = min(f0 + 32 * wr + 16 * i + d_row(q, v), F - 1);
       bz[v] = p.bias ? (double)p.bias[f] : 0.0;  // the listing's first statement
     }
-    acc[i][0] = bz;
-    acc[i][1] = bz;
+#pragma unroll
+    for (int j = 0; j < TJ; j++) acc[i][j] = bz;
   }
 
   // chunk c sits in ring[c % 2] until staged into LDS buffer c % 2; iteration c stages chunk c+1,
@@ -169,23 +181,28 @@ __global__ __launch_bounds__(WG_THREADS, 2) void sconv_tile_kernel(SconvArgs p) 
         if (c + 1 < nck) stage(ring[(i + 1) & 1], c + 1, sc_lds + ((i + 1) & 1) * SC_BUF);
         fetch(ring[(i + 1) & 1]);
         const double* As = sc_lds + (i & 1) * SC_BUF + (32 * wr + r16) * SC_RSA + q;
-        const double* Bs = sc_lds + (i & 1) * SC_BUF + SC_BF * SC_RSA + q * SC_RSB + 32 * wc + r16;
+        const double* Bs = sc_lds + (i & 1) * SC_BUF + SC_BF * SC_RSA + q * SC_RSB + 16 * TJ * wc + r16;
         // LDS reads of step s+1 are issued before the MFMAs of step s
-        double a0 = As[0], a1 = As[16 * SC_RSA], b0 = Bs[0], b1 = Bs[16];
+        double a0 = As[0], a1 = As[16 * SC_RSA], b[TJ], nb[TJ];
+#pragma unroll
+        for (int j = 0; j < TJ; j++) b[j] = Bs[16 * j];
 #pragma unroll
         for (int s = 0; s < SC_KC / 4; s++) {
-          double na0 = 0, na1 = 0, nb0 = 0, nb1 = 0;
+          double na0 = 0, na1 = 0;
           if (s + 1 < SC_KC / 4) {
             na0 = As[4 * s + 4]; na1 = As[16 * SC_RSA + 4 * s + 4];
-            nb0 = Bs[(4 * s + 4) * SC_RSB]; nb1 = Bs[(4 * s + 4) * SC_RSB + 16];
+#pragma unroll
+            for (int j = 0; j < TJ; j++) nb[j] = Bs[(4 * s + 4) * SC_RSB + 16 * j];
           }
           __builtin_amdgcn_sched_barrier(0);
-          acc[0][0] = mfma_f64(a0, b0, acc[0][0]);
-          acc[0][1] = mfma_f64(a0, b1, acc[0][1]);
-          acc[1][0] = mfma_f64(a1, b0, acc[1][0]);
-          acc[1][1] = mfma_f64(a1, b1, acc[1][1]);
+#pragma unroll
+          for (int j = 0; j < TJ; j++) acc[0][j] = mfma_f64(a0, b[j], acc[0][j]);
+#pragma unroll
+          for (int j = 0; j < TJ; j++) acc[1][j] = mfma_f64(a1, b[j], acc[1][j]);
           __builtin_amdgcn_sched_barrier(0);
-          a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
+          a0 = na0; a1 = na1;
+#pragma unroll
+          for (int j = 0; j < TJ; j++) b[j] = nb[j];
         }
         __syncthreads();
       }
@@ -193,8 +210,8 @@ __global__ __launch_bounds__(WG_THREADS, 2) void sconv_tile_kernel(SconvArgs p) 
   }
 
 #pragma unroll
-  for (int j = 0; j < 2; j++) {
-    const int px = p0 + 32 * wc + 16 * j + r16;
+  for (int j = 0; j < TJ; j++) {
+    const int px = p0 + 16 * TJ * wc + 16 * j + r16;
     const int pc = min(px, P - 1);
     const int n = pc / OHW, r = pc - n * OHW;
     float* out = p.O + (int64_t)n * F * OHW + r;

@@ -552,20 +552,18 @@ tc_status tc_sconv2d(const float* I, const float* Wt, const float* bias, float* 
   a.sh = (int)sh; a.sw = (int)sw; a.OH = (int)OH; a.OW = (int)OW;
   a.K = (int)K; a.P = (int)(N * OH * OW);
   a.tiles_f = (int)ceil_div(F, SC_BF);
-  const int64_t grid = (int64_t)a.tiles_f * ceil_div(a.P, SC_BP);
+  // 64-pixel blocks when there are at least two of them per compute unit, else 32-pixel blocks (twice as many)
+  const bool wide = (int64_t)a.tiles_f * ceil_div(a.P, 64) >= 2 * (int64_t)std::max(1, device_cus());
+  const int64_t grid = (int64_t)a.tiles_f * ceil_div(a.P, wide ? 64 : 32);
   if (grid > kMaxGrid) return TC_ERR_UNSUPPORTED;
-  static std::atomic<int> lds_ok{0};  // the kernels stage more than the default 64 KiB of LDS
-  if (!lds_ok.load(std::memory_order_acquire)) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(sconv_tile_kernel<4>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, SC_LDS_BYTES) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void*>(sconv_tile_kernel<1>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, SC_LDS_BYTES) != hipSuccess)
-      return TC_ERR_LAUNCH;
-    lds_ok.store(1, std::memory_order_release);
-  }
   const dim3 gd((unsigned)grid), bd(WG_THREADS);
-  if (K % 4 == 0) sconv_tile_kernel<4><<<gd, bd, SC_LDS_BYTES, s>>>(a);
-  else sconv_tile_kernel<1><<<gd, bd, SC_LDS_BYTES, s>>>(a);
+  if (wide) {
+    if (K % 4 == 0) sconv_tile_kernel<4, 64><<<gd, bd, SconvGeom<64>::LDS_BYTES, s>>>(a);
+    else sconv_tile_kernel<1, 64><<<gd, bd, SconvGeom<64>::LDS_BYTES, s>>>(a);
+  } else {
+    if (K % 4 == 0) sconv_tile_kernel<4, 32><<<gd, bd, SconvGeom<32>::LDS_BYTES, s>>>(a);
+    else sconv_tile_kernel<1, 32><<<gd, bd, SconvGeom<32>::LDS_BYTES, s>>>(a);
+  }
   return launch_status();
 }
 
