@@ -170,3 +170,40 @@ def test_lut_stays_inside_its_output(tc, oracle_threads):
     tc.tc_lut([dev(LUT)], [dev(Idx)], [O])
     check(O, oracle.lut(LUT, Idx), "lut guard band")
     assert torch.all(buf[:256] == 7.0) and torch.all(buf[256 + B * D:] == 7.0)
+
+
+# ---------------------------------------------------------------- both operators from a HIP graph
+def test_sconv2d_and_lut_replay_from_a_hip_graph(tc, oracle_threads):
+    # Both entry points enqueue one kernel and nothing else, so they can be captured and replayed; replays are
+    # interleaved with eager work and every one is checked.
+    I, Wt, bias = inputs.make_sconv2d(2, 16, 24, 23, 21, 3, 3, seed=31)
+    LUT1, Idx1 = inputs.make_lut(3000, 64, 32, 50, seed=32)
+    LUT2, Idx2 = inputs.make_lut(500, 64, 32, 7, seed=33)
+    ref_s = oracle.sconv2d(I, Wt, bias, 2, 2)
+    ref_1, ref_2 = oracle.lut(LUT1, Idx1), oracle.lut(LUT2, Idx2)
+    Id, Wd, bd = dev(I), dev(Wt), dev(bias)
+    T = [dev(LUT1), dev(LUT2)]
+    J = [dev(Idx1), dev(Idx2)]
+    Os = torch.empty(ref_s.shape, device="cuda")
+    O1, O2 = torch.empty((32, 64), device="cuda"), torch.empty((32, 64), device="cuda")
+
+    def step():
+        tc.tc_sconv2d(Id, Wd, bd, Os, 2, 2)
+        tc.tc_lut(T, J, [O1, O2])
+
+    step()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for rep in range(3):
+        for t in (Os, O1, O2):
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        scratch = torch.randn(1 << 20, device="cuda").sum()  # eager work between replays
+        torch.cuda.synchronize()
+        check(Os, ref_s, "graph replay %d sconv2d" % rep)
+        check(O1, ref_1, "graph replay %d lut 1" % rep)
+        check(O2, ref_2, "graph replay %d lut 2" % rep)
+        del scratch
