@@ -256,31 +256,34 @@ __device__ __forceinline__ void mlp_layer(const TA* __restrict__ A, const float*
     for (int i = 0; i < NR; i++) {
       const int t = t0 + i;
       if (t < total) {  // uniform over the workgroup
+        char* buf = smem + (i & 1) * MLP_BUF_BYTES;
+        // this wavefront's quarter of the chunk: k = (KC/4)*wave + 16*j + 4*q + e.  Its LDS reads are issued first,
+        // the staging of the next chunk (LDS writes to the other buffer, the next global loads) runs while they are
+        // in flight, the MFMAs come last: one LDS latency per chunk is hidden instead of two being paid.
+        const TA* As = reinterpret_cast<const TA*>(buf) + r16 * RSA + (KC / 4) * wave + 4 * q;
+        const float* Bs = reinterpret_cast<const float*>(buf + 16 * MLP_RS_D * 8) + r16 * MLP_RS_F + (KC / 4) * wave + 4 * q;
+        // (a ragged tail was staged as zeros, so every step can run unconditionally)
+        Vec<TA, 4> av[KC / 64];
+        Vec<float, 4> bv[KC / 64];
+#pragma unroll
+        for (int j = 0; j < KC / 64; j++) {
+          if constexpr (A64) {  // rows are 16-byte, not 32-byte, aligned: two 16-byte reads
+            const Vec<TA, 2> lo = load_vec<TA, 2>(As + 16 * j), hi = load_vec<TA, 2>(As + 16 * j + 2);
+            av[j].e[0] = lo.e[0]; av[j].e[1] = lo.e[1]; av[j].e[2] = hi.e[0]; av[j].e[3] = hi.e[1];
+          } else {
+            av[j] = load_vec<TA, 4>(As + 16 * j);
+          }
+          bv[j] = load_vec<float, 4>(Bs + 16 * j);
+        }
         if (t + 1 < total) {
           stage(ring[(i + 1) % NR], smem + ((i + 1) & 1) * MLP_BUF_BYTES);
           load_next(ring[(i + 1) % NR]);
         }
-        char* buf = smem + (i & 1) * MLP_BUF_BYTES;
         TC355_TRACE(trace, 3);
-        // this wavefront's quarter of the chunk: k = (KC/4)*wave + 16*j + 4*q + e
-        const TA* As = reinterpret_cast<const TA*>(buf) + r16 * RSA + (KC / 4) * wave + 4 * q;
-        const float* Bs = reinterpret_cast<const float*>(buf + 16 * MLP_RS_D * 8) + r16 * MLP_RS_F + (KC / 4) * wave + 4 * q;
-        // (a ragged tail was staged as zeros, so every step can run unconditionally)
 #pragma unroll
-        for (int j = 0; j < KC / 64; j++) {
-          {
-            Vec<TA, 4> av;
-            if constexpr (A64) {  // rows are 16-byte, not 32-byte, aligned: two 16-byte reads
-              const Vec<TA, 2> lo = load_vec<TA, 2>(As + 16 * j), hi = load_vec<TA, 2>(As + 16 * j + 2);
-              av.e[0] = lo.e[0]; av.e[1] = lo.e[1]; av.e[2] = hi.e[0]; av.e[3] = hi.e[1];
-            } else {
-              av = load_vec<TA, 4>(As + 16 * j);
-            }
-            const Vec<float, 4> bv = load_vec<float, 4>(Bs + 16 * j);
+        for (int j = 0; j < KC / 64; j++)
 #pragma unroll
-            for (int e = 0; e < 4; e++) acc = mfma_f64((double)av.e[e], (double)bv.e[e], acc);
-          }
-        }
+          for (int e = 0; e < 4; e++) acc = mfma_f64((double)av[j].e[e], (double)bv[j].e[e], acc);
         TC355_TRACE(trace, 4);
         const bool last = (++ck == nck);
         d4* part = part_base + parity * (WAVES_PER_WG * WAVE);
