@@ -307,3 +307,39 @@ def test_2lut_text_matches_the_oracle():
     got = fe.evaluate(LUT2, {"LUT1": LUT1, "I1": I1, "LUT2": T2, "I2": I2})
     close(got["O1"], oracle.lut(LUT1, I1))
     close(got["O2"], oracle.lut(T2, I2))
+
+
+# ------------------------------------------------------- many small random shapes: text route vs loop-nest route
+def test_random_small_shapes_agree_on_all_six_comprehensions():
+    r = np.random.default_rng(20180213)
+    for trial in range(25):
+        B, N, M, K = (int(x) for x in r.integers(1, 7, size=4))
+        X, Y = inputs.make_tbmm(B, N, M, K, seed=1000 + trial)
+        close(fe.evaluate(TBMM, {"X": X, "Y": Y})["Z"], oracle.tbmm(X, Y))
+
+        d = [int(x) for x in r.integers(1, 9, size=4)]
+        I, Ws, bs = inputs.make_mlp(int(r.integers(1, 6)), d, seed=2000 + trial, w_std=0.5, b_std=0.5)
+        got = fe.evaluate(MLP3, {"I": I, "W1": Ws[0], "B1": bs[0], "W2": Ws[1], "B2": bs[1], "W3": Ws[2], "B3": bs[2]})
+        for name, w in zip(("O1", "O2", "O3"), oracle.mlp_fcrelu(I, Ws, bs)):
+            close(got[name], w)
+
+        n, g, c, f, kh, kw = (int(x) for x in r.integers(1, 4, size=6))
+        h, w_ = kh + int(r.integers(0, 5)), kw + int(r.integers(0, 5))
+        Ig, W1, bias = inputs.make_gconv(n, g, c, f, h, w_, kh, kw, seed=3000 + trial, w_std=0.5, b_std=0.5)
+        close(fe.evaluate(GCONV, {"I": Ig, "W1": W1, "B": bias})["O"], oracle.group_conv(Ig, W1, bias))
+
+        b, i, k, j, l = (int(x) for x in r.integers(1, 6, size=5))
+        K1, K2, Xk = inputs.make_kron(b, i, k, j, l, seed=4000 + trial)
+        close(fe.evaluate(KRON, {"W1": K1, "W2": K2, "X": Xk})["Y"], oracle.kron(K1, K2, Xk))
+
+        sh, sw = int(r.integers(1, 4)), int(r.integers(1, 4))
+        Is, Wt, bs2 = inputs.make_sconv2d(n, c, f, h + 3, w_ + 2, kh, kw, seed=5000 + trial, w_std=0.5, b_std=0.5)
+        close(fe.evaluate(SCONV2D, {"I": Is, "W": Wt, "B": bs2}, {"sh": sh, "sw": sw})["O"],
+              oracle.sconv2d(Is, Wt, bs2, sh, sw))
+
+        e1, e2, dd, bb, l1, l2 = (int(x) for x in r.integers(1, 9, size=6))
+        T1, J1 = inputs.make_lut(e1, dd, bb, l1, seed=6000 + trial)
+        T2, J2 = inputs.make_lut(e2, dd, bb, l2, seed=7000 + trial)
+        got = fe.evaluate(LUT2, {"LUT1": T1, "I1": J1, "LUT2": T2, "I2": J2})
+        close(got["O1"], oracle.lut(T1, J1))
+        close(got["O2"], oracle.lut(T2, J2))
