@@ -40,7 +40,9 @@
 // up while slower wavefronts still read the other); wavefront w owns output rows 2w and 2w+1 of the band: three
 // full 16-pixel columns swept over 4 input rows each, and the last 8 columns of
 // both rows packed into one tile (lanes 0-7: row 2w, lanes 8-15: row 2w+1).
-// Every wavefront executes the same 21 groups per band.  The next band (of this
+// Every wavefront executes the same 21 groups per band; its outputs (16 filters
+// x 2 rows) are collected in the idle band buffer and leave as 16-byte stores of
+// whole row pairs.  The next band (of this
 // or of the next image) is fetched into registers piecemeal between the groups,
 // with 16-byte loads: the kernel takes only heights whose bands are whole and
 // 16-byte aligned (H even, H - 2 a multiple of 8); a band's rows are then one
@@ -80,6 +82,12 @@ struct GconvI8Geom {
   static constexpr int MISC = 2 * BUF;                                  // byte offset of the small arrays
   static constexpr int LDS_BYTES = 2 * BUF + 128;
   static constexpr int NFC = OW / 16;                                   // full 16-pixel columns
+  // output staging of a wavefront (16 filters x 2 rows x OW pixels, fp32) in the idle band buffer: filter stride
+  // in floats = 4 (mod 16), so that the four filter rows a store instruction writes fall into different banks
+  static constexpr int OSF = ((2 * OW + 11) / 16) * 16 + 4;
+  static constexpr int OSTAGE = 16 * OSF * 4;                           // bytes per wavefront
+  static_assert(OSF >= 2 * OW && WAVES_PER_WG * OSTAGE <= BUF, "output staging must fit the idle band buffer");
+  static_assert((2 * OW * 4) % 16 == 0 && 2 * OW * 4 / 16 <= 32, "a filter's two rows are at most 32 16-byte pieces");
   static_assert(ROWS == 2 * WAVES_PER_WG, "two output rows per wavefront");
   static_assert(OW % 16 == 8, "the last 8 columns of two rows share one tile");
   static_assert(3 * PLANE + 3 * W * 16 < 65536, "LDS immediates out of range");
@@ -203,6 +211,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
     // channels 4w..4w+3 and the four share their dwords through LDS: record (kh, k) of a lane at
     // arec + ((kh*4 + k)*64 + lane)*16, dword w.
     {
+      __syncthreads();  // slower wavefronts may still be reading their output staging in this buffer
       float* wl = reinterpret_cast<float*>(gi8_lds + (it & 1) * BUF);
       char* arec = reinterpret_cast<char*>(wl) + 16384;
       static_assert(WN * 4 <= 16384 && 16384 + KH * 4 * WAVE * 16 <= BUF, "scratch must fit one band buffer");
@@ -312,11 +321,16 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
       }
 
       const int h0 = b * ROWS + 2 * wave;  // first output row of this wavefront in this band
+      // Outputs are staged per wavefront in the idle band buffer as [filter][2 rows][OW] and written out after the
+      // sweeps with 16-byte stores, a filter's two rows (2*OW*4 contiguous bytes of O) at a time: 4-byte stores of
+      // 64-byte pieces of four different rows keep the path to HBM busy four times as long.
+      char* ostage = gi8_lds + ((it + 1) & 1) * BUF + wave * Gm::OSTAGE;
+      char* olane = ostage + (4 * q) * (Gm::OSF * 4) + r16 * 4;
       // One sweep: NR output rows per lane, NR + 2 input rows starting at the lane's LDS pointer `base`
       // (input row of its first output row, column of its pixel + kw).  orow/ocol: the lane's first output
       // row and its column.  PIECE: the fetch piece of the next band to issue during this sweep, or -1.
-      auto sweep = [&](auto nr_c, auto piece_c, const char* base, int orow, int ocol) {
-        constexpr int NR = decltype(nr_c)::value, PIECE = decltype(piece_c)::value;
+      auto sweep = [&](auto nr_c, auto piece_c, auto col_c, const char* base, char* obase) {
+        constexpr int NR = decltype(nr_c)::value, PIECE = decltype(piece_c)::value, COL = decltype(col_c)::value;
         i4 acc[NR][5];
 #pragma unroll
         for (int hl = 0; hl < NR; hl++)
@@ -358,27 +372,41 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
         // ---- exact recombination of the diagonals, scaling, bias, single rounding
 #pragma unroll
         for (int hl = 0; hl < NR; hl++) {
-          const int h = orow + hl;
 #pragma unroll
           for (int v = 0; v < 4; v++) {
             const int hi = acc[hl][4][v] * 256 + acc[hl][3][v];  // |.| < 2^28
             const int lo = acc[hl][2][v] * 256 + acc[hl][1][v];  // |.| < 2^31
-            const unsigned off = 4u * (unsigned)((4 * q + v) * npix + h * OW + ocol);
             double rr = __builtin_fma((double)hi, 65536.0, (double)lo);  // sum_d P_d 256^(d-3), exact
             rr = __builtin_fma((double)acc[hl][0][v], 0.00390625, rr);
-            *reinterpret_cast<float*>(dst + off) = (float)__builtin_fma(rr, __hiloint2double(scale_hi[v], 0), (double)bz[v]);
+            *reinterpret_cast<float*>(obase + (v * Gm::OSF + hl * OW + COL) * 4) =
+                (float)__builtin_fma(rr, __hiloint2double(scale_hi[v], 0), (double)bz[v]);
           }
         }
       };
       const char* lbase = buf + ((2 * wave) * W + r16 + kwq) * 16;
-      sweep(integral_constant<int, 2>{}, integral_constant<int, 0>{}, lbase, h0, r16);
-      sweep(integral_constant<int, 2>{}, integral_constant<int, 1>{}, lbase + 256, h0, 16 + r16);
-      sweep(integral_constant<int, 2>{}, integral_constant<int, 2>{}, lbase + 512, h0, 32 + r16);
+      sweep(integral_constant<int, 2>{}, integral_constant<int, 0>{}, integral_constant<int, 0>{}, lbase, olane);
+      sweep(integral_constant<int, 2>{}, integral_constant<int, 1>{}, integral_constant<int, 16>{}, lbase + 256, olane);
+      sweep(integral_constant<int, 2>{}, integral_constant<int, 2>{}, integral_constant<int, 32>{}, lbase + 512, olane);
       static_assert(NFC == 3, "three full columns are written out above");
-      // last 8 columns of both rows in one tile
+      // last 8 columns of both rows in one tile: lanes 0-7 row h0, lanes 8-15 row h0 + 1
       const int hr = r16 >> 3;
-      sweep(integral_constant<int, 1>{}, integral_constant<int, -1>{},
-            buf + ((2 * wave + hr) * W + 16 * NFC + (r16 & 7) + kwq) * 16, h0 + hr, 16 * NFC + (r16 & 7));
+      sweep(integral_constant<int, 1>{}, integral_constant<int, -1>{}, integral_constant<int, 16 * NFC>{},
+            buf + ((2 * wave + hr) * W + 16 * NFC + (r16 & 7) + kwq) * 16, olane + (hr * OW + (r16 & 7) - r16) * 4);
+      // ---- staged outputs -> O: instruction j writes filters 2j (lanes 0-31) and 2j+1 (lanes 32-63), 16 bytes per
+      // lane; the staging is private to the wavefront, so its own LDS writes only have to have landed
+      {
+        constexpr int PIECES = 2 * OW * 4 / 16;  // 16-byte pieces of a filter's two rows
+        const int pc = lane & 31, fsel = lane >> 5;
+        const char* srd = ostage + fsel * (Gm::OSF * 4) + pc * 16;
+        char* gwr = dst + 4 * (fsel * npix + h0 * OW) + pc * 16;
+        if (pc < PIECES) {
+#pragma unroll
+          for (int j = 0; j < 8; j++) {
+            const f4 v = *reinterpret_cast<const f4*>(srd + j * 2 * Gm::OSF * 4);
+            *reinterpret_cast<f4*>(gwr + (int64_t)j * 2 * npix * 4) = v;
+          }
+        }
+      }
       TC355_TRACE_R(trace, 5);
     }
     img += stride;
