@@ -211,7 +211,7 @@ __global__ __launch_bounds__(WG_THREADS, MINW) void gconv_band_kernel(GconvBandA
         const int pl = (4 * (t_first + t) + wr) * 16 + r16;  // pixel within the band
         if (pl < ROWS * OW && P0 + pl < npix) {
 #pragma unroll
-          for (int v = 0; v < 4; v++) dst[(int64_t)d_row(q, v) * npix + P0 + pl] = (float)acc[t][v];
+          for (int v = 0; v < 4; v++) store_stream(&dst[(int64_t)d_row(q, v) * npix + P0 + pl], (float)acc[t][v]);
         }
       }
     };

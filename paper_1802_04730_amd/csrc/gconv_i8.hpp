@@ -403,7 +403,9 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
 #pragma unroll
           for (int j = 0; j < 8; j++) {
             const f4 v = *reinterpret_cast<const f4*>(srd + j * 2 * Gm::OSF * 4);
-            *reinterpret_cast<f4*>(gwr + (int64_t)j * 2 * npix * 4) = v;
+            // written once, never read again by this kernel: a streaming store keeps the output out of the way of
+            // the input rows that the next band re-reads from L2 (measured: 10 % of the launch)
+            store_stream(reinterpret_cast<f4*>(gwr + (int64_t)j * 2 * npix * 4), v);
           }
         }
       }

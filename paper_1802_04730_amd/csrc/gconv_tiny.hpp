@@ -131,7 +131,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_tiny_kernel(GconvTinyArgs
     if (16 * pt + r16 < NPIX) {
       float* dst = p.O + (((int64_t)n * p.G + g) * F + 16 * ft) * NPIX + 16 * pt + r16;
 #pragma unroll
-      for (int v = 0; v < 4; v++) dst[(int64_t)d_row(q, v) * NPIX] = (float)acc[v];
+      for (int v = 0; v < 4; v++) store_stream(&dst[(int64_t)d_row(q, v) * NPIX], (float)acc[v]);
     }
     __syncthreads();  // the next image is staged; this image's buffer is free
   }
