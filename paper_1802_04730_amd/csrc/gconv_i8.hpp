@@ -33,8 +33,12 @@
 // therefore covers one filter row kh for a 16-pixel tile, and the B operand of
 // input row r is shared by the output rows r, r-1 and r-2.
 //
-// Work split: persistent workgroups (two per compute unit), each taking (image,
-// group) pairs round-robin; bands of 8 output rows; the band's 10 input rows sit
+// Work split: bands of 8 output rows, numbered group-major ((g, n, band), band
+// fastest); persistent workgroups (two per compute unit), each taking one
+// contiguous run of bands, so that its filter bank changes at most once or
+// twice.  Workgroups w and w + gridDim/2 come to share a compute unit; the
+// first is dispatched earlier, wins the issue slots and runs about a quarter
+// faster, so it is given more than half of the pair's bands (num/den).  The the band's 10 input rows sit
 // in LDS as four digit planes [pixel][16 channels] (two buffers, used in turn:
 // the idle one is the scratch through which the next image's filter bank is set
 // up while slower wavefronts still read the other); wavefront w owns output rows 2w and 2w+1 of the band: three
@@ -62,7 +66,9 @@ struct GconvI8Args {
   const float* bias;  // or nullptr
   float* O;
   int G, H;
-  int total;  // N*G (image, group) pairs
+  int N;        // images
+  int halves;   // gridDim.x / 2 if workgroups w and w + halves share a compute unit's work, else 0 (even split)
+  int num, den; // of the bands that such a pair owns, workgroup w takes the first num/den
   TC355_TRACE_FIELD
 };
 
@@ -163,9 +169,31 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
   const int npix = OH * OW;
   const int nbands = OH / ROWS;
   const int plane = H * W;
-  const int stride = gridDim.x;
-  int img = blockIdx.x;  // n*G + g
-  if (img >= p.total) return;
+  // ---- this workgroup's run of bands [u, u1) in the order (g, n, band)
+  int u, u1;
+  {
+    const long long tb = (long long)p.N * p.G * nbands;
+    const int w = blockIdx.x;
+    if (p.halves) {
+      const int pr = w % p.halves;
+      const long long s0 = tb * pr / p.halves, e0 = tb * (pr + 1) / p.halves;
+      const long long mid = s0 + (e0 - s0) * p.num / p.den;
+      u = (int)(w < p.halves ? s0 : mid);
+      u1 = (int)(w < p.halves ? mid : e0);
+    } else {
+      u = (int)(tb * w / gridDim.x);
+      u1 = (int)(tb * (w + 1) / gridDim.x);
+    }
+  }
+  if (u >= u1) return;
+  // band number -> group, image, band of the image
+  int g, b, img;
+  auto decode = [&](int unit) {
+    const int pair = unit / nbands;
+    b = unit - pair * nbands;
+    g = pair / p.N;
+    img = (pair - g * p.N) * p.G + g;  // n*G + g
+  };
 
   // ---- the band being fetched: two units and (first NHALF threads) one half unit per thread
   const bool has_half = wave * WAVE < NHALF;  // whole wavefronts only
@@ -194,7 +222,8 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
     }
   };
   using std::integral_constant;
-  set_fetch(img, 0);
+  decode(u);
+  set_fetch(img, b);
   fetch_piece(integral_constant<int, 0>{});
   fetch_piece(integral_constant<int, 1>{});
   fetch_piece(integral_constant<int, 2>{});
@@ -203,14 +232,16 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
   int ea_v[4];     // exponent of filter row 4q + v
   float bz[4];     // bias of filter row 4q + v
   int it = 0;      // bands staged so far by this workgroup: LDS buffer parity
-  for (;;) {
-    const int g = img % p.G;
+  int g_bank = -1; // group whose filter bank the A operands hold
+  for (; u < u1; u++, it++) {
+    decode(u);
     char* dst = reinterpret_cast<char*>(p.O + (int64_t)img * F * npix);
     // ---- filter bank -> A operands, through the band buffer that is staged next (free: it was last read two bands ago).
     // Every lane needs digit records of all 16 channels of its (filter row, kw) for the 3 kh; wavefront w slices
     // channels 4w..4w+3 and the four share their dwords through LDS: record (kh, k) of a lane at
     // arec + ((kh*4 + k)*64 + lane)*16, dword w.
-    {
+    if (g != g_bank) {
+      g_bank = g;
       __syncthreads();  // slower wavefronts may still be reading their output staging in this buffer
       float* wl = reinterpret_cast<float*>(gi8_lds + (it & 1) * BUF);
       char* arec = reinterpret_cast<char*>(wl) + 16384;
@@ -252,7 +283,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
     }
     TC355_TRACE_R(trace, 2);
 
-    for (int b = 0; b < nbands; b++, it++) {
+    {
       char* buf = gi8_lds + (it & 1) * BUF;
       // ---- largest magnitude of the band: bit patterns order like magnitudes.  Positive values (and NaNs) win a
       // signed maximum, negative ones an unsigned maximum: one instruction per two elements each.
@@ -307,11 +338,13 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
       __syncthreads();
       TC355_TRACE_R(trace, 4);
 
-      // ---- what to fetch while this band is contracted: the next band, or the next image's first band
-      const bool last = b + 1 == nbands;
-      const bool more = !last || img + stride < p.total;
-      if (!last) set_fetch(img, b + 1);
-      else if (more) set_fetch(img + stride, 0);
+      // ---- what to fetch while this band is contracted: the next band of the run
+      const bool more = u + 1 < u1;
+      const int b_now = b;
+      if (more) {
+        decode(u + 1);
+        set_fetch(img, b);
+      }
       // 2^(ea+eb-36) per filter row of this lane: high word of the fp64 bit pattern; NaN if the band or the row holds Inf/NaN
       int scale_hi[4];
 #pragma unroll
@@ -320,7 +353,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
         scale_hi[v] = bad ? 0x7ff80000 : (1023 + ea_v[v] + eb - 36) << 20;
       }
 
-      const int h0 = b * ROWS + 2 * wave;  // first output row of this wavefront in this band
+      const int h0 = b_now * ROWS + 2 * wave;  // first output row of this wavefront in this band
       // Outputs are staged per wavefront in the idle band buffer as [filter][2 rows][OW] and written out after the
       // sweeps with 16-byte stores, a filter's two rows (2*OW*4 contiguous bytes of O) at a time: 4-byte stores of
       // 64-byte pieces of four different rows keep the path to HBM busy four times as long.
@@ -411,8 +444,6 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
       }
       TC355_TRACE_R(trace, 5);
     }
-    img += stride;
-    if (img >= p.total) break;
   }
   TC355_TRACE_FLUSH(trace);
 }
