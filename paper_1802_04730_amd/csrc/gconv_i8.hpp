@@ -106,6 +106,24 @@ __device__ __forceinline__ int i8_digits(float x, int sh) {
   return (v + 0x00808080) ^ 0x00808080;
 }
 
+// The same rounding for the hot loop, two instructions instead of three: x * 2^sh + 1.5 * 2^52 in fp64 (one fused
+// operation, exact product, round to nearest even) leaves rint(x * 2^sh) in the low word of the sum for |.| < 2^31.
+// scale = 2^sh as a double.
+__device__ __forceinline__ int i8_fixed(float x, double scale) {
+  return __double2loint(__builtin_fma((double)x, scale, 6755399441055744.0));
+}
+
+__device__ __forceinline__ int i8_max3(int a, int b, int c) {
+  int d;
+  asm("v_max3_i32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+  return d;
+}
+__device__ __forceinline__ unsigned i8_max3(unsigned a, unsigned b, unsigned c) {
+  unsigned d;
+  asm("v_max3_u32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+  return d;
+}
+
 // Exponent e with m < 2^e for the magnitude whose bit pattern is mbits (sign cleared), denormals included; 129 for
 // Inf/NaN.  A block scaled by it fills bit 29 of the fixed-point numbers, so that the digit pairs that are dropped
 // stay 2^-35 below the leading ones.
@@ -290,8 +308,8 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
       int mp = 0;
       unsigned mn = 0;
       auto take = [&](float x, float y) {
-        mp = max(mp, max(__float_as_int(x), __float_as_int(y)));
-        mn = max(mn, max(__float_as_uint(x), __float_as_uint(y)));
+        mp = i8_max3(mp, __float_as_int(x), __float_as_int(y));
+        mn = i8_max3(mn, __float_as_uint(x), __float_as_uint(y));
       };
 #pragma unroll
       for (int j = 0; j < 2; j++)
@@ -314,12 +332,16 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
 
       // ---- slice and stage: digit plane k, record of pixel pi at byte k*PLANE + 16*pi, channels 4cg.. at +4cg
       {
-        const int sh = 30 - eb;
+        const double scale = __hiloint2double((1023 + 30 - eb) << 20, 0);  // 2^(30-eb)
         auto put = [&](float x0, float x1, float x2, float x3, int cg, int pixel) {  // 4 channels of one pixel
-          int d[4] = {i8_digits(x0, sh), i8_digits(x1, sh), i8_digits(x2, sh), i8_digits(x3, sh)}, y[4];
+          // v + 0x00808080 makes byte k digit k plus 128; flipping bit 7 of bytes 0..2 afterwards gives the digits,
+          // and that flip commutes with the byte transpose: three instructions per four elements instead of four
+          int d[4] = {i8_fixed(x0, scale) + 0x00808080, i8_fixed(x1, scale) + 0x00808080,
+                      i8_fixed(x2, scale) + 0x00808080, i8_fixed(x3, scale) + 0x00808080}, y[4];
           i8_transpose4(d, y);
 #pragma unroll
-          for (int k = 0; k < 4; k++) *reinterpret_cast<int*>(buf + k * PLANE + 16 * pixel + 4 * cg) = y[k];
+          for (int k = 0; k < 4; k++)
+            *reinterpret_cast<int*>(buf + k * PLANE + 16 * pixel + 4 * cg) = k < 3 ? y[k] ^ (int)0x80808080 : y[k];
         };
 #pragma unroll
         for (int j = 0; j < 2; j++) {
