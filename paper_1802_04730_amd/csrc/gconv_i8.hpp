@@ -38,7 +38,7 @@
 // contiguous run of bands, so that its filter bank changes at most once or
 // twice.  Workgroups w and w + gridDim/2 come to share a compute unit; the
 // first is dispatched earlier, wins the issue slots and runs about a quarter
-// faster, so it is given more than half of the pair's bands (num/den).  The the band's 10 input rows sit
+// faster, so it is given more than half of the pair's bands (num/den).  The band's 10 input rows sit
 // in LDS as four digit planes [pixel][16 channels] (two buffers, used in turn:
 // the idle one is the scratch through which the next image's filter bank is set
 // up while slower wavefronts still read the other); wavefront w owns output rows 2w and 2w+1 of the band: three
@@ -108,9 +108,12 @@ __device__ __forceinline__ int i8_digits(float x, int sh) {
 
 // The same rounding for the hot loop, two instructions instead of three: x * 2^sh + 1.5 * 2^52 in fp64 (one fused
 // operation, exact product, round to nearest even) leaves rint(x * 2^sh) in the low word of the sum for |.| < 2^31.
-// scale = 2^sh as a double.
+// scale = 2^sh as a double.  An even integer `plus` < 2^31 added to the constant comes out added to the result
+// (mod 2^32) for free: the sum is still an integer plus the product, and ties still go to the even neighbour.
+template <int plus = 0>
 __device__ __forceinline__ int i8_fixed(float x, double scale) {
-  return __double2loint(__builtin_fma((double)x, scale, 6755399441055744.0));
+  static_assert(plus >= 0 && plus % 2 == 0, "an even offset keeps round-to-nearest-even on the product");
+  return __double2loint(__builtin_fma((double)x, scale, 6755399441055744.0 + (double)plus));
 }
 
 __device__ __forceinline__ int i8_max3(int a, int b, int c) {
@@ -190,14 +193,15 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
   // ---- this workgroup's run of bands [u, u1) in the order (g, n, band)
   int u, u1;
   {
-    const long long tb = (long long)p.N * p.G * nbands;
-    const int w = blockIdx.x;
+    // 32-bit arithmetic: the host checks bands * (workgroups + 1) < 2^31
+    const unsigned tb = (unsigned)(p.N * p.G * nbands);
+    const unsigned w = blockIdx.x;
     if (p.halves) {
-      const int pr = w % p.halves;
-      const long long s0 = tb * pr / p.halves, e0 = tb * (pr + 1) / p.halves;
-      const long long mid = s0 + (e0 - s0) * p.num / p.den;
-      u = (int)(w < p.halves ? s0 : mid);
-      u1 = (int)(w < p.halves ? mid : e0);
+      const unsigned hv = (unsigned)p.halves, pr = w % hv;
+      const unsigned s0 = tb * pr / hv, e0 = tb * (pr + 1) / hv;
+      const unsigned mid = s0 + (e0 - s0) * (unsigned)p.num / (unsigned)p.den;
+      u = (int)(w < hv ? s0 : mid);
+      u1 = (int)(w < hv ? mid : e0);
     } else {
       u = (int)(tb * w / gridDim.x);
       u1 = (int)(tb * (w + 1) / gridDim.x);
@@ -241,6 +245,15 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
   };
   using std::integral_constant;
   decode(u);
+  // The first filter bank is requested before the first band: loads return in order, and at the start of the
+  // launch every workgroup's band fetch (20 MB over the chip) would otherwise stand between a workgroup and the
+  // 9 KB it needs before anything else can begin.
+  float wpre[WPT];
+  {
+    const float* wg = p.W1 + (int64_t)g * WN;
+#pragma unroll
+    for (int j = 0; j < WPT; j++) wpre[j] = wg[tid + j * WG_THREADS];
+  }
   set_fetch(img, b);
   fetch_piece(integral_constant<int, 0>{});
   fetch_piece(integral_constant<int, 1>{});
@@ -259,16 +272,26 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
     // channels 4w..4w+3 and the four share their dwords through LDS: record (kh, k) of a lane at
     // arec + ((kh*4 + k)*64 + lane)*16, dword w.
     if (g != g_bank) {
+      if (g_bank >= 0) {  // a later bank of the run (the first one is already on its way)
+        const float* wg = p.W1 + (int64_t)g * WN;
+#pragma unroll
+        for (int j = 0; j < WPT; j++) wpre[j] = wg[tid + j * WG_THREADS];
+      }
       g_bank = g;
       __syncthreads();  // slower wavefronts may still be reading their output staging in this buffer
       float* wl = reinterpret_cast<float*>(gi8_lds + (it & 1) * BUF);
       char* arec = reinterpret_cast<char*>(wl) + 16384;
       static_assert(WN * 4 <= 16384 && 16384 + KH * 4 * WAVE * 16 <= BUF, "scratch must fit one band buffer");
-      const float* wg = p.W1 + (int64_t)g * WN;
+      // filter rows are WROW floats apart (odd): the 16 rows that the lanes of a read address fall into 16 banks
+      constexpr int WROW = C * KH * KW + 1;
+      static_assert(F * WROW * 4 <= 16384, "padded filter bank must end before the digit records");
 #pragma unroll
-      for (int j = 0; j < WPT; j++) wl[tid + j * WG_THREADS] = wg[tid + j * WG_THREADS];
+      for (int j = 0; j < WPT; j++) {
+        const int i = tid + j * WG_THREADS, f = i / (C * KH * KW);
+        wl[i + f] = wpre[j];
+      }
       __syncthreads();
-      const float* wp = wl + r16 * (C * KH * KW) + kwq;
+      const float* wp = wl + r16 * WROW + kwq;
       unsigned m = 0;
 #pragma unroll
       for (int kh = 0; kh < KH; kh++)
@@ -334,10 +357,10 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
       {
         const double scale = __hiloint2double((1023 + 30 - eb) << 20, 0);  // 2^(30-eb)
         auto put = [&](float x0, float x1, float x2, float x3, int cg, int pixel) {  // 4 channels of one pixel
-          // v + 0x00808080 makes byte k digit k plus 128; flipping bit 7 of bytes 0..2 afterwards gives the digits,
+          // v + 0x00808080 (added inside the rounding) makes byte k digit k plus 128; flipping bit 7 of bytes 0..2 afterwards gives the digits,
           // and that flip commutes with the byte transpose: three instructions per four elements instead of four
-          int d[4] = {i8_fixed(x0, scale) + 0x00808080, i8_fixed(x1, scale) + 0x00808080,
-                      i8_fixed(x2, scale) + 0x00808080, i8_fixed(x3, scale) + 0x00808080}, y[4];
+          int d[4] = {i8_fixed<0x00808080>(x0, scale), i8_fixed<0x00808080>(x1, scale),
+                      i8_fixed<0x00808080>(x2, scale), i8_fixed<0x00808080>(x3, scale)}, y[4];
           i8_transpose4(d, y);
 #pragma unroll
           for (int k = 0; k < 4; k++)

@@ -272,6 +272,7 @@ bool try_gconv_i8(const GconvArgs& g, hipStream_t s, tc_status* st) {
   const int64_t bands = (int64_t)g.N * g.G * ((g.H - (Gm::KH - 1)) / ROWS);
   if (bands >= (1ll << 31)) return false;
   const int64_t grid = std::min<int64_t>(bands, 2 * (int64_t)device_cus());  // persistent: two workgroups per compute unit
+  if (bands * (grid + 1) >= (1ll << 31)) return false;  // the kernel splits the bands in 32-bit arithmetic
   static std::atomic<int> lds_ok{0};  // more than the default 64 KiB of dynamic LDS
   if (!lds_ok.load(std::memory_order_acquire)) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(gconv_i8_kernel<W, ROWS>),
