@@ -12,6 +12,12 @@ float64 CPU oracle timed on the host cores on a bounded sample of the same
 workload.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+`--sustain SECONDS` (supplementary) runs the grouped convolution, a plain copy
+and the whole step back to back and prints the launch time beside the board's
+power and clock sensors: the int8 grouped convolution runs at the board's
+power limit, so its time depends on what ran in the tens of milliseconds
+before it.
 """
 from __future__ import annotations
 
@@ -39,13 +45,21 @@ GCONV_I8_PRODUCTS = 13
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--op-reps", type=int, default=200, help="launches per operator in the per-operator timing loops")
+    # The defaults run long enough for the board's power management to settle (the shader clock needs about 50 ms
+    # of load to come up from idle and, under the grouped convolution, settles at the 1400 W power limit): the
+    # warm-up is 80 ms and the timed region 0.3 s.
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=500)
+    ap.add_argument("--op-reps", type=int, default=1000, help="launches per operator in the per-operator timing loops")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--scaling", action="store_true",
                     help="supplementary: time tbmm, the MLP and the Kronecker layer at 1x, 8x and 64x the benchmark "
                          "batch (one JSON line per point), to separate launch/latency floors from kernel throughput")
+    ap.add_argument("--sustain", type=float, default=0.0, metavar="SECONDS",
+                    help="supplementary: run the grouped convolution (both arithmetic paths), a plain copy of its "
+                         "input and the whole step back to back for SECONDS each and report the launch time next to "
+                         "the board's power, power limit and shader clock (amdgpu sysfs sensors, read-only): one "
+                         "JSON line per leg")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="only launch the grouped convolution and a plain 512 MiB device copy a few times (for "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs; the copy calibrates the counters)")
@@ -115,6 +129,10 @@ def main():
                           "gconv_algorithmic_bytes": ops["gconv"][2]}), flush=True)
         return
 
+    if args.sustain > 0:
+        sustained_study(torch, tc355, ops, Ig, (W1g, bg, Og), args.sustain)
+        return
+
     def step(ev=None):
         ops["tbmm"][0]()
         ops["mlp"][0]()
@@ -173,24 +191,13 @@ def main():
     Xt = torch.randn((1, 128, 4096), device="cuda")
     Yt = torch.randn((1, 16384, 4096), device="cuda")
     Zt = torch.empty((1, 128, 16384), device="cuda")
-    for _ in range(3):
-        tc355.tc_tbmm(Xt, Yt, Zt)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(20):
-        tc355.tc_tbmm(Xt, Yt, Zt)
-    e1.record()
-    torch.cuda.synchronize()
-    tmm_us = e0.elapsed_time(e1) * 1e3 / 20
-    tmm_flops = inputs.flops_tbmm(1, 128, 16384, 4096)
-    extra = {"tmm_128x4096x16384": {"us": round(tmm_us, 1), "gflops": round(tmm_flops / tmm_us * 1e-3, 1),
-                                    "bound": "mfma",
-                                    "frac": round(tmm_flops / (PEAK_F64_MFMA_TFLOPS * 1e12) * 1e6 / tmm_us, 4)}}
-    # the other workloads of the paper's Section 7 tables, through the same entry points (fp64 matrix path)
     def timed(fn, reps=20):
-        for _ in range(3):
-            fn()
+        # 50 ms of the same launches first: the shader clock follows the load of the last tens of milliseconds
+        t_end = time.perf_counter() + 0.05
+        while time.perf_counter() < t_end:
+            for _ in range(5):
+                fn()
+            torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         e0.record()
@@ -200,6 +207,12 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / reps
 
+    tmm_us = timed(lambda: tc355.tc_tbmm(Xt, Yt, Zt))
+    tmm_flops = inputs.flops_tbmm(1, 128, 16384, 4096)
+    extra = {"tmm_128x4096x16384": {"us": round(tmm_us, 1), "gflops": round(tmm_flops / tmm_us * 1e-3, 1),
+                                    "bound": "mfma",
+                                    "frac": round(tmm_flops / (PEAK_F64_MFMA_TFLOPS * 1e12) * 1e6 / tmm_us, 4)}}
+    # the other workloads of the paper's Section 7 tables, through the same entry points (fp64 matrix path)
     def entry(us, flops, nbytes):
         t_mfma, t_hbm = flops / (PEAK_F64_MFMA_TFLOPS * 1e12), nbytes / (PEAK_HBM_GBS * 1e9)
         return {"us": round(us, 1), "gflops": round(flops / us * 1e-3, 1), "bound": "mfma" if t_mfma >= t_hbm else "hbm",
@@ -261,17 +274,8 @@ def main():
 
     # the grouped convolution on the fp64 matrix path (what every other shape of the operator takes), for comparison
     os.environ["TC355_GCONV_ARITH"] = "f64"
-    for _ in range(3):
-        ops["gconv"][0]()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(20):
-        ops["gconv"][0]()
-    e1.record()
-    torch.cuda.synchronize()
+    g64_us = timed(ops["gconv"][0])
     del os.environ["TC355_GCONV_ARITH"]
-    g64_us = e0.elapsed_time(e1) * 1e3 / 20
     extra["gconv_cfg4_fp64_path"] = {"us": round(g64_us, 1), "gflops": round(ops["gconv"][1] / g64_us * 1e-3, 1), "bound": "mfma",
                                      "frac": round(ops["gconv"][1] / (PEAK_F64_MFMA_TFLOPS * 1e12) * 1e6 / g64_us, 4)}
 
@@ -329,6 +333,76 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inputs, Ih, Wsh, bsh)
     print(json.dumps(out), flush=True)
+
+
+def board_sensors():
+    """Power (W), power limit (W) and shader clock (MHz) of the first amdgpu card, from sysfs; missing ones are None.
+    The driver's figures are moving averages: they settle about half a second after the load changes."""
+    import glob
+    out = {"power_w": None, "power_cap_w": None, "sclk_mhz": None}
+    for hw in sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*")):
+        for key, name in (("power_w", "power1_input"), ("power_w", "power1_average"), ("power_cap_w", "power1_cap")):
+            try:
+                if out[key] is None:
+                    out[key] = int(open(os.path.join(hw, name)).read()) / 1e6
+            except (OSError, ValueError):
+                pass
+        break
+    for dev in sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk")):
+        try:
+            cur = [ln for ln in open(dev).read().splitlines() if ln.rstrip().endswith("*")]
+            m = re.search(r"(\d+)\s*Mhz", cur[0]) if cur else None
+            out["sclk_mhz"] = int(m.group(1)) if m else None
+        except OSError:
+            pass
+        break
+    return out
+
+
+def sustained_study(torch, tc355, ops, Ig, gconv_tensors, seconds):
+    """Launch time under sustained load next to the board's power and clock sensors."""
+    Icopy = torch.empty_like(Ig)
+
+    def gconv_fp64():
+        os.environ["TC355_GCONV_ARITH"] = "f64"
+        try:
+            ops["gconv"][0]()
+        finally:
+            del os.environ["TC355_GCONV_ARITH"]
+
+    def whole_step():
+        for name in ("tbmm", "mlp", "gconv", "kron"):
+            ops[name][0]()
+
+    # the same launch with all-zero weights: same instructions, same memory traffic, but the multipliers see zeros
+    # on one side, the board stays under its power limit and the clock at its nominal value
+    W1g, bg, Og = gconv_tensors
+    Wzero = torch.zeros_like(W1g)
+    legs = [("gconv_int8_path", ops["gconv"][0]),
+            ("gconv_int8_path_zero_weights", lambda: tc355.tc_group_conv(Ig, Wzero, bg, Og)),
+            ("gconv_fp64_path", gconv_fp64),
+            ("copy_of_gconv_input", lambda: Icopy.copy_(Ig)), ("whole_step", whole_step)]
+    idle = board_sensors()
+    for name, fn in legs:
+        fn()
+        torch.cuda.synchronize()
+        t_end = time.time() + seconds
+        windows = []
+        while time.time() < t_end:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(200):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            windows.append(e0.elapsed_time(e1) * 1e3 / 200)
+        sens = board_sensors()  # read while the last window's heat is still in the averages
+        tail = windows[-max(1, len(windows) // 4):]
+        print(json.dumps({"sustained": name, "seconds": seconds, "us_per_launch_first_window": round(windows[0], 1),
+                          "us_per_launch_last_quarter": round(sum(tail) / len(tail), 1), "launches": 200 * len(windows),
+                          **{k: (round(v, 0) if v is not None else None) for k, v in sens.items()},
+                          "idle_power_w": idle["power_w"]}), flush=True)
+        time.sleep(1.0)  # let the averages fall back before the next leg
 
 
 def scaling_study(torch, tc355, inputs):
