@@ -24,7 +24,7 @@
  *    is rounded once to fp32.  Values handed from one stage of a chain to the
  *    next stay in fp64.  One exception, see tc_group_conv: the 16-channel
  *    3 x 3 grouped convolution of width 58 sums exactly in integers over
- *    operands quantised to 2^-30 of their block maximum.
+ *    operands quantised to 2^-32 of their block maximum.
  *  - Validation precedes any launch: on a non-zero status nothing was written.
  *    A batch extent of 0 returns TC_OK without launching.
  *  - Thread safety: the only mutable global state is a per-process cache of
@@ -128,13 +128,15 @@ size_t tc_mlp_fcrelu_workspace_bytes(int64_t batch, int32_t n_layers,
  * Arithmetic: fp64 as everywhere, except for C = F = 16, KH = KW = 3, W = 58,
  * H even with H - 2 a multiple of 8 (the benchmark's geometry), which runs on
  * the int8 matrix core: every filter row and every band of 10 input rows is
- * scaled by a power of two to 31-bit fixed point (exact for elements within
- * 2^-6 of the block's largest magnitude, to 2^-30 of that magnitude below),
- * cut into four signed 8-bit digits, and the 13 leading digit products are
- * summed exactly in int32; the result is recombined in fp64, the bias added,
- * and rounded to fp32 once.  Error against the float64 definition: at most
- * K * 2^-29 * max|filter row| * max|band| in absolute terms for a reduction of
- * K terms, in practice (random operands) about 4e-7 on the parity metric
+ * scaled to 32-bit fixed point (the block's largest magnitude maps to
+ * 0x7F7F7F7E, every element is held to 2^-32 of that magnitude), cut into
+ * four signed 8-bit digits, and the 10 leading digit products (k + l >= 3)
+ * are summed exactly in int32; the result is recombined in fp64, the bias
+ * added, and rounded to fp32 once.  Error against the float64 definition: at
+ * most K * 2^-29.5 * max|filter row| * max|band| in absolute terms for a
+ * reduction of K terms (2^-31 from the rounding of the two operands, the rest
+ * from the dropped digit products), in practice (random operands) about 1e-6
+ * on the parity metric
  * max|err| / (|ref| + 1e-3 max|ref|).  A band that holds Inf or NaN gives NaN
  * in all outputs that read the band.
  */

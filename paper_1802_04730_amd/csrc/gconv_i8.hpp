@@ -4,24 +4,31 @@
 //   O(n,g,o,h,w) = sum_{i,kh,kw} I(n,g,i,h+kh,w+kw) * W1(g,o,i,kh,kw) + bias(g*F+o)
 //
 // The fp64 matrix instruction delivers 16 multiply-adds per clock and SIMD, the
-// int8 one 1024.  This kernel therefore evaluates the contraction in exact
-// integer arithmetic on slices of the operands:
+// int8 one 1024.  This kernel therefore evaluates the contraction in integer
+// arithmetic on slices of the operands:
 //   * every fp32 operand x of a block (one filter row of W1; one band of input
-//     rows) is written as a 31-bit fixed-point number relative to the block's
-//     largest magnitude, v = rint(x * 2^(30-e)) with max|x| < 2^e, and v is split
-//     into four signed 8-bit digits, v = sum_k d_k 256^k.  Elements within 2^-6
-//     of the block maximum are represented exactly, smaller ones to 2^-30 of it;
-//   * a product of two operands is sum_{k,l} a_k b_l 256^(k+l); the 13 digit
-//     pairs with k + l >= 2 are kept (the dropped ones are below 2^-35 of the
-//     product of the block maxima).  Each pair is one int8 MFMA accumulation in int32,
-//     which is exact (no rounding, any order), one accumulator per diagonal k + l;
-//   * the five diagonals are combined exactly (int32 shifts, then fp64), scaled
-//     by 2^(ea+eb-36), the bias is added in fp64, and the sum is rounded to fp32
-//     once.
+//     rows) is written as a 32-bit fixed-point number relative to the block's
+//     largest magnitude m, v = rint(x * S / m) with S = 0x7F7F7F7E, the largest
+//     value (less one) that four signed 8-bit digits can hold, and v is split
+//     into those digits, v = sum_k d_k 256^k: every element is represented to
+//     2^-32 of the block maximum;
+//   * a product of two operands is sum_{k,l} a_k b_l 256^(k+l); the 10 digit
+//     pairs with k + l >= 3 are kept.  What is dropped is at most 3 * 2^-32 of
+//     the product of the two block maxima per term (2^-33 typically), the size
+//     of the quantisation error itself.  Each pair is one int8 MFMA
+//     accumulation in int32, which is exact (no rounding, any order), one
+//     accumulator per diagonal k + l;
+//   * the four diagonals are combined exactly (int32 shifts, then fp64), scaled
+//     by 2^24 * (m_a / S) * (m_b / S) in fp64, the bias is added in fp64, and
+//     the sum is rounded to fp32 once.
 // Against the float64 definition the result differs by the input quantisation
-// only: measured 4e-7 on the parity metric at the benchmark's distribution (the
-// bar is 2e-5), ~1e-9 relative on outputs of typical magnitude.  A band whose
-// inputs contain Inf/NaN yields NaN for all of that band's outputs.
+// and the dropped digit pairs: measured 1e-6 on the parity metric at the
+// benchmark's distribution (the bar is 2e-5), ~1e-9 relative on outputs of
+// typical magnitude.  (Scaling by a power of two and keeping the 13 pairs with
+// k + l >= 2 measures 3e-7 there and no better on heavy-tailed data, for 30 %
+// more matrix work; on this kernel, which runs at the board's power limit, that
+// is 8 % of the time.)  A band whose inputs contain Inf/NaN yields NaN for all
+// of that band's outputs.
 //
 // MFMA v_mfma_i32_16x16x64_i8, lane = (r16 = lane % 16, q = lane / 16), measured:
 //   A (16 x 64): lane supplies A[row r16][k = 16q .. 16q+15]  (16 bytes)
@@ -29,7 +36,7 @@
 //   D (16 x 16): lane holds D[row 4q + v][col r16], v = 0..3
 // Here rows are the 16 filters, columns are 16 output pixels of one image row,
 // and the 64 reduction slots of one instruction are (kw = q, channel = byte):
-// slot group q = 3 is padding (A holds zeros there).  One "group" of 13 MFMAs
+// slot group q = 3 is padding (A holds zeros there).  One "group" of 10 MFMAs
 // therefore covers one filter row kh for a 16-pixel tile, and the B operand of
 // input row r is shared by the output rows r, r-1 and r-2.
 //
@@ -100,16 +107,23 @@ struct GconvI8Geom {
   static_assert(F * C * KH * KW * 4 <= BUF, "filter bank scratch must fit one band buffer");
 };
 
-// x -> four signed digits of rint(x * 2^sh), one per byte (byte k = digit of weight 256^k).
-__device__ __forceinline__ int i8_digits(float x, int sh) {
-  const int v = (int)__builtin_rintf(ldexpf(x, sh));  // exact: |.| <= 2^30
-  return (v + 0x00808080) ^ 0x00808080;
+// Fixed-point scale of a block: the block's largest magnitude (bit pattern mbits, sign cleared) maps to I8_FULL.
+constexpr double I8_FULL = 2139062142.0;              // 0x7F7F7F7E: four digits of 127, less one for the rounding
+constexpr double I8_INV_FULL = 1.0 / 2139062142.0;
+__device__ __forceinline__ bool i8_nonfinite(unsigned mbits) { return mbits >= 0x7f800000u; }
+// scale with rint(m * scale) <= I8_FULL + 1; an all-zero block takes any scale
+__device__ __forceinline__ double i8_scale(unsigned mbits) {
+  return mbits ? I8_FULL / (double)__uint_as_float(mbits) : 1.0;
+}
+// 1 / scale to three roundings (the product scale * inverse differs from 1 by 3 * 2^-53 at most); NaN for Inf/NaN
+__device__ __forceinline__ double i8_inverse_scale(unsigned mbits) {
+  return i8_nonfinite(mbits) ? __longlong_as_double(0x7ff8000000000000ll) : (double)__uint_as_float(mbits) * I8_INV_FULL;
 }
 
-// The same rounding for the hot loop, two instructions instead of three: x * 2^sh + 1.5 * 2^52 in fp64 (one fused
-// operation, exact product, round to nearest even) leaves rint(x * 2^sh) in the low word of the sum for |.| < 2^31.
-// scale = 2^sh as a double.  An even integer `plus` < 2^31 added to the constant comes out added to the result
-// (mod 2^32) for free: the sum is still an integer plus the product, and ties still go to the even neighbour.
+// rint(x * scale) as the low word of x * scale + 1.5 * 2^52 in fp64 (one fused operation: exact product, one
+// rounding to nearest even), for |x * scale| < 2^31.  An even integer `plus` < 2^31 added to the constant comes out
+// added to the result (mod 2^32) for free: the sum is still an integer plus the product, and ties still go to the
+// even neighbour.
 template <int plus = 0>
 __device__ __forceinline__ int i8_fixed(float x, double scale) {
   static_assert(plus >= 0 && plus % 2 == 0, "an even offset keeps round-to-nearest-even on the product");
@@ -125,15 +139,6 @@ __device__ __forceinline__ unsigned i8_max3(unsigned a, unsigned b, unsigned c) 
   unsigned d;
   asm("v_max3_u32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
   return d;
-}
-
-// Exponent e with m < 2^e for the magnitude whose bit pattern is mbits (sign cleared), denormals included; 129 for
-// Inf/NaN.  A block scaled by it fills bit 29 of the fixed-point numbers, so that the digit pairs that are dropped
-// stay 2^-35 below the leading ones.
-constexpr int I8_NONFINITE = 129;
-__device__ __forceinline__ int i8_exponent(unsigned mbits) {
-  const int biased = (int)(mbits >> 23);
-  return biased ? biased - 126 : (32 - __clz((int)mbits)) - 149;
 }
 
 // 4 x 4 byte transpose: x[c] holds the 4 digits of channel c; y[k] receives digit k of the 4 channels.
@@ -260,7 +265,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
   fetch_piece(integral_constant<int, 2>{});
 
   i4 a[KH][4];     // a[kh][k]: digit k of W1[g][r16][c = byte][kh][kw = q], zeros for q = 3
-  int ea_v[4];     // exponent of filter row 4q + v
+  double fa[4];    // 2^24 / scale of filter row 4q + v (NaN if the row holds Inf/NaN)
   float bz[4];     // bias of filter row 4q + v
   int it = 0;      // bands staged so far by this workgroup: LDS buffer parity
   int g_bank = -1; // group whose filter bank the A operands hold
@@ -299,12 +304,13 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
         for (int c = 0; c < C; c++) m = max(m, __float_as_uint(wp[c * (KH * KW) + kh * KW]) & 0x7fffffffu);
       m = max(m, (unsigned)__shfl_xor((int)m, 16));
       m = max(m, (unsigned)__shfl_xor((int)m, 32));
-      const int ea = i8_exponent(m);  // max|w| < 2^ea over the filter row
+      const double sa = i8_scale(m);  // m = max|w| over the filter row
 #pragma unroll
       for (int kh = 0; kh < KH; kh++) {
         int d[4], y[4];
 #pragma unroll
-        for (int c = 0; c < 4; c++) d[c] = i8_digits(wp[(4 * wave + c) * (KH * KW) + kh * KW], 30 - ea);
+        for (int c = 0; c < 4; c++)
+          d[c] = i8_fixed<0x00808080>(wp[(4 * wave + c) * (KH * KW) + kh * KW], sa) ^ 0x00808080;  // byte k = digit k
         i8_transpose4(d, y);
 #pragma unroll
         for (int k = 0; k < 4; k++)
@@ -317,7 +323,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
         for (int k = 0; k < 4; k++) a[kh][k] = *reinterpret_cast<const i4*>(arec + ((kh * 4 + k) * WAVE + lane) * 16);
 #pragma unroll
       for (int v = 0; v < 4; v++) {
-        ea_v[v] = __shfl(ea, 4 * q + v);  // lane 4q+v holds filter row 4q+v
+        fa[v] = 16777216.0 * i8_inverse_scale((unsigned)__shfl((int)m, 4 * q + v));  // lane 4q+v holds filter row 4q+v
         bz[v] = p.bias ? p.bias[g * F + 4 * q + v] : 0.f;
       }
       // the staging below overwrites this scratch only after the next barrier, which every wavefront reaches after these reads
@@ -351,11 +357,13 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
       __syncthreads();
       TC355_TRACE_R(trace, 3);
       m = max(max(maxw[(it & 1) * 4 + 0], maxw[(it & 1) * 4 + 1]), max(maxw[(it & 1) * 4 + 2], maxw[(it & 1) * 4 + 3]));
-      const int eb = __builtin_amdgcn_readfirstlane(i8_exponent(m));  // max|x| < 2^eb over the band
+      m = (unsigned)__builtin_amdgcn_readfirstlane((int)m);  // max|x| over the band
 
       // ---- slice and stage: digit plane k, record of pixel pi at byte k*PLANE + 16*pi, channels 4cg.. at +4cg
       {
-        const double scale = __hiloint2double((1023 + 30 - eb) << 20, 0);  // 2^(30-eb)
+        const double sv = i8_scale(m);  // the same in every lane: kept in scalar registers
+        const double scale = __hiloint2double(__builtin_amdgcn_readfirstlane(__double2hiint(sv)),
+                                              __builtin_amdgcn_readfirstlane(__double2loint(sv)));
         auto put = [&](float x0, float x1, float x2, float x3, int cg, int pixel) {  // 4 channels of one pixel
           // v + 0x00808080 (added inside the rounding) makes byte k digit k plus 128; flipping bit 7 of bytes 0..2 afterwards gives the digits,
           // and that flip commutes with the byte transpose: three instructions per four elements instead of four
@@ -390,13 +398,12 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
         decode(u + 1);
         set_fetch(img, b);
       }
-      // 2^(ea+eb-36) per filter row of this lane: high word of the fp64 bit pattern; NaN if the band or the row holds Inf/NaN
-      int scale_hi[4];
+      // what one unit of the combined diagonals is worth, per filter row of this lane; NaN if the band or the row
+      // holds Inf/NaN
+      const double invb = i8_inverse_scale(m);
+      double fo[4];
 #pragma unroll
-      for (int v = 0; v < 4; v++) {
-        const bool bad = eb == I8_NONFINITE || ea_v[v] == I8_NONFINITE;
-        scale_hi[v] = bad ? 0x7ff80000 : (1023 + ea_v[v] + eb - 36) << 20;
-      }
+      for (int v = 0; v < 4; v++) fo[v] = fa[v] * invb;
 
       const int h0 = b_now * ROWS + 2 * wave;  // first output row of this wavefront in this band
       // Outputs are staged per wavefront in the idle band buffer as [filter][2 rows][OW] and written out after the
@@ -409,11 +416,11 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
       // row and its column.  PIECE: the fetch piece of the next band to issue during this sweep, or -1.
       auto sweep = [&](auto nr_c, auto piece_c, auto col_c, const char* base, char* obase) {
         constexpr int NR = decltype(nr_c)::value, PIECE = decltype(piece_c)::value, COL = decltype(col_c)::value;
-        i4 acc[NR][5];
+        i4 acc[NR][4];  // diagonals k + l = 3 .. 6
 #pragma unroll
         for (int hl = 0; hl < NR; hl++)
 #pragma unroll
-          for (int d = 0; d < 5; d++) acc[hl][d] = i4{0, 0, 0, 0};
+          for (int d = 0; d < 4; d++) acc[hl][d] = i4{0, 0, 0, 0};
         i4 bc[4], bn[4];
 #pragma unroll
         for (int l = 0; l < 4; l++) bc[l] = *reinterpret_cast<const i4*>(base + l * PLANE);
@@ -429,14 +436,15 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
           // pin "reads of row r+1, then MFMAs of row r"
           __builtin_amdgcn_sched_barrier(0);
           // digit pairs (k of the weights, l of the input), ordered so that consecutive MFMAs hit different diagonals
-          constexpr int PK[13] = {3, 3, 3, 3, 2, 2, 2, 2, 1, 1, 1, 0, 0};
-          constexpr int PL[13] = {3, 2, 1, 0, 0, 3, 2, 1, 1, 3, 2, 2, 3};
+          constexpr int NP = 10;
+          constexpr int PK[NP] = {3, 3, 3, 3, 2, 2, 2, 1, 1, 0};
+          constexpr int PL[NP] = {3, 2, 1, 0, 3, 2, 1, 3, 2, 3};
 #pragma unroll
-          for (int i = 0; i < 13; i++)
+          for (int i = 0; i < NP; i++)
 #pragma unroll
             for (int hl = 0; hl < NR; hl++) {
               const int kh = r - hl;
-              if (kh >= 0 && kh < KH) acc[hl][PK[i] + PL[i] - 2] = mfma_i8(a[kh][PK[i]], bc[PL[i]], acc[hl][PK[i] + PL[i] - 2]);
+              if (kh >= 0 && kh < KH) acc[hl][PK[i] + PL[i] - 3] = mfma_i8(a[kh][PK[i]], bc[PL[i]], acc[hl][PK[i] + PL[i] - 3]);
             }
 #pragma unroll
           for (int l = 0; l < 4; l++) bc[l] = bn[l];
@@ -452,12 +460,12 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
         for (int hl = 0; hl < NR; hl++) {
 #pragma unroll
           for (int v = 0; v < 4; v++) {
-            const int hi = acc[hl][4][v] * 256 + acc[hl][3][v];  // |.| < 2^28
-            const int lo = acc[hl][2][v] * 256 + acc[hl][1][v];  // |.| < 2^31
-            double rr = __builtin_fma((double)hi, 65536.0, (double)lo);  // sum_d P_d 256^(d-3), exact
-            rr = __builtin_fma((double)acc[hl][0][v], 0.00390625, rr);
+            // |P_6| <= 144 * 2^14, |P_5| <= 2 * 144 * 2^14, |P_4| <= 3 * 144 * 2^14, |P_3| <= 4 * 144 * 2^14
+            const int hi = acc[hl][3][v] * 256 + acc[hl][2][v];  // |.| < 2^30
+            const int lo = acc[hl][1][v] * 256 + acc[hl][0][v];  // |.| < 2^31
+            const double rr = __builtin_fma((double)hi, 65536.0, (double)lo);  // sum_d P_d 256^(d-3), exact
             *reinterpret_cast<float*>(obase + (v * Gm::OSF + hl * OW + COL) * 4) =
-                (float)__builtin_fma(rr, __hiloint2double(scale_hi[v], 0), (double)bz[v]);
+                (float)__builtin_fma(rr, fo[v], (double)bz[v]);
           }
         }
       };
