@@ -147,6 +147,7 @@ __device__ __forceinline__ void mlp_layer(const TA* __restrict__ A, const float*
                                           const float* __restrict__ bias, float* __restrict__ O,
                                           double* __restrict__ act, int batch, int K, int M, char* smem,
                                           unsigned long long* trace) {
+  TC355_TRACE_RESUME(trace)
   constexpr bool A64 = sizeof(TA) == 8;
   constexpr int KC = MLP_KC, NR = 4;
   constexpr int RSA = A64 ? MLP_RS_D : MLP_RS_F;  // row stride of the A stage, in elements of TA
@@ -241,7 +242,7 @@ __device__ __forceinline__ void mlp_layer(const TA* __restrict__ A, const float*
   Regs ring[NR];
 #pragma unroll
   for (int i = 0; i < NR; i++) load_next(ring[i]);
-  TC355_TRACE(trace, 2);
+  TC355_TRACE_R(trace, 2);
 
   // Chunk t of the stream sits in ring[t % NR] until it is staged into LDS buffer t % 2.
   // Iteration t stages chunk t+1 (LDS writes and the next global loads are only issued
@@ -284,12 +285,12 @@ __device__ __forceinline__ void mlp_layer(const TA* __restrict__ A, const float*
           stage(ring[(i + 1) % NR], smem + ((i + 1) & 1) * MLP_BUF_BYTES);
           load_next(ring[(i + 1) % NR]);
         }
-        TC355_TRACE(trace, 3);
+        TC355_TRACE_R(trace, 3);
 #pragma unroll
         for (int j = 0; j < KC / 64; j++)
 #pragma unroll
           for (int e = 0; e < 4; e++) acc = mfma_f64((double)av[j].e[e], (double)bv[j].e[e], acc);
-        TC355_TRACE(trace, 4);
+        TC355_TRACE_R(trace, 4);
         const bool last = (++ck == nck);
         d4* part = part_base + parity * (WAVES_PER_WG * WAVE);
         if (last) part[wave * WAVE + lane] = acc;
@@ -311,7 +312,7 @@ __device__ __forceinline__ void mlp_layer(const TA* __restrict__ A, const float*
             if (O) O[o] = (float)x;
             if (act) act_store(act + o, x);
           }
-          TC355_TRACE(trace, 5);
+          TC355_TRACE_R(trace, 5);
           ck = 0;
           parity ^= 1;
           job += step;
@@ -321,6 +322,7 @@ __device__ __forceinline__ void mlp_layer(const TA* __restrict__ A, const float*
       }
     }
   }
+  TC355_TRACE_FLUSH(trace);
   __syncthreads();  // the LDS stage is reused by the next layer
 }
 

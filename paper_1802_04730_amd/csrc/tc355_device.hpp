@@ -118,12 +118,15 @@ __device__ __forceinline__ Vec<T, V> load_vec(const T* p) {
     }                                                                                          \
   } while (0)
 #define TC355_TRACE_FLUSH(p_) do { if ((p_) && threadIdx.x == 0) (p_)[(size_t)blockIdx.x * 256] = trace_n_; } while (0)
+// continue a log that another function of the same kernel has flushed
+#define TC355_TRACE_RESUME(p_) unsigned long long trace_n_ = ((p_) && threadIdx.x == 0) ? (p_)[(size_t)blockIdx.x * 256] : 0;
 #else
 #define TC355_TRACE_FIELD
 #define TC355_TRACE(p_, tag_) do { } while (0)
 #define TC355_TRACE_DECL
 #define TC355_TRACE_R(p_, tag_) do { } while (0)
 #define TC355_TRACE_FLUSH(p_) do { } while (0)
+#define TC355_TRACE_RESUME(p_)
 #endif
 
 }  // namespace tc355
