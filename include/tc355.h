@@ -34,7 +34,8 @@
  *    forces one launch per MLP layer, =1 the single fused kernel (by default
  *    very large batches take one launch per layer); TC355_MLP_SPIN_LIMIT=<n> bounds the
  *    polls of a device-wide wait; TC355_GCONV_ARITH=f64 keeps every grouped
- *    convolution on the fp64 path.
+ *    convolution on the fp64 path, =i8x13 makes the int8 path keep 13 instead
+ *    of 10 digit products (see tc_group_conv).
  */
 #ifndef TC355_H
 #define TC355_H
@@ -137,8 +138,15 @@ size_t tc_mlp_fcrelu_workspace_bytes(int64_t batch, int32_t n_layers,
  * reduction of K terms (2^-31 from the rounding of the two operands, the rest
  * from the dropped digit products), in practice (random operands) about 1e-6
  * on the parity metric
- * max|err| / (|ref| + 1e-3 max|ref|).  A band that holds Inf or NaN gives NaN
- * in all outputs that read the band.
+ * max|err| / (|ref| + 1e-3 max|ref|).  The bound is relative to the block
+ * maxima: when both operands are heavy-tailed (a few elements far above the
+ * rest in every band and every filter row) the maxima say little about the
+ * outputs, and the dropped products come close to 2e-5 on that metric
+ * (1.6e-5 measured with log-normal magnitudes of sigma 1.5 and 1).  For such
+ * data TC355_GCONV_ARITH=i8x13 keeps the next diagonal of digit products
+ * (13 in all: 1.4e-6 on the same data, 16 % slower), and
+ * TC355_GCONV_ARITH=f64 takes the fp64 path.  A band that holds Inf or NaN
+ * gives NaN in all outputs that read the band.
  */
 tc_status tc_group_conv(const float *I, const float *W1, const float *bias,
                         float *O, int64_t N, int64_t G, int64_t C, int64_t F,

@@ -27,8 +27,12 @@
 // typical magnitude.  (Scaling by a power of two and keeping the 13 pairs with
 // k + l >= 2 measures 3e-7 there and no better on heavy-tailed data, for 30 %
 // more matrix work; on this kernel, which runs at the board's power limit, that
-// is 8 % of the time.)  A band whose inputs contain Inf/NaN yields NaN for all
-// of that band's outputs.
+// is 8 % of the time.)  What the dropped diagonal costs grows when BOTH operands
+// are heavy-tailed (a few elements far above the rest in every block): with
+// log-normal magnitudes of sigma 1.5 and 1 the 10 products measure 1.6e-5 and
+// 13 products at the same scaling 1.4e-6; the kernel can therefore be
+// instantiated with the diagonal k + l = 2 kept (MIND = 2).  A band whose
+// inputs contain Inf/NaN yields NaN for all of that band's outputs.
 //
 // MFMA v_mfma_i32_16x16x64_i8, lane = (r16 = lane % 16, q = lane / 16), measured:
 //   A (16 x 64): lane supplies A[row r16][k = 16q .. 16q+15]  (16 bytes)
@@ -168,8 +172,10 @@ __device__ __forceinline__ unsigned i8_wave_max(unsigned m) {
 
 __device__ __forceinline__ i4 mfma_i8(i4 a, i4 b, i4 c) { return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0); }
 
-template <int W, int ROWS>
+// MIND: the lowest digit diagonal k + l that is kept: 3 (10 products, the default) or 2 (13 products).
+template <int W, int ROWS, int MIND = 3>
 __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) {
+  static_assert(MIND == 2 || MIND == 3, "10 or 13 digit products");
   using Gm = GconvI8Geom<W, ROWS>;
   constexpr int C = Gm::C, F = Gm::F, KH = Gm::KH, KW = Gm::KW, OW = Gm::OW, PLANE = Gm::PLANE, BUF = Gm::BUF,
                 NFC = Gm::NFC, NHALF = Gm::NHALF;
@@ -416,11 +422,12 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
       // row and its column.  PIECE: the fetch piece of the next band to issue during this sweep, or -1.
       auto sweep = [&](auto nr_c, auto piece_c, auto col_c, const char* base, char* obase) {
         constexpr int NR = decltype(nr_c)::value, PIECE = decltype(piece_c)::value, COL = decltype(col_c)::value;
-        i4 acc[NR][4];  // diagonals k + l = 3 .. 6
+        constexpr int ND = 7 - MIND;
+        i4 acc[NR][ND];  // diagonals k + l = MIND .. 6
 #pragma unroll
         for (int hl = 0; hl < NR; hl++)
 #pragma unroll
-          for (int d = 0; d < 4; d++) acc[hl][d] = i4{0, 0, 0, 0};
+          for (int d = 0; d < ND; d++) acc[hl][d] = i4{0, 0, 0, 0};
         i4 bc[4], bn[4];
 #pragma unroll
         for (int l = 0; l < 4; l++) bc[l] = *reinterpret_cast<const i4*>(base + l * PLANE);
@@ -436,15 +443,16 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
           // pin "reads of row r+1, then MFMAs of row r"
           __builtin_amdgcn_sched_barrier(0);
           // digit pairs (k of the weights, l of the input), ordered so that consecutive MFMAs hit different diagonals
-          constexpr int NP = 10;
-          constexpr int PK[NP] = {3, 3, 3, 3, 2, 2, 2, 1, 1, 0};
-          constexpr int PL[NP] = {3, 2, 1, 0, 3, 2, 1, 3, 2, 3};
+          constexpr int NP = MIND == 3 ? 10 : 13;  // the last three pairs are the diagonal k + l = 2
+          constexpr int PK[13] = {3, 3, 3, 3, 2, 2, 2, 1, 1, 0, 2, 1, 0};
+          constexpr int PL[13] = {3, 2, 1, 0, 3, 2, 1, 3, 2, 3, 0, 1, 2};
 #pragma unroll
           for (int i = 0; i < NP; i++)
 #pragma unroll
             for (int hl = 0; hl < NR; hl++) {
               const int kh = r - hl;
-              if (kh >= 0 && kh < KH) acc[hl][PK[i] + PL[i] - 3] = mfma_i8(a[kh][PK[i]], bc[PL[i]], acc[hl][PK[i] + PL[i] - 3]);
+              if (kh >= 0 && kh < KH)
+                acc[hl][PK[i] + PL[i] - MIND] = mfma_i8(a[kh][PK[i]], bc[PL[i]], acc[hl][PK[i] + PL[i] - MIND]);
             }
 #pragma unroll
           for (int l = 0; l < 4; l++) bc[l] = bn[l];
@@ -461,9 +469,10 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
 #pragma unroll
           for (int v = 0; v < 4; v++) {
             // |P_6| <= 144 * 2^14, |P_5| <= 2 * 144 * 2^14, |P_4| <= 3 * 144 * 2^14, |P_3| <= 4 * 144 * 2^14
-            const int hi = acc[hl][3][v] * 256 + acc[hl][2][v];  // |.| < 2^30
-            const int lo = acc[hl][1][v] * 256 + acc[hl][0][v];  // |.| < 2^31
-            const double rr = __builtin_fma((double)hi, 65536.0, (double)lo);  // sum_d P_d 256^(d-3), exact
+            const int hi = acc[hl][ND - 1][v] * 256 + acc[hl][ND - 2][v];  // |.| < 2^30
+            const int lo = acc[hl][ND - 3][v] * 256 + acc[hl][ND - 4][v];  // |.| < 2^31
+            double rr = __builtin_fma((double)hi, 65536.0, (double)lo);  // sum_d P_d 256^(d-3), exact
+            if constexpr (MIND == 2) rr = __builtin_fma((double)acc[hl][0][v], 0.00390625, rr);
             *reinterpret_cast<float*>(obase + (v * Gm::OSF + hl * OW + COL) * 4) =
                 (float)__builtin_fma(rr, fo[v], (double)bz[v]);
           }

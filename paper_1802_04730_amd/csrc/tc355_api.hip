@@ -9,6 +9,7 @@
 #include <chrono>
 #include <cstdint>
 #include <cstdlib>
+#include <cstring>
 #include <random>
 #include <type_traits>
 
@@ -263,7 +264,7 @@ bool try_gconv_band(const GconvArgs& g, hipStream_t s, tc_status* st) {
 }
 
 // ---- grouped convolution on the int8 matrix core (sliced fixed-point operands, exact int32 sums) ----
-template <int W, int ROWS>
+template <int W, int ROWS, int MIND>
 bool try_gconv_i8(const GconvArgs& g, hipStream_t s, tc_status* st) {
   using Gm = GconvI8Geom<W, ROWS>;
   if (g.C != Gm::C || g.F != Gm::F || g.KH != Gm::KH || g.KW != Gm::KW || g.W != W) return false;
@@ -275,7 +276,7 @@ bool try_gconv_i8(const GconvArgs& g, hipStream_t s, tc_status* st) {
   if (bands * (grid + 1) >= (1ll << 31)) return false;  // the kernel splits the bands in 32-bit arithmetic
   static std::atomic<int> lds_ok{0};  // more than the default 64 KiB of dynamic LDS
   if (!lds_ok.load(std::memory_order_acquire)) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gconv_i8_kernel<W, ROWS>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gconv_i8_kernel<W, ROWS, MIND>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, Gm::LDS_BYTES) != hipSuccess) {
       *st = TC_ERR_LAUNCH;
       return true;
@@ -291,7 +292,7 @@ bool try_gconv_i8(const GconvArgs& g, hipStream_t s, tc_status* st) {
   a.halves = (grid == 2 * (int64_t)device_cus()) ? (int)(grid / 2) : 0;
   a.num = 3;
   a.den = 5;
-  gconv_i8_kernel<W, ROWS><<<dim3((unsigned)grid), dim3(WG_THREADS), Gm::LDS_BYTES, s>>>(a);
+  gconv_i8_kernel<W, ROWS, MIND><<<dim3((unsigned)grid), dim3(WG_THREADS), Gm::LDS_BYTES, s>>>(a);
   *st = launch_status();
   return true;
 }
@@ -466,10 +467,13 @@ tc_status tc_group_conv(const float* I, const float* W1, const float* bias, floa
   a.N = (int)N; a.G = (int)G; a.C = (int)C; a.F = (int)F; a.H = (int)H; a.W = (int)W;
   a.KH = (int)KH; a.KW = (int)KW; a.OH = (int)OH; a.OW = (int)OW;
   tc_status st = TC_OK;
-  // TC355_GCONV_ARITH=f64 keeps the fp64 matrix path for every shape
+  // TC355_GCONV_ARITH: unset or "i8" = the int8 path with 10 digit products where it applies; "i8x13" = the same
+  // with 13 (for operands that are both heavy-tailed, 16 % slower); "f64" = the fp64 matrix path for every shape
   const char* arith = std::getenv("TC355_GCONV_ARITH");
-  const bool i8 = !(arith && arith[0] == 'f');
-  if (i8 && try_gconv_i8<58, 8>(a, s, &st)) return st;
+  const bool f64_only = arith && arith[0] == 'f';
+  const bool thirteen = arith && std::strcmp(arith, "i8x13") == 0;
+  if (!f64_only && !thirteen && try_gconv_i8<58, 8, 3>(a, s, &st)) return st;
+  if (thirteen && try_gconv_i8<58, 8, 2>(a, s, &st)) return st;
   if (try_gconv_band<16, 3, 3, 58, 8, 2>(a, s, &st)) return st;
   if (try_gconv_band<16, 3, 3, 14, 12, 2>(a, s, &st)) return st;  // the paper's (32,32,16,16,14,14): the whole image is one band
   if (try_gconv_quad<4, 4, 3, 3, 56, 16, 4>(a, s, &st)) return st;    // the paper's (32,32,4,4,56,56)

@@ -303,6 +303,38 @@ def test_gconv_i8_extreme_magnitudes(tc, oracle_threads, in_exp, w_exp):
     assert err <= TIGHT_I8 * (4 if in_exp < -126 else 1)   # denormal inputs carry fewer bits themselves
 
 
+def test_gconv_i8_heavy_tailed_operands(tc, oracle_threads, monkeypatch):
+    """A few large elements in every band AND every filter row: the digit products that the default int8 path drops
+    (k + l = 2) then weigh most against the largest output.  The default path still meets the bar; with
+    TC355_GCONV_ARITH=i8x13 the diagonal is kept (tests/test_i8_scheme.py emulates both)."""
+    shape = (2, 3, 16, 16, 26, 58, 3, 3)
+    I, W1, bias = inputs.make_gconv(*shape, seed=11)
+    rng = np.random.default_rng(5)
+    I = (I * np.exp(rng.normal(size=I.shape) * 1.5)).astype(np.float32)     # log-normal magnitudes
+    W1 = (W1 * np.exp(rng.normal(size=W1.shape))).astype(np.float32)
+    ref = oracle.group_conv(I, W1, bias)
+    errs = {}
+    for arith in ("i8", "i8x13"):
+        monkeypatch.setenv("TC355_GCONV_ARITH", arith)
+        O = torch.full(ref.shape, float("nan"), device="cuda")
+        tc.tc_group_conv(dev(I), dev(W1), dev(bias), O)
+        torch.cuda.synchronize()
+        errs[arith] = parity_error(O.cpu().numpy().astype(np.float64), ref)
+        print("gconv %s, log-normal magnitudes: parity error %.3e" % (arith, errs[arith]), flush=True)
+    assert errs["i8"] <= PARITY_BAR, errs
+    assert errs["i8x13"] <= PARITY_BAR / 10, errs
+
+
+@pytest.mark.parametrize("shape", [(3, 5, 16, 16, 18, 58, 3, 3), (37, 29, 16, 16, 26, 58, 3, 3)])
+def test_gconv_i8_with_thirteen_digit_products(tc, shape, oracle_threads, monkeypatch):
+    monkeypatch.setenv("TC355_GCONV_ARITH", "i8x13")
+    I, W1, bias = inputs.make_gconv(*shape, seed=inputs.SEED_BASE + 4)
+    ref = oracle.group_conv(I, W1, bias)
+    O = torch.full(ref.shape, float("nan"), device="cuda")
+    tc.tc_group_conv(dev(I), dev(W1), dev(bias), O)
+    check(O, ref, "gconv int8 with 13 products %s" % (shape,), 1e-6)
+
+
 def test_gconv_without_bias(tc, oracle_threads):
     I, W1, _ = inputs.make_gconv(1, 3, 4, 6, 10, 9, 3, 3, seed=2)
     ref = oracle.group_conv(I, W1, None)

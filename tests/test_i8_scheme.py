@@ -113,6 +113,20 @@ def test_heavy_tailed_inputs_cost_the_full_range_scheme_nothing_extra():
     assert full10 <= PARITY_BAR / 2 and full10 <= 2 * pow13, (full10, pow13)
 
 
+def test_operands_that_are_both_heavy_tailed_are_what_the_thirteen_product_variant_is_for():
+    """Large elements in every band and every filter row: the block maxima are far above what sets the largest output,
+    and the dropped diagonal k + l = 2 (proportional to the product of the maxima) comes close to the bar; kept
+    (TC355_GCONV_ARITH=i8x13), the error is that of the quantisation alone."""
+    I, W1, bias = inputs.make_gconv(1, 2, 16, 16, 18, 58, 3, 3, seed=11)
+    rng = np.random.default_rng(5)
+    I = (I * np.exp(rng.normal(size=I.shape) * 1.5)).astype(np.float32)
+    W1 = (W1 * np.exp(rng.normal(size=W1.shape))).astype(np.float32)
+    ref = oracle.group_conv(I, W1, bias)
+    ten = parity_error(emulate(I, W1, bias, min_diagonal=3)[0], ref)
+    thirteen = parity_error(emulate(I, W1, bias, min_diagonal=2)[0], ref)
+    assert thirteen <= PARITY_BAR / 10 and ten <= 1.5 * PARITY_BAR and ten > 3 * thirteen, (ten, thirteen)
+
+
 def test_digit_decomposition_round_trips():
     rng = np.random.default_rng(1)
     v = rng.integers(-0x7F7F7F7F, 0x7F7F7F7F + 1, size=100000, dtype=np.int64)
