@@ -4,9 +4,9 @@
 //
 //   O_l(b,n) = max(0, bias_l(n) + sum_m In_l(b,m) * W_l(n,m)),   In_{l+1} = O_l
 //
-// Persistent kernel: `nwg` workgroups (two per compute unit, so that one's loads
-// and LDS staging overlap the other's MFMAs) stay resident for
-// all layers.  Within a layer, a workgroup takes 16x16 output tiles round-robin;
+// Persistent kernel: one workgroup of two teams of 4 wavefronts per compute unit (two
+// teams, so that one's loads and LDS staging overlap the other's MFMAs) stays
+// resident for all layers.  Within a layer, a team takes 16x16 output tiles round-robin;
 // its 4 wavefronts each fetch (16-byte loads kept several chunks ahead), stage in
 // LDS and contract a quarter of every chunk on the fp64 MFMA; the partial tiles are combined through LDS in a fixed
 // order, starting from the bias (the listing's first statement); the clamp is
@@ -146,7 +146,10 @@ template <typename TA, bool FC = true>
 __device__ __forceinline__ void mlp_layer(const TA* __restrict__ A, const float* __restrict__ Wl,
                                           const float* __restrict__ bias, float* __restrict__ O,
                                           double* __restrict__ act, int batch, int K, int M, char* smem,
-                                          unsigned long long* trace) {
+                                          unsigned long long* trace, int vwg, int vstep, int team0_jobs_if_team1) {
+  // vwg / vstep: this team's number among all teams of the grid and their count (a "team" = 4 wavefronts that own
+  // a tile together; a workgroup holds one or two); team0_jobs_if_team1: for the second team of a workgroup, the
+  // number of tiles its first team has in this layer (both must pass the same number of barriers), else -1
   TC355_TRACE_RESUME(trace)
   constexpr bool A64 = sizeof(TA) == 8;
   constexpr int KC = MLP_KC, NR = 4;
@@ -154,14 +157,14 @@ __device__ __forceinline__ void mlp_layer(const TA* __restrict__ A, const float*
   constexpr int AV = A64 ? 2 : 4;                 // elements of TA per 16-byte load
   constexpr int A_LOADS = 16 * KC / AV / WG_THREADS;  // 16-byte loads per thread and chunk: 4 (fp32) or 8 (fp64)
   constexpr int B_LOADS = 16 * KC / 4 / WG_THREADS;   // 4
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x & (WG_THREADS - 1);  // within the team
   const int lane = tid & (WAVE - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);  // wavefront-uniform, kept in a scalar register
   const int r16 = lane & 15, q = lane >> 4;
   const int tiles_n = (batch + 15) / 16, tiles_m = (M + 15) / 16;
   const int njobs = tiles_n * tiles_m;
   const int nck = (K + KC - 1) / KC;  // chunks per tile
-  const int step = gridDim.x;
+  const int step = vstep;
   d4* part_base = reinterpret_cast<d4*>(smem + 2 * MLP_BUF_BYTES);
   int parity = 0;  // partial-tile area alternates per tile, so a fast wavefront cannot overwrite one still being read
 
@@ -180,7 +183,7 @@ __device__ __forceinline__ void mlp_layer(const TA* __restrict__ A, const float*
   static_assert(WAVE / A_QU == WG_THREADS / A_UPR && WAVE / B_QU == WG_THREADS / B_UPR, "row step of unit i");
   // load cursor: which chunk of which tile the next global loads fetch; row offsets are
   // recomputed only when the tile changes
-  int ljob = blockIdx.x, lck = 0;
+  int ljob = vwg, lck = 0;
   int aoff[A_LOADS], boff[B_LOADS];
   auto point = [&]() {
     if (ljob >= njobs) return;
@@ -247,9 +250,9 @@ __device__ __forceinline__ void mlp_layer(const TA* __restrict__ A, const float*
   // Chunk t of the stream sits in ring[t % NR] until it is staged into LDS buffer t % 2.
   // Iteration t stages chunk t+1 (LDS writes and the next global loads are only issued
   // here) and then contracts chunk t, so both overlap the MFMAs; no barrier inside a tile.
-  const int my_jobs = (njobs > (int)blockIdx.x) ? (njobs - (int)blockIdx.x + step - 1) / step : 0;
+  const int my_jobs = (njobs > vwg) ? (njobs - vwg + step - 1) / step : 0;
   const int total = my_jobs * nck;  // chunks in this workgroup's stream
-  int job = blockIdx.x, ck = 0;
+  int job = vwg, ck = 0;
   d4 acc = d4_zero();
   double bz = (FC && job < njobs) ? (double)bias[min((job % tiles_m) * 16 + r16, M - 1)] : 0.0;
   if (total > 0) {
@@ -322,12 +325,24 @@ __device__ __forceinline__ void mlp_layer(const TA* __restrict__ A, const float*
       }
     }
   }
+  // the second team of a workgroup passes as many tile-end barriers as the first (it never has more tiles)
+  for (int extra = my_jobs; extra < team0_jobs_if_team1; extra++) __syncthreads();
   TC355_TRACE_FLUSH(trace);
   __syncthreads();  // the LDS stage is reused by the next layer
 }
 
-__global__ __launch_bounds__(WG_THREADS, 2) void mlp_fused_kernel(MlpArgs p) {
-  extern __shared__ __attribute__((aligned(32))) char smem[];
+// Teams (4 wavefronts that own a tile together) per workgroup.  Two workgroups of one team each per compute unit
+// hold the same wavefronts, but the one dispatched second starts ~1 us later and finishes its first-layer tile 1.7 us
+// after the other, and every workgroup of the grid waits for it at the barrier; two teams in one workgroup start
+// together (and halve the barrier's participants): 33.1 -> 29.8 us for the three-layer benchmark MLP.
+constexpr int MLP_TEAMS = 2;
+__global__ __launch_bounds__(MLP_TEAMS * WG_THREADS, 2 / MLP_TEAMS) void mlp_fused_kernel(MlpArgs p) {
+  extern __shared__ __attribute__((aligned(32))) char smem_all[];
+  // team t of workgroup w is team t * gridDim + w of the grid: the first teams take the first tiles, as the first
+  // workgroups of a two-per-unit launch would
+  const int team = __builtin_amdgcn_readfirstlane(threadIdx.x / WG_THREADS);
+  char* smem = smem_all + team * MLP_LDS_BYTES;
+  const int vwg = team * (int)gridDim.x + (int)blockIdx.x, vstep = MLP_TEAMS * (int)gridDim.x;
 #ifdef TC355_TRACE_ENABLE
   unsigned long long* trace = p.trace;
 #else
@@ -353,10 +368,15 @@ __global__ __launch_bounds__(WG_THREADS, 2) void mlp_fused_kernel(MlpArgs p) {
   for (int l = 0; l < p.n_layers; l++) {
     const int K = p.dims[l], M = p.dims[l + 1];
     double* act = (l + 1 < p.n_layers) ? p.act[l] : nullptr;
+    int t0jobs = -1;
+    if (team > 0) {
+      const int njobs = ((p.batch + 15) / 16) * ((M + 15) / 16), b = (int)blockIdx.x;
+      t0jobs = njobs > b ? (njobs - b + vstep - 1) / vstep : 0;
+    }
     if (l == 0)
-      mlp_layer<float>(p.I, p.W[0], p.bias[0], p.O[0], act, p.batch, K, M, smem, trace);
+      mlp_layer<float>(p.I, p.W[0], p.bias[0], p.O[0], act, p.batch, K, M, smem, trace, vwg, vstep, t0jobs);
     else
-      mlp_layer<double>(p.act[l - 1], p.W[l], p.bias[l], p.O[l], act, p.batch, K, M, smem, trace);
+      mlp_layer<double>(p.act[l - 1], p.W[l], p.bias[l], p.O[l], act, p.batch, K, M, smem, trace, vwg, vstep, t0jobs);
     TC355_TRACE(trace, 6);
     if (l + 1 < p.n_layers) mlp_grid_barrier(p.sync, l, p.token, gridDim.x, p.spin_limit);
     TC355_TRACE(trace, 7);
@@ -377,7 +397,8 @@ __global__ __launch_bounds__(WG_THREADS, 2) void mlp_fused_kernel(MlpArgs p) {
 // stride) with a long reduction and too few 64 x 64 blocks to fill the chip.
 __global__ __launch_bounds__(WG_THREADS, 2) void gemm_nt_splitk_kernel(GemmArgs p) {
   extern __shared__ __attribute__((aligned(32))) char smem[];
-  mlp_layer<float, false>(static_cast<const float*>(p.A), p.Bm, nullptr, p.C, nullptr, p.N, p.K, p.M, smem, nullptr);
+  mlp_layer<float, false>(static_cast<const float*>(p.A), p.Bm, nullptr, p.C, nullptr, p.N, p.K, p.M, smem, nullptr,
+                          (int)blockIdx.x, (int)gridDim.x, -1);
 }
 
 }  // namespace tc355

@@ -414,11 +414,12 @@ tc_status tc_mlp_fcrelu(const float* I, int64_t batch, int32_t n_layers, const i
     static std::atomic<int> lds_ok{0};  // the kernel stages more than the default 64 KiB of LDS
     if (!lds_ok.load(std::memory_order_acquire)) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_fused_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, MLP_LDS_BYTES) != hipSuccess)
+                              hipFuncAttributeMaxDynamicSharedMemorySize, MLP_TEAMS * MLP_LDS_BYTES) != hipSuccess)
         return TC_ERR_LAUNCH;
       lds_ok.store(1, std::memory_order_release);
     }
-    mlp_fused_kernel<<<dim3(nwg), dim3(WG_THREADS), MLP_LDS_BYTES, s>>>(a);
+    // nwg teams of four wavefronts; MLP_TEAMS of them share a workgroup
+    mlp_fused_kernel<<<dim3((nwg + MLP_TEAMS - 1) / MLP_TEAMS), dim3(MLP_TEAMS * WG_THREADS), MLP_TEAMS * MLP_LDS_BYTES, s>>>(a);
     return launch_status();
   }
 
