@@ -410,7 +410,7 @@ tc_status tc_mlp_fcrelu(const float* I, int64_t batch, int32_t n_layers, const i
     a.sync = reinterpret_cast<unsigned*>(ws);
     a.token = next_token();
     a.spin_limit = (unsigned)std::max<long>(1, env_long("TC355_MLP_SPIN_LIMIT", 4000000));
-    const unsigned nwg = (unsigned)std::min<int64_t>(std::min(2 * cus, MLP_FANIN * MLP_GROUPS), max_jobs);  // all resident: two per compute unit
+    const unsigned nwg = (unsigned)std::min<int64_t>(std::min(2 * cus, MLP_FANIN * MLP_GROUPS), max_jobs);  // teams of four wavefronts, all resident: two per compute unit
     static std::atomic<int> lds_ok{0};  // the kernel stages more than the default 64 KiB of LDS
     if (!lds_ok.load(std::memory_order_acquire)) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_fused_kernel),
