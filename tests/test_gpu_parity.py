@@ -128,6 +128,8 @@ MLP_SHAPES = [
     (16, (64, 48, 32, 16)),
     (37, (130, 70, 50, 10, 4)),
     (128, (1024, 1000)),            # odd output extent 1000 (the C3 weight of Section 7)
+    (48, (256, 336, 80)),           # 63 and 15 tiles: an odd number of four-wavefront teams, the last workgroup half empty
+    (2048, (64, 128, 64)),          # 1024 and 512 tiles on 512 teams: two tiles per team, then one
 ]
 
 
