@@ -126,9 +126,11 @@ size_t tc_mlp_fcrelu_workspace_bytes(int64_t batch, int32_t n_layers,
  * bias: [G*F] or NULL (no bias statement)      O: [N,G,F,H-KH+1,W-KW+1].
  * Output extents follow range inference (Section 3.1); H < KH or W < KW gives
  * TC_ERR_SHAPE.
- * Arithmetic: fp64 as everywhere, except for C = F = 16, KH = KW = 3, W = 58,
- * H even with H - 2 a multiple of 8 (the benchmark's geometry), which runs on
- * the int8 matrix core: every filter row and every band of 10 input rows is
+ * Arithmetic: fp64 as everywhere, except for C = F = 16, KH = KW = 3 with
+ * W = 58, H even and H - 2 a multiple of 8 (the benchmark's geometry) or with
+ * H = W = 14 and N a multiple of 4, which run on
+ * the int8 matrix core: every filter row and every band of 10 input rows
+ * (for 14 x 14: every whole block of 16 input planes) is
  * scaled to 32-bit fixed point (the block's largest magnitude maps to
  * 0x7F7F7F7E, every element is held to 2^-32 of that magnitude), cut into
  * four signed 8-bit digits, and the 10 leading digit products (k + l >= 3)

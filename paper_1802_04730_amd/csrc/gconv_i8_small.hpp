@@ -1,0 +1,223 @@
+// Grouped convolution (Section 7, listing gconv) on the int8 matrix core for SMALL images: C = F = 16 channels per
+// group, a 3 x 3 filter and a compile-time H x W (the paper's table shape (32,32,16,16,14,14)).  Arithmetic, digit
+// layout and MFMA operand layout are those of gconv_i8.hpp (block scaling to 0x7F7F7F7E, four signed 8-bit digits, the
+// 10 digit products with k + l >= 3 summed exactly in int32, one rounding to fp32); the blocks here are one filter
+// row and one whole (image, group) block of 16 planes.
+//
+// Work split: a workgroup takes four images of one group at a time, one per wavefront, so that the four share one
+// filter bank; everything else is private to the wavefront (its image's digit planes in LDS, its maximum, its
+// outputs), and the wavefronts of a workgroup meet only where the filter bank changes.  The H x W image is small
+// enough that a wavefront holds it whole: [4 digit planes][pixel][16 channels] bytes.  The OH x OW output pixels are
+// numbered row-major and cut into tiles of 16 (144 = 9 tiles for 14 x 14: none is padded); a lane's B operand for
+// (tile, kh) is the 16-byte record of pixel (h + kh, w + kw) of its own output pixel, so every (tile, kh) costs four
+// LDS reads for 10 MFMAs.  The next image is fetched into registers while the current one is contracted.
+#pragma once
+#include "gconv_i8.hpp"
+
+namespace tc355 {
+
+struct GconvI8SmallArgs {
+  const float* I;
+  const float* W1;
+  const float* bias;  // or nullptr
+  float* O;
+  int G, N;           // N is a multiple of 4
+};
+
+template <int H, int W>
+struct GconvI8SmallGeom {
+  static constexpr int C = 16, F = 16, KH = 3, KW = 3;
+  static constexpr int OH = H - KH + 1, OW = W - KW + 1;
+  static constexpr int NPX = H * W, NOUT = OH * OW;
+  static constexpr int TILES = (NOUT + 15) / 16;
+  static constexpr int PLANE = NPX * 16;                     // bytes of one digit plane
+  static constexpr int IMG = 4 * PLANE;                      // bytes of one wavefront's image
+  static constexpr int NUNIT = NPX;                          // staging units of 4 channels x 4 pixels: (NPX / 4) * 4
+  static constexpr int ROUNDS = (NUNIT + WAVE - 1) / WAVE;   // units per lane
+  static constexpr int BANK = 16384 + KH * 4 * WAVE * 16;    // filter-bank scratch: padded fp32 rows, then digit records
+  static constexpr int LDS_BYTES = WAVES_PER_WG * IMG + BANK;
+  static_assert(NPX % 4 == 0, "a channel plane is a whole number of 16-byte pieces");
+  static_assert(3 * PLANE + ((H - 1) * W + W) * 16 < 65536, "LDS immediates out of range");
+};
+
+template <int H, int W>
+__global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_small_kernel(GconvI8SmallArgs p) {
+  using Gm = GconvI8SmallGeom<H, W>;
+  constexpr int C = Gm::C, F = Gm::F, KH = Gm::KH, KW = Gm::KW, OW = Gm::OW, NPX = Gm::NPX, NOUT = Gm::NOUT,
+                TILES = Gm::TILES, PLANE = Gm::PLANE, ROUNDS = Gm::ROUNDS;
+  constexpr int WN = F * C * KH * KW, WPT = WN / WG_THREADS;
+  static_assert(WN % WG_THREADS == 0, "whole filter-bank floats per thread");
+  extern __shared__ __attribute__((aligned(16))) char gs_lds[];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & (WAVE - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
+  const int r16 = lane & 15, q = lane >> 4;
+  const int kwq = q < KW ? q : KW - 1;  // slot group 3 is padding: it re-reads kw = 2 against zero weights
+  char* img = gs_lds + wave * Gm::IMG;                       // this wavefront's digit planes
+  float* wl = reinterpret_cast<float*>(gs_lds + WAVES_PER_WG * Gm::IMG);
+  char* arec = reinterpret_cast<char*>(wl) + 16384;
+
+  // this workgroup's run of iterations [u, u1); iteration = (group g, images 4j .. 4j+3), group-major
+  const int per_group = p.N / WAVES_PER_WG;
+  const unsigned iters = (unsigned)(p.G * per_group);
+  unsigned u = iters * blockIdx.x / gridDim.x;
+  const unsigned u1 = iters * (blockIdx.x + 1) / gridDim.x;
+  if (u >= u1) return;
+
+  // byte offset of this lane's B record for (tile t, kh = 0) inside a digit plane; pixels past the end repeat the last one
+  int boff[TILES];
+#pragma unroll
+  for (int t = 0; t < TILES; t++) {
+    const int px = min(16 * t + r16, NOUT - 1), h = px / OW, w = px - h * OW;
+    boff[t] = (h * W + w + kwq) * 16;
+  }
+
+  // ---- staging units of this lane: unit = 4 channels (group cg) x 4 consecutive pixels (quad px4), unit = 4*px4 + cg
+  f4 pre[ROUNDS][4];
+  auto fetch = [&](int g, int n) {
+    const float* src = p.I + ((int64_t)n * p.G + g) * (C * NPX);
+#pragma unroll
+    for (int r = 0; r < ROUNDS; r++) {
+      const int unit = min(lane + r * WAVE, Gm::NUNIT - 1), cg = unit & 3, px4 = unit >> 2;
+#pragma unroll
+      for (int c = 0; c < 4; c++) pre[r][c] = *reinterpret_cast<const f4*>(src + (4 * cg + c) * NPX + 4 * px4);
+    }
+  };
+  {
+    const int g = (int)(u / per_group), n = (int)(u % per_group) * WAVES_PER_WG + wave;
+    fetch(g, n);
+  }
+
+  i4 a[KH][4];     // a[kh][k]: digit k of W1[g][r16][c = byte][kh][kw = q], zeros for q = 3
+  double fa[4];    // 2^24 / scale of filter row 4q + v (NaN if the row holds Inf/NaN)
+  float bz[4];     // bias of filter row 4q + v
+  int g_bank = -1;
+  for (; u < u1; u++) {
+    const int g = (int)(u / per_group), n = (int)(u % per_group) * WAVES_PER_WG + wave;
+    // ---- filter bank -> A operands (as in gconv_i8.hpp: wavefront w slices channels 4w .. 4w+3, records exchanged
+    // through LDS: record (kh, k) of a lane at arec + ((kh*4 + k)*64 + lane)*16, dword w)
+    if (g != g_bank) {  // uniform over the workgroup
+      g_bank = g;
+      const float* wg = p.W1 + (int64_t)g * WN;
+      float wpre[WPT];
+#pragma unroll
+      for (int j = 0; j < WPT; j++) wpre[j] = wg[tid + j * WG_THREADS];
+      __syncthreads();  // a slower wavefront may still be reading the records of the last bank
+      constexpr int WROW = C * KH * KW + 1;  // odd row distance: the 16 rows of a read fall into 16 banks
+      static_assert(F * WROW * 4 <= 16384, "padded filter bank must end before the digit records");
+#pragma unroll
+      for (int j = 0; j < WPT; j++) {
+        const int i = tid + j * WG_THREADS, f = i / (C * KH * KW);
+        wl[i + f] = wpre[j];
+      }
+      __syncthreads();
+      const float* wp = wl + r16 * WROW + kwq;
+      unsigned m = 0;
+#pragma unroll
+      for (int kh = 0; kh < KH; kh++)
+#pragma unroll
+        for (int c = 0; c < C; c++) m = max(m, __float_as_uint(wp[c * (KH * KW) + kh * KW]) & 0x7fffffffu);
+      m = max(m, (unsigned)__shfl_xor((int)m, 16));
+      m = max(m, (unsigned)__shfl_xor((int)m, 32));
+      const double sa = i8_scale(m);  // m = max|w| over the filter row
+#pragma unroll
+      for (int kh = 0; kh < KH; kh++) {
+        int d[4], y[4];
+#pragma unroll
+        for (int c = 0; c < 4; c++)
+          d[c] = i8_fixed<0x00808080>(wp[(4 * wave + c) * (KH * KW) + kh * KW], sa) ^ 0x00808080;  // byte k = digit k
+        i8_transpose4(d, y);
+#pragma unroll
+        for (int k = 0; k < 4; k++)
+          *reinterpret_cast<int*>(arec + ((kh * 4 + k) * WAVE + lane) * 16 + 4 * wave) = q < KW ? y[k] : 0;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int kh = 0; kh < KH; kh++)
+#pragma unroll
+        for (int k = 0; k < 4; k++) a[kh][k] = *reinterpret_cast<const i4*>(arec + ((kh * 4 + k) * WAVE + lane) * 16);
+#pragma unroll
+      for (int v = 0; v < 4; v++) {
+        fa[v] = 16777216.0 * i8_inverse_scale((unsigned)__shfl((int)m, 4 * q + v));  // lane 4q+v holds filter row 4q+v
+        bz[v] = p.bias ? p.bias[g * F + 4 * q + v] : 0.f;
+      }
+    }
+
+    // ---- largest magnitude of the image block (this wavefront only)
+    int mp = 0;
+    unsigned mn = 0;
+#pragma unroll
+    for (int r = 0; r < ROUNDS; r++)
+#pragma unroll
+      for (int c = 0; c < 4; c++) {
+        mp = i8_max3(mp, __float_as_int(pre[r][c][0]), __float_as_int(pre[r][c][1]));
+        mn = i8_max3(mn, __float_as_uint(pre[r][c][0]), __float_as_uint(pre[r][c][1]));
+        mp = i8_max3(mp, __float_as_int(pre[r][c][2]), __float_as_int(pre[r][c][3]));
+        mn = i8_max3(mn, __float_as_uint(pre[r][c][2]), __float_as_uint(pre[r][c][3]));
+      }
+    const unsigned m = (unsigned)__builtin_amdgcn_readfirstlane((int)i8_wave_max(max((unsigned)mp, mn & 0x7fffffffu)));
+
+    // ---- slice and stage: digit plane k, record of pixel pi at byte k*PLANE + 16*pi, channels 4cg.. at +4cg
+    {
+      const double sv = i8_scale(m);
+      const double scale = __hiloint2double(__builtin_amdgcn_readfirstlane(__double2hiint(sv)),
+                                            __builtin_amdgcn_readfirstlane(__double2loint(sv)));
+#pragma unroll
+      for (int r = 0; r < ROUNDS; r++) {
+        const int unit = lane + r * WAVE, cg = unit & 3, px4 = unit >> 2;
+        if (unit < Gm::NUNIT) {
+#pragma unroll
+          for (int e = 0; e < 4; e++) {
+            int d[4] = {i8_fixed<0x00808080>(pre[r][0][e], scale), i8_fixed<0x00808080>(pre[r][1][e], scale),
+                        i8_fixed<0x00808080>(pre[r][2][e], scale), i8_fixed<0x00808080>(pre[r][3][e], scale)}, y[4];
+            i8_transpose4(d, y);
+#pragma unroll
+            for (int k = 0; k < 4; k++)
+              *reinterpret_cast<int*>(img + k * PLANE + 16 * (4 * px4 + e) + 4 * cg) = k < 3 ? y[k] ^ (int)0x80808080 : y[k];
+          }
+        }
+      }
+    }
+    // the next image of this wavefront, fetched while this one is contracted
+    if (u + 1 < u1) {
+      const unsigned un = u + 1;
+      fetch((int)(un / per_group), (int)(un % per_group) * WAVES_PER_WG + wave);
+    }
+    const double invb = i8_inverse_scale(m);
+    double fo[4];
+#pragma unroll
+    for (int v = 0; v < 4; v++) fo[v] = fa[v] * invb;
+
+    // ---- contract: LDS operations of one wavefront execute in order, so its reads see the records staged above
+    float* dst = p.O + ((int64_t)n * p.G + g) * (F * NOUT);
+    const char* lbase = img;
+#pragma unroll
+    for (int t = 0; t < TILES; t++) {
+      i4 acc[4];  // diagonals k + l = 3 .. 6
+#pragma unroll
+      for (int d = 0; d < 4; d++) acc[d] = i4{0, 0, 0, 0};
+#pragma unroll
+      for (int kh = 0; kh < KH; kh++) {
+        i4 b[4];
+#pragma unroll
+        for (int l = 0; l < 4; l++) b[l] = *reinterpret_cast<const i4*>(lbase + boff[t] + l * PLANE + kh * W * 16);
+        constexpr int PK[10] = {3, 3, 3, 3, 2, 2, 2, 1, 1, 0};
+        constexpr int PL[10] = {3, 2, 1, 0, 3, 2, 1, 3, 2, 3};
+#pragma unroll
+        for (int i = 0; i < 10; i++) acc[PK[i] + PL[i] - 3] = mfma_i8(a[kh][PK[i]], b[PL[i]], acc[PK[i] + PL[i] - 3]);
+      }
+      const int px = 16 * t + r16;
+#pragma unroll
+      for (int v = 0; v < 4; v++) {
+        const int hi = acc[3][v] * 256 + acc[2][v];  // |.| < 2^30
+        const int lo = acc[1][v] * 256 + acc[0][v];  // |.| < 2^31
+        const double rr = __builtin_fma((double)hi, 65536.0, (double)lo);  // sum_d P_d 256^(d-3), exact
+        const float o = (float)__builtin_fma(rr, fo[v], (double)bz[v]);
+        if (px < NOUT) store_stream(dst + (4 * q + v) * NOUT + px, o);
+      }
+    }
+  }
+}
+
+}  // namespace tc355
