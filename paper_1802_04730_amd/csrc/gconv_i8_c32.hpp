@@ -1,0 +1,237 @@
+// Grouped convolution (Section 7, listing gconv) on the int8 matrix core for C = F = 32 channels per group, a 3 x 3
+// filter and small compile-time H x W images (the paper's table shape (32,32,32,32,7,7)).  Arithmetic and digit
+// layout are those of gconv_i8.hpp (block scaling to 0x7F7F7F7E, four signed 8-bit digits, the 10 digit products
+// with k + l >= 3 summed exactly in int32, one rounding to fp32); the blocks are one filter row (288 weights) and
+// one whole (image, group) block of 32 planes.
+//
+// v_mfma_i32_16x16x64_i8: rows = 16 filters (two filter tiles), columns = 16 output pixels (the OH x OW pixels
+// numbered row-major and cut into tiles of 16), and the 64 reduction slots of one instruction are four slot groups
+// of 16 channels: slot group sg = 4j + q of instruction j (q = lane / 16) carries tap sg / 2 = 3 kh + kw and channel
+// half sg % 2.  The 9 taps x 2 halves fill 18 of the 20 slot groups of five instructions; the last two hold zero
+// weights.  A lane's B operand for (pixel tile, j) is the 16-byte half record of its own output pixel shifted by the
+// tap, so the image needs no im2col: it sits in LDS as [4 digit planes][pixel][32 channels] bytes.
+//
+// Work split as in gconv_i8_small.hpp: a workgroup takes four images of one group at a time, one per wavefront; the
+// filter bank (2 filter tiles x 5 instructions x 4 digits of A operands: too many for the register file) is sliced
+// once per group into LDS records that all four wavefronts read; everything else is private to a wavefront.
+#pragma once
+#include "gconv_i8.hpp"
+
+namespace tc355 {
+
+struct GconvI8C32Args {
+  const float* I;
+  const float* W1;
+  const float* bias;  // or nullptr
+  float* O;
+  int G, N;           // N is a multiple of 4
+};
+
+template <int H, int W>
+struct GconvI8C32Geom {
+  static constexpr int C = 32, F = 32, KH = 3, KW = 3, TAPS = KH * KW;
+  static constexpr int OH = H - KH + 1, OW = W - KW + 1;
+  static constexpr int NPX = H * W, NOUT = OH * OW;
+  static constexpr int PT = (NOUT + 15) / 16;               // pixel tiles
+  static constexpr int FT = F / 16;                         // filter tiles
+  static constexpr int NJ = (2 * TAPS + 3) / 4;             // instructions per (filter tile, pixel tile, digit pair): 5
+  static constexpr int PLANE = NPX * C;                     // bytes of one digit plane
+  static constexpr int IMG = 4 * PLANE;                     // bytes of one wavefront's image
+  static constexpr int NUNIT = NPX * (C / 4);               // staging units: one pixel x 4 channels
+  static constexpr int ROUNDS = (NUNIT + WAVE - 1) / WAVE;
+  static constexpr int AREC = FT * NJ * 4 * WAVE * 16;      // A operand records: [ft][j][digit][lane] x 16 bytes
+  static constexpr int WROW = C * TAPS + 1;                 // padded fp32 filter row (odd: conflict-free column reads)
+  static constexpr int SCRATCH = 16 * WROW * 4;             // one filter tile of fp32 weights, staged in the image area
+  static constexpr int LDS_BYTES = WAVES_PER_WG * IMG + AREC;
+  static_assert(SCRATCH <= WAVES_PER_WG * IMG, "the weight scratch borrows the image area");
+  static_assert(3 * PLANE + NPX * C < 65536, "LDS immediates out of range");
+};
+
+template <int H, int W>
+__global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_c32_kernel(GconvI8C32Args p) {
+  using Gm = GconvI8C32Geom<H, W>;
+  constexpr int C = Gm::C, F = Gm::F, KW = Gm::KW, TAPS = Gm::TAPS, OW = Gm::OW, NPX = Gm::NPX, NOUT = Gm::NOUT,
+                PT = Gm::PT, FT = Gm::FT, NJ = Gm::NJ, PLANE = Gm::PLANE, ROUNDS = Gm::ROUNDS, WROW = Gm::WROW;
+  extern __shared__ __attribute__((aligned(16))) char gc_lds[];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & (WAVE - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
+  const int r16 = lane & 15, q = lane >> 4;
+  char* img = gc_lds + wave * Gm::IMG;                       // this wavefront's digit planes
+  float* wl = reinterpret_cast<float*>(gc_lds);              // weight scratch (only during the bank setup)
+  char* arec = gc_lds + WAVES_PER_WG * Gm::IMG;
+
+  // this workgroup's run of iterations [u, u1); iteration = (group g, images 4i .. 4i+3), group-major
+  const int per_group = p.N / WAVES_PER_WG;
+  const unsigned iters = (unsigned)(p.G * per_group);
+  unsigned u = iters * blockIdx.x / gridDim.x;
+  const unsigned u1 = iters * (blockIdx.x + 1) / gridDim.x;
+  if (u >= u1) return;
+
+  // tap and channel half of this lane's slot group in instruction j; slot groups past the 18 real ones are padding
+  int tapj[NJ], halfj[NJ];
+  bool realj[NJ];
+#pragma unroll
+  for (int j = 0; j < NJ; j++) {
+    const int sg = 4 * j + q;
+    realj[j] = sg < 2 * TAPS;
+    tapj[j] = min(sg >> 1, TAPS - 1);
+    halfj[j] = sg & 1;
+  }
+  // byte offset of this lane's B half record for (pixel tile t, instruction j) inside a digit plane
+  int boff[PT][NJ];
+#pragma unroll
+  for (int t = 0; t < PT; t++) {
+    const int px = min(16 * t + r16, NOUT - 1), h = px / OW, w = px - h * OW;
+#pragma unroll
+    for (int j = 0; j < NJ; j++) {
+      const int kh = tapj[j] / KW, kw = tapj[j] - kh * KW;
+      boff[t][j] = ((h + kh) * W + w + kw) * C + 16 * halfj[j];
+    }
+  }
+
+  // ---- staging units of this lane: unit = (channel group cg of 4, pixel px), pixels fastest (coalesced 4-byte loads)
+  float pre[ROUNDS][4];
+  auto fetch = [&](int g, int n) {
+    const float* src = p.I + ((int64_t)n * p.G + g) * (C * NPX);
+#pragma unroll
+    for (int r = 0; r < ROUNDS; r++) {
+      const int unit = min(lane + r * WAVE, Gm::NUNIT - 1), cg = unit / NPX, px = unit - cg * NPX;
+#pragma unroll
+      for (int c = 0; c < 4; c++) pre[r][c] = src[(4 * cg + c) * NPX + px];
+    }
+  };
+  fetch((int)(u / per_group), (int)(u % per_group) * WAVES_PER_WG + wave);
+
+  double fa[FT][4];  // 2^24 / scale of filter row 16 ft + 4q + v (NaN if the row holds Inf/NaN)
+  float bz[FT][4];   // bias of that row
+  int g_bank = -1;
+  for (; u < u1; u++) {
+    const int g = (int)(u / per_group), n = (int)(u % per_group) * WAVES_PER_WG + wave;
+    // ---- filter bank -> A operand records in LDS, one filter tile at a time through the (idle) image area:
+    // record (ft, j, k) of a lane at arec + (((ft*NJ + j)*4 + k)*64 + lane)*16; wavefront w slices bytes 4w .. 4w+3
+    if (g != g_bank) {  // uniform over the workgroup
+      g_bank = g;
+#pragma unroll 1
+      for (int ft = 0; ft < FT; ft++) {
+        __syncthreads();  // every wavefront is done with its image (and with the scratch of the last filter tile)
+        const float* wg = p.W1 + ((int64_t)g * F + 16 * ft) * (C * TAPS);
+        for (int i = tid; i < 16 * C * TAPS; i += WG_THREADS) wl[i + i / (C * TAPS)] = wg[i];
+        __syncthreads();
+        const float* wrow = wl + r16 * WROW;  // filter 16 ft + r16: [channel][tap]
+        unsigned m = 0;
+#pragma unroll
+        for (int j = 0; j < NJ; j++)
+#pragma unroll
+          for (int c = 0; c < 16; c++)
+            if (realj[j]) m = max(m, __float_as_uint(wrow[(16 * halfj[j] + c) * TAPS + tapj[j]]) & 0x7fffffffu);
+        m = max(m, (unsigned)__shfl_xor((int)m, 16));
+        m = max(m, (unsigned)__shfl_xor((int)m, 32));
+        const double sa = i8_scale(m);  // m = max|w| over the filter row
+#pragma unroll
+        for (int j = 0; j < NJ; j++) {
+          int d[4], y[4];
+#pragma unroll
+          for (int c = 0; c < 4; c++)
+            d[c] = i8_fixed<0x00808080>(wrow[(16 * halfj[j] + 4 * wave + c) * TAPS + tapj[j]], sa) ^ 0x00808080;
+          i8_transpose4(d, y);
+#pragma unroll
+          for (int k = 0; k < 4; k++)
+            *reinterpret_cast<int*>(arec + (((ft * NJ + j) * 4 + k) * WAVE + lane) * 16 + 4 * wave) = realj[j] ? y[k] : 0;
+        }
+#pragma unroll
+        for (int v = 0; v < 4; v++) {
+          const unsigned mv = (unsigned)__shfl((int)m, 4 * q + v);  // lane 4q+v holds filter row 4q+v of this tile
+          if (ft == 0) {
+            fa[0][v] = 16777216.0 * i8_inverse_scale(mv);
+            bz[0][v] = p.bias ? p.bias[g * F + 4 * q + v] : 0.f;
+          } else {
+            fa[FT - 1][v] = 16777216.0 * i8_inverse_scale(mv);
+            bz[FT - 1][v] = p.bias ? p.bias[g * F + 16 * (FT - 1) + 4 * q + v] : 0.f;
+          }
+        }
+      }
+      static_assert(FT == 2, "the scales of the two filter tiles are kept in named registers above");
+      __syncthreads();  // records complete; the image area is free again
+    }
+
+    // ---- largest magnitude of the image block (this wavefront only)
+    int mp = 0;
+    unsigned mn = 0;
+#pragma unroll
+    for (int r = 0; r < ROUNDS; r++) {
+      mp = i8_max3(mp, __float_as_int(pre[r][0]), __float_as_int(pre[r][1]));
+      mn = i8_max3(mn, __float_as_uint(pre[r][0]), __float_as_uint(pre[r][1]));
+      mp = i8_max3(mp, __float_as_int(pre[r][2]), __float_as_int(pre[r][3]));
+      mn = i8_max3(mn, __float_as_uint(pre[r][2]), __float_as_uint(pre[r][3]));
+    }
+    const unsigned m = (unsigned)__builtin_amdgcn_readfirstlane((int)i8_wave_max(max((unsigned)mp, mn & 0x7fffffffu)));
+
+    // ---- slice and stage: digit plane k, record of pixel px at byte k*PLANE + 32*px, channels 4cg.. at +4cg
+    {
+      const double sv = i8_scale(m);
+      const double scale = __hiloint2double(__builtin_amdgcn_readfirstlane(__double2hiint(sv)),
+                                            __builtin_amdgcn_readfirstlane(__double2loint(sv)));
+#pragma unroll
+      for (int r = 0; r < ROUNDS; r++) {
+        const int unit = lane + r * WAVE, cg = unit / NPX, px = unit - cg * NPX;
+        if (unit < Gm::NUNIT) {
+          int d[4] = {i8_fixed<0x00808080>(pre[r][0], scale), i8_fixed<0x00808080>(pre[r][1], scale),
+                      i8_fixed<0x00808080>(pre[r][2], scale), i8_fixed<0x00808080>(pre[r][3], scale)}, y[4];
+          i8_transpose4(d, y);
+#pragma unroll
+          for (int k = 0; k < 4; k++)
+            *reinterpret_cast<int*>(img + k * PLANE + C * px + 4 * cg) = k < 3 ? y[k] ^ (int)0x80808080 : y[k];
+        }
+      }
+    }
+    // the next image of this wavefront, fetched while this one is contracted
+    if (u + 1 < u1) {
+      const unsigned un = u + 1;
+      fetch((int)(un / per_group), (int)(un % per_group) * WAVES_PER_WG + wave);
+    }
+    const double invb = i8_inverse_scale(m);
+
+    // ---- contract: LDS operations of one wavefront execute in order, so its reads see the records staged above
+    float* dst = p.O + ((int64_t)n * p.G + g) * (F * NOUT);
+#pragma unroll
+    for (int ft = 0; ft < FT; ft++) {
+      i4 a[NJ][4];
+#pragma unroll
+      for (int j = 0; j < NJ; j++)
+#pragma unroll
+        for (int k = 0; k < 4; k++)
+          a[j][k] = *reinterpret_cast<const i4*>(arec + (((ft * NJ + j) * 4 + k) * WAVE + lane) * 16);
+#pragma unroll
+      for (int t = 0; t < PT; t++) {
+        i4 acc[4];  // diagonals k + l = 3 .. 6
+#pragma unroll
+        for (int d = 0; d < 4; d++) acc[d] = i4{0, 0, 0, 0};
+#pragma unroll
+        for (int j = 0; j < NJ; j++) {
+          i4 b[4];
+#pragma unroll
+          for (int l = 0; l < 4; l++) b[l] = *reinterpret_cast<const i4*>(img + boff[t][j] + l * PLANE);
+          constexpr int PK[10] = {3, 3, 3, 3, 2, 2, 2, 1, 1, 0};
+          constexpr int PL[10] = {3, 2, 1, 0, 3, 2, 1, 3, 2, 3};
+#pragma unroll
+          for (int i = 0; i < 10; i++) acc[PK[i] + PL[i] - 3] = mfma_i8(a[j][PK[i]], b[PL[i]], acc[PK[i] + PL[i] - 3]);
+        }
+        const int px = 16 * t + r16;
+#pragma unroll
+        for (int v = 0; v < 4; v++) {
+          // sum_d P_d 256^(d-3), exact.  (With 288 terms per output 256 * P_4 + P_3 can pass 2^31, so the diagonals
+          // are combined in fp64 rather than pairwise in int32 as in the 16-channel kernels.)
+          const double rr = __builtin_fma((double)acc[3][v], 16777216.0,
+                                          __builtin_fma((double)acc[2][v], 65536.0,
+                                                        __builtin_fma((double)acc[1][v], 256.0, (double)acc[0][v])));
+          const float o = (float)__builtin_fma(rr, fa[ft][v] * invb, (double)bz[ft][v]);
+          if (px < NOUT) store_stream(dst + (16 * ft + 4 * q + v) * NOUT + px, o);
+        }
+      }
+    }
+  }
+}
+
+}  // namespace tc355

@@ -15,6 +15,7 @@
 
 #include "gconv_band.hpp"
 #include "gconv_i8.hpp"
+#include "gconv_i8_c32.hpp"
 #include "gconv_i8_small.hpp"
 #include "gconv_lds.hpp"
 #include "gconv_quad.hpp"
@@ -298,6 +299,32 @@ bool try_gconv_i8(const GconvArgs& g, hipStream_t s, tc_status* st) {
   return true;
 }
 
+// ---- the same arithmetic for small images with 32 channels per group ----
+template <int H, int W>
+bool try_gconv_i8_c32(const GconvArgs& g, hipStream_t s, tc_status* st) {
+  using Gm = GconvI8C32Geom<H, W>;
+  if (g.C != Gm::C || g.F != Gm::F || g.KH != Gm::KH || g.KW != Gm::KW || g.W != W || g.H != H) return false;
+  if (g.N % WAVES_PER_WG != 0) return false;  // four images of a group per workgroup
+  const int64_t iters = (int64_t)g.G * (g.N / WAVES_PER_WG);
+  const int64_t grid = std::min<int64_t>(iters, 2 * (int64_t)device_cus());
+  if (iters * (grid + 1) >= (1ll << 32)) return false;  // the kernel splits the iterations in 32-bit arithmetic
+  static std::atomic<int> lds_ok{0};  // more than the default 64 KiB of dynamic LDS
+  if (!lds_ok.load(std::memory_order_acquire)) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gconv_i8_c32_kernel<H, W>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, Gm::LDS_BYTES) != hipSuccess) {
+      *st = TC_ERR_LAUNCH;
+      return true;
+    }
+    lds_ok.store(1, std::memory_order_release);
+  }
+  GconvI8C32Args a{};
+  a.I = g.I; a.W1 = g.W1; a.bias = g.bias; a.O = g.O;
+  a.G = g.G; a.N = g.N;
+  gconv_i8_c32_kernel<H, W><<<dim3((unsigned)grid), dim3(WG_THREADS), Gm::LDS_BYTES, s>>>(a);
+  *st = launch_status();
+  return true;
+}
+
 // ---- the same arithmetic for small images (one whole image per wavefront) ----
 template <int H, int W>
 bool try_gconv_i8_small(const GconvArgs& g, hipStream_t s, tc_status* st) {
@@ -502,6 +529,7 @@ tc_status tc_group_conv(const float* I, const float* W1, const float* bias, floa
   const bool thirteen = arith && std::strcmp(arith, "i8x13") == 0;
   if (!f64_only && !thirteen && try_gconv_i8<58, 8, 3>(a, s, &st)) return st;
   if (!f64_only && !thirteen && try_gconv_i8_small<14, 14>(a, s, &st)) return st;  // the paper's (32,32,16,16,14,14)
+  if (!f64_only && !thirteen && try_gconv_i8_c32<7, 7>(a, s, &st)) return st;      // the paper's (32,32,32,32,7,7)
   if (thirteen && try_gconv_i8<58, 8, 2>(a, s, &st)) return st;
   if (try_gconv_band<16, 3, 3, 58, 8, 2>(a, s, &st)) return st;
   if (try_gconv_band<16, 3, 3, 14, 12, 2>(a, s, &st)) return st;  // the paper's (32,32,16,16,14,14): the whole image is one band

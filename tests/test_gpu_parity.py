@@ -45,7 +45,7 @@ def check(gpu_tensor, ref, what, tight=TIGHT):
 
 def takes_i8_path(shape):
     N, G, C, F, H, W, KH, KW = shape
-    if (C, F, H, W, KH, KW) == (16, 16, 14, 14, 3, 3) and N % 4 == 0:
+    if (C, F, H, W, KH, KW) in ((16, 16, 14, 14, 3, 3), (32, 32, 7, 7, 3, 3)) and N % 4 == 0:
         return True   # small images: one per wavefront, four of a group per workgroup
     return (C, F, W, KH, KW) == (16, 16, 58, 3, 3) and H % 2 == 0 and (H - 2) % 8 == 0
 
@@ -227,6 +227,8 @@ GCONV_SHAPES = [
     (37, 29, 16, 16, 26, 58, 3, 3), # int8 kernel: 1073 pairs on 512 persistent workgroups (2 or 3 images each)
     (1, 3, 16, 16, 20, 30, 3, 3),   # 16x16 channels, other width: runtime-width LDS kernel
     (2, 3, 16, 16, 14, 14, 3, 3),   # width-14 band kernel (paper table shape), whole image = one band
+    (4, 3, 32, 32, 7, 7, 3, 3),     # int8 kernel for 32-channel small images: three iterations of four images
+    (12, 5, 32, 32, 7, 7, 3, 3),    # 15 iterations: runs that cross a group boundary
     (4, 3, 16, 16, 14, 14, 3, 3),   # int8 kernel for small images: three iterations of four images
     (12, 5, 16, 16, 14, 14, 3, 3),  # 15 iterations: runs that cross a group boundary
     (2052, 1, 16, 16, 14, 14, 3, 3),  # 513 iterations on 512 workgroups: one run of two
