@@ -147,7 +147,8 @@ size_t tc_mlp_fcrelu_workspace_bytes(int64_t batch, int32_t n_layers,
  * outputs, and the dropped products come close to 2e-5 on that metric
  * (1.6e-5 measured with log-normal magnitudes of sigma 1.5 and 1).  For such
  * data TC355_GCONV_ARITH=i8x13 keeps the next diagonal of digit products
- * (13 in all: 1.4e-6 on the same data, 16 % slower), and
+ * (13 in all: 1.4e-6 on the same data, 16 % slower; the 14 x 14 and 7 x 7
+ * geometries then take the fp64 path), and
  * TC355_GCONV_ARITH=f64 takes the fp64 path.  A band that holds Inf or NaN
  * gives NaN in all outputs that read the band.
  */
