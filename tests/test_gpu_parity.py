@@ -344,6 +344,36 @@ def test_gconv_i8_with_thirteen_digit_products(tc, shape, oracle_threads, monkey
     check(O, ref, "gconv int8 with 13 products %s" % (shape,), 1e-6)
 
 
+@pytest.mark.parametrize("shape", [(8, 3, 16, 16, 14, 14, 3, 3), (8, 3, 32, 32, 7, 7, 3, 3)])
+def test_gconv_i8_small_images_wide_range_and_nonfinite(tc, shape, oracle_threads):
+    """The small-image int8 kernels: block scaling per whole image, magnitudes spread over binades, an all-zero image,
+    and an Inf that must poison exactly the image block that holds it."""
+    N, G, C, F, H, W, KH, KW = shape
+    I, W1, bias = inputs.make_gconv(*shape, seed=123)
+    rng = np.random.default_rng(9)
+    I = (I * np.exp2(rng.integers(-8, 8, size=I.shape))).astype(np.float32)
+    I[2, 1] = 0.0
+    W1 = (W1 * np.exp2(rng.integers(-20, 20, size=(G, F, 1, 1, 1)))).astype(np.float32)
+    ref = oracle.group_conv(I, W1, bias)
+    O = torch.full(ref.shape, float("nan"), device="cuda")
+    tc.tc_group_conv(dev(I), dev(W1), dev(bias), O)
+    torch.cuda.synchronize()
+    got = O.cpu().numpy().astype(np.float64)
+    worst = max(parity_error(got[:, g, f], ref[:, g, f]) for g in range(G) for f in range(F))
+    print("gconv int8 small images %s, 16 binades inside every image: worst filter plane %.3e" % (shape, worst), flush=True)
+    assert worst <= PARITY_BAR / 4
+    assert np.array_equal(got[2, 1], np.broadcast_to(bias.reshape(G, F)[1][:, None, None], got[2, 1].shape).astype(np.float32))
+    Ibad = I.copy()
+    Ibad[5, 2, 3, 4, 4] = np.inf
+    O2 = torch.zeros(ref.shape, device="cuda")
+    tc.tc_group_conv(dev(Ibad), dev(W1), dev(bias), O2)
+    torch.cuda.synchronize()
+    got2 = O2.cpu().numpy()
+    assert np.isnan(got2[5, 2]).all(), "the block that holds the Inf"
+    mask = np.ones((N, G), dtype=bool); mask[5, 2] = False
+    assert np.array_equal(got2[mask], got.astype(np.float32)[mask]), "every other block is untouched"
+
+
 def test_gconv_without_bias(tc, oracle_threads):
     I, W1, _ = inputs.make_gconv(1, 3, 4, 6, 10, 9, 3, 3, seed=2)
     ref = oracle.group_conv(I, W1, None)
