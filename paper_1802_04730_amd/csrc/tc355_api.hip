@@ -16,6 +16,7 @@
 #include "gconv_band.hpp"
 #include "gconv_i8.hpp"
 #include "gconv_i8_c32.hpp"
+#include "gemm_i8.hpp"
 #include "gconv_i8_small.hpp"
 #include "gconv_lds.hpp"
 #include "gconv_quad.hpp"
@@ -382,6 +383,26 @@ tc_status tc_tbmm(const float* X, const float* Y, float* Z, int64_t B, int64_t N
     return TC_ERR_UNSUPPORTED;
   if (B == 0) return TC_OK;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+  // The paper's largest tmm shape class (128 rows against many, long reduction) on the int8 matrix core;
+  // TC355_TBMM_ARITH=f64 keeps it on the fp64 kernels.
+  if (N == GI8_TN && K % GI8_KB == 0 && K >= 4 * GI8_KB && M % GI8_TM == 0 && B <= 65535 &&
+      (M / GI8_TM) * B >= 128) {
+    const char* arith = std::getenv("TC355_TBMM_ARITH");
+    if (!(arith && std::strcmp(arith, "f64") == 0)) {
+      static std::atomic<int> lds_ok{0};  // more than the default 64 KiB of dynamic LDS
+      if (!lds_ok.load(std::memory_order_acquire)) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, GI8_LDS_BYTES) != hipSuccess)
+          return TC_ERR_LAUNCH;
+        lds_ok.store(1, std::memory_order_release);
+      }
+      GemmI8Args g{};
+      g.X = X; g.Y = Y; g.Z = Z; g.M = (int)M; g.K = (int)K;
+      gemm_i8_kernel<<<dim3((unsigned)(M / GI8_TM), (unsigned)B), dim3(GI8_THREADS), GI8_LDS_BYTES, s>>>(g);
+      return launch_status();
+    }
+  }
 
   GemmArgs a{};
   a.A = X; a.Bm = Y; a.bias = nullptr; a.C = Z; a.C64 = nullptr;

@@ -66,7 +66,15 @@ TBMM_SHAPES = [
     (1, 100, 200, 260),   # split-reduction kernel: ragged 16x16 tiles, reduction tail of 4 past two chunks
     (1, 128, 4096, 96),   # LDS-tiled kernel, one batch element, three chunks
     (130, 64, 64, 4),     # LDS-tiled kernel: a single short chunk
+    (1, 128, 8192, 256),  # int8 matrix-core kernel (128 rows, >= 128 blocks of 64 columns): four reduction blocks
+    (2, 128, 4096, 320),  # the same, two batch elements, an odd number of reduction blocks
+    (3, 128, 3072, 448),
 ]
+
+
+def tbmm_takes_i8_path(shape):
+    B, N, M, K = shape
+    return N == 128 and K % 64 == 0 and K >= 256 and M % 64 == 0 and (M // 64) * B >= 128
 
 
 @pytest.mark.parametrize("shape", TBMM_SHAPES)
@@ -76,7 +84,39 @@ def test_tbmm(tc, shape, oracle_threads):
     ref = oracle.tbmm(X, Y)
     Z = torch.full((B, N, M), float("nan"), device="cuda")
     tc.tc_tbmm(dev(X), dev(Y), Z)
-    check(Z, ref, "tbmm %s" % (shape,))
+    check(Z, ref, "tbmm %s" % (shape,), TIGHT_I8 if tbmm_takes_i8_path(shape) else TIGHT)
+
+
+def test_tbmm_i8_blocks_of_any_magnitude_zero_rows_and_nonfinite_rows(tc, oracle_threads):
+    """The int8 kernel scales every 64-element block of every row on its own: magnitudes that differ by 2^40 between
+    blocks, all-zero blocks and rows, and an Inf / a NaN that must poison exactly their own output row / column."""
+    B, N, M, K = 1, 128, 8192, 256
+    X, Y = inputs.make_tbmm(B, N, M, K, seed=31)
+    rng = np.random.default_rng(4)
+    X = (X * np.exp2(rng.integers(-20, 21, size=(B, N, K // 64)).repeat(64, axis=2))).astype(np.float32)
+    Y = (Y * np.exp2(rng.integers(-20, 21, size=(B, M, K // 64)).repeat(64, axis=2))).astype(np.float32)
+    X[0, 5] = 0.0
+    X[0, 6, 64:128] = 0.0
+    Y[0, 77] = 0.0
+    ref = oracle.tbmm(X, Y)
+    Z = torch.full((B, N, M), float("nan"), device="cuda")
+    tc.tc_tbmm(dev(X), dev(Y), Z)
+    torch.cuda.synchronize()
+    got = Z.cpu().numpy().astype(np.float64)
+    assert np.all(got[0, 5] == 0.0) and np.all(got[0, :, 77] == 0.0)
+    worst = max(parity_error(got[0, n], ref[0, n]) for n in range(N))
+    print("tbmm int8, block magnitudes over 40 binades: worst output row %.3e" % worst, flush=True)
+    assert worst <= PARITY_BAR / 2
+    Xb, Yb = X.copy(), Y.copy()
+    Xb[0, 9, 100] = np.inf
+    Yb[0, 4000, 3] = np.nan
+    Z2 = torch.zeros((B, N, M), device="cuda")
+    tc.tc_tbmm(dev(Xb), dev(Yb), Z2)
+    torch.cuda.synchronize()
+    got2 = Z2.cpu().numpy()
+    assert np.isnan(got2[0, 9]).all() and np.isnan(got2[0, :, 4000]).all()
+    keep = np.ones((N, M), dtype=bool); keep[9] = False; keep[:, 4000] = False
+    assert np.array_equal(got2[0][keep], got.astype(np.float32)[0][keep])
 
 
 def test_tbmm_empty_batch_and_guard_band(tc):
@@ -514,7 +554,7 @@ def test_tmm_largest_paper_shape_sampled(tc, oracle_threads):
     pick = np.sort(rng.choice(16384, size=96, replace=False))
     pick[:4] = [0, 63, 64, 16383]
     ref = oracle.tbmm(X, np.ascontiguousarray(Y[:, pick]))
-    check(Z[:, :, torch.from_numpy(pick).cuda()], ref, "tmm 128x4096x16384, 96 sampled columns")
+    check(Z[:, :, torch.from_numpy(pick).cuda()], ref, "tmm 128x4096x16384, 96 sampled columns", TIGHT_I8)
 
 
 @pytest.mark.parametrize("shape", [
