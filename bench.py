@@ -207,17 +207,24 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / reps
 
-    tmm_us = timed(lambda: tc355.tc_tbmm(Xt, Yt, Zt))
-    tmm_flops = inputs.flops_tbmm(1, 128, 16384, 4096)
-    extra = {"tmm_128x4096x16384": {"us": round(tmm_us, 1), "gflops": round(tmm_flops / tmm_us * 1e-3, 1),
-                                    "bound": "mfma",
-                                    "frac": round(tmm_flops / (PEAK_F64_MFMA_TFLOPS * 1e12) * 1e6 / tmm_us, 4)}}
-    # the other workloads of the paper's Section 7 tables, through the same entry points (fp64 matrix path)
-    def entry(us, flops, nbytes):
+    # the other workloads of the paper's Section 7 tables, through the same entry points
+    def entry(us, flops, nbytes):  # fp64 matrix path
         t_mfma, t_hbm = flops / (PEAK_F64_MFMA_TFLOPS * 1e12), nbytes / (PEAK_HBM_GBS * 1e9)
         return {"us": round(us, 1), "gflops": round(flops / us * 1e-3, 1), "bound": "mfma" if t_mfma >= t_hbm else "hbm",
                 "frac": round(max(t_mfma, t_hbm) * 1e6 / us, 4)}
 
+    def entry_i8(us, flops, nbytes):  # int8 matrix path: GCONV_I8_PRODUCTS int8 multiply-adds per fp32 one
+        t_mfma, t_hbm = GCONV_I8_PRODUCTS * flops / (PEAK_I8_MFMA_TOPS * 1e12), nbytes / (PEAK_HBM_GBS * 1e9)
+        return {"us": round(us, 1), "gflops": round(flops / us * 1e-3, 1), "bound": "mfma_int8" if t_mfma >= t_hbm else "hbm",
+                "frac": round(max(t_mfma, t_hbm) * 1e6 / us, 4)}
+
+    tmm_flops, tmm_bytes = inputs.flops_tbmm(1, 128, 16384, 4096), 4 * (128 * 4096 + 16384 * 4096 + 128 * 16384)
+    extra = {"tmm_128x4096x16384": entry_i8(timed(lambda: tc355.tc_tbmm(Xt, Yt, Zt)), tmm_flops, tmm_bytes)}
+    os.environ["TC355_TBMM_ARITH"] = "f64"
+    try:
+        extra["tmm_128x4096x16384_fp64_path"] = entry(timed(lambda: tc355.tc_tbmm(Xt, Yt, Zt)), tmm_flops, tmm_bytes)
+    finally:
+        del os.environ["TC355_TBMM_ARITH"]
     for (M_, K_, N_) in [(128, 32, 256), (128, 1024, 1024)]:
         Xt = torch.randn((1, M_, K_), device="cuda")
         Yt = torch.randn((1, N_, K_), device="cuda")
@@ -236,7 +243,7 @@ def main():
         Wt = torch.randn((32, F_, C_, 3, 3), device="cuda") * 0.05
         bt = torch.randn((32 * F_,), device="cuda") * 0.05
         Ot = torch.empty((32, 32, F_, HW - 2, HW - 2), device="cuda")
-        extra["gconv_32x32x%dx%dx%dx%d" % (F_, C_, HW, HW)] = entry(
+        extra["gconv_32x32x%dx%dx%dx%d" % (F_, C_, HW, HW)] = (entry_i8 if C_ >= 16 else entry)(
             timed(lambda: tc355.tc_group_conv(It, Wt, bt, Ot)), inputs.flops_gconv(32, 32, C_, F_, HW, HW, 3, 3),
             4 * (It.numel() + Wt.numel() + bt.numel() + Ot.numel()))
     # strided convolution (Section 3, listing sconv2d; the paper states no size: a ResNeXt-like down-sampling layer)

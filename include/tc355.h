@@ -22,9 +22,10 @@
  *  - Arithmetic: inputs are widened exactly to fp64, products and sums are
  *    taken in fp64 (fp64 matrix-core instructions), and each declared output
  *    is rounded once to fp32.  Values handed from one stage of a chain to the
- *    next stay in fp64.  One exception, see tc_group_conv: the 16-channel
- *    3 x 3 grouped convolution of width 58 sums exactly in integers over
- *    operands quantised to 2^-32 of their block maximum.
+ *    next stay in fp64.  The exceptions, see tc_group_conv and tc_tbmm: some
+ *    16- and 32-channel 3 x 3 grouped convolutions and the transposed matmul
+ *    with 128 rows sum exactly in integers over operands quantised to 2^-32
+ *    of their block maximum.
  *  - Validation precedes any launch: on a non-zero status nothing was written.
  *    A batch extent of 0 returns TC_OK without launching.
  *  - Thread safety: the only mutable global state is a per-process cache of
@@ -35,7 +36,8 @@
  *    very large batches take one launch per layer); TC355_MLP_SPIN_LIMIT=<n> bounds the
  *    polls of a device-wide wait; TC355_GCONV_ARITH=f64 keeps every grouped
  *    convolution on the fp64 path, =i8x13 makes the int8 path keep 13 instead
- *    of 10 digit products (see tc_group_conv).
+ *    of 10 digit products (see tc_group_conv); TC355_TBMM_ARITH=f64 keeps
+ *    every transposed matmul on the fp64 path (see tc_tbmm).
  */
 #ifndef TC355_H
 #define TC355_H
@@ -72,6 +74,20 @@ int tc355_version(void);
  * X: [B,N,K]   Y: [B,M,K]   Z: [B,N,M]  (all device, fp32).
  * The reduction index is the fastest index of both operands.  B = 1 gives the
  * transposed matmul of Section 7 (listing tmm).
+ * Arithmetic: fp64 products and sums, one rounding to fp32 -- except for
+ * N = 128 with K a multiple of 64 (at least 256), M a multiple of 64 and at
+ * least 128 blocks of 64 columns in all (the paper's (M,K,N) =
+ * (128,4096,16384) is of this kind), which run on the int8 matrix core: in
+ * every block of 64 reduction indices each row of X and of Y is scaled so that
+ * its largest magnitude m maps to 0x7F7F7F7E, rounded to a 32-bit integer
+ * (off by at most 2^-32 m) and cut into four signed 8-bit digits; the 10 digit
+ * products of weight 256^3 and above are summed exactly in int32, scaled back
+ * and added over the blocks in fp64, and the sum is rounded to fp32 once.
+ * Error bound: K * 2^-29.5 * max|X row block| * max|Y row block| absolute,
+ * worst case; measured 3e-7 .. 6e-7 on max|gpu - ref| / (|ref| + 1e-3
+ * max|ref|) for uniform and Gaussian operands.  A row of X (of Y) that holds
+ * Inf or NaN gives NaN in all of that row's (column's) outputs.
+ * TC355_TBMM_ARITH=f64 takes the fp64 path for these shapes too.
  */
 tc_status tc_tbmm(const float *X, const float *Y, float *Z, int64_t B,
                   int64_t N, int64_t M, int64_t K, void *hip_stream);

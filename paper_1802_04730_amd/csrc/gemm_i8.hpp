@@ -17,8 +17,10 @@
 //
 // One workgroup of 8 wavefronts = all 128 rows of X against 64 rows of Y.
 // Both operands are sliced by the workgroup that uses them (no workspace): X is
-// sliced again by every workgroup, which is what bounds this kernel -- about
-// twice the vector-ALU work of its matrix work.  Per block of 64 k a thread
+// sliced again by every workgroup, and slicing plus the per-block scaling of
+// the sums is about 300 vector-ALU instructions per wavefront and block beside
+// its 40 MFMAs: the vector ALU, not the matrix core or memory, bounds this
+// kernel.  Per block of 64 k a thread
 // owns 16 elements of one X row (four lanes per row) and 8 of one Y row (eight
 // lanes per row): row maximum across those lanes (data-parallel primitives),
 // scale = S / max by a reciprocal and two Newton steps, digits, and one 16-byte
@@ -97,27 +99,35 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
 #pragma unroll
     for (int j = 0; j < 2; j++) r.y[j] = *reinterpret_cast<const f4*>(ys + 16 * j);
   };
-  auto absmax4 = [](const f4& v, unsigned m) {
-    const unsigned a0 = __float_as_uint(v.x) & 0x7fffffffu, a1 = __float_as_uint(v.y) & 0x7fffffffu;
-    const unsigned a2 = __float_as_uint(v.z) & 0x7fffffffu, a3 = __float_as_uint(v.w) & 0x7fffffffu;
-    return i8_max3(i8_max3(a0, a1, a2), a3, m);
+  // Largest magnitude without clearing sign bits: as signed integers the non-negative floats order by magnitude
+  // and lie above every negative one; as unsigned integers the negative ones order by magnitude and lie above
+  // every non-negative one.  One signed and one unsigned three-way maximum per two elements, merged at the end.
+  auto absmax4 = [](const f4& v, int& smax, unsigned& umax) {
+    const int s0 = __float_as_int(v.x), s1 = __float_as_int(v.y), s2 = __float_as_int(v.z), s3 = __float_as_int(v.w);
+    smax = i8_max3(i8_max3(s0, s1, s2), s3, smax);
+    umax = i8_max3(i8_max3((unsigned)s0, (unsigned)s1, (unsigned)s2), (unsigned)s3, umax);
   };
+  auto magnitude = [](int smax, unsigned umax) { return max(max(smax, 0), (int)(umax & 0x7fffffffu)); };
+  // digits of four elements, transposed: y[k] = digit k of the four (the offset that makes the digits signed
+  // is removed after the transposition: three instructions instead of four)
   auto digits4 = [](const f4& v, double scale, int (&y)[4]) {
     int d[4];
-    d[0] = i8_fixed<0x00808080>(v.x, scale) ^ 0x00808080;  // byte k = digit k
-    d[1] = i8_fixed<0x00808080>(v.y, scale) ^ 0x00808080;
-    d[2] = i8_fixed<0x00808080>(v.z, scale) ^ 0x00808080;
-    d[3] = i8_fixed<0x00808080>(v.w, scale) ^ 0x00808080;
+    d[0] = i8_fixed<0x00808080>(v.x, scale);
+    d[1] = i8_fixed<0x00808080>(v.y, scale);
+    d[2] = i8_fixed<0x00808080>(v.z, scale);
+    d[3] = i8_fixed<0x00808080>(v.w, scale);
     i8_transpose4(d, y);
+    y[0] ^= 0x80808080; y[1] ^= 0x80808080; y[2] ^= 0x80808080;
   };
   auto slice = [&](const Raw& r, int buf) {
     char* base = gi8g_lds + buf * GI8_BUF;
     double* invs = reinterpret_cast<double*>(base + 4 * GI8_PLANE);
     {  // X: 16 elements, row shared by the 4 lanes of a quad
-      unsigned m = 0;
+      int sm = 0;
+      unsigned um = 0;
 #pragma unroll
-      for (int j = 0; j < 4; j++) m = absmax4(r.x[j], m);
-      int v = (int)m;
+      for (int j = 0; j < 4; j++) absmax4(r.x[j], sm, um);
+      int v = magnitude(sm, um);
       v = max(v, __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false));  // quad_perm [1,0,3,2]
       v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false));  // quad_perm [2,3,0,1]
       double scale, inverse;
@@ -132,12 +142,14 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
         rec.x = y[0][k]; rec.y = y[1][k]; rec.z = y[2][k]; rec.w = y[3][k];
         *reinterpret_cast<i4*>(dst + k * GI8_PLANE) = rec;
       }
-      if (cx == 0) invs[xrow] = inverse;
+      invs[xrow] = inverse;  // the four lanes of the row write the same value: no branch in the step
     }
     {  // Y: 8 elements, row shared by 8 lanes
-      unsigned m = absmax4(r.y[0], 0u);
-      m = absmax4(r.y[1], m);
-      int v = (int)m;
+      int sm = 0;
+      unsigned um = 0;
+      absmax4(r.y[0], sm, um);
+      absmax4(r.y[1], sm, um);
+      int v = magnitude(sm, um);
       v = max(v, __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
       v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
       v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x141, 0xF, 0xF, false));  // row_half_mirror: the other quad
@@ -153,7 +165,7 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
         rec.x = y[0][k]; rec.y = y[1][k];
         *reinterpret_cast<int2*>(dst + k * GI8_PLANE) = rec;
       }
-      if (cy == 0) invs[GI8_TN + yrow] = inverse * 16777216.0;  // 2^24: the weight of the lowest kept diagonal
+      invs[GI8_TN + yrow] = inverse * 16777216.0;  // 2^24: the weight of the lowest kept diagonal
     }
   };
 
@@ -174,28 +186,39 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
     double fy[4];
 #pragma unroll
     for (int v = 0; v < 4; v++) fy[v] = invs[GI8_TN + 16 * mt + 4 * q + v];
-    constexpr int PK[10] = {3, 3, 3, 3, 2, 2, 2, 1, 1, 0};
-    constexpr int PL[10] = {3, 2, 1, 0, 3, 2, 1, 3, 2, 3};
-#pragma unroll
-    for (int j = 0; j < 4; j++) {
+    // order: no two consecutive products on one diagonal
+    constexpr int PK[10] = {3, 2, 3, 3, 2, 1, 2, 1, 0, 3};
+    constexpr int PL[10] = {0, 1, 1, 2, 2, 2, 3, 3, 3, 3};
+    i4 d[2][4];  // d[.][i]: diagonal k + l = 3 + i; two sets, so that a tile's MFMAs run under the previous tile's epilogue
+    double fx[2];
+    auto mma = [&](int j, i4 (&dd)[4], double& fxj) {
       const int xr = 64 * nh + 16 * j + r16;
       const char* xb = base + xr * GI8_RS + 16 * q;
       i4 bq[4];
 #pragma unroll
       for (int l = 0; l < 4; l++) bq[l] = *reinterpret_cast<const i4*>(xb + l * GI8_PLANE);
-      const double fx = invs[xr];
-      i4 d[4];  // d[i]: diagonal k + l = 3 + i
+      fxj = invs[xr];
 #pragma unroll
-      for (int i = 0; i < 4; i++) d[i] = i4{0, 0, 0, 0};
+      for (int i = 0; i < 4; i++) dd[i] = i4{0, 0, 0, 0};
 #pragma unroll
-      for (int pr = 0; pr < 10; pr++) d[PK[pr] + PL[pr] - 3] = mfma_i8(a[PK[pr]], bq[PL[pr]], d[PK[pr] + PL[pr] - 3]);
+      for (int pr = 0; pr < 10; pr++) dd[PK[pr] + PL[pr] - 3] = mfma_i8(a[PK[pr]], bq[PL[pr]], dd[PK[pr] + PL[pr] - 3]);
+    };
+    auto epilogue = [&](int j, const i4 (&dd)[4], double fxj) {
 #pragma unroll
       for (int v = 0; v < 4; v++) {
-        const int hi = d[3][v] * 256 + d[2][v], lo = d[1][v] * 256 + d[0][v];  // < 2^29: 64 terms of 2^14 per pair
+        const int hi = dd[3][v] * 256 + dd[2][v], lo = dd[1][v] * 256 + dd[0][v];  // < 2^30: 64 terms of 2^14 per pair
         const double rr = __builtin_fma((double)hi, 65536.0, (double)lo);
-        acc[j][v] = __builtin_fma(rr, fy[v] * fx, acc[j][v]);
+        acc[j][v] = __builtin_fma(rr, fy[v] * fxj, acc[j][v]);
       }
-    }
+    };
+    mma(0, d[0], fx[0]);
+    mma(1, d[1], fx[1]);
+    epilogue(0, d[0], fx[0]);
+    mma(2, d[0], fx[0]);
+    epilogue(1, d[1], fx[1]);
+    mma(3, d[1], fx[1]);
+    epilogue(2, d[0], fx[0]);
+    epilogue(3, d[1], fx[1]);
   };
 
   Raw r0, r1;
@@ -204,18 +227,22 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
   slice(r0, 0);
   fetch(r0, min(2, nb - 1));
   __syncthreads();
-  for (int t = 0; t < nb; t += 2) {
+  // One step: stage the block after the current one, refill its registers two blocks further on, contract the
+  // current block.  The step has no branch (the last one stages a re-read block into the buffer nobody reads any
+  // more) and the loop has no exit in its middle: either would make the compiler wait for the loads just issued.
+  auto step = [&](Raw& r, int fetch_blk, int cur) {
+    slice(r, cur ^ 1);
+    fetch(r, fetch_blk);
+    contract(cur);
+    __syncthreads();
+  };
+  int t = 0;
+  for (; t + 1 < nb; t += 2) {
     // block t is in buffer 0; r1 holds block t + 1, r0 block t + 2 (indices past the end re-read the last block)
-    if (t + 1 < nb) slice(r1, 1);
-    fetch(r1, min(t + 3, nb - 1));
-    contract(0);
-    __syncthreads();
-    if (t + 1 >= nb) break;
-    if (t + 2 < nb) slice(r0, 0);
-    fetch(r0, min(t + 4, nb - 1));
-    contract(1);
-    __syncthreads();
+    step(r1, min(t + 3, nb - 1), 0);
+    step(r0, min(t + 4, nb - 1), 1);
   }
+  if (t < nb) step(r1, nb - 1, 0);
 
 #pragma unroll
   for (int j = 0; j < 4; j++) {

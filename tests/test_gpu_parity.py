@@ -119,6 +119,24 @@ def test_tbmm_i8_blocks_of_any_magnitude_zero_rows_and_nonfinite_rows(tc, oracle
     assert np.array_equal(got2[0][keep], got.astype(np.float32)[0][keep])
 
 
+def test_tbmm_arith_switch_keeps_the_fp64_kernels(tc, oracle_threads, monkeypatch):
+    """TC355_TBMM_ARITH=f64: the same shape on the fp64 matrix core, to one fp32 rounding."""
+    shape = (1, 128, 8192, 256)
+    X, Y = inputs.make_tbmm(*shape, seed=12)
+    ref = oracle.tbmm(X, Y)
+    Z = torch.full((1, 128, 8192), float("nan"), device="cuda")
+    monkeypatch.setenv("TC355_TBMM_ARITH", "f64")
+    tc.tc_tbmm(dev(X), dev(Y), Z)
+    torch.cuda.synchronize()
+    check(Z, ref, "tbmm %s, fp64 path by switch" % (shape,), TIGHT)
+    monkeypatch.delenv("TC355_TBMM_ARITH")
+    Z8 = torch.full((1, 128, 8192), float("nan"), device="cuda")
+    tc.tc_tbmm(dev(X), dev(Y), Z8)
+    torch.cuda.synchronize()
+    check(Z8, ref, "tbmm %s, int8 path" % (shape,), TIGHT_I8)
+    assert not torch.equal(Z, Z8), "the switch selects a different kernel"
+
+
 def test_tbmm_empty_batch_and_guard_band(tc):
     X = torch.zeros((0, 4, 5), device="cuda")
     Y = torch.zeros((0, 6, 5), device="cuda")

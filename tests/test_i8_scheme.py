@@ -135,3 +135,38 @@ def test_digit_decomposition_round_trips():
     assert np.abs(d[3]).max() <= 127
     # the largest value the rounding can produce: the block maximum maps to FULL, half a unit more at most
     assert FULL + 1 <= 0x7F7F7F7F
+
+
+def emulate_tmm(X, Y, block=64, min_diagonal=3):
+    """The transposed matmul's variant of the scheme: every row of X and of Y is scaled on its own in every block of
+    64 reduction indices; the blocks' exact integer sums are scaled back and added in float64."""
+    N, K = X.shape
+    M = Y.shape[0]
+    out = np.zeros((N, M))
+    for k0 in range(0, K, block):
+        xb, yb = X[:, k0:k0 + block].astype(np.float64), Y[:, k0:k0 + block].astype(np.float64)
+        mx, my = np.abs(xb).max(axis=1), np.abs(yb).max(axis=1)
+        sx, sy = FULL / np.where(mx > 0, mx, 1.0), FULL / np.where(my > 0, my, 1.0)
+        dx, dy = digits(np.rint(xb * sx[:, None]).astype(np.int64)), digits(np.rint(yb * sy[:, None]).astype(np.int64))
+        total = np.zeros((N, M), dtype=object)                 # exact python integers
+        for k in range(4):
+            for l in range(4):
+                if k + l >= min_diagonal:
+                    part = dx[k] @ dy[l].T
+                    assert np.abs(part).max() < 2 ** 22        # 64 terms of 2^14: far inside an int32 accumulator
+                    total = total + part.astype(object) * (256 ** (k + l))
+        out += total.astype(np.float64) / (sx[:, None] * sy[None, :])
+    return out.astype(np.float32).astype(np.float64)
+
+
+def test_transposed_matmul_in_blocks_of_64_with_ten_products():
+    X, Y = inputs.make_tbmm(1, 128, 192, 1024, seed=3)
+    ref = oracle.tbmm(X, Y)[0]
+    ten = parity_error(emulate_tmm(X[0], Y[0]), ref)
+    six = parity_error(emulate_tmm(X[0], Y[0], min_diagonal=4), ref)
+    assert ten <= 1e-6 and ten <= PARITY_BAR / 20, ten
+    assert six > 20 * ten, (six, ten)   # the diagonal k + l = 3 is needed
+    # Gaussian operands (the distribution of the full-size GPU test)
+    rng = np.random.default_rng(8)
+    Xg, Yg = rng.standard_normal((128, 2048)).astype(np.float32), rng.standard_normal((96, 2048)).astype(np.float32)
+    assert parity_error(emulate_tmm(Xg, Yg), oracle.tbmm(Xg[None], Yg[None])[0]) <= 2e-6
