@@ -28,7 +28,7 @@
 // of the instruction is free as long as X and Y agree; lanes fetch 16-byte
 // pieces so that four (eight) neighbours read one contiguous 256-byte row piece
 // and still own 16 (8) consecutive slots.  Digit planes are double-buffered in
-// LDS ([plane][row][64 + 16 bytes]); the fp32 blocks are fetched two blocks
+// LDS ([plane][row][64 bytes], chunks of rows 8..15 of every 16 exchanged); the fp32 blocks are fetched two blocks
 // ahead into registers; one barrier per block.  Wavefront w contracts the 16
 // rows of Y number w % 4 against 64 rows of X (half w / 4): 4 tiles x 10 MFMAs
 // per block.  MFMA rows = rows of Y, columns = rows of X, so a lane ends up with
@@ -51,10 +51,16 @@ struct GemmI8Args {
 
 constexpr int GI8_TN = 128, GI8_TM = 64, GI8_KB = 64, GI8_THREADS = 512;
 constexpr int GI8_ROWS = GI8_TN + GI8_TM;               // rows staged per block: X rows, then Y rows
-constexpr int GI8_RS = GI8_KB + 16;                     // bytes between rows of a digit plane: 16 rows -> 16 bank groups
+constexpr int GI8_RS = GI8_KB;                          // bytes between rows of a digit plane (no padding, see gi8_chunk)
 constexpr int GI8_PLANE = GI8_ROWS * GI8_RS;
 constexpr int GI8_BUF = 4 * GI8_PLANE + GI8_ROWS * 8;   // four digit planes and the rows' inverse scales (fp64)
-constexpr int GI8_LDS_BYTES = 2 * GI8_BUF;              // 125,952 bytes: one workgroup per compute unit
+constexpr int GI8_LDS_BYTES = 2 * GI8_BUF;              // 101,376 bytes: one workgroup per compute unit
+// Where 16-byte chunk c (0..3) of row `row` sits inside the row.  Measured on this chip: a 16-byte LDS read is
+// conflict-free when the 32 lanes of each half of the wavefront address 32 different 16-byte columns of a 512-byte
+// window.  An MFMA operand read has lanes (r16, q) = (row, chunk), so half a wavefront covers 16 rows x 2 chunks:
+// with 64-byte rows, rows r and r + 8 share their columns, and exchanging the chunk pairs of rows 8..15 separates
+// them (a row stride of 80 bytes, conflict-free for 16 lanes, measured twice as slow).
+__device__ __forceinline__ int gi8_chunk(int row, int c) { return c ^ ((row >> 2) & 2); }
 static_assert(GI8_BUF % 16 == 0 && (4 * GI8_PLANE) % 16 == 0, "16-byte LDS accesses");
 
 // S / max and max / S for a block with largest magnitude bits mbits: the reciprocal by two Newton steps on the
@@ -135,7 +141,7 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
       int y[4][4];
 #pragma unroll
       for (int j = 0; j < 4; j++) digits4(r.x[j], scale, y[j]);
-      char* dst = base + xrow * GI8_RS + 16 * cx;
+      char* dst = base + xrow * GI8_RS + 16 * gi8_chunk(xrow, cx);
 #pragma unroll
       for (int k = 0; k < 4; k++) {
         i4 rec;
@@ -158,7 +164,7 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
       int y[2][4];
 #pragma unroll
       for (int j = 0; j < 2; j++) digits4(r.y[j], scale, y[j]);
-      char* dst = base + (GI8_TN + yrow) * GI8_RS + 8 * cy;
+      char* dst = base + (GI8_TN + yrow) * GI8_RS + 16 * gi8_chunk(yrow, cy >> 1) + 8 * (cy & 1);
 #pragma unroll
       for (int k = 0; k < 4; k++) {
         int2 rec;
@@ -179,7 +185,7 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
   auto contract = [&](int buf) {
     const char* base = gi8g_lds + buf * GI8_BUF;
     const double* invs = reinterpret_cast<const double*>(base + 4 * GI8_PLANE);
-    const char* ya = base + (GI8_TN + 16 * mt + r16) * GI8_RS + 16 * q;
+    const char* ya = base + (GI8_TN + 16 * mt + r16) * GI8_RS + 16 * gi8_chunk(r16, q);
     i4 a[4];
 #pragma unroll
     for (int k = 0; k < 4; k++) a[k] = *reinterpret_cast<const i4*>(ya + k * GI8_PLANE);
@@ -193,7 +199,7 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
     double fx[2];
     auto mma = [&](int j, i4 (&dd)[4], double& fxj) {
       const int xr = 64 * nh + 16 * j + r16;
-      const char* xb = base + xr * GI8_RS + 16 * q;
+      const char* xb = base + xr * GI8_RS + 16 * gi8_chunk(r16, q);
       i4 bq[4];
 #pragma unroll
       for (int l = 0; l < 4; l++) bq[l] = *reinterpret_cast<const i4*>(xb + l * GI8_PLANE);
