@@ -75,16 +75,16 @@ int tc355_version(void);
  * The reduction index is the fastest index of both operands.  B = 1 gives the
  * transposed matmul of Section 7 (listing tmm).
  * Arithmetic: fp64 products and sums, one rounding to fp32 -- except for
- * N = 128 with K a multiple of 64 (at least 256), M a multiple of 64 and at
+ * N = 128 with K a multiple of 128 (at least 256), M a multiple of 64 and at
  * least 128 blocks of 64 columns in all (the paper's (M,K,N) =
  * (128,4096,16384) is of this kind), which run on the int8 matrix core: in
- * every block of 64 reduction indices each row of X and of Y is scaled so that
+ * every block of 128 reduction indices each row of X and of Y is scaled so that
  * its largest magnitude m maps to 0x7F7F7F7E, rounded to a 32-bit integer
  * (off by at most 2^-32 m) and cut into four signed 8-bit digits; the 10 digit
  * products of weight 256^3 and above are summed exactly in int32, scaled back
  * and added over the blocks in fp64, and the sum is rounded to fp32 once.
  * Error bound: K * 2^-29.5 * max|X row block| * max|Y row block| absolute,
- * worst case; measured 3e-7 .. 6e-7 on max|gpu - ref| / (|ref| + 1e-3
+ * worst case; measured 3e-7 .. 9e-7 on max|gpu - ref| / (|ref| + 1e-3
  * max|ref|) for uniform and Gaussian operands.  A row of X (of Y) that holds
  * Inf or NaN gives NaN in all of that row's (column's) outputs.
  * TC355_TBMM_ARITH=f64 takes the fp64 path for these shapes too.

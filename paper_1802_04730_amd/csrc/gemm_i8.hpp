@@ -1,5 +1,5 @@
 // Transposed matmul (Section 7, listing tmm / tbmm) on the int8 matrix core, for
-// 128 rows of X, a reduction that is a multiple of 64 and a multiple of 64 rows
+// 128 rows of X, a reduction that is a multiple of 128 and a multiple of 64 rows
 // of Y -- the paper's largest tmm, (M,K,N) = (128,4096,16384):
 //
 //   Z(b,n,m) = sum_k X(b,n,k) * Y(b,m,k)
@@ -7,32 +7,36 @@
 // Arithmetic as in the int8 grouped convolution (gconv_i8.hpp): operands become
 // 32-bit fixed-point numbers relative to the largest magnitude of their block,
 // four signed 8-bit digits each, and the 10 digit products with k + l >= 3 are
-// summed exactly in int32 by v_mfma_i32_16x16x64_i8.  A block here is 64
-// consecutive k of one matrix row: the reduction is walked in blocks of 64 (one
-// MFMA step), every row of X and of Y gets its own scale in every block, and
-// the block's integer sums are scaled back and added up in fp64 (one fp64
-// fused multiply-add per output and block), so the only roundings are the
-// operands' quantisation (2^-32 of the block maximum), the dropped digit pairs
-// (the same size) and K/64 fp64 additions; the result is rounded to fp32 once.
+// summed exactly in int32 by v_mfma_i32_16x16x64_i8.  A block here is 128
+// consecutive k of one matrix row (two MFMA steps): every row of X and of Y
+// gets its own scale in every block, and the block's integer sums are scaled
+// back and added up in fp64 (one fp64 fused multiply-add per output and
+// block), so the only roundings are the operands' quantisation (2^-32 of the
+// block maximum), the dropped digit pairs (the same size) and K/128 fp64
+// additions; the result is rounded to fp32 once.
 //
 // One workgroup of 8 wavefronts = all 128 rows of X against 64 rows of Y.
 // Both operands are sliced by the workgroup that uses them (no workspace): X is
 // sliced again by every workgroup, and slicing plus the per-block scaling of
-// the sums is about 300 vector-ALU instructions per wavefront and block beside
-// its 40 MFMAs: the vector ALU, not the matrix core or memory, bounds this
-// kernel.  Per block of 64 k a thread
-// owns 16 elements of one X row (four lanes per row) and 8 of one Y row (eight
-// lanes per row): row maximum across those lanes (data-parallel primitives),
-// scale = S / max by a reciprocal and two Newton steps, digits, and one 16-byte
-// (8-byte) LDS write per digit plane.  The position of a k inside the 64 slots
-// of the instruction is free as long as X and Y agree; lanes fetch 16-byte
-// pieces so that four (eight) neighbours read one contiguous 256-byte row piece
-// and still own 16 (8) consecutive slots.  Digit planes are double-buffered in
-// LDS ([plane][row][64 bytes], chunks of rows 8..15 of every 16 exchanged); the fp32 blocks are fetched two blocks
-// ahead into registers; one barrier per block.  Wavefront w contracts the 16
-// rows of Y number w % 4 against 64 rows of X (half w / 4): 4 tiles x 10 MFMAs
-// per block.  MFMA rows = rows of Y, columns = rows of X, so a lane ends up with
-// four consecutive m of one n: one 16-byte store.
+// the sums is about 490 vector-ALU instructions per wavefront and block beside
+// its 80 MFMAs.  On this chip the vector ALU and the matrix core of a SIMD do
+// not work at the same time (the time of this kernel is the sum of its two
+// halves whatever their order or interleaving), so the kernel is bound by that
+// sum; blocks of 128 instead of 64 halve the per-block scaling work.
+// Per block a thread owns 32 elements of one X row (four lanes per row) and 16
+// of one Y row (eight lanes per row): row maximum across those lanes
+// (data-parallel primitives), scale = S / max by a reciprocal and two Newton
+// steps, digits, and 16-byte (8-byte) LDS writes per digit plane.  The position
+// of a k inside the 64 slots of an MFMA step is free as long as X and Y agree;
+// lanes fetch 16-byte pieces so that four (eight) neighbours read one
+// contiguous 256-byte row piece and still own 16 (8) consecutive slots.  The
+// digit planes sit in LDS once ([plane][row][128 bytes], 16-byte chunks
+// permuted per row against bank conflicts); the next fp32 block is fetched into
+// registers while the current one is contracted; two barriers per block.
+// Wavefront w contracts the 16 rows of Y number w % 4 against 64 rows of X
+// (half w / 4): 4 tiles x 20 MFMAs per block.  MFMA rows = rows of Y, columns =
+// rows of X, so a lane ends up with four consecutive m of one n: one 16-byte
+// store.
 //
 // A row of X (of Y) that holds Inf or NaN gives NaN in every output of that row
 // (column), as the exact sum would except where an Inf meets only zeros or Infs
@@ -49,19 +53,20 @@ struct GemmI8Args {
   int M, K;
 };
 
-constexpr int GI8_TN = 128, GI8_TM = 64, GI8_KB = 64, GI8_THREADS = 512;
+constexpr int GI8_TN = 128, GI8_TM = 64, GI8_KB = 128, GI8_THREADS = 512;
+constexpr int GI8_STEPS = GI8_KB / 64;                  // MFMA steps (64 reduction slots each) per block
 constexpr int GI8_ROWS = GI8_TN + GI8_TM;               // rows staged per block: X rows, then Y rows
 constexpr int GI8_RS = GI8_KB;                          // bytes between rows of a digit plane (no padding, see gi8_chunk)
 constexpr int GI8_PLANE = GI8_ROWS * GI8_RS;
-constexpr int GI8_BUF = 4 * GI8_PLANE + GI8_ROWS * 8;   // four digit planes and the rows' inverse scales (fp64)
-constexpr int GI8_LDS_BYTES = 2 * GI8_BUF;              // 101,376 bytes: one workgroup per compute unit
-// Where 16-byte chunk c (0..3) of row `row` sits inside the row.  Measured on this chip: a 16-byte LDS read is
+constexpr int GI8_LDS_BYTES = 4 * GI8_PLANE + GI8_ROWS * 8;  // four digit planes and the rows' inverse scales (fp64): 99,840 bytes
+static_assert(GI8_LDS_BYTES % 16 == 0 && (4 * GI8_PLANE) % 16 == 0, "16-byte LDS accesses");
+// Where 16-byte chunk c (0..7) of row `row` sits inside the row.  Measured on this chip: a 16-byte LDS read is
 // conflict-free when the 32 lanes of each half of the wavefront address 32 different 16-byte columns of a 512-byte
-// window.  An MFMA operand read has lanes (r16, q) = (row, chunk), so half a wavefront covers 16 rows x 2 chunks:
-// with 64-byte rows, rows r and r + 8 share their columns, and exchanging the chunk pairs of rows 8..15 separates
-// them (a row stride of 80 bytes, conflict-free for 16 lanes, measured twice as slow).
-__device__ __forceinline__ int gi8_chunk(int row, int c) { return c ^ ((row >> 2) & 2); }
-static_assert(GI8_BUF % 16 == 0 && (4 * GI8_PLANE) % 16 == 0, "16-byte LDS accesses");
+// window.  An MFMA operand read has lanes (r16, q) = (row, chunk 4 s + q), so half a wavefront covers 16 rows x 2
+// chunks: with 128-byte rows, rows r, r + 4, r + 8 and r + 12 share their columns, and exchanging chunk pairs by
+// the row's second digit in base 4 separates them (row strides of 80 or 144 bytes, conflict-free for 16 lanes,
+// measured twice as slow).
+__device__ __forceinline__ int gi8_chunk(int row, int c) { return c ^ ((row >> 1) & 6); }
 
 // S / max and max / S for a block with largest magnitude bits mbits: the reciprocal by two Newton steps on the
 // hardware estimate (relative error far below the 2^-31 that keeps rint(max * scale) inside four digits).
@@ -86,24 +91,26 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
   const float* X = p.X + b * (int64_t)GI8_TN * K;
   const float* Y = p.Y + (b * M + m0) * (int64_t)K;
   float* Z = p.Z + b * (int64_t)GI8_TN * M;
+  double* invs = reinterpret_cast<double*>(gi8g_lds + 4 * GI8_PLANE);
 
-  // ---- staging role: 16 slots of X row tid / 4 (slots 16 cx ..), 8 slots of Y row tid / 8 (slots 8 cy ..).
-  // Slot 16 c + 4 j + e holds k = 16 j + 4 c + e: the j-th 16-byte piece of lane c.
+  // ---- staging role: 16 slots per MFMA step of X row tid / 4 (chunk cx of the step), 8 slots per step of Y row
+  // tid / 8 (half hy of chunk cyc).  Slot 16 c + 4 j + e of step s holds k = 64 s + 16 j + 4 c + e: the j-th
+  // 16-byte piece of lane c in that step's 256 bytes of the row.
   const int xrow = tid >> 2, cx = tid & 3;
-  const int yrow = tid >> 3, cy = tid & 7;
+  const int yrow = tid >> 3, cyc = (tid & 7) >> 1, hy = tid & 1;
   const float* xsrc = X + (int64_t)xrow * K + 4 * cx;
-  const float* ysrc = Y + (int64_t)yrow * K + 32 * (cy & 1) + 4 * (cy >> 1);
-  struct Raw {
-    f4 x[4];
-    f4 y[2];
-  };
-  auto fetch = [&](Raw& r, int blk) {
+  const float* ysrc = Y + (int64_t)yrow * K + 32 * hy + 4 * cyc;
+  f4 rx[GI8_STEPS][4], ry[GI8_STEPS][2];
+  auto fetch = [&](int blk) {
     const float* xs = xsrc + blk * GI8_KB;
     const float* ys = ysrc + blk * GI8_KB;
 #pragma unroll
-    for (int j = 0; j < 4; j++) r.x[j] = *reinterpret_cast<const f4*>(xs + 16 * j);
+    for (int s = 0; s < GI8_STEPS; s++) {
 #pragma unroll
-    for (int j = 0; j < 2; j++) r.y[j] = *reinterpret_cast<const f4*>(ys + 16 * j);
+      for (int j = 0; j < 4; j++) rx[s][j] = *reinterpret_cast<const f4*>(xs + 64 * s + 16 * j);
+#pragma unroll
+      for (int j = 0; j < 2; j++) ry[s][j] = *reinterpret_cast<const f4*>(ys + 64 * s + 16 * j);
+    }
   };
   // Largest magnitude without clearing sign bits: as signed integers the non-negative floats order by magnitude
   // and lie above every negative one; as unsigned integers the negative ones order by magnitude and lie above
@@ -125,51 +132,60 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
     i8_transpose4(d, y);
     y[0] ^= 0x80808080; y[1] ^= 0x80808080; y[2] ^= 0x80808080;
   };
-  auto slice = [&](const Raw& r, int buf) {
-    char* base = gi8g_lds + buf * GI8_BUF;
-    double* invs = reinterpret_cast<double*>(base + 4 * GI8_PLANE);
-    {  // X: 16 elements, row shared by the 4 lanes of a quad
+  auto slice = [&]() {
+    {  // X: 16 elements per step, row shared by the 4 lanes of a quad
       int sm = 0;
       unsigned um = 0;
 #pragma unroll
-      for (int j = 0; j < 4; j++) absmax4(r.x[j], sm, um);
+      for (int s = 0; s < GI8_STEPS; s++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) absmax4(rx[s][j], sm, um);
       int v = magnitude(sm, um);
       v = max(v, __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false));  // quad_perm [1,0,3,2]
       v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false));  // quad_perm [2,3,0,1]
       double scale, inverse;
       gi8_scales((unsigned)v, scale, inverse);
-      int y[4][4];
 #pragma unroll
-      for (int j = 0; j < 4; j++) digits4(r.x[j], scale, y[j]);
-      char* dst = base + xrow * GI8_RS + 16 * gi8_chunk(xrow, cx);
+      for (int s = 0; s < GI8_STEPS; s++) {
+        int y[4][4];
 #pragma unroll
-      for (int k = 0; k < 4; k++) {
-        i4 rec;
-        rec.x = y[0][k]; rec.y = y[1][k]; rec.z = y[2][k]; rec.w = y[3][k];
-        *reinterpret_cast<i4*>(dst + k * GI8_PLANE) = rec;
+        for (int j = 0; j < 4; j++) digits4(rx[s][j], scale, y[j]);
+        char* dst = gi8g_lds + xrow * GI8_RS + 16 * gi8_chunk(xrow, 4 * s + cx);
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+          i4 rec;
+          rec.x = y[0][k]; rec.y = y[1][k]; rec.z = y[2][k]; rec.w = y[3][k];
+          *reinterpret_cast<i4*>(dst + k * GI8_PLANE) = rec;
+        }
       }
       invs[xrow] = inverse;  // the four lanes of the row write the same value: no branch in the step
     }
-    {  // Y: 8 elements, row shared by 8 lanes
+    {  // Y: 8 elements per step, row shared by 8 lanes
       int sm = 0;
       unsigned um = 0;
-      absmax4(r.y[0], sm, um);
-      absmax4(r.y[1], sm, um);
+#pragma unroll
+      for (int s = 0; s < GI8_STEPS; s++) {
+        absmax4(ry[s][0], sm, um);
+        absmax4(ry[s][1], sm, um);
+      }
       int v = magnitude(sm, um);
       v = max(v, __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
       v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
       v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x141, 0xF, 0xF, false));  // row_half_mirror: the other quad
       double scale, inverse;
       gi8_scales((unsigned)v, scale, inverse);
-      int y[2][4];
 #pragma unroll
-      for (int j = 0; j < 2; j++) digits4(r.y[j], scale, y[j]);
-      char* dst = base + (GI8_TN + yrow) * GI8_RS + 16 * gi8_chunk(yrow, cy >> 1) + 8 * (cy & 1);
+      for (int s = 0; s < GI8_STEPS; s++) {
+        int y[2][4];
 #pragma unroll
-      for (int k = 0; k < 4; k++) {
-        int2 rec;
-        rec.x = y[0][k]; rec.y = y[1][k];
-        *reinterpret_cast<int2*>(dst + k * GI8_PLANE) = rec;
+        for (int j = 0; j < 2; j++) digits4(ry[s][j], scale, y[j]);
+        char* dst = gi8g_lds + (GI8_TN + yrow) * GI8_RS + 16 * gi8_chunk(yrow, 4 * s + cyc) + 8 * hy;
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+          int2 rec;
+          rec.x = y[0][k]; rec.y = y[1][k];
+          *reinterpret_cast<int2*>(dst + k * GI8_PLANE) = rec;
+        }
       }
       invs[GI8_TN + yrow] = inverse * 16777216.0;  // 2^24: the weight of the lowest kept diagonal
     }
@@ -182,13 +198,14 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
   for (int j = 0; j < 4; j++)
 #pragma unroll
     for (int v = 0; v < 4; v++) acc[j][v] = 0.0;
-  auto contract = [&](int buf) {
-    const char* base = gi8g_lds + buf * GI8_BUF;
-    const double* invs = reinterpret_cast<const double*>(base + 4 * GI8_PLANE);
-    const char* ya = base + (GI8_TN + 16 * mt + r16) * GI8_RS + 16 * gi8_chunk(r16, q);
-    i4 a[4];
+  auto contract = [&]() {
+    i4 a[GI8_STEPS][4];
 #pragma unroll
-    for (int k = 0; k < 4; k++) a[k] = *reinterpret_cast<const i4*>(ya + k * GI8_PLANE);
+    for (int s = 0; s < GI8_STEPS; s++) {
+      const char* ya = gi8g_lds + (GI8_TN + 16 * mt + r16) * GI8_RS + 16 * gi8_chunk(r16, 4 * s + q);
+#pragma unroll
+      for (int k = 0; k < 4; k++) a[s][k] = *reinterpret_cast<const i4*>(ya + k * GI8_PLANE);
+    }
     double fy[4];
 #pragma unroll
     for (int v = 0; v < 4; v++) fy[v] = invs[GI8_TN + 16 * mt + 4 * q + v];
@@ -199,20 +216,25 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
     double fx[2];
     auto mma = [&](int j, i4 (&dd)[4], double& fxj) {
       const int xr = 64 * nh + 16 * j + r16;
-      const char* xb = base + xr * GI8_RS + 16 * gi8_chunk(r16, q);
-      i4 bq[4];
-#pragma unroll
-      for (int l = 0; l < 4; l++) bq[l] = *reinterpret_cast<const i4*>(xb + l * GI8_PLANE);
-      fxj = invs[xr];
 #pragma unroll
       for (int i = 0; i < 4; i++) dd[i] = i4{0, 0, 0, 0};
 #pragma unroll
-      for (int pr = 0; pr < 10; pr++) dd[PK[pr] + PL[pr] - 3] = mfma_i8(a[PK[pr]], bq[PL[pr]], dd[PK[pr] + PL[pr] - 3]);
+      for (int s = 0; s < GI8_STEPS; s++) {
+        const char* xb = gi8g_lds + xr * GI8_RS + 16 * gi8_chunk(r16, 4 * s + q);
+        i4 bq[4];
+#pragma unroll
+        for (int l = 0; l < 4; l++) bq[l] = *reinterpret_cast<const i4*>(xb + l * GI8_PLANE);
+#pragma unroll
+        for (int pr = 0; pr < 10; pr++)
+          dd[PK[pr] + PL[pr] - 3] = mfma_i8(a[s][PK[pr]], bq[PL[pr]], dd[PK[pr] + PL[pr] - 3]);
+      }
+      fxj = invs[xr];
     };
     auto epilogue = [&](int j, const i4 (&dd)[4], double fxj) {
 #pragma unroll
       for (int v = 0; v < 4; v++) {
-        const int hi = dd[3][v] * 256 + dd[2][v], lo = dd[1][v] * 256 + dd[0][v];  // < 2^30: 64 terms of 2^14 per pair
+        // 128 terms of at most 2^14 per digit pair: 2^21 x 256 + 2 x 2^21 and 3 x 2^21 x 256 + 4 x 2^21, below 2^31
+        const int hi = dd[3][v] * 256 + dd[2][v], lo = dd[1][v] * 256 + dd[0][v];
         const double rr = __builtin_fma((double)hi, 65536.0, (double)lo);
         acc[j][v] = __builtin_fma(rr, fy[v] * fxj, acc[j][v]);
       }
@@ -227,28 +249,18 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
     epilogue(3, d[1], fx[1]);
   };
 
-  Raw r0, r1;
-  fetch(r0, 0);
-  fetch(r1, min(1, nb - 1));
-  slice(r0, 0);
-  fetch(r0, min(2, nb - 1));
-  __syncthreads();
-  // One step: stage the block after the current one, refill its registers two blocks further on, contract the
-  // current block.  The step has no branch (the last one stages a re-read block into the buffer nobody reads any
-  // more) and the loop has no exit in its middle: either would make the compiler wait for the loads just issued.
-  auto step = [&](Raw& r, int fetch_blk, int cur) {
-    slice(r, cur ^ 1);
-    fetch(r, fetch_blk);
-    contract(cur);
+  // One block: stage it from the registers, refill them with the next block (a whole block of time ahead of its
+  // use; past the end the last block is read again), contract.  The vector ALU and the matrix core of a SIMD do
+  // not run at the same time on this chip, so nothing is lost by not overlapping the two halves, and a single
+  // LDS buffer makes room for blocks of 128.
+  fetch(0);
+  for (int t = 0; t < nb; t++) {
+    slice();
+    fetch(min(t + 1, nb - 1));
     __syncthreads();
-  };
-  int t = 0;
-  for (; t + 1 < nb; t += 2) {
-    // block t is in buffer 0; r1 holds block t + 1, r0 block t + 2 (indices past the end re-read the last block)
-    step(r1, min(t + 3, nb - 1), 0);
-    step(r0, min(t + 4, nb - 1), 1);
+    contract();
+    __syncthreads();
   }
-  if (t < nb) step(r1, nb - 1, 0);
 
 #pragma unroll
   for (int j = 0; j < 4; j++) {

@@ -386,7 +386,7 @@ tc_status tc_tbmm(const float* X, const float* Y, float* Z, int64_t B, int64_t N
 
   // The paper's largest tmm shape class (128 rows against many, long reduction) on the int8 matrix core;
   // TC355_TBMM_ARITH=f64 keeps it on the fp64 kernels.
-  if (N == GI8_TN && K % GI8_KB == 0 && K >= 4 * GI8_KB && M % GI8_TM == 0 && B <= 65535 &&
+  if (N == GI8_TN && K % GI8_KB == 0 && K >= 2 * GI8_KB && M % GI8_TM == 0 && B <= 65535 &&
       (M / GI8_TM) * B >= 128) {
     const char* arith = std::getenv("TC355_TBMM_ARITH");
     if (!(arith && std::strcmp(arith, "f64") == 0)) {

@@ -66,15 +66,16 @@ TBMM_SHAPES = [
     (1, 100, 200, 260),   # split-reduction kernel: ragged 16x16 tiles, reduction tail of 4 past two chunks
     (1, 128, 4096, 96),   # LDS-tiled kernel, one batch element, three chunks
     (130, 64, 64, 4),     # LDS-tiled kernel: a single short chunk
-    (1, 128, 8192, 256),  # int8 matrix-core kernel (128 rows, >= 128 blocks of 64 columns): four reduction blocks
-    (2, 128, 4096, 320),  # the same, two batch elements, an odd number of reduction blocks
-    (3, 128, 3072, 448),
+    (1, 128, 8192, 256),  # int8 matrix-core kernel (128 rows, >= 128 blocks of 64 columns): two reduction blocks of 128
+    (2, 128, 4096, 384),  # the same, two batch elements, three reduction blocks
+    (3, 128, 3072, 640),
+    (1, 128, 8192, 320),  # reduction not a multiple of 128: stays on the fp64 kernels
 ]
 
 
 def tbmm_takes_i8_path(shape):
     B, N, M, K = shape
-    return N == 128 and K % 64 == 0 and K >= 256 and M % 64 == 0 and (M // 64) * B >= 128
+    return N == 128 and K % 128 == 0 and K >= 256 and M % 64 == 0 and (M // 64) * B >= 128
 
 
 @pytest.mark.parametrize("shape", TBMM_SHAPES)
@@ -88,15 +89,15 @@ def test_tbmm(tc, shape, oracle_threads):
 
 
 def test_tbmm_i8_blocks_of_any_magnitude_zero_rows_and_nonfinite_rows(tc, oracle_threads):
-    """The int8 kernel scales every 64-element block of every row on its own: magnitudes that differ by 2^40 between
+    """The int8 kernel scales every 128-element block of every row on its own: magnitudes that differ by 2^40 between
     blocks, all-zero blocks and rows, and an Inf / a NaN that must poison exactly their own output row / column."""
     B, N, M, K = 1, 128, 8192, 256
     X, Y = inputs.make_tbmm(B, N, M, K, seed=31)
     rng = np.random.default_rng(4)
-    X = (X * np.exp2(rng.integers(-20, 21, size=(B, N, K // 64)).repeat(64, axis=2))).astype(np.float32)
-    Y = (Y * np.exp2(rng.integers(-20, 21, size=(B, M, K // 64)).repeat(64, axis=2))).astype(np.float32)
+    X = (X * np.exp2(rng.integers(-20, 21, size=(B, N, K // 128)).repeat(128, axis=2))).astype(np.float32)
+    Y = (Y * np.exp2(rng.integers(-20, 21, size=(B, M, K // 128)).repeat(128, axis=2))).astype(np.float32)
     X[0, 5] = 0.0
-    X[0, 6, 64:128] = 0.0
+    X[0, 6, 128:256] = 0.0
     Y[0, 77] = 0.0
     ref = oracle.tbmm(X, Y)
     Z = torch.full((B, N, M), float("nan"), device="cuda")

@@ -137,9 +137,9 @@ def test_digit_decomposition_round_trips():
     assert FULL + 1 <= 0x7F7F7F7F
 
 
-def emulate_tmm(X, Y, block=64, min_diagonal=3):
+def emulate_tmm(X, Y, block=128, min_diagonal=3):
     """The transposed matmul's variant of the scheme: every row of X and of Y is scaled on its own in every block of
-    64 reduction indices; the blocks' exact integer sums are scaled back and added in float64."""
+    128 reduction indices; the blocks' exact integer sums are scaled back and added in float64."""
     N, K = X.shape
     M = Y.shape[0]
     out = np.zeros((N, M))
@@ -153,18 +153,21 @@ def emulate_tmm(X, Y, block=64, min_diagonal=3):
             for l in range(4):
                 if k + l >= min_diagonal:
                     part = dx[k] @ dy[l].T
-                    assert np.abs(part).max() < 2 ** 22        # 64 terms of 2^14: far inside an int32 accumulator
+                    assert np.abs(part).max() < 2 ** 21        # 128 terms of 127^2
                     total = total + part.astype(object) * (256 ** (k + l))
         out += total.astype(np.float64) / (sx[:, None] * sy[None, :])
     return out.astype(np.float32).astype(np.float64)
 
 
-def test_transposed_matmul_in_blocks_of_64_with_ten_products():
+def test_transposed_matmul_in_blocks_of_128_with_ten_products():
     X, Y = inputs.make_tbmm(1, 128, 192, 1024, seed=3)
     ref = oracle.tbmm(X, Y)[0]
     ten = parity_error(emulate_tmm(X[0], Y[0]), ref)
     six = parity_error(emulate_tmm(X[0], Y[0], min_diagonal=4), ref)
     assert ten <= 1e-6 and ten <= PARITY_BAR / 20, ten
+    # the kernel merges the diagonals pairwise in int32; worst case of 128 terms per digit pair
+    worst = 128 * 127 * 127
+    assert 256 * worst + 2 * worst < 2 ** 31 and 256 * 3 * worst + 4 * worst < 2 ** 31
     assert six > 20 * ten, (six, ten)   # the diagonal k + l = 3 is needed
     # Gaussian operands (the distribution of the full-size GPU test)
     rng = np.random.default_rng(8)
