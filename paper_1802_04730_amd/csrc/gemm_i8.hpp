@@ -1,6 +1,6 @@
 // Transposed matmul (Section 7, listing tmm / tbmm) on the int8 matrix core, for
-// 128 rows of X, a reduction that is a multiple of 128 and a multiple of 64 rows
-// of Y -- the paper's largest tmm, (M,K,N) = (128,4096,16384):
+// a multiple of 128 rows of X, a reduction that is a multiple of 128 and a
+// multiple of 64 rows of Y -- the paper's largest tmm, (M,K,N) = (128,4096,16384):
 //
 //   Z(b,n,m) = sum_k X(b,n,k) * Y(b,m,k)
 //
@@ -15,7 +15,7 @@
 // block maximum), the dropped digit pairs (the same size) and K/128 fp64
 // additions; the result is rounded to fp32 once.
 //
-// One workgroup of 8 wavefronts = all 128 rows of X against 64 rows of Y.
+// One workgroup of 8 wavefronts = 128 rows of X against 64 rows of Y.
 // Both operands are sliced by the workgroup that uses them (no workspace): X is
 // sliced again by every workgroup, and slicing plus the per-block scaling of
 // the sums is about 490 vector-ALU instructions per wavefront and block beside
@@ -47,9 +47,9 @@
 namespace tc355 {
 
 struct GemmI8Args {
-  const float* X;  // [B][128][K]
+  const float* X;  // [B][N][K], N = 128 * gridDim.z
   const float* Y;  // [B][M][K]
-  float* Z;        // [B][128][M]
+  float* Z;        // [B][N][M]
   int M, K;
 };
 
@@ -88,9 +88,10 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
   const int M = p.M, K = p.K, nb = K / GI8_KB;
   const int m0 = blockIdx.x * GI8_TM;
   const int64_t b = blockIdx.y;
-  const float* X = p.X + b * (int64_t)GI8_TN * K;
+  const int64_t n0 = (b * gridDim.z + blockIdx.z) * GI8_TN;  // first row of this workgroup's 128 in [B * N]
+  const float* X = p.X + n0 * K;
   const float* Y = p.Y + (b * M + m0) * (int64_t)K;
-  float* Z = p.Z + b * (int64_t)GI8_TN * M;
+  float* Z = p.Z + n0 * M;
   double* invs = reinterpret_cast<double*>(gi8g_lds + 4 * GI8_PLANE);
 
   // ---- staging role: 16 slots per MFMA step of X row tid / 4 (chunk cx of the step), 8 slots per step of Y row

@@ -384,10 +384,10 @@ tc_status tc_tbmm(const float* X, const float* Y, float* Z, int64_t B, int64_t N
   if (B == 0) return TC_OK;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
-  // The paper's largest tmm shape class (128 rows against many, long reduction) on the int8 matrix core;
+  // The paper's largest tmm shape class (blocks of 128 rows against many, long reduction) on the int8 matrix core;
   // TC355_TBMM_ARITH=f64 keeps it on the fp64 kernels.
-  if (N == GI8_TN && K % GI8_KB == 0 && K >= 2 * GI8_KB && M % GI8_TM == 0 && B <= 65535 &&
-      (M / GI8_TM) * B >= 128) {
+  if (N % GI8_TN == 0 && K % GI8_KB == 0 && K >= 2 * GI8_KB && M % GI8_TM == 0 && B <= 65535 &&
+      N / GI8_TN <= 65535 && (M / GI8_TM) * (N / GI8_TN) * B >= 128) {
     const char* arith = std::getenv("TC355_TBMM_ARITH");
     if (!(arith && std::strcmp(arith, "f64") == 0)) {
       static std::atomic<int> lds_ok{0};  // more than the default 64 KiB of dynamic LDS
@@ -399,7 +399,7 @@ tc_status tc_tbmm(const float* X, const float* Y, float* Z, int64_t B, int64_t N
       }
       GemmI8Args g{};
       g.X = X; g.Y = Y; g.Z = Z; g.M = (int)M; g.K = (int)K;
-      gemm_i8_kernel<<<dim3((unsigned)(M / GI8_TM), (unsigned)B), dim3(GI8_THREADS), GI8_LDS_BYTES, s>>>(g);
+      gemm_i8_kernel<<<dim3((unsigned)(M / GI8_TM), (unsigned)B, (unsigned)(N / GI8_TN)), dim3(GI8_THREADS), GI8_LDS_BYTES, s>>>(g);
       return launch_status();
     }
   }

@@ -70,12 +70,13 @@ TBMM_SHAPES = [
     (2, 128, 4096, 384),  # the same, two batch elements, three reduction blocks
     (3, 128, 3072, 640),
     (1, 128, 8192, 320),  # reduction not a multiple of 128: stays on the fp64 kernels
+    (2, 384, 1408, 256),  # int8 kernel, three row blocks of 128 per batch element
 ]
 
 
 def tbmm_takes_i8_path(shape):
     B, N, M, K = shape
-    return N == 128 and K % 128 == 0 and K >= 256 and M % 64 == 0 and (M // 64) * B >= 128
+    return N % 128 == 0 and K % 128 == 0 and K >= 256 and M % 64 == 0 and (M // 64) * (N // 128) * B >= 128
 
 
 @pytest.mark.parametrize("shape", TBMM_SHAPES)
