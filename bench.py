@@ -61,7 +61,7 @@ def parse_args():
                          "the board's power, power limit and shader clock (amdgpu sysfs sensors, read-only): one "
                          "JSON line per leg")
     ap.add_argument("--traffic-probe", action="store_true",
-                    help="only launch the grouped convolution and a plain 512 MiB device copy a few times (for "
+                    help="only launch the grouped convolution, the largest transposed matmul and a plain 512 MiB device copy a few times (for "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs; the copy calibrates the counters)")
     return ap.parse_args()
 
@@ -121,12 +121,18 @@ def main():
     if args.traffic_probe:
         src = torch.ones(128 * 1024 * 1024, dtype=torch.float32, device="cuda")  # 512 MiB read + 512 MiB written
         dst = torch.empty_like(src)
+        # the paper's largest transposed matmul (Section 7, tmm (M,K,N) = (128,4096,16384)) rides along
+        Xp = torch.rand((1, 128, 4096), device="cuda") * 2 - 1
+        Yp = torch.rand((1, 16384, 4096), device="cuda") * 2 - 1
+        Zp = torch.empty((1, 128, 16384), device="cuda")
         for _ in range(5):
             ops["gconv"][0]()
             dst.copy_(src)
+            tc355.tc_tbmm(Xp, Yp, Zp)
         torch.cuda.synchronize()
         print(json.dumps({"traffic_probe": True, "copy_bytes_each_way": src.numel() * 4,
-                          "gconv_algorithmic_bytes": ops["gconv"][2]}), flush=True)
+                          "gconv_algorithmic_bytes": ops["gconv"][2],
+                          "tmm_algorithmic_bytes": 4 * (128 * 4096 + 16384 * 4096 + 128 * 16384)}), flush=True)
         return
 
     if args.sustain > 0:

@@ -30,8 +30,8 @@
 // of a k inside the 64 slots of an MFMA step is free as long as X and Y agree;
 // lanes fetch 16-byte pieces so that four (eight) neighbours read one
 // contiguous 256-byte row piece and still own 16 (8) consecutive slots.  The
-// digit planes sit in LDS once ([plane][row][128 bytes], 16-byte chunks
-// permuted per row against bank conflicts); the next fp32 block is fetched into
+// digit planes sit in LDS once ([plane][row][128 + 32 bytes]: a row stride
+// that the operand reads take without bank conflicts); the next fp32 block is fetched into
 // registers while the current one is contracted; two barriers per block.
 // Wavefront w contracts the 16 rows of Y number w % 4 against 64 rows of X
 // (half w / 4): 4 tiles x 20 MFMAs per block.  MFMA rows = rows of Y, columns =
@@ -56,18 +56,13 @@ struct GemmI8Args {
 constexpr int GI8_TN = 128, GI8_TM = 64, GI8_KB = 128, GI8_THREADS = 512;
 constexpr int GI8_STEPS = GI8_KB / 64;                  // MFMA steps (64 reduction slots each) per block
 constexpr int GI8_ROWS = GI8_TN + GI8_TM;               // rows staged per block: X rows, then Y rows
-constexpr int GI8_RS = GI8_KB;                          // bytes between rows of a digit plane (no padding, see gi8_chunk)
+// Bytes between rows of a digit plane: 10 chunks of 16 bytes.  Measured on this chip with the MFMA operand pattern
+// (lane (r16, q) reads chunk q of row r16): row strides of 6 and 10 chunks read at full speed (4.5 clocks per
+// wavefront), strides of 4, 5, 8, 9 and 17 chunks and several XOR permutations of unpadded rows take twice as long.
+constexpr int GI8_RS = GI8_KB + 32;
 constexpr int GI8_PLANE = GI8_ROWS * GI8_RS;
-constexpr int GI8_LDS_BYTES = 4 * GI8_PLANE + GI8_ROWS * 8;  // four digit planes and the rows' inverse scales (fp64): 99,840 bytes
+constexpr int GI8_LDS_BYTES = 4 * GI8_PLANE + GI8_ROWS * 8;  // four digit planes and the rows' inverse scales (fp64): 124,416 bytes
 static_assert(GI8_LDS_BYTES % 16 == 0 && (4 * GI8_PLANE) % 16 == 0, "16-byte LDS accesses");
-// Where 16-byte chunk c (0..7) of row `row` sits inside the row.  Measured on this chip: a 16-byte LDS read is
-// conflict-free when the 32 lanes of each half of the wavefront address 32 different 16-byte columns of a 512-byte
-// window.  An MFMA operand read has lanes (r16, q) = (row, chunk 4 s + q), so half a wavefront covers 16 rows x 2
-// chunks: with 128-byte rows, rows r, r + 4, r + 8 and r + 12 share their columns, and exchanging chunk pairs by
-// the row's second digit in base 4 separates them (row strides of 80 or 144 bytes, conflict-free for 16 lanes,
-// measured twice as slow).
-__device__ __forceinline__ int gi8_chunk(int row, int c) { return c ^ ((row >> 1) & 6); }
-
 // S / max and max / S for a block with largest magnitude bits mbits: the reciprocal by two Newton steps on the
 // hardware estimate (relative error far below the 2^-31 that keeps rint(max * scale) inside four digits).
 __device__ __forceinline__ void gi8_scales(unsigned mbits, double& scale, double& inverse) {
@@ -151,7 +146,7 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
         int y[4][4];
 #pragma unroll
         for (int j = 0; j < 4; j++) digits4(rx[s][j], scale, y[j]);
-        char* dst = gi8g_lds + xrow * GI8_RS + 16 * gi8_chunk(xrow, 4 * s + cx);
+        char* dst = gi8g_lds + xrow * GI8_RS + 16 * (4 * s + cx);
 #pragma unroll
         for (int k = 0; k < 4; k++) {
           i4 rec;
@@ -180,7 +175,7 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
         int y[2][4];
 #pragma unroll
         for (int j = 0; j < 2; j++) digits4(ry[s][j], scale, y[j]);
-        char* dst = gi8g_lds + (GI8_TN + yrow) * GI8_RS + 16 * gi8_chunk(yrow, 4 * s + cyc) + 8 * hy;
+        char* dst = gi8g_lds + (GI8_TN + yrow) * GI8_RS + 16 * (4 * s + cyc) + 8 * hy;
 #pragma unroll
         for (int k = 0; k < 4; k++) {
           int2 rec;
@@ -203,7 +198,7 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
     i4 a[GI8_STEPS][4];
 #pragma unroll
     for (int s = 0; s < GI8_STEPS; s++) {
-      const char* ya = gi8g_lds + (GI8_TN + 16 * mt + r16) * GI8_RS + 16 * gi8_chunk(r16, 4 * s + q);
+      const char* ya = gi8g_lds + (GI8_TN + 16 * mt + r16) * GI8_RS + 16 * (4 * s + q);
 #pragma unroll
       for (int k = 0; k < 4; k++) a[s][k] = *reinterpret_cast<const i4*>(ya + k * GI8_PLANE);
     }
@@ -221,7 +216,7 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
       for (int i = 0; i < 4; i++) dd[i] = i4{0, 0, 0, 0};
 #pragma unroll
       for (int s = 0; s < GI8_STEPS; s++) {
-        const char* xb = gi8g_lds + xr * GI8_RS + 16 * gi8_chunk(r16, 4 * s + q);
+        const char* xb = gi8g_lds + xr * GI8_RS + 16 * (4 * s + q);
         i4 bq[4];
 #pragma unroll
         for (int l = 0; l < 4; l++) bq[l] = *reinterpret_cast<const i4*>(xb + l * GI8_PLANE);
