@@ -184,38 +184,48 @@ __device__ __forceinline__ void mlp_layer(const TA* __restrict__ A, const float*
   // load cursor: which chunk of which tile the next global loads fetch; row offsets are
   // recomputed only when the tile changes
   int ljob = vwg, lck = 0;
-  int aoff[A_LOADS], boff[B_LOADS];
+  // Per-lane BYTE offsets from the operands' base pointers, 32 bits (the host checks that both operands are
+  // smaller than 4 GiB): a load is then "uniform 64-bit base + 32-bit lane offset" and costs no address arithmetic
+  // on the vector ALU, which on this chip does not work while the matrix core does.
+  unsigned aoff[A_LOADS], boff[B_LOADS];
+  const char* Abase = reinterpret_cast<const char*>(A);
+  const char* Wbase = reinterpret_cast<const char*>(Wl);
   auto point = [&]() {
     if (ljob >= njobs) return;
     // Column tiles vary fastest, so the workgroups of one XCD (ids equal modulo 8) share few weight rows.
     const int ct = ljob % tiles_m, rt = ljob / tiles_m;
 #pragma unroll
     for (int i = 0; i < A_LOADS; i++)
-      aoff[i] = min(rt * 16 + a_row0 + i * (WG_THREADS / A_UPR), batch - 1) * K + a_k;
+      aoff[i] = ((unsigned)min(rt * 16 + a_row0 + i * (WG_THREADS / A_UPR), batch - 1) * (unsigned)K + (unsigned)a_k) *
+                (unsigned)sizeof(TA);
 #pragma unroll
     for (int i = 0; i < B_LOADS; i++)
-      boff[i] = min(ct * 16 + b_row0 + i * (WG_THREADS / B_UPR), M - 1) * K + b_k;
+      boff[i] = ((unsigned)min(ct * 16 + b_row0 + i * (WG_THREADS / B_UPR), M - 1) * (unsigned)K + (unsigned)b_k) * 4u;
   };
   point();
   auto load_next = [&](Regs& r) {
     if (ljob >= njobs) return;
     const int k0 = lck * KC;
     if (k0 + KC <= K) {  // whole chunk inside the reduction: no per-lane checks (uniform branch)
+      const char* Ak = Abase + (size_t)k0 * sizeof(TA);  // uniform
+      const char* Wk = Wbase + (size_t)k0 * 4;
 #pragma unroll
-      for (int i = 0; i < A_LOADS; i++) r.a[i] = load_vec<TA, AV>(A + aoff[i] + k0);
+      for (int i = 0; i < A_LOADS; i++) r.a[i] = load_vec<TA, AV>(reinterpret_cast<const TA*>(Ak + aoff[i]));
 #pragma unroll
-      for (int i = 0; i < B_LOADS; i++) r.b[i] = load_vec<float, 4>(Wl + boff[i] + k0);
+      for (int i = 0; i < B_LOADS; i++) r.b[i] = load_vec<float, 4>(reinterpret_cast<const float*>(Wk + boff[i]));
     } else {  // ragged last chunk: clamp the address, zero what lies past K
       const bool ain = k0 + a_k < K, bin = k0 + b_k < K;
+      const unsigned ashift = ain ? (unsigned)k0 * (unsigned)sizeof(TA) : 0u - (unsigned)a_k * (unsigned)sizeof(TA);
+      const unsigned bshift = bin ? (unsigned)k0 * 4u : 0u - (unsigned)b_k * 4u;
 #pragma unroll
       for (int i = 0; i < A_LOADS; i++) {
-        r.a[i] = load_vec<TA, AV>(A + aoff[i] + (ain ? k0 : -a_k));
+        r.a[i] = load_vec<TA, AV>(reinterpret_cast<const TA*>(Abase + (aoff[i] + ashift)));
 #pragma unroll
         for (int e = 0; e < AV; e++) r.a[i].e[e] = ain ? r.a[i].e[e] : (TA)0;
       }
 #pragma unroll
       for (int i = 0; i < B_LOADS; i++) {
-        r.b[i] = load_vec<float, 4>(Wl + boff[i] + (bin ? k0 : -b_k));
+        r.b[i] = load_vec<float, 4>(reinterpret_cast<const float*>(Wbase + (boff[i] + bshift)));
 #pragma unroll
         for (int e = 0; e < 4; e++) r.b[i].e[e] = bin ? r.b[i].e[e] : 0.0f;
       }

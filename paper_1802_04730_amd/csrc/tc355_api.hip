@@ -135,6 +135,8 @@ bool try_gconv_tiny(const GconvArgs& g, hipStream_t s, tc_status* st) {
 // and too few 64 x 64 blocks for the kernel above; returns false if it does not apply.
 bool try_gemm_splitk(const GemmArgs& a, int64_t batch, hipStream_t s, tc_status* st) {
   if (batch != 1 || a.K % 4 != 0 || a.K < 2 * MLP_KC || !a.C || a.C64) return false;
+  // the kernel addresses its operands with 32-bit byte offsets
+  if ((int64_t)a.N * a.K * 4 >= (1ll << 32) || (int64_t)a.M * a.K * 4 >= (1ll << 32)) return false;
   const int64_t jobs = ceil_div(a.N, 16) * ceil_div(a.M, 16);
   const int cus = device_cus();
   if (jobs < 64 || cus <= 0) return false;
@@ -464,6 +466,9 @@ tc_status tc_mlp_fcrelu(const float* I, int64_t batch, int32_t n_layers, const i
   // One persistent kernel for the whole chain when every reduction extent allows 16-byte loads.
   bool fused = env_long("TC355_MLP_FUSED", 1) != 0;
   for (int l = 0; l < n_layers; l++) fused = fused && (dims[l] % 4 == 0);
+  // the fused kernel addresses its operands (fp64 activations, fp32 weights) with 32-bit byte offsets
+  for (int l = 0; l < n_layers; l++)
+    fused = fused && batch * dims[l] * 8 < (1ll << 32) && dims[l + 1] * dims[l] * 4 < (1ll << 32);
   // Large batches: when every layer fills the chip with 64 x 64 blocks, one LDS-tiled launch per layer (70 % of the
   // fp64 matrix peak) beats the fused kernel's 16 x 16 tiles (43 %), and the launches no longer matter.
   if (n_layers > 1 && env_long("TC355_MLP_FUSED", -1) != 1) {
