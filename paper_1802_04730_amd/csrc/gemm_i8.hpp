@@ -18,7 +18,7 @@
 // One workgroup of 8 wavefronts = 128 rows of X against 64 rows of Y.
 // Both operands are sliced by the workgroup that uses them (no workspace): X is
 // sliced again by every workgroup, and slicing plus the per-block scaling of
-// the sums is about 490 vector-ALU instructions per wavefront and block beside
+// the sums is about 440 vector-ALU instructions per wavefront and block beside
 // its 80 MFMAs.  On this chip the vector ALU and the matrix core of a SIMD do
 // not work at the same time (the time of this kernel is the sum of its two
 // halves whatever their order or interleaving), so the kernel is bound by that
@@ -31,8 +31,9 @@
 // lanes fetch 16-byte pieces so that four (eight) neighbours read one
 // contiguous 256-byte row piece and still own 16 (8) consecutive slots.  The
 // digit planes sit in LDS once ([plane][row][128 + 32 bytes]: a row stride
-// that the operand reads take without bank conflicts); the next fp32 block is fetched into
-// registers while the current one is contracted; two barriers per block.
+// that the operand reads take without bank conflicts); the next fp32 block is
+// fetched into registers while the current one is contracted; two barriers
+// per block.
 // Wavefront w contracts the 16 rows of Y number w % 4 against 64 rows of X
 // (half w / 4): 4 tiles x 20 MFMAs per block.  MFMA rows = rows of Y, columns =
 // rows of X, so a lane ends up with four consecutive m of one n: one 16-byte
@@ -58,7 +59,7 @@ constexpr int GI8_STEPS = GI8_KB / 64;                  // MFMA steps (64 reduct
 constexpr int GI8_ROWS = GI8_TN + GI8_TM;               // rows staged per block: X rows, then Y rows
 // Bytes between rows of a digit plane: 10 chunks of 16 bytes.  Measured on this chip with the MFMA operand pattern
 // (lane (r16, q) reads chunk q of row r16): row strides of 6 and 10 chunks read at full speed (4.5 clocks per
-// wavefront), strides of 4, 5, 8, 9 and 17 chunks and several XOR permutations of unpadded rows take twice as long.
+// wavefront), strides of 4, 5, 9 and 17 chunks and several XOR permutations of unpadded rows take twice as long.
 constexpr int GI8_RS = GI8_KB + 32;
 constexpr int GI8_PLANE = GI8_ROWS * GI8_RS;
 constexpr int GI8_LDS_BYTES = 4 * GI8_PLANE + GI8_ROWS * 8;  // four digit planes and the rows' inverse scales (fp64): 124,416 bytes
