@@ -65,8 +65,9 @@ struct MlpArgs {
 // release word, and each workgroup polls only its own group's word.
 //
 // Memory visibility: the fp64 activations are STORED with agent-scope (sc1)
-// write-through accesses, so once the __syncthreads() on entry has waited for
-// this workgroup's stores there is nothing left to write back; after the wait,
+// write-through accesses, so once every wavefront has waited for its own stores
+// (s_waitcnt vmcnt(0): stores count there on this target) and the wavefronts
+// have met at __syncthreads(), there is nothing left to write back; after the wait,
 // one agent-scope acquire per workgroup drops stale lines from the caches this
 // workgroup reads through, and the activations are then LOADED with ordinary
 // cached 16-byte loads.  (A whole-cache write-back per workgroup, which a
@@ -81,8 +82,12 @@ constexpr int MLP_BAR_WORDS = 16 + 32 * MLP_GROUPS;
 
 __device__ __forceinline__ void mlp_grid_barrier(unsigned* sync, int which, unsigned long long token, unsigned nwg,
                                                  unsigned spin_limit) {
+  // Every wavefront first waits until its own vector-memory operations, the write-through activation stores
+  // included, have been acknowledged: neither a workgroup-scope release nor the workgroup barrier waits for
+  // outstanding global stores on this target, and the arrival below must not overtake them.
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  __syncthreads();  // all of this workgroup's write-through stores are acknowledged
+  __syncthreads();  // now all of this workgroup's write-through stores are acknowledged
   if (threadIdx.x == 0) {
     unsigned* bar = sync + MLP_SYNC_WORDS + which * MLP_BAR_WORDS;
     unsigned* err = sync + MLP_SYNC_ERROR;

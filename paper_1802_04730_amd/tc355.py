@@ -33,12 +33,12 @@ class TcError(RuntimeError):
 
 
 def lib() -> ctypes.CDLL:
-    """Load libtc355.so (building it first only if no built library exists)."""
+    """Load libtc355.so, building it first if it is missing or older than its sources (and hipcc is there)."""
     global _LIB
     if _LIB is not None:
         return _LIB
     path = _build.LIB
-    if not os.path.exists(path):
+    if not os.path.exists(path) or (_build.is_stale() and _build.have_hipcc()):
         _build.build(force=True)
     L = ctypes.CDLL(path)
     i64, i32, vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p
