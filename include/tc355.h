@@ -57,7 +57,8 @@ typedef enum {
   TC_ERR_ALIGN = 4,     /* a base pointer is not 16-byte aligned               */
   TC_ERR_WORKSPACE = 5, /* workspace missing, misaligned or too small          */
   TC_ERR_LAUNCH = 6,    /* the HIP runtime refused the launch                  */
-  TC_ERR_UNSUPPORTED = 7 /* extents beyond what the kernels index (>= 2^31 elements per tensor) */
+  TC_ERR_UNSUPPORTED = 7, /* extents beyond what the kernels index (>= 2^31 elements per tensor) */
+  TC_ERR_SCRATCH_LIMIT = 8 /* tc_mlp_fcrelu_static: the call needs more than TC_MLP_STATIC_SCRATCH_BYTES */
 } tc_status;
 
 /* Human-readable name of a status; static storage, never freed. */
@@ -134,6 +135,31 @@ tc_status tc_mlp_fcrelu(const float *I, int64_t batch, int32_t n_layers,
 /* Bytes of workspace tc_mlp_fcrelu needs for these extents (0 on bad input). */
 size_t tc_mlp_fcrelu_workspace_bytes(int64_t batch, int32_t n_layers,
                                      const int64_t *dims);
+
+/*
+ * tc_mlp_fcrelu for callers that cannot allocate device memory and have no
+ * workspace to pass: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels and same
+ * results as tc_mlp_fcrelu, but the scratch (synchronisation words and fp64
+ * activations) is a static device array inside the library instead of a
+ * workspace argument.  The call allocates and frees nothing.
+ *   - Limit: tc_mlp_fcrelu_workspace_bytes(batch, n_layers, dims) must not
+ *     exceed TC_MLP_STATIC_SCRATCH_BYTES (8 MiB, enough for the benchmark's
+ *     128 x 1024 -> 1024 -> 512 -> 256 chain four times over); beyond it the
+ *     call returns TC_ERR_SCRATCH_LIMIT and launches nothing.
+ *   - Every GPU the library runs on holds its own copy of the array until the
+ *     process ends.  Its device address is looked up once per device, at the
+ *     first call on that device (make that first call outside a capture).
+ *   - All calls on one GPU share that GPU's array and it keeps the previous
+ *     call's contents; the kernel initialises the words it needs, so nothing
+ *     has to be cleared between calls.  Calls that overlap in time on one GPU
+ *     (different streams, different host threads) race on it: order them.
+ */
+#define TC_MLP_STATIC_SCRATCH_BYTES (8u << 20)
+tc_status tc_mlp_fcrelu_static(const float *I, int64_t batch, int32_t n_layers,
+                               const int64_t *dims, const float *const *W,
+                               const float *const *bias, float *const *O,
+                               void *hip_stream);
 
 /*
  * Grouped 2-D convolution, stride 1, no padding, plus per-output-channel bias

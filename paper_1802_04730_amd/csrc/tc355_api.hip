@@ -368,6 +368,7 @@ const char* tc_status_string(tc_status s) {
     case TC_ERR_WORKSPACE: return "TC_ERR_WORKSPACE: workspace missing, misaligned or too small";
     case TC_ERR_LAUNCH: return "TC_ERR_LAUNCH: the HIP runtime refused the launch";
     case TC_ERR_UNSUPPORTED: return "TC_ERR_UNSUPPORTED: extents exceed the kernels' index range";
+    case TC_ERR_SCRATCH_LIMIT: return "TC_ERR_SCRATCH_LIMIT: the call needs more than the library's static scratch array holds";
   }
   return "unknown tc_status";
 }
@@ -425,9 +426,34 @@ size_t tc_mlp_fcrelu_workspace_bytes(int64_t batch, int32_t n_layers, const int6
   return total;
 }
 
-tc_status tc_mlp_fcrelu(const float* I, int64_t batch, int32_t n_layers, const int64_t* dims,
-                        const float* const* W, const float* const* bias, float* const* O, void* workspace,
-                        size_t workspace_bytes, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// Scratch of tc_mlp_fcrelu_static: one array per GPU that the library runs on, held until the process ends.
+// In host code the array's name is only a stand-in; its device address comes from hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char scratch[TC_MLP_STATIC_SCRATCH_BYTES];
+
+// Device address of `scratch` on the current device (looked up once per device), or nullptr on failure.
+void* static_scratch_ptr() {
+  static std::atomic<void*> cache[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  void* ptr = cache[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    cache[dev].store(ptr, std::memory_order_release);
+  }
+  return ptr;
+}
+
+// Both MLP entry points: validation, then the fused kernel or one launch per layer.  `workspace` is device memory.
+tc_status mlp_run(const float* I, int64_t batch, int32_t n_layers, const int64_t* dims, const float* const* W,
+                  const float* const* bias, float* const* O, void* workspace, size_t workspace_bytes,
+                  bool static_scratch, void* hip_stream) {
   if (!I || !dims || !W || !bias || !O) return TC_ERR_NULL;
   if (batch < 0 || n_layers <= 0 || n_layers > MLP_MAX_LAYERS) return TC_ERR_SHAPE;
   for (int l = 0; l <= n_layers; l++)
@@ -448,6 +474,15 @@ tc_status tc_mlp_fcrelu(const float* I, int64_t batch, int32_t n_layers, const i
       return TC_ERR_UNSUPPORTED;
   }
   const size_t need = tc_mlp_fcrelu_workspace_bytes(batch, n_layers, dims);
+  if (static_scratch) {
+    if (need > TC_MLP_STATIC_SCRATCH_BYTES) return TC_ERR_SCRATCH_LIMIT;
+    if (batch == 0) return TC_OK;
+    if (need > 0) {
+      workspace = static_scratch_ptr();
+      workspace_bytes = TC_MLP_STATIC_SCRATCH_BYTES;
+      if (!workspace) return TC_ERR_LAUNCH;
+    }
+  }
   if (need > 0 && (!workspace || misaligned(workspace, 256) || workspace_bytes < need)) return TC_ERR_WORKSPACE;
   if (batch == 0) return TC_OK;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -517,6 +552,22 @@ tc_status tc_mlp_fcrelu(const float* I, int64_t batch, int32_t n_layers, const i
     in = act[l];
   }
   return TC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+tc_status tc_mlp_fcrelu(const float* I, int64_t batch, int32_t n_layers, const int64_t* dims,
+                        const float* const* W, const float* const* bias, float* const* O, void* workspace,
+                        size_t workspace_bytes, void* hip_stream) {
+  return mlp_run(I, batch, n_layers, dims, W, bias, O, workspace, workspace_bytes, false, hip_stream);
+}
+
+tc_status tc_mlp_fcrelu_static(const float* I, int64_t batch, int32_t n_layers, const int64_t* dims,
+                               const float* const* W, const float* const* bias, float* const* O,
+                               void* hip_stream) {
+  return mlp_run(I, batch, n_layers, dims, W, bias, O, nullptr, 0, true, hip_stream);
 }
 
 tc_status tc_group_conv_infer(int64_t H, int64_t W, int64_t KH, int64_t KW, int64_t* OH, int64_t* OW) {

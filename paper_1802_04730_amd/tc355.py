@@ -20,9 +20,11 @@ _LIB = None
 
 TC_OK = 0
 STATUS_NAMES = {0: "TC_OK", 1: "TC_ERR_NULL", 2: "TC_ERR_SHAPE", 3: "TC_ERR_ALIAS", 4: "TC_ERR_ALIGN",
-                5: "TC_ERR_WORKSPACE", 6: "TC_ERR_LAUNCH", 7: "TC_ERR_UNSUPPORTED"}
+                5: "TC_ERR_WORKSPACE", 6: "TC_ERR_LAUNCH", 7: "TC_ERR_UNSUPPORTED", 8: "TC_ERR_SCRATCH_LIMIT"}
+TC_MLP_STATIC_SCRATCH_BYTES = 8 << 20
 
 EXPORTS = ["tc_status_string", "tc355_version", "tc_tbmm", "tc_mlp_fcrelu", "tc_mlp_fcrelu_workspace_bytes",
+           "tc_mlp_fcrelu_static",
            "tc_group_conv", "tc_group_conv_infer", "tc_kron", "tc_sconv2d", "tc_sconv2d_infer", "tc_lut"]
 
 
@@ -50,6 +52,9 @@ def lib() -> ctypes.CDLL:
     L.tc_mlp_fcrelu.argtypes = [vp, i64, i32, ctypes.POINTER(i64), ctypes.POINTER(vp), ctypes.POINTER(vp),
                                 ctypes.POINTER(vp), vp, ctypes.c_size_t, vp]
     L.tc_mlp_fcrelu.restype = ctypes.c_int
+    L.tc_mlp_fcrelu_static.argtypes = [vp, i64, i32, ctypes.POINTER(i64), ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                       ctypes.POINTER(vp), vp]
+    L.tc_mlp_fcrelu_static.restype = ctypes.c_int
     L.tc_mlp_fcrelu_workspace_bytes.argtypes = [i64, i32, ctypes.POINTER(i64)]
     L.tc_mlp_fcrelu_workspace_bytes.restype = ctypes.c_size_t
     L.tc_group_conv.argtypes = [vp, vp, vp, vp] + [i64] * 8 + [vp]
@@ -115,25 +120,30 @@ def tc_mlp_fcrelu_workspace_bytes(batch: int, dims) -> int:
     return int(lib().tc_mlp_fcrelu_workspace_bytes(int(batch), n, arr))
 
 
+def _mlp_args(I, W, bias, O, where):
+    n = len(W)
+    batch, d0 = I.shape
+    dims = [d0] + [int(w.shape[0]) for w in W]
+    for l in range(n):
+        if tuple(W[l].shape) != (dims[l + 1], dims[l]) or tuple(bias[l].shape) != (dims[l + 1],):
+            raise ValueError("%s: layer %d shapes do not chain" % (where, l))
+        if O[l] is not None and tuple(O[l].shape) != (batch, dims[l + 1]):
+            raise ValueError("%s: O[%d] has the wrong shape" % (where, l))
+    vp = ctypes.c_void_p
+    Wp = (vp * n)(*[_ptr(w, "W[%d]" % l) for l, w in enumerate(W)])
+    bp = (vp * n)(*[_ptr(b, "bias[%d]" % l) for l, b in enumerate(bias)])
+    Op = (vp * n)(*[_ptr(o, "O[%d]" % l) for l, o in enumerate(O)])
+    dm = (ctypes.c_int64 * (n + 1))(*dims)
+    return batch, n, dm, Wp, bp, Op
+
+
 def tc_mlp_fcrelu(I, W, bias, O, workspace=None, stream=None) -> None:
     """Chained fcrelu layers.  W, bias, O are lists (O[l] may be None for l < last).
 
     ``workspace`` is a torch CUDA uint8 tensor of at least
     tc_mlp_fcrelu_workspace_bytes(batch, dims) bytes (None only when that is 0).
     """
-    n = len(W)
-    batch, d0 = I.shape
-    dims = [d0] + [int(w.shape[0]) for w in W]
-    for l in range(n):
-        if tuple(W[l].shape) != (dims[l + 1], dims[l]) or tuple(bias[l].shape) != (dims[l + 1],):
-            raise ValueError("tc_mlp_fcrelu: layer %d shapes do not chain" % l)
-        if O[l] is not None and tuple(O[l].shape) != (batch, dims[l + 1]):
-            raise ValueError("tc_mlp_fcrelu: O[%d] has the wrong shape" % l)
-    vp = ctypes.c_void_p
-    Wp = (vp * n)(*[_ptr(w, "W[%d]" % l) for l, w in enumerate(W)])
-    bp = (vp * n)(*[_ptr(b, "bias[%d]" % l) for l, b in enumerate(bias)])
-    Op = (vp * n)(*[_ptr(o, "O[%d]" % l) for l, o in enumerate(O)])
-    dm = (ctypes.c_int64 * (n + 1))(*dims)
+    batch, n, dm, Wp, bp, Op = _mlp_args(I, W, bias, O, "tc_mlp_fcrelu")
     ws_ptr, ws_bytes = None, 0
     if workspace is not None:
         if not workspace.is_cuda or not workspace.is_contiguous():
@@ -141,6 +151,13 @@ def tc_mlp_fcrelu(I, W, bias, O, workspace=None, stream=None) -> None:
         ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
     _check(lib().tc_mlp_fcrelu(_ptr(I, "I"), batch, n, dm, Wp, bp, Op, ws_ptr, ws_bytes, _stream(stream)),
            "tc_mlp_fcrelu")
+
+
+def tc_mlp_fcrelu_static(I, W, bias, O, stream=None) -> None:
+    """tc_mlp_fcrelu on the library's static scratch array: no workspace argument, no allocation."""
+    batch, n, dm, Wp, bp, Op = _mlp_args(I, W, bias, O, "tc_mlp_fcrelu_static")
+    _check(lib().tc_mlp_fcrelu_static(_ptr(I, "I"), batch, n, dm, Wp, bp, Op, _stream(stream)),
+           "tc_mlp_fcrelu_static")
 
 
 def tc_group_conv_infer(H: int, W: int, KH: int, KW: int):
