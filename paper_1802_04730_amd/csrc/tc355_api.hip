@@ -29,6 +29,7 @@
 #include "lut_sum.hpp"
 #include "mlp_fused.hpp"
 #include "sconv_tile.hpp"
+#include "tbmm_lds.hpp"
 
 using namespace tc355;
 
@@ -302,6 +303,85 @@ bool try_gconv_i8(const GconvArgs& g, hipStream_t s, tc_status* st) {
   return true;
 }
 
+// ---- transposed batched matmul on small per-batch matrices: flat coalesced strips through per-wavefront LDS ----
+struct TbmmLdsPlan {
+  int tn, tm, nx, ny, store, ks;  // what a job is and what it needs: load instructions per strip, store mode, k steps
+};
+
+// The instantiations that exist; a shape takes the first one that covers its plan.  (KS = 0: any reduction length.)
+#define TC355_TBMM_LDS_VARIANTS(V) \
+  V(2, 5, 3, 8, TBMM_STORE_FLAT, 7)   /* the benchmark's 26 x 72 x 26, a whole batch element per job */ \
+  V(2, 5, 3, 8, TBMM_STORE_FLAT, 0)   \
+  V(2, 5, 8, 16, TBMM_STORE_FLAT, 0)  \
+  V(2, 1, 3, 2, TBMM_STORE_PIECES, 7) /* the same shape, one 16-column tile per job: few batch elements */ \
+  V(2, 1, 3, 2, TBMM_STORE_PIECES, 0) \
+  V(2, 1, 3, 2, TBMM_STORE_SCALAR, 0) \
+  V(2, 2, 8, 8, TBMM_STORE_PIECES, 0) \
+  V(2, 2, 8, 8, TBMM_STORE_SCALAR, 0) /* the paper's own naming of tbmm: output 26 x 26, reduction 72 */ \
+  V(2, 1, 8, 8, TBMM_STORE_PIECES, 0) \
+  V(2, 1, 8, 8, TBMM_STORE_SCALAR, 0) \
+  V(1, 1, 4, 4, TBMM_STORE_PIECES, 0) \
+  V(1, 1, 4, 4, TBMM_STORE_SCALAR, 0)
+
+bool launch_tbmm_lds(const TbmmLdsPlan& pl, const TbmmLdsArgs& a, int64_t wgs, size_t lds, hipStream_t s, tc_status* st) {
+#define TC355_TBMM_LDS_TRY(TN_, TM_, NX_, NY_, ST_, KS_)                                                       \
+  if (pl.tn == TN_ && pl.tm == TM_ && pl.nx <= NX_ && pl.ny <= NY_ && pl.store == ST_ && (KS_ == 0 || pl.ks == KS_)) { \
+    tbmm_lds_kernel<TN_, TM_, NX_, NY_, 1, ST_, KS_><<<dim3((unsigned)wgs), dim3(WG_THREADS), lds, s>>>(a);     \
+    *st = launch_status();                                                                                     \
+    return true;                                                                                               \
+  }
+  TC355_TBMM_LDS_VARIANTS(TC355_TBMM_LDS_TRY)
+#undef TC355_TBMM_LDS_TRY
+  return false;
+}
+
+// Returns false if the shape is not one for this kernel (the caller then takes the shape-generic kernels).
+bool try_tbmm_lds(const float* X, const float* Y, float* Z, int64_t B, int64_t N, int64_t M, int64_t K, hipStream_t s,
+                  tc_status* st) {
+  if ((N * K) % 4 != 0 || (M * K) % 4 != 0 || K > 256) return false;  // strips must start and end on 16-byte boundaries
+  const int cus = device_cus();
+  if (cus <= 0) return false;
+  const int64_t tiles_n = ceil_div(N, 16), tiles_m = ceil_div(M, 16);
+  TbmmLdsPlan pl{};
+  pl.tn = tiles_n >= 2 ? 2 : 1;
+  const int64_t strips_n = ceil_div(tiles_n, pl.tn);
+  // A whole row of tiles per job (most reuse of the X strip, contiguous results) when that still leaves two
+  // wavefronts for every SIMD of the chip; with few jobs, fewer tiles per job: a shorter chain from launch to the
+  // last store.
+  pl.tm = 1;
+  for (int c : {5, 2}) {
+    if ((c == 5 ? tiles_m <= 5 && M % 4 == 0 : c <= tiles_m) && B * strips_n * ceil_div(tiles_m, c) >= 8 * (int64_t)cus) {
+      pl.tm = c;
+      break;
+    }
+  }
+  const int64_t strips_m = ceil_div(tiles_m, pl.tm);
+  const int64_t xrows = std::min<int64_t>(16 * pl.tn, N), yrows = std::min<int64_t>(16 * pl.tm, M);
+  const int64_t xu = xrows * K / 4, yu = yrows * K / 4;  // 16-byte pieces per strip
+  pl.nx = (int)ceil_div(xu, WAVE);
+  pl.ny = (int)ceil_div(yu, WAVE);
+  pl.store = (pl.tm == 5) ? TBMM_STORE_FLAT : (M % 4 == 0 ? TBMM_STORE_PIECES : TBMM_STORE_SCALAR);
+  pl.ks = (int)ceil_div(K, 4);
+  // LDS per wavefront: both strips (one spare piece: the last step of a ragged reduction reads past its row); in
+  // the flat store mode the same region then holds the job's block of Z
+  size_t wave_units = (size_t)(xu + yu) + 1;
+  if (pl.store == TBMM_STORE_FLAT) wave_units = std::max<size_t>(wave_units, (size_t)(xrows * M / 4));
+  const size_t lds = WAVES_PER_WG * wave_units * 16;
+  if (lds > 64 * 1024) return false;
+  if (B >= kMaxElems / (strips_n * strips_m)) return false;  // 32-bit job numbers
+  TbmmLdsArgs a{};
+  a.X = X; a.Y = Y; a.Z = Z;
+  a.N = (int)N; a.M = (int)M; a.K = (int)K;
+  a.strips_n = (int)strips_n; a.strips_m = (int)strips_m;
+  a.jobs = (int)(B * strips_n * strips_m);
+  a.wave_lds_units = (int)wave_units;
+  // persistent wavefronts, two workgroups per compute unit (the kernel is compiled for two wavefronts per SIMD);
+  // small jobs take fewer registers and less LDS, so more of their workgroups are resident at once
+  const int64_t per_cu = pl.tm == 5 ? 2 : std::max<int64_t>(2, std::min<int64_t>(4, (160 * 1024) / (int64_t)lds));
+  const int64_t wgs = std::min<int64_t>(ceil_div((int64_t)a.jobs, WAVES_PER_WG), per_cu * cus);
+  return launch_tbmm_lds(pl, a, wgs, lds, s, st);
+}
+
 // ---- the same arithmetic for small images with 32 channels per group ----
 template <int H, int W>
 bool try_gconv_i8_c32(const GconvArgs& g, hipStream_t s, tc_status* st) {
@@ -405,6 +485,11 @@ tc_status tc_tbmm(const float* X, const float* Y, float* Z, int64_t B, int64_t N
       gemm_i8_kernel<<<dim3((unsigned)(M / GI8_TM), (unsigned)B, (unsigned)(N / GI8_TN)), dim3(GI8_THREADS), GI8_LDS_BYTES, s>>>(g);
       return launch_status();
     }
+  }
+
+  {
+    tc_status st = TC_OK;
+    if (try_tbmm_lds(X, Y, Z, B, N, M, K, s, &st)) return st;
   }
 
   GemmArgs a{};
