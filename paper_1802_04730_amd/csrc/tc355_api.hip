@@ -28,6 +28,7 @@
 #include "kron_wave.hpp"
 #include "lut_sum.hpp"
 #include "mlp_fused.hpp"
+#include "mlp_rows.hpp"
 #include "sconv_tile.hpp"
 #include "tbmm_lds.hpp"
 
@@ -243,7 +244,10 @@ long env_long(const char* name, long dflt) {
 
 size_t mlp_sync_bytes() { return round256((MLP_SYNC_WORDS + (size_t)(MLP_MAX_LAYERS - 1) * MLP_BAR_WORDS) * sizeof(unsigned)); }
 
-size_t mlp_act_bytes(int64_t batch, int64_t width) { return round256((size_t)batch * (size_t)width * sizeof(double)); }
+// fp64 copy of one layer's output; whole 16-row tiles (the small-batch kernel keeps it in a tiled layout)
+size_t mlp_act_bytes(int64_t batch, int64_t width) {
+  return round256((size_t)ceil_div(batch, 16) * 16 * (size_t)width * sizeof(double));
+}
 
 // ---- fastest grouped convolution: compile-time width, one workgroup per (image, group) -----
 template <int C, int KH, int KW, int W, int ROWS, int MINW>
@@ -597,6 +601,43 @@ tc_status mlp_run(const float* I, int64_t batch, int32_t n_layers, const int64_t
     if (min_blocks >= 256) fused = false;
   }
   const int cus = device_cus();
+  // Small batches with reductions of at most 1024: one group of workgroups per 16-row tile of the batch carries the
+  // tile through all layers (mlp_rows.hpp).  TC355_MLP_KERNEL=tiles keeps the tile-stream kernel below.
+  if (fused && cus > 0) {
+    const char* which = std::getenv("TC355_MLP_KERNEL");
+    const int64_t G = ceil_div(batch, 16);
+    const int64_t nwg = std::min<int64_t>(cus, MR_MAX_WG);
+    // (a single layer with two tiles per workgroup has nothing to hand over and nothing to hide its second tile's
+    // weights behind: the tile-stream kernel, which pipelines its loads, is faster there: 9.1 against 10.4 us at
+    // 128 x 1024 -> 1024; with one tile per workgroup this kernel is: 6.8 against 8.6 us)
+    bool rows = !(which && std::strcmp(which, "tiles") == 0) && G <= nwg &&
+                (n_layers > 1 || ceil_div(dims[1], 16) <= nwg / G) &&
+                mr_flag_words(n_layers, G, nwg) <= (int64_t)(MLP_MAX_LAYERS - 1) * MLP_BAR_WORDS;
+    for (int l = 0; l < n_layers && rows; l++)
+      rows = (dims[l] == 128 || dims[l] == 256 || dims[l] == 512 || dims[l] == 1024) &&
+             ceil_div(dims[l + 1], 16) <= MR_MAXT * (nwg / G);
+    if (rows) {
+      MlpRowsArgs a{};
+      a.I = I;
+      for (int l = 0; l < n_layers; l++) {
+        a.W[l] = W[l]; a.bias[l] = bias[l]; a.O[l] = O[l]; a.act[l] = act[l];
+      }
+      for (int l = 0; l <= n_layers; l++) a.dims[l] = (int)dims[l];
+      a.batch = (int)batch; a.n_layers = n_layers; a.groups = (int)G;
+      a.sync = reinterpret_cast<unsigned*>(ws);
+      a.token = next_token();
+      a.spin_limit = (unsigned)std::max<long>(1, env_long("TC355_MLP_SPIN_LIMIT", 4000000));
+      static std::atomic<int> lds_ok{0};  // more than the default 64 KiB of dynamic LDS
+      if (!lds_ok.load(std::memory_order_acquire)) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_rows_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                MR_LDS_BYTES) != hipSuccess)
+          return TC_ERR_LAUNCH;
+        lds_ok.store(1, std::memory_order_release);
+      }
+      mlp_rows_kernel<<<dim3((unsigned)nwg), dim3(MR_THREADS), MR_LDS_BYTES, s>>>(a);
+      return launch_status();
+    }
+  }
   if (fused && cus > 0) {
     MlpArgs a{};
     a.I = I;

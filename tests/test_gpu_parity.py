@@ -192,6 +192,12 @@ MLP_SHAPES = [
     (128, (1024, 1000)),            # odd output extent 1000 (the C3 weight of Section 7)
     (48, (256, 336, 80)),           # 63 and 15 tiles: an odd number of four-wavefront teams, the last workgroup half empty
     (2048, (64, 128, 64)),          # 1024 and 512 tiles on 512 teams: two tiles per team, then one
+    # the row-tile kernel (reductions of 128, 256, 512 or 1024, small batch):
+    (100, (512, 256, 1000)),        # 7 row tiles, the last with 4 rows; ragged last column tile; two tiles per workgroup
+    (16, (128, 128, 128)),          # one row tile: every workgroup in one group, most without a tile
+    (200, (1024, 512, 40)),         # 13 row tiles: groups of 19 and 20 workgroups
+    (64, (1024, 512)),              # a single layer with one tile per workgroup
+    (128, (256, 1024, 128, 512, 256, 128)),  # five layers
 ]
 
 
@@ -204,6 +210,23 @@ def test_mlp(tc, shape, oracle_threads):
     for l in range(len(Ws)):
         check(O[l], ref[l], "mlp %s layer %d" % (shape, l))
         assert float(O[l].min()) >= 0.0
+
+
+def test_mlp_tile_stream_kernel_by_switch(tc, oracle_threads, monkeypatch):
+    # TC355_MLP_KERNEL=tiles: the benchmark chain on the persistent tile-stream kernel (what shapes outside the
+    # row-tile kernel's range take), with a workspace full of garbage
+    monkeypatch.setenv("TC355_MLP_KERNEL", "tiles")
+    batch, dims = 128, (1024, 1024, 512, 256)
+    I, Ws, bs = inputs.make_mlp(batch, dims, seed=inputs.SEED_BASE + 3)
+    ref = oracle.mlp_fcrelu(I, Ws, bs)
+    O = [torch.full((batch, d), float("nan"), device="cuda") for d in dims[1:]]
+    ws = torch.full((tc.tc_mlp_fcrelu_workspace_bytes(batch, dims),), 0xCD, dtype=torch.uint8, device="cuda")
+    Id, Wd, bd = dev(I), [dev(w) for w in Ws], [dev(b) for b in bs]
+    for _ in range(2):
+        tc.tc_mlp_fcrelu(Id, Wd, bd, O, ws)
+    for l in range(3):
+        check(O[l], ref[l], "mlp tile-stream kernel, layer %d" % l)
+    assert int(ws[:256].view(torch.int32)[33]) == 0
 
 
 def test_mlp_per_layer_launch_path(tc, oracle_threads, monkeypatch):
