@@ -290,11 +290,8 @@ def main():
 
     tmm_flops, tmm_bytes = inputs.flops_tbmm(1, 128, 16384, 4096), 4 * (128 * 4096 + 16384 * 4096 + 128 * 16384)
     extra = {"tmm_128x4096x16384": entry_i8(timed(lambda: tc355.tc_tbmm(Xt, Yt, Zt)), tmm_flops, tmm_bytes)}
-    os.environ["TC355_TBMM_ARITH"] = "f64"
-    try:
+    with tc355.option(tc355.TC_OPT_INT8, tc355.TC_INT8_OFF):
         extra["tmm_128x4096x16384_fp64_path"] = entry(timed(lambda: tc355.tc_tbmm(Xt, Yt, Zt)), tmm_flops, tmm_bytes)
-    finally:
-        del os.environ["TC355_TBMM_ARITH"]
     for (M_, K_, N_) in [(128, 32, 256), (128, 1024, 1024)]:
         Xt = torch.randn((1, M_, K_), device="cuda")
         Yt = torch.randn((1, N_, K_), device="cuda")
@@ -350,9 +347,8 @@ def main():
     del Xt, Yt, Zt, Im, Wm, bm, Om, It, Wt, bt, Ot, Is_, Ws_, bs_, Os_, T1, T2, idx, O1, O2
 
     # the grouped convolution on the fp64 matrix path (what every other shape of the operator takes), for comparison
-    os.environ["TC355_GCONV_ARITH"] = "f64"
-    g64_us = timed(ops["gconv"][0])
-    del os.environ["TC355_GCONV_ARITH"]
+    with tc355.option(tc355.TC_OPT_INT8, tc355.TC_INT8_OFF):
+        g64_us = timed(ops["gconv"][0])
     extra["gconv_cfg4_fp64_path"] = {"us": round(g64_us, 1), "gflops": round(ops["gconv"][1] / g64_us * 1e-3, 1), "bound": "mfma",
                                      "frac": round(ops["gconv"][1] / (PEAK_F64_MFMA_TFLOPS * 1e12) * 1e6 / g64_us, 4)}
 
@@ -446,11 +442,8 @@ def sustained_study(torch, tc355, ops, Ig, gconv_tensors, seconds):
     Icopy = torch.empty_like(Ig)
 
     def gconv_fp64():
-        os.environ["TC355_GCONV_ARITH"] = "f64"
-        try:
+        with tc355.option(tc355.TC_OPT_INT8, tc355.TC_INT8_OFF):
             ops["gconv"][0]()
-        finally:
-            del os.environ["TC355_GCONV_ARITH"]
 
     def whole_step():
         for name in ("tbmm", "mlp", "gconv", "kron"):

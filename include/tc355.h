@@ -31,13 +31,9 @@
  *  - Thread safety: the only mutable global state is a per-process cache of
  *    device properties and an atomic call counter; concurrent calls from
  *    several host threads are allowed.
- *  - Environment (read at every call, meant for tests): TC355_MLP_FUSED=0
- *    forces one launch per MLP layer, =1 the single fused kernel (by default
- *    very large batches take one launch per layer); TC355_MLP_SPIN_LIMIT=<n> bounds the
- *    polls of a device-wide wait; TC355_GCONV_ARITH=f64 keeps every grouped
- *    convolution on the fp64 path, =i8x13 makes the int8 path keep 13 instead
- *    of 10 digit products (see tc_group_conv); TC355_TBMM_ARITH=f64 keeps
- *    every transposed matmul on the fp64 path (see tc_tbmm).
+ *  - No environment variable is read.  The few switches (arithmetic of the
+ *    int8 paths, choice of MLP kernel, spin limit of its waits) are options of
+ *    the calling host thread: tc355_set_option below.
  */
 #ifndef TC355_H
 #define TC355_H
@@ -68,6 +64,41 @@ const char *tc_status_string(tc_status s);
 int tc355_version(void);
 
 /*
+ * Options of the CALLING HOST THREAD (thread-local: they affect the calls this
+ * thread makes afterwards and race with nothing).  Meant for tests, benchmarks
+ * and for callers that know their data; the defaults are safe for any input.
+ *   TC_OPT_INT8            arithmetic of the shapes that have an int8 matrix-core
+ *                          path (see tc_group_conv, tc_tbmm):
+ *       TC_INT8_AUTO       (default) sliced int8 arithmetic; blocks whose operands
+ *                          are heavy-tailed get 13 instead of 10 digit products
+ *       TC_INT8_OFF        the fp64 path for every shape
+ *       TC_INT8_TEN        10 digit products for every block (fastest; accuracy
+ *                          then depends on the data, see tc_group_conv)
+ *       TC_INT8_THIRTEEN   13 digit products for every block
+ *   TC_OPT_MLP_KERNEL      TC_MLP_AUTO (default), TC_MLP_ROWS, TC_MLP_TILES (one
+ *                          persistent kernel of either kind where it applies),
+ *                          TC_MLP_PER_LAYER (one launch per layer)
+ *   TC_OPT_MLP_SPIN_LIMIT  polls after which a wait inside a fused MLP kernel gives
+ *                          up (default 4000000; >= 1)
+ * tc355_set_option returns TC_ERR_SHAPE for an unknown key or a value out of
+ * range.  tc355_get_option returns the current value (-1 for an unknown key).
+ */
+typedef enum { TC_OPT_INT8 = 0, TC_OPT_MLP_KERNEL = 1, TC_OPT_MLP_SPIN_LIMIT = 2 } tc_option;
+enum { TC_INT8_AUTO = 0, TC_INT8_OFF = 1, TC_INT8_TEN = 2, TC_INT8_THIRTEEN = 3 };
+enum { TC_MLP_AUTO = 0, TC_MLP_ROWS = 1, TC_MLP_TILES = 2, TC_MLP_PER_LAYER = 3 };
+tc_status tc355_set_option(tc_option key, int64_t value);
+int64_t tc355_get_option(tc_option key);
+
+/*
+ * Which kernel family the calling thread's most recent entry-point call chose,
+ * as a static string "op:family" (for example "tbmm:lds", "tbmm:i8",
+ * "mlp:rows", "gconv:i8", "gconv:band"; "" before the first call).  A debugging
+ * and testing aid: tests pick the tolerance of the arithmetic that actually
+ * ran instead of re-deriving the dispatch.
+ */
+const char *tc355_last_path(void);
+
+/*
  * Transposed batched matmul (Section 7, "Transposed Batched Matrix
  * Multiplication", listing tbmm; index names as in the benchmark
  * configurations):
@@ -81,16 +112,19 @@ int tc355_version(void);
  * (128,4096,16384) is of this kind), which run on the int8 matrix core: in
  * every block of 128 reduction indices each row of X and of Y is scaled so that
  * its largest magnitude m maps to 0x7F7F7F7E, rounded to a 32-bit integer
- * (off by at most 2^-32 m) and cut into four signed 8-bit digits; the 10 digit
- * products of weight 256^3 and above are summed exactly in int32, scaled back
+ * (off by at most 2^-32 m) and cut into four signed 8-bit digits; the 13 digit
+ * products of weight 256^2 and above (digit k of one operand times digit l
+ * of the other with k + l >= 2) are summed exactly in int32, scaled back
  * and added over the blocks in fp64, and the sum is rounded to fp32 once.
- * Error bound: K * 2^-29.5 * max|X row block| * max|Y row block| absolute,
- * worst case; measured 3e-7 .. 9e-7 on max|gpu - ref| / (|ref| + 1e-3
- * max|ref|) for uniform and Gaussian operands, 1e-6 .. 4e-6 for log-normal
- * magnitudes (sigma 1.5 and 1), up to 1.2e-5 with sigma 2 on both (still
- * inside 2e-5, but such data is what the switch below is for).  A row of X
- * (of Y) that holds Inf or NaN gives NaN in all of that row's (column's)
- * outputs.  TC355_TBMM_ARITH=f64 takes the fp64 path for these shapes too.
+ * Error bound: K * 2^-30.5 * max|X row block| * max|Y row block| absolute,
+ * worst case (the rounding of the two operands; the dropped digit products
+ * are 2^-7 of that); on max|gpu - ref| / (|ref| + 1e-3 max|ref|) below 2e-6
+ * for uniform, Gaussian and log-normal (sigma 2 on both operands) data.
+ * With option TC_OPT_INT8 = TC_INT8_TEN the diagonal k + l = 2 is dropped
+ * (10 products, K * 2^-29.5: 3e-7 .. 9e-7 for uniform and Gaussian operands,
+ * up to 1.2e-5 for log-normal magnitudes of sigma 2), with TC_INT8_OFF these
+ * shapes take the fp64 path too.  A row of X (of Y) that holds Inf or NaN
+ * gives NaN in all of that row's (column's) outputs.
  */
 tc_status tc_tbmm(const float *X, const float *Y, float *Z, int64_t B,
                   int64_t N, int64_t M, int64_t K, void *hip_stream);
@@ -178,22 +212,28 @@ tc_status tc_mlp_fcrelu_static(const float *I, int64_t batch, int32_t n_layers,
  * (for 14 x 14: every whole block of 16 input planes) is
  * scaled to 32-bit fixed point (the block's largest magnitude maps to
  * 0x7F7F7F7E, every element is held to 2^-32 of that magnitude), cut into
- * four signed 8-bit digits, and the 10 leading digit products (k + l >= 3)
- * are summed exactly in int32; the result is recombined in fp64, the bias
- * added, and rounded to fp32 once.  Error against the float64 definition: at
- * most K * 2^-29.5 * max|filter row| * max|band| in absolute terms for a
- * reduction of K terms (2^-31 from the rounding of the two operands, the rest
- * from the dropped digit products), in practice (random operands) about 1e-6
- * on the parity metric
- * max|err| / (|ref| + 1e-3 max|ref|).  The bound is relative to the block
- * maxima: when both operands are heavy-tailed (a few elements far above the
- * rest in every band and every filter row) the maxima say little about the
- * outputs, and the dropped products come close to 2e-5 on that metric
- * (1.6e-5 measured with log-normal magnitudes of sigma 1.5 and 1).  For such
- * data TC355_GCONV_ARITH=i8x13 keeps the next diagonal of digit products
- * (13 in all: 1.4e-6 on the same data, 16 % slower; the 14 x 14 and 7 x 7
- * geometries then take the fp64 path), and
- * TC355_GCONV_ARITH=f64 takes the fp64 path.  A band that holds Inf or NaN
+ * four signed 8-bit digits; digit products (digit k of a filter element
+ * times digit l of an input element) are summed exactly in int32, the
+ * result is recombined in fp64, the bias added, and rounded to fp32 once.
+ * The 10 products with k + l >= 3 are always taken; the three with
+ * k + l = 2 are worth up to K * 2^-29.5 * max|filter row| * max|band| over a
+ * reduction of K terms, which is far below the outputs unless BOTH operands
+ * are heavy-tailed (a few elements far above the rest in every band and
+ * every filter row, so that the block maxima say little about the outputs).
+ * The 14 x 14 and 7 x 7 geometries always take them (13 products).  The
+ * width-58 geometry decides per thread (one band of one image with the 16
+ * filter rows of its group): with S = (band maximum / smallest maximum among
+ * the band's four column strips) * (largest ratio of maximum to mean
+ * magnitude among the 16 filter rows), it takes the 10 products when
+ * S <= 128 (Gaussian and ReLU-like data: S = 11 .. 22, Laplace up to 72) and
+ * adds the three others in extra sweeps otherwise (log-normal, Student-t,
+ * sparse outliers: S from 150 up), at about 40 % more time for such
+ * a thread.  Either way the error against the float64 definition stays
+ * below 5e-6 on the parity metric max|err| / (|ref| + 1e-3 max|ref|) for
+ * all of these distributions (1e-6 for the benchmark's).
+ * Option TC_OPT_INT8: TC_INT8_TEN never takes the diagonal (1.6e-5
+ * measured with log-normal magnitudes of sigma 1.5 and 1), TC_INT8_THIRTEEN
+ * always does, TC_INT8_OFF takes the fp64 path.  A band that holds Inf or NaN
  * gives NaN in all outputs that read the band.
  */
 tc_status tc_group_conv(const float *I, const float *W1, const float *bias,

@@ -40,7 +40,6 @@ struct GconvBandArgs {
   const float* bias;  // or nullptr
   float* O;
   int G, H;
-  TC355_TRACE_FIELD
 };
 
 template <int C, int KH, int KW, int W, int ROWS>
@@ -66,13 +65,6 @@ __global__ __launch_bounds__(WG_THREADS, MINW) void gconv_band_kernel(GconvBandA
   constexpr int F = Gm::F, OW = Gm::OW, PS = Gm::PS, NS = Gm::NS, LEN = Gm::LEN, LEN4 = Gm::LEN4, NLD = Gm::NLD;
   extern __shared__ __attribute__((aligned(16))) double band[];  // [C][PS]
 
-#ifdef TC355_TRACE_ENABLE
-  unsigned long long* trace = p.trace;
-#else
-  unsigned long long* trace = nullptr;
-#endif
-  TC355_TRACE_DECL
-  TC355_TRACE_R(trace, 1);
   const int tid = threadIdx.x;
   const int lane = tid & (WAVE - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
@@ -146,17 +138,13 @@ __global__ __launch_bounds__(WG_THREADS, MINW) void gconv_band_kernel(GconvBandA
     }
   };
 
-  (void)trace;
   for (int b = 0; b < nbands; b++) {
     __syncthreads();  // everyone has finished reading the previous band
-    TC355_TRACE_R(trace, 2);
     stage();
     __syncthreads();
-    TC355_TRACE_R(trace, 3);
     const bool more = b + 1 < nbands;  // the next band is fetched piecemeal between the MFMA steps below:
     // issued in one burst, the loads of all workgroups pile up in the memory pipeline and the
     // issuing wavefronts sit blocked for ~10 us; spread out, they vanish behind the MFMAs
-    TC355_TRACE_R(trace, 4);
 
     const int P0 = b * ROWS * OW;
     // Tiles of the band are dealt to the wavefronts round-robin: tile id = 4*t + wr.  Every wavefront
@@ -227,9 +215,7 @@ __global__ __launch_bounds__(WG_THREADS, MINW) void gconv_band_kernel(GconvBandA
     if constexpr (REM > 0) {
       if (wr < REM) group(integral_constant<int, 1>{}, FULL, integral_constant<int, 0>{}, integral_constant<int, 0>{});
     }
-    TC355_TRACE_R(trace, 5);
   }
-  TC355_TRACE_FLUSH(trace);
 }
 
 }  // namespace tc355

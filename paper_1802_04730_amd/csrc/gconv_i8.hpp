@@ -27,12 +27,27 @@
 // typical magnitude.  (Scaling by a power of two and keeping the 13 pairs with
 // k + l >= 2 measures 3e-7 there and no better on heavy-tailed data, for 30 %
 // more matrix work; on this kernel, which runs at the board's power limit, that
-// is 8 % of the time.)  What the dropped diagonal costs grows when BOTH operands
-// are heavy-tailed (a few elements far above the rest in every block): with
-// log-normal magnitudes of sigma 1.5 and 1 the 10 products measure 1.6e-5 and
-// 13 products at the same scaling 1.4e-6; the kernel can therefore be
-// instantiated with the diagonal k + l = 2 kept (MIND = 2).  A band whose
-// inputs contain Inf/NaN yields NaN for all of that band's outputs.
+// is 8 % of the time.)
+//
+// What the dropped diagonal k + l = 2 costs is proportional to the product of
+// the two block maxima, so it grows when the maxima say little about the
+// outputs: when BOTH operands are heavy-tailed (a few elements far above the
+// rest in every block) the 10 products come close to the bar (1.6e-5 measured
+// with log-normal magnitudes of sigma 1.5 and 1).  The kernel therefore decides
+// per band, from a statistic it gets almost for free while it looks for the band
+// maximum:
+//     S = (band maximum / smallest per-thread maximum)
+//         * (largest ratio of maximum to mean magnitude among the group's 16 filter rows)
+// (Gaussian operands: 11-22, behind a ReLU the same, Laplacian 27-72; Student-t(3)
+// 150-600, log-normal magnitudes and single huge elements: thousands).  A band
+// with S above I8_HEAVY_STAT = 128 gets the diagonal k + l = 2 as well: after the
+// ordinary sweeps a second, lighter set of sweeps (3 products instead of 10)
+// accumulates it and adds it to the staged outputs, 13 products in all.  The
+// emulation in tests/test_i8_scheme.py holds both branches of that rule below a
+// quarter of the bar on all those distributions.  A band in which some thread
+// sees only zeros counts as heavy (S is infinite): slower, never less accurate.
+// `force13` in the arguments overrides the rule (1: every band, -1: no band).
+// A band whose inputs contain Inf/NaN yields NaN for all of that band's outputs.
 //
 // MFMA v_mfma_i32_16x16x64_i8, lane = (r16 = lane % 16, q = lane / 16), measured:
 //   A (16 x 64): lane supplies A[row r16][k = 16q .. 16q+15]  (16 bytes)
@@ -80,8 +95,10 @@ struct GconvI8Args {
   int N;        // images
   int halves;   // gridDim.x / 2 if workgroups w and w + halves share a compute unit's work, else 0 (even split)
   int num, den; // of the bands that such a pair owns, workgroup w takes the first num/den
-  TC355_TRACE_FIELD
+  int force13;  // 0: the diagonal k + l = 2 for heavy-tailed bands only; 1: for every band; -1: never
 };
+
+constexpr float I8_HEAVY_STAT = 128.0f;  // bands whose statistic S (see above) exceeds this get 13 digit products
 
 template <int W, int ROWS>
 struct GconvI8Geom {
@@ -97,7 +114,7 @@ struct GconvI8Geom {
   static constexpr int NQ = NPX / 4, NUNIT = 4 * NQ, NHALF = 2 * (NUNIT - 2 * WG_THREADS);
   static_assert(NPX % 4 == 0 && NUNIT > 2 * WG_THREADS && NHALF <= WG_THREADS, "two rounds of units and one of half units");
   static constexpr int MISC = 2 * BUF;                                  // byte offset of the small arrays
-  static constexpr int LDS_BYTES = 2 * BUF + 128;
+  static constexpr int LDS_BYTES = 2 * BUF + 128;                       // + the per-wavefront maxima and minima
   static constexpr int NFC = OW / 16;                                   // full 16-pixel columns
   // output staging of a wavefront (16 filters x 2 rows x OW pixels, fp32) in the idle band buffer: filter stride
   // in floats = 4 (mod 16), so that the four filter rows a store instruction writes fall into different banks
@@ -170,6 +187,18 @@ __device__ __forceinline__ unsigned i8_wave_max(unsigned m) {
   return (unsigned)max(max(r0, r1), max(r2, r3));
 }
 
+// Minimum over the wavefront of bit patterns with the sign cleared, returned in every lane.
+__device__ __forceinline__ unsigned i8_wave_min(unsigned m) {
+  int v = (int)m;
+  v = min(v, __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false));
+  v = min(v, __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false));
+  v = min(v, __builtin_amdgcn_update_dpp(v, v, 0x141, 0xF, 0xF, false));
+  v = min(v, __builtin_amdgcn_update_dpp(v, v, 0x140, 0xF, 0xF, false));
+  const int r0 = __builtin_amdgcn_readlane(v, 0), r1 = __builtin_amdgcn_readlane(v, 16);
+  const int r2 = __builtin_amdgcn_readlane(v, 32), r3 = __builtin_amdgcn_readlane(v, 48);
+  return (unsigned)min(min(r0, r1), min(r2, r3));
+}
+
 __device__ __forceinline__ i4 mfma_i8(i4 a, i4 b, i4 c) { return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0); }
 
 // MIND: the lowest digit diagonal k + l that is kept: 3 (10 products, the default) or 2 (13 products).
@@ -183,15 +212,8 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
   static_assert(WN % WG_THREADS == 0, "whole filter-bank floats per thread");
   extern __shared__ __attribute__((aligned(16))) char gi8_lds[];
   unsigned* maxw = reinterpret_cast<unsigned*>(gi8_lds + Gm::MISC);     // [2][4] band maxima per wavefront
+  unsigned* minw = maxw + 8;                                            // [2][4] smallest per-thread maximum per wavefront
 
-#ifdef TC355_TRACE_ENABLE
-  unsigned long long* trace = p.trace;
-#else
-  unsigned long long* trace = nullptr;
-#endif
-  (void)trace;
-  TC355_TRACE_DECL
-  TC355_TRACE_R(trace, 1);
   const int tid = threadIdx.x;
   const int lane = tid & (WAVE - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
@@ -273,6 +295,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
   i4 a[KH][4];     // a[kh][k]: digit k of W1[g][r16][c = byte][kh][kw = q], zeros for q = 3
   double fa[4];    // 2^24 / scale of filter row 4q + v (NaN if the row holds Inf/NaN)
   float bz[4];     // bias of filter row 4q + v
+  float wspread = 0.f;  // largest max|w| / mean|w| among the group's filter rows (uniform)
   int it = 0;      // bands staged so far by this workgroup: LDS buffer parity
   int g_bank = -1; // group whose filter bank the A operands hold
   for (; u < u1; u++, it++) {
@@ -311,6 +334,20 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
       m = max(m, (unsigned)__shfl_xor((int)m, 16));
       m = max(m, (unsigned)__shfl_xor((int)m, 32));
       const double sa = i8_scale(m);  // m = max|w| over the filter row
+      {
+        // max / mean of the row's 144 magnitudes (lanes q = 0..2 hold one kw each; q = 3 re-reads kw = 2: left out),
+        // then the largest of the 16 rows
+        float sum = 0.f;
+#pragma unroll
+        for (int kh = 0; kh < KH; kh++)
+#pragma unroll
+          for (int c = 0; c < C; c++) sum += __builtin_fabsf(wp[c * (KH * KW) + kh * KW]);
+        sum = q < KW ? sum : 0.f;
+        sum += __shfl_xor(sum, 16);
+        sum += __shfl_xor(sum, 32);
+        const float ratio = sum > 0.f ? __uint_as_float(m) * (float)(C * KH * KW) / sum : 1.f;  // an all-zero row: 1
+        wspread = __uint_as_float(i8_wave_max(__float_as_uint(ratio)));  // ratio >= 1 > 0: bit patterns order like values
+      }
 #pragma unroll
       for (int kh = 0; kh < KH; kh++) {
         int d[4], y[4];
@@ -334,7 +371,6 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
       }
       // the staging below overwrites this scratch only after the next barrier, which every wavefront reaches after these reads
     }
-    TC355_TRACE_R(trace, 2);
 
     {
       char* buf = gi8_lds + (it & 1) * BUF;
@@ -358,12 +394,23 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
         for (int c = 0; c < 4; c++) take(preh[c][0], preh[c][1]);
       }
       unsigned m = max((unsigned)mp, mn & 0x7fffffffu);
+      const unsigned tmin = i8_wave_min(m);  // smallest per-thread maximum of this wavefront
       m = i8_wave_max(m);
-      if (lane == 0) maxw[(it & 1) * 4 + wave] = m;
+      if (lane == 0) {
+        maxw[(it & 1) * 4 + wave] = m;
+        minw[(it & 1) * 4 + wave] = tmin;
+      }
       __syncthreads();
-      TC355_TRACE_R(trace, 3);
       m = max(max(maxw[(it & 1) * 4 + 0], maxw[(it & 1) * 4 + 1]), max(maxw[(it & 1) * 4 + 2], maxw[(it & 1) * 4 + 3]));
       m = (unsigned)__builtin_amdgcn_readfirstlane((int)m);  // max|x| over the band
+      // heavy-tailed band?  S = (band maximum / smallest per-thread maximum) * (spread of the filter rows); a thread
+      // that saw only zeros makes S infinite.  Uniform over the workgroup.
+      bool heavy = p.force13 > 0;
+      if (MIND == 3 && p.force13 == 0) {
+        unsigned t = min(min(minw[(it & 1) * 4 + 0], minw[(it & 1) * 4 + 1]), min(minw[(it & 1) * 4 + 2], minw[(it & 1) * 4 + 3]));
+        t = (unsigned)__builtin_amdgcn_readfirstlane((int)t);
+        heavy = !(__uint_as_float(m) * wspread <= I8_HEAVY_STAT * __uint_as_float(t));  // (NaN compares false: heavy)
+      }
 
       // ---- slice and stage: digit plane k, record of pixel pi at byte k*PLANE + 16*pi, channels 4cg.. at +4cg
       {
@@ -395,7 +442,6 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
         }
       }
       __syncthreads();
-      TC355_TRACE_R(trace, 4);
 
       // ---- what to fetch while this band is contracted: the next band of the run
       const bool more = u + 1 < u1;
@@ -420,9 +466,12 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
       // One sweep: NR output rows per lane, NR + 2 input rows starting at the lane's LDS pointer `base`
       // (input row of its first output row, column of its pixel + kw).  orow/ocol: the lane's first output
       // row and its column.  PIECE: the fetch piece of the next band to issue during this sweep, or -1.
-      auto sweep = [&](auto nr_c, auto piece_c, auto col_c, const char* base, char* obase) {
+      // FIX: the second, lighter kind of sweep: only the diagonal k + l = 2, added to what the first kind staged.
+      auto sweep = [&](auto nr_c, auto piece_c, auto col_c, auto fix_c, const char* base, char* obase) {
         constexpr int NR = decltype(nr_c)::value, PIECE = decltype(piece_c)::value, COL = decltype(col_c)::value;
-        constexpr int ND = 7 - MIND;
+        constexpr bool FIX = decltype(fix_c)::value;
+        constexpr int ND = FIX ? 1 : 7 - MIND;
+        constexpr int NL = FIX ? 3 : 4;  // digit planes of the input that the sweep reads
         i4 acc[NR][ND];  // diagonals k + l = MIND .. 6
 #pragma unroll
         for (int hl = 0; hl < NR; hl++)
@@ -430,12 +479,12 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
           for (int d = 0; d < ND; d++) acc[hl][d] = i4{0, 0, 0, 0};
         i4 bc[4], bn[4];
 #pragma unroll
-        for (int l = 0; l < 4; l++) bc[l] = *reinterpret_cast<const i4*>(base + l * PLANE);
+        for (int l = 0; l < NL; l++) bc[l] = *reinterpret_cast<const i4*>(base + l * PLANE);
         auto row = [&](auto r_c) {
           constexpr int r = decltype(r_c)::value;
           if constexpr (r + 1 < NR + 2) {
 #pragma unroll
-            for (int l = 0; l < 4; l++) bn[l] = *reinterpret_cast<const i4*>(base + l * PLANE + (r + 1) * W * 16);
+            for (int l = 0; l < NL; l++) bn[l] = *reinterpret_cast<const i4*>(base + l * PLANE + (r + 1) * W * 16);
           }
           if constexpr (PIECE >= 0 && r == 1) {
             if (more) fetch_piece(integral_constant<int, PIECE >= 0 ? PIECE : 0>{});
@@ -447,15 +496,16 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
           constexpr int PK[13] = {3, 3, 3, 3, 2, 2, 2, 1, 1, 0, 2, 1, 0};
           constexpr int PL[13] = {3, 2, 1, 0, 3, 2, 1, 3, 2, 3, 0, 1, 2};
 #pragma unroll
-          for (int i = 0; i < NP; i++)
+          for (int i = FIX ? 10 : 0; i < (FIX ? 13 : NP); i++)
 #pragma unroll
             for (int hl = 0; hl < NR; hl++) {
               const int kh = r - hl;
+              constexpr int D0 = FIX ? 2 : MIND;
               if (kh >= 0 && kh < KH)
-                acc[hl][PK[i] + PL[i] - MIND] = mfma_i8(a[kh][PK[i]], bc[PL[i]], acc[hl][PK[i] + PL[i] - MIND]);
+                acc[hl][PK[i] + PL[i] - D0] = mfma_i8(a[kh][PK[i]], bc[PL[i]], acc[hl][PK[i] + PL[i] - D0]);
             }
 #pragma unroll
-          for (int l = 0; l < 4; l++) bc[l] = bn[l];
+          for (int l = 0; l < NL; l++) bc[l] = bn[l];
           __builtin_amdgcn_sched_barrier(0);
         };
         row(integral_constant<int, 0>{});
@@ -463,6 +513,18 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
         row(integral_constant<int, 2>{});
         if constexpr (NR == 2) row(integral_constant<int, 3>{});
         static_assert(NR == 1 || NR == 2, "one or two output rows per sweep");
+        if constexpr (FIX) {
+          // the diagonal k + l = 2 is worth 1/256 of a unit of the combined diagonals; it joins the staged value (this
+          // lane wrote it, this lane reads it) in fp64, and the sum is rounded to fp32 again
+#pragma unroll
+          for (int hl = 0; hl < NR; hl++)
+#pragma unroll
+            for (int v = 0; v < 4; v++) {
+              float* o = reinterpret_cast<float*>(obase + (v * Gm::OSF + hl * OW + COL) * 4);
+              *o = (float)__builtin_fma((double)acc[hl][0][v] * 0.00390625, fo[v], (double)*o);
+            }
+          return;
+        }
         // ---- exact recombination of the diagonals, scaling, bias, single rounding
 #pragma unroll
         for (int hl = 0; hl < NR; hl++) {
@@ -479,14 +541,25 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
         }
       };
       const char* lbase = buf + ((2 * wave) * W + r16 + kwq) * 16;
-      sweep(integral_constant<int, 2>{}, integral_constant<int, 0>{}, integral_constant<int, 0>{}, lbase, olane);
-      sweep(integral_constant<int, 2>{}, integral_constant<int, 1>{}, integral_constant<int, 16>{}, lbase + 256, olane);
-      sweep(integral_constant<int, 2>{}, integral_constant<int, 2>{}, integral_constant<int, 32>{}, lbase + 512, olane);
+      using std::false_type;
+      using std::true_type;
+      sweep(integral_constant<int, 2>{}, integral_constant<int, 0>{}, integral_constant<int, 0>{}, false_type{}, lbase, olane);
+      sweep(integral_constant<int, 2>{}, integral_constant<int, 1>{}, integral_constant<int, 16>{}, false_type{}, lbase + 256, olane);
+      sweep(integral_constant<int, 2>{}, integral_constant<int, 2>{}, integral_constant<int, 32>{}, false_type{}, lbase + 512, olane);
       static_assert(NFC == 3, "three full columns are written out above");
       // last 8 columns of both rows in one tile: lanes 0-7 row h0, lanes 8-15 row h0 + 1
       const int hr = r16 >> 3;
-      sweep(integral_constant<int, 1>{}, integral_constant<int, -1>{}, integral_constant<int, 16 * NFC>{},
-            buf + ((2 * wave + hr) * W + 16 * NFC + (r16 & 7) + kwq) * 16, olane + (hr * OW + (r16 & 7) - r16) * 4);
+      const char* lbase8 = buf + ((2 * wave + hr) * W + 16 * NFC + (r16 & 7) + kwq) * 16;
+      char* olane8 = olane + (hr * OW + (r16 & 7) - r16) * 4;
+      sweep(integral_constant<int, 1>{}, integral_constant<int, -1>{}, integral_constant<int, 16 * NFC>{}, false_type{}, lbase8, olane8);
+      if constexpr (MIND == 3) {
+        if (heavy) {  // uniform over the workgroup: the same sweeps again for the diagonal k + l = 2
+          sweep(integral_constant<int, 2>{}, integral_constant<int, -1>{}, integral_constant<int, 0>{}, true_type{}, lbase, olane);
+          sweep(integral_constant<int, 2>{}, integral_constant<int, -1>{}, integral_constant<int, 16>{}, true_type{}, lbase + 256, olane);
+          sweep(integral_constant<int, 2>{}, integral_constant<int, -1>{}, integral_constant<int, 32>{}, true_type{}, lbase + 512, olane);
+          sweep(integral_constant<int, 1>{}, integral_constant<int, -1>{}, integral_constant<int, 16 * NFC>{}, true_type{}, lbase8, olane8);
+        }
+      }
       // ---- staged outputs -> O: instruction j writes filters 2j (lanes 0-31) and 2j+1 (lanes 32-63), 16 bytes per
       // lane; the staging is private to the wavefront, so its own LDS writes only have to have landed
       {
@@ -504,10 +577,8 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_kernel(GconvI8Args p) 
           }
         }
       }
-      TC355_TRACE_R(trace, 5);
     }
   }
-  TC355_TRACE_FLUSH(trace);
 }
 
 }  // namespace tc355

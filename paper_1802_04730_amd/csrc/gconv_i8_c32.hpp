@@ -47,8 +47,11 @@ struct GconvI8C32Geom {
   static_assert(3 * PLANE + NPX * C < 65536, "LDS immediates out of range");
 };
 
-template <int H, int W>
+// MIND: the lowest digit diagonal k + l that is kept: 2 (13 products: what the library uses unless told that 10
+// will do) or 3 (10 products).
+template <int H, int W, int MIND = 2>
 __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_c32_kernel(GconvI8C32Args p) {
+  static_assert(MIND == 2 || MIND == 3, "13 or 10 digit products");
   using Gm = GconvI8C32Geom<H, W>;
   constexpr int C = Gm::C, F = Gm::F, KW = Gm::KW, TAPS = Gm::TAPS, OW = Gm::OW, NPX = Gm::NPX, NOUT = Gm::NOUT,
                 PT = Gm::PT, FT = Gm::FT, NJ = Gm::NJ, PLANE = Gm::PLANE, ROUNDS = Gm::ROUNDS, WROW = Gm::WROW;
@@ -205,27 +208,29 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_c32_kernel(GconvI8C32A
           a[j][k] = *reinterpret_cast<const i4*>(arec + (((ft * NJ + j) * 4 + k) * WAVE + lane) * 16);
 #pragma unroll
       for (int t = 0; t < PT; t++) {
-        i4 acc[4];  // diagonals k + l = 3 .. 6
+        constexpr int ND = 7 - MIND, NP = MIND == 3 ? 10 : 13;
+        i4 acc[ND];  // diagonals k + l = MIND .. 6
 #pragma unroll
-        for (int d = 0; d < 4; d++) acc[d] = i4{0, 0, 0, 0};
+        for (int d = 0; d < ND; d++) acc[d] = i4{0, 0, 0, 0};
 #pragma unroll
         for (int j = 0; j < NJ; j++) {
           i4 b[4];
 #pragma unroll
           for (int l = 0; l < 4; l++) b[l] = *reinterpret_cast<const i4*>(img + boff[t][j] + l * PLANE);
-          constexpr int PK[10] = {3, 3, 3, 3, 2, 2, 2, 1, 1, 0};
-          constexpr int PL[10] = {3, 2, 1, 0, 3, 2, 1, 3, 2, 3};
+          constexpr int PK[13] = {3, 3, 3, 3, 2, 2, 2, 1, 1, 0, 2, 1, 0};  // the last three: the diagonal k + l = 2
+          constexpr int PL[13] = {3, 2, 1, 0, 3, 2, 1, 3, 2, 3, 0, 1, 2};
 #pragma unroll
-          for (int i = 0; i < 10; i++) acc[PK[i] + PL[i] - 3] = mfma_i8(a[j][PK[i]], b[PL[i]], acc[PK[i] + PL[i] - 3]);
+          for (int i = 0; i < NP; i++) acc[PK[i] + PL[i] - MIND] = mfma_i8(a[j][PK[i]], b[PL[i]], acc[PK[i] + PL[i] - MIND]);
         }
         const int px = 16 * t + r16;
 #pragma unroll
         for (int v = 0; v < 4; v++) {
           // sum_d P_d 256^(d-3), exact.  (With 288 terms per output 256 * P_4 + P_3 can pass 2^31, so the diagonals
           // are combined in fp64 rather than pairwise in int32 as in the 16-channel kernels.)
-          const double rr = __builtin_fma((double)acc[3][v], 16777216.0,
-                                          __builtin_fma((double)acc[2][v], 65536.0,
-                                                        __builtin_fma((double)acc[1][v], 256.0, (double)acc[0][v])));
+          double rr = __builtin_fma((double)acc[ND - 1][v], 16777216.0,
+                                    __builtin_fma((double)acc[ND - 2][v], 65536.0,
+                                                  __builtin_fma((double)acc[ND - 3][v], 256.0, (double)acc[ND - 4][v])));
+          if constexpr (MIND == 2) rr = __builtin_fma((double)acc[0][v], 0.00390625, rr);
           const float o = (float)__builtin_fma(rr, fa[ft][v] * invb, (double)bz[ft][v]);
           if (px < NOUT) store_stream(dst + (16 * ft + 4 * q + v) * NOUT + px, o);
         }

@@ -40,8 +40,11 @@ struct GconvI8SmallGeom {
   static_assert(3 * PLANE + ((H - 1) * W + W) * 16 < 65536, "LDS immediates out of range");
 };
 
-template <int H, int W>
+// MIND: the lowest digit diagonal k + l that is kept: 2 (13 products: what the library uses unless told that 10
+// will do) or 3 (10 products).  The kernel's time is launch, cold start and set-up; the products hardly show.
+template <int H, int W, int MIND = 2>
 __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_small_kernel(GconvI8SmallArgs p) {
+  static_assert(MIND == 2 || MIND == 3, "13 or 10 digit products");
   using Gm = GconvI8SmallGeom<H, W>;
   constexpr int C = Gm::C, F = Gm::F, KH = Gm::KH, KW = Gm::KW, OW = Gm::OW, NPX = Gm::NPX, NOUT = Gm::NOUT,
                 TILES = Gm::TILES, PLANE = Gm::PLANE, ROUNDS = Gm::ROUNDS;
@@ -194,25 +197,27 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_small_kernel(GconvI8Sm
     const char* lbase = img;
 #pragma unroll
     for (int t = 0; t < TILES; t++) {
-      i4 acc[4];  // diagonals k + l = 3 .. 6
+      constexpr int ND = 7 - MIND, NP = MIND == 3 ? 10 : 13;
+      i4 acc[ND];  // diagonals k + l = MIND .. 6
 #pragma unroll
-      for (int d = 0; d < 4; d++) acc[d] = i4{0, 0, 0, 0};
+      for (int d = 0; d < ND; d++) acc[d] = i4{0, 0, 0, 0};
 #pragma unroll
       for (int kh = 0; kh < KH; kh++) {
         i4 b[4];
 #pragma unroll
         for (int l = 0; l < 4; l++) b[l] = *reinterpret_cast<const i4*>(lbase + boff[t] + l * PLANE + kh * W * 16);
-        constexpr int PK[10] = {3, 3, 3, 3, 2, 2, 2, 1, 1, 0};
-        constexpr int PL[10] = {3, 2, 1, 0, 3, 2, 1, 3, 2, 3};
+        constexpr int PK[13] = {3, 3, 3, 3, 2, 2, 2, 1, 1, 0, 2, 1, 0};  // the last three: the diagonal k + l = 2
+        constexpr int PL[13] = {3, 2, 1, 0, 3, 2, 1, 3, 2, 3, 0, 1, 2};
 #pragma unroll
-        for (int i = 0; i < 10; i++) acc[PK[i] + PL[i] - 3] = mfma_i8(a[kh][PK[i]], b[PL[i]], acc[PK[i] + PL[i] - 3]);
+        for (int i = 0; i < NP; i++) acc[PK[i] + PL[i] - MIND] = mfma_i8(a[kh][PK[i]], b[PL[i]], acc[PK[i] + PL[i] - MIND]);
       }
       const int px = 16 * t + r16;
 #pragma unroll
       for (int v = 0; v < 4; v++) {
-        const int hi = acc[3][v] * 256 + acc[2][v];  // |.| < 2^30
-        const int lo = acc[1][v] * 256 + acc[0][v];  // |.| < 2^31
-        const double rr = __builtin_fma((double)hi, 65536.0, (double)lo);  // sum_d P_d 256^(d-3), exact
+        const int hi = acc[ND - 1][v] * 256 + acc[ND - 2][v];  // |.| < 2^30
+        const int lo = acc[ND - 3][v] * 256 + acc[ND - 4][v];  // |.| < 2^31
+        double rr = __builtin_fma((double)hi, 65536.0, (double)lo);  // sum_d P_d 256^(d-3), exact
+        if constexpr (MIND == 2) rr = __builtin_fma((double)acc[0][v], 0.00390625, rr);
         const float o = (float)__builtin_fma(rr, fo[v], (double)bz[v]);
         if (px < NOUT) store_stream(dst + (4 * q + v) * NOUT + px, o);
       }

@@ -75,7 +75,11 @@ __device__ __forceinline__ void gi8_scales(unsigned mbits, double& scale, double
   inverse = i8_nonfinite(mbits) ? __longlong_as_double(0x7ff8000000000000ll) : inv;
 }
 
+// MIND: the lowest digit diagonal k + l that is kept: 2 (13 products: what the library uses unless told that 10
+// will do) or 3 (10 products).
+template <int MIND = 2>
 __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
+  static_assert(MIND == 2 || MIND == 3, "13 or 10 digit products");
   extern __shared__ __attribute__((aligned(16))) char gi8g_lds[];
   const int tid = threadIdx.x;
   const int lane = tid & (WAVE - 1);
@@ -207,14 +211,15 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
 #pragma unroll
     for (int v = 0; v < 4; v++) fy[v] = invs[GI8_TN + 16 * mt + 4 * q + v];
     // order: no two consecutive products on one diagonal
-    constexpr int PK[10] = {3, 2, 3, 3, 2, 1, 2, 1, 0, 3};
-    constexpr int PL[10] = {0, 1, 1, 2, 2, 2, 3, 3, 3, 3};
-    i4 d[2][4];  // d[.][i]: diagonal k + l = 3 + i; two sets, so that a tile's MFMAs run under the previous tile's epilogue
+    constexpr int ND = 7 - MIND, NP = MIND == 3 ? 10 : 13;
+    constexpr int PK[13] = {3, 2, 3, 3, 2, 1, 2, 1, 0, 3, 2, 1, 0};  // the last three: the diagonal k + l = 2
+    constexpr int PL[13] = {0, 1, 1, 2, 2, 2, 3, 3, 3, 3, 0, 1, 2};
+    i4 d[2][ND];  // d[.][i]: diagonal k + l = MIND + i; two sets, so that a tile's MFMAs run under the previous tile's epilogue
     double fx[2];
-    auto mma = [&](int j, i4 (&dd)[4], double& fxj) {
+    auto mma = [&](int j, i4 (&dd)[ND], double& fxj) {
       const int xr = 64 * nh + 16 * j + r16;
 #pragma unroll
-      for (int i = 0; i < 4; i++) dd[i] = i4{0, 0, 0, 0};
+      for (int i = 0; i < ND; i++) dd[i] = i4{0, 0, 0, 0};
 #pragma unroll
       for (int s = 0; s < GI8_STEPS; s++) {
         const char* xb = gi8g_lds + xr * GI8_RS + 16 * (4 * s + q);
@@ -222,17 +227,18 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
 #pragma unroll
         for (int l = 0; l < 4; l++) bq[l] = *reinterpret_cast<const i4*>(xb + l * GI8_PLANE);
 #pragma unroll
-        for (int pr = 0; pr < 10; pr++)
-          dd[PK[pr] + PL[pr] - 3] = mfma_i8(a[s][PK[pr]], bq[PL[pr]], dd[PK[pr] + PL[pr] - 3]);
+        for (int pr = 0; pr < NP; pr++)
+          dd[PK[pr] + PL[pr] - MIND] = mfma_i8(a[s][PK[pr]], bq[PL[pr]], dd[PK[pr] + PL[pr] - MIND]);
       }
       fxj = invs[xr];
     };
-    auto epilogue = [&](int j, const i4 (&dd)[4], double fxj) {
+    auto epilogue = [&](int j, const i4 (&dd)[ND], double fxj) {
 #pragma unroll
       for (int v = 0; v < 4; v++) {
         // 128 terms of at most 2^14 per digit pair: 2^21 x 256 + 2 x 2^21 and 3 x 2^21 x 256 + 4 x 2^21, below 2^31
-        const int hi = dd[3][v] * 256 + dd[2][v], lo = dd[1][v] * 256 + dd[0][v];
-        const double rr = __builtin_fma((double)hi, 65536.0, (double)lo);
+        const int hi = dd[ND - 1][v] * 256 + dd[ND - 2][v], lo = dd[ND - 3][v] * 256 + dd[ND - 4][v];
+        double rr = __builtin_fma((double)hi, 65536.0, (double)lo);
+        if constexpr (MIND == 2) rr = __builtin_fma((double)dd[0][v], 0.00390625, rr);
         acc[j][v] = __builtin_fma(rr, fy[v] * fxj, acc[j][v]);
       }
     };

@@ -54,7 +54,6 @@ struct MlpArgs {
   int batch;
   int n_layers;
   unsigned spin_limit;
-  TC355_TRACE_FIELD
 };
 
 // Device-wide barrier, built as a two-level tree so that no address sees more
@@ -151,11 +150,10 @@ template <typename TA, bool FC = true>
 __device__ __forceinline__ void mlp_layer(const TA* __restrict__ A, const float* __restrict__ Wl,
                                           const float* __restrict__ bias, float* __restrict__ O,
                                           double* __restrict__ act, int batch, int K, int M, char* smem,
-                                          unsigned long long* trace, int vwg, int vstep, int team0_jobs_if_team1) {
+                                          int vwg, int vstep, int team0_jobs_if_team1) {
   // vwg / vstep: this team's number among all teams of the grid and their count (a "team" = 4 wavefronts that own
   // a tile together; a workgroup holds one or two); team0_jobs_if_team1: for the second team of a workgroup, the
   // number of tiles its first team has in this layer (both must pass the same number of barriers), else -1
-  TC355_TRACE_RESUME(trace)
   constexpr bool A64 = sizeof(TA) == 8;
   constexpr int KC = MLP_KC, NR = 4;
   constexpr int RSA = A64 ? MLP_RS_D : MLP_RS_F;  // row stride of the A stage, in elements of TA
@@ -260,7 +258,6 @@ __device__ __forceinline__ void mlp_layer(const TA* __restrict__ A, const float*
   Regs ring[NR];
 #pragma unroll
   for (int i = 0; i < NR; i++) load_next(ring[i]);
-  TC355_TRACE_R(trace, 2);
 
   // Chunk t of the stream sits in ring[t % NR] until it is staged into LDS buffer t % 2.
   // Iteration t stages chunk t+1 (LDS writes and the next global loads are only issued
@@ -303,12 +300,10 @@ __device__ __forceinline__ void mlp_layer(const TA* __restrict__ A, const float*
           stage(ring[(i + 1) % NR], smem + ((i + 1) & 1) * MLP_BUF_BYTES);
           load_next(ring[(i + 1) % NR]);
         }
-        TC355_TRACE_R(trace, 3);
 #pragma unroll
         for (int j = 0; j < KC / 64; j++)
 #pragma unroll
           for (int e = 0; e < 4; e++) acc = mfma_f64((double)av[j].e[e], (double)bv[j].e[e], acc);
-        TC355_TRACE_R(trace, 4);
         const bool last = (++ck == nck);
         d4* part = part_base + parity * (WAVES_PER_WG * WAVE);
         if (last) part[wave * WAVE + lane] = acc;
@@ -330,7 +325,6 @@ __device__ __forceinline__ void mlp_layer(const TA* __restrict__ A, const float*
             if (O) O[o] = (float)x;
             if (act) act_store(act + o, x);
           }
-          TC355_TRACE_R(trace, 5);
           ck = 0;
           parity ^= 1;
           job += step;
@@ -342,7 +336,6 @@ __device__ __forceinline__ void mlp_layer(const TA* __restrict__ A, const float*
   }
   // the second team of a workgroup passes as many tile-end barriers as the first (it never has more tiles)
   for (int extra = my_jobs; extra < team0_jobs_if_team1; extra++) __syncthreads();
-  TC355_TRACE_FLUSH(trace);
   __syncthreads();  // the LDS stage is reused by the next layer
 }
 
@@ -358,12 +351,6 @@ __global__ __launch_bounds__(MLP_TEAMS * WG_THREADS, 2 / MLP_TEAMS) void mlp_fus
   const int team = __builtin_amdgcn_readfirstlane(threadIdx.x / WG_THREADS);
   char* smem = smem_all + team * MLP_LDS_BYTES;
   const int vwg = team * (int)gridDim.x + (int)blockIdx.x, vstep = MLP_TEAMS * (int)gridDim.x;
-#ifdef TC355_TRACE_ENABLE
-  unsigned long long* trace = p.trace;
-#else
-  unsigned long long* trace = nullptr;
-#endif
-  TC355_TRACE(trace, 1);
   if (blockIdx.x == 0 && threadIdx.x == 0 && p.n_layers > 1) {
     const unsigned ngroups = (gridDim.x + MLP_FANIN - 1) / MLP_FANIN;
     for (int l = 0; l + 1 < p.n_layers; l++) {
@@ -389,12 +376,10 @@ __global__ __launch_bounds__(MLP_TEAMS * WG_THREADS, 2 / MLP_TEAMS) void mlp_fus
       t0jobs = njobs > b ? (njobs - b + vstep - 1) / vstep : 0;
     }
     if (l == 0)
-      mlp_layer<float>(p.I, p.W[0], p.bias[0], p.O[0], act, p.batch, K, M, smem, trace, vwg, vstep, t0jobs);
+      mlp_layer<float>(p.I, p.W[0], p.bias[0], p.O[0], act, p.batch, K, M, smem, vwg, vstep, t0jobs);
     else
-      mlp_layer<double>(p.act[l - 1], p.W[l], p.bias[l], p.O[l], act, p.batch, K, M, smem, trace, vwg, vstep, t0jobs);
-    TC355_TRACE(trace, 6);
+      mlp_layer<double>(p.act[l - 1], p.W[l], p.bias[l], p.O[l], act, p.batch, K, M, smem, vwg, vstep, t0jobs);
     if (l + 1 < p.n_layers) mlp_grid_barrier(p.sync, l, p.token, gridDim.x, p.spin_limit);
-    TC355_TRACE(trace, 7);
   }
   // The last workgroup out withdraws the token.  A replay of a captured HIP graph launches this
   // kernel again with the SAME token; with the token withdrawn, the other workgroups again wait
@@ -412,7 +397,7 @@ __global__ __launch_bounds__(MLP_TEAMS * WG_THREADS, 2 / MLP_TEAMS) void mlp_fus
 // stride) with a long reduction and too few 64 x 64 blocks to fill the chip.
 __global__ __launch_bounds__(WG_THREADS, 2) void gemm_nt_splitk_kernel(GemmArgs p) {
   extern __shared__ __attribute__((aligned(32))) char smem[];
-  mlp_layer<float, false>(static_cast<const float*>(p.A), p.Bm, nullptr, p.C, nullptr, p.N, p.K, p.M, smem, nullptr,
+  mlp_layer<float, false>(static_cast<const float*>(p.A), p.Bm, nullptr, p.C, nullptr, p.N, p.K, p.M, smem,
                           (int)blockIdx.x, (int)gridDim.x, -1);
 }
 

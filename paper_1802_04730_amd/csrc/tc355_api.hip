@@ -10,6 +10,7 @@
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
+#include <initializer_list>
 #include <random>
 #include <type_traits>
 
@@ -43,7 +44,34 @@ inline bool misaligned(const void* p, size_t a = 16) { return (reinterpret_cast<
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// True if the product of the (positive) extents reaches `limit`; never overflows: it stops at the first factor
+// that takes the running product there.
+inline bool prod_reaches(std::initializer_list<int64_t> factors, int64_t limit) {
+  int64_t p = 1;
+  for (int64_t f : factors) {
+    if (f >= limit || p > limit / f) return true;  // p * f > limit
+    p *= f;
+    if (p >= limit) return true;
+  }
+  return false;
+}
+
 inline tc_status launch_status() { return hipGetLastError() == hipSuccess ? TC_OK : TC_ERR_LAUNCH; }
+
+// Options of the calling host thread (tc355_set_option) and the kernel family its last call chose (tc355_last_path).
+struct ThreadOptions {
+  int64_t int8 = TC_INT8_AUTO;
+  int64_t mlp_kernel = TC_MLP_AUTO;
+  int64_t mlp_spin_limit = 4000000;
+};
+thread_local ThreadOptions t_opt;
+thread_local const char* t_path = "";
+
+inline tc_status took(const char* path, tc_status st) {
+  t_path = path;
+  return st;
+}
+
 
 // ---- generic wave-level contraction launcher --------------------------------
 template <typename TA, int VEC, int EPI>
@@ -160,10 +188,12 @@ bool try_gemm_splitk(const GemmArgs& a, int64_t batch, hipStream_t s, tc_status*
 template <typename TA, int EPI>
 tc_status launch_gemm(const GemmArgs& a, int64_t batch, int tm, hipStream_t s) {
   tc_status st = TC_OK;
-  if (try_gemm_tile<TA, EPI>(a, batch, s, &st)) return st;
+  constexpr bool plain = EPI == EPI_NONE;  // tc_tbmm (else: one MLP layer)
+  if (try_gemm_tile<TA, EPI>(a, batch, s, &st)) return took(plain ? "tbmm:tile" : "mlp:layers", st);
   if constexpr (std::is_same<TA, float>::value && EPI == EPI_NONE) {
-    if (try_gemm_splitk(a, batch, s, &st)) return st;
+    if (try_gemm_splitk(a, batch, s, &st)) return took("tbmm:splitk", st);
   }
+  t_path = plain ? "tbmm:wave" : "mlp:layers";
   // widest per-lane load that keeps every row start aligned
   if (a.K % 4 == 0) return launch_gemm_tm<TA, 4, EPI>(a, batch, tm, s);
   if (a.K % 2 == 0) return launch_gemm_tm<TA, 2, EPI>(a, batch, tm, s);
@@ -234,14 +264,6 @@ unsigned long long next_token() {
   return t;
 }
 
-long env_long(const char* name, long dflt) {
-  const char* v = std::getenv(name);
-  if (!v || !*v) return dflt;
-  char* end = nullptr;
-  const long x = std::strtol(v, &end, 10);
-  return (end && *end == 0) ? x : dflt;
-}
-
 size_t mlp_sync_bytes() { return round256((MLP_SYNC_WORDS + (size_t)(MLP_MAX_LAYERS - 1) * MLP_BAR_WORDS) * sizeof(unsigned)); }
 
 // fp64 copy of one layer's output; whole 16-row tiles (the small-batch kernel keeps it in a tiled layout)
@@ -275,7 +297,7 @@ bool try_gconv_band(const GconvArgs& g, hipStream_t s, tc_status* st) {
 
 // ---- grouped convolution on the int8 matrix core (sliced fixed-point operands, exact int32 sums) ----
 template <int W, int ROWS, int MIND>
-bool try_gconv_i8(const GconvArgs& g, hipStream_t s, tc_status* st) {
+bool try_gconv_i8(const GconvArgs& g, int force13, hipStream_t s, tc_status* st) {
   using Gm = GconvI8Geom<W, ROWS>;
   if (g.C != Gm::C || g.F != Gm::F || g.KH != Gm::KH || g.KW != Gm::KW || g.W != W) return false;
   if ((int64_t)g.H * W >= (1 << 24)) return false;  // 32-bit byte offsets inside one (image, group) block of 16 planes
@@ -302,6 +324,7 @@ bool try_gconv_i8(const GconvArgs& g, hipStream_t s, tc_status* st) {
   a.halves = (grid == 2 * (int64_t)device_cus()) ? (int)(grid / 2) : 0;
   a.num = 3;
   a.den = 5;
+  a.force13 = force13;
   gconv_i8_kernel<W, ROWS, MIND><<<dim3((unsigned)grid), dim3(WG_THREADS), Gm::LDS_BYTES, s>>>(a);
   *st = launch_status();
   return true;
@@ -387,7 +410,7 @@ bool try_tbmm_lds(const float* X, const float* Y, float* Z, int64_t B, int64_t N
 }
 
 // ---- the same arithmetic for small images with 32 channels per group ----
-template <int H, int W>
+template <int H, int W, int MIND>
 bool try_gconv_i8_c32(const GconvArgs& g, hipStream_t s, tc_status* st) {
   using Gm = GconvI8C32Geom<H, W>;
   if (g.C != Gm::C || g.F != Gm::F || g.KH != Gm::KH || g.KW != Gm::KW || g.W != W || g.H != H) return false;
@@ -397,7 +420,7 @@ bool try_gconv_i8_c32(const GconvArgs& g, hipStream_t s, tc_status* st) {
   if (iters * (grid + 1) >= (1ll << 32)) return false;  // the kernel splits the iterations in 32-bit arithmetic
   static std::atomic<int> lds_ok{0};  // more than the default 64 KiB of dynamic LDS
   if (!lds_ok.load(std::memory_order_acquire)) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gconv_i8_c32_kernel<H, W>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gconv_i8_c32_kernel<H, W, MIND>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, Gm::LDS_BYTES) != hipSuccess) {
       *st = TC_ERR_LAUNCH;
       return true;
@@ -407,13 +430,13 @@ bool try_gconv_i8_c32(const GconvArgs& g, hipStream_t s, tc_status* st) {
   GconvI8C32Args a{};
   a.I = g.I; a.W1 = g.W1; a.bias = g.bias; a.O = g.O;
   a.G = g.G; a.N = g.N;
-  gconv_i8_c32_kernel<H, W><<<dim3((unsigned)grid), dim3(WG_THREADS), Gm::LDS_BYTES, s>>>(a);
+  gconv_i8_c32_kernel<H, W, MIND><<<dim3((unsigned)grid), dim3(WG_THREADS), Gm::LDS_BYTES, s>>>(a);
   *st = launch_status();
   return true;
 }
 
 // ---- the same arithmetic for small images (one whole image per wavefront) ----
-template <int H, int W>
+template <int H, int W, int MIND>
 bool try_gconv_i8_small(const GconvArgs& g, hipStream_t s, tc_status* st) {
   using Gm = GconvI8SmallGeom<H, W>;
   if (g.C != Gm::C || g.F != Gm::F || g.KH != Gm::KH || g.KW != Gm::KW || g.W != W || g.H != H) return false;
@@ -423,7 +446,7 @@ bool try_gconv_i8_small(const GconvArgs& g, hipStream_t s, tc_status* st) {
   if (iters * (grid + 1) >= (1ll << 32)) return false;  // the kernel splits the iterations in 32-bit arithmetic
   static std::atomic<int> lds_ok{0};  // more than the default 64 KiB of dynamic LDS
   if (!lds_ok.load(std::memory_order_acquire)) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gconv_i8_small_kernel<H, W>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gconv_i8_small_kernel<H, W, MIND>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, Gm::LDS_BYTES) != hipSuccess) {
       *st = TC_ERR_LAUNCH;
       return true;
@@ -433,7 +456,7 @@ bool try_gconv_i8_small(const GconvArgs& g, hipStream_t s, tc_status* st) {
   GconvI8SmallArgs a{};
   a.I = g.I; a.W1 = g.W1; a.bias = g.bias; a.O = g.O;
   a.G = g.G; a.N = g.N;
-  gconv_i8_small_kernel<H, W><<<dim3((unsigned)grid), dim3(WG_THREADS), Gm::LDS_BYTES, s>>>(a);
+  gconv_i8_small_kernel<H, W, MIND><<<dim3((unsigned)grid), dim3(WG_THREADS), Gm::LDS_BYTES, s>>>(a);
   *st = launch_status();
   return true;
 }
@@ -457,7 +480,36 @@ const char* tc_status_string(tc_status s) {
   return "unknown tc_status";
 }
 
-int tc355_version(void) { return 100; }
+int tc355_version(void) { return 200; }
+
+tc_status tc355_set_option(tc_option key, int64_t value) {
+  switch (key) {
+    case TC_OPT_INT8:
+      if (value < TC_INT8_AUTO || value > TC_INT8_THIRTEEN) return TC_ERR_SHAPE;
+      t_opt.int8 = value;
+      return TC_OK;
+    case TC_OPT_MLP_KERNEL:
+      if (value < TC_MLP_AUTO || value > TC_MLP_PER_LAYER) return TC_ERR_SHAPE;
+      t_opt.mlp_kernel = value;
+      return TC_OK;
+    case TC_OPT_MLP_SPIN_LIMIT:
+      if (value < 1) return TC_ERR_SHAPE;
+      t_opt.mlp_spin_limit = value;
+      return TC_OK;
+  }
+  return TC_ERR_SHAPE;
+}
+
+int64_t tc355_get_option(tc_option key) {
+  switch (key) {
+    case TC_OPT_INT8: return t_opt.int8;
+    case TC_OPT_MLP_KERNEL: return t_opt.mlp_kernel;
+    case TC_OPT_MLP_SPIN_LIMIT: return t_opt.mlp_spin_limit;
+  }
+  return -1;
+}
+
+const char* tc355_last_path(void) { return t_path; }
 
 tc_status tc_tbmm(const float* X, const float* Y, float* Z, int64_t B, int64_t N, int64_t M, int64_t K,
                   void* hip_stream) {
@@ -465,8 +517,7 @@ tc_status tc_tbmm(const float* X, const float* Y, float* Z, int64_t B, int64_t N
   if (B < 0 || N <= 0 || M <= 0 || K <= 0) return TC_ERR_SHAPE;
   if (Z == X || Z == Y) return TC_ERR_ALIAS;
   if (misaligned(X) || misaligned(Y) || misaligned(Z)) return TC_ERR_ALIGN;
-  if (N >= kMaxElems || M >= kMaxElems || K >= kMaxElems || N * K >= kMaxElems || M * K >= kMaxElems ||
-      N * M >= kMaxElems)
+  if (B >= kMaxElems || prod_reaches({N, K}, kMaxElems) || prod_reaches({M, K}, kMaxElems) || prod_reaches({N, M}, kMaxElems))
     return TC_ERR_UNSUPPORTED;
   if (B == 0) return TC_OK;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -475,25 +526,29 @@ tc_status tc_tbmm(const float* X, const float* Y, float* Z, int64_t B, int64_t N
   // TC355_TBMM_ARITH=f64 keeps it on the fp64 kernels.
   if (N % GI8_TN == 0 && K % GI8_KB == 0 && K >= 2 * GI8_KB && M % GI8_TM == 0 && B <= 65535 &&
       N / GI8_TN <= 65535 && (M / GI8_TM) * (N / GI8_TN) * B >= 128) {
-    const char* arith = std::getenv("TC355_TBMM_ARITH");
-    if (!(arith && std::strcmp(arith, "f64") == 0)) {
+    if (t_opt.int8 != TC_INT8_OFF) {
       static std::atomic<int> lds_ok{0};  // more than the default 64 KiB of dynamic LDS
       if (!lds_ok.load(std::memory_order_acquire)) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, GI8_LDS_BYTES) != hipSuccess)
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                GI8_LDS_BYTES) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel<3>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                GI8_LDS_BYTES) != hipSuccess)
           return TC_ERR_LAUNCH;
         lds_ok.store(1, std::memory_order_release);
       }
       GemmI8Args g{};
       g.X = X; g.Y = Y; g.Z = Z; g.M = (int)M; g.K = (int)K;
-      gemm_i8_kernel<<<dim3((unsigned)(M / GI8_TM), (unsigned)B, (unsigned)(N / GI8_TN)), dim3(GI8_THREADS), GI8_LDS_BYTES, s>>>(g);
-      return launch_status();
+      const dim3 grid((unsigned)(M / GI8_TM), (unsigned)B, (unsigned)(N / GI8_TN));
+      // 13 digit products unless the caller has said that 10 will do (TC_INT8_TEN)
+      if (t_opt.int8 == TC_INT8_TEN) gemm_i8_kernel<3><<<grid, dim3(GI8_THREADS), GI8_LDS_BYTES, s>>>(g);
+      else gemm_i8_kernel<2><<<grid, dim3(GI8_THREADS), GI8_LDS_BYTES, s>>>(g);
+      return took("tbmm:i8", launch_status());
     }
   }
 
   {
     tc_status st = TC_OK;
-    if (try_tbmm_lds(X, Y, Z, B, N, M, K, s, &st)) return st;
+    if (try_tbmm_lds(X, Y, Z, B, N, M, K, s, &st)) return took("tbmm:lds", st);
   }
 
   GemmArgs a{};
@@ -501,7 +556,7 @@ tc_status tc_tbmm(const float* X, const float* Y, float* Z, int64_t B, int64_t N
   a.strideA = N * K; a.strideB = M * K; a.strideC = N * M;
   a.N = (int)N; a.M = (int)M; a.K = (int)K;
   const int tm = pick_strip(M, B * ceil_div(N, 16) * ceil_div(M, 16));
-  return launch_gemm<float, EPI_NONE>(a, B, tm, s);
+  return launch_gemm<float, EPI_NONE>(a, B, tm, s);  // records tbmm:tile, tbmm:splitk or tbmm:wave
 }
 
 size_t tc_mlp_fcrelu_workspace_bytes(int64_t batch, int32_t n_layers, const int64_t* dims) {
@@ -558,8 +613,8 @@ tc_status mlp_run(const float* I, int64_t batch, int32_t n_layers, const int64_t
       if (O[l] && (O[l] == W[m] || O[l] == bias[m])) return TC_ERR_ALIAS;
       if (O[l] && m != l && O[l] == O[m]) return TC_ERR_ALIAS;
     }
-    if (dims[l] >= kMaxElems || dims[l + 1] >= kMaxElems || dims[l] * dims[l + 1] >= kMaxElems ||
-        batch * dims[l] >= kMaxElems || batch * dims[l + 1] >= kMaxElems)
+    if (prod_reaches({dims[l], dims[l + 1]}, kMaxElems) || prod_reaches({std::max<int64_t>(batch, 1), dims[l]}, kMaxElems) ||
+        prod_reaches({std::max<int64_t>(batch, 1), dims[l + 1]}, kMaxElems))
       return TC_ERR_UNSUPPORTED;
   }
   const size_t need = tc_mlp_fcrelu_workspace_bytes(batch, n_layers, dims);
@@ -588,30 +643,29 @@ tc_status mlp_run(const float* I, int64_t batch, int32_t n_layers, const int64_t
   }
 
   // One persistent kernel for the whole chain when every reduction extent allows 16-byte loads.
-  bool fused = env_long("TC355_MLP_FUSED", 1) != 0;
+  bool fused = t_opt.mlp_kernel != TC_MLP_PER_LAYER;
   for (int l = 0; l < n_layers; l++) fused = fused && (dims[l] % 4 == 0);
   // the fused kernel addresses its operands (fp64 activations, fp32 weights) with 32-bit byte offsets
   for (int l = 0; l < n_layers; l++)
     fused = fused && batch * dims[l] * 8 < (1ll << 32) && dims[l + 1] * dims[l] * 4 < (1ll << 32);
   // Large batches: when every layer fills the chip with 64 x 64 blocks, one LDS-tiled launch per layer (70 % of the
   // fp64 matrix peak) beats the fused kernel's 16 x 16 tiles (43 %), and the launches no longer matter.
-  if (n_layers > 1 && env_long("TC355_MLP_FUSED", -1) != 1) {
+  if (n_layers > 1 && t_opt.mlp_kernel == TC_MLP_AUTO) {
     int64_t min_blocks = INT64_MAX;
     for (int l = 0; l < n_layers; l++) min_blocks = std::min(min_blocks, ceil_div(batch, GT_BM) * ceil_div(dims[l + 1], GT_BN));
     if (min_blocks >= 256) fused = false;
   }
   const int cus = device_cus();
   // Small batches with reductions of at most 1024: one group of workgroups per 16-row tile of the batch carries the
-  // tile through all layers (mlp_rows.hpp).  TC355_MLP_KERNEL=tiles keeps the tile-stream kernel below.
+  // tile through all layers (mlp_rows.hpp).  Option TC_OPT_MLP_KERNEL = TC_MLP_TILES keeps the tile-stream kernel below.
   if (fused && cus > 0) {
-    const char* which = std::getenv("TC355_MLP_KERNEL");
     const int64_t G = ceil_div(batch, 16);
     const int64_t nwg = std::min<int64_t>(cus, MR_MAX_WG);
     // (a single layer with two tiles per workgroup has nothing to hand over and nothing to hide its second tile's
     // weights behind: the tile-stream kernel, which pipelines its loads, is faster there: 9.1 against 10.4 us at
     // 128 x 1024 -> 1024; with one tile per workgroup this kernel is: 6.8 against 8.6 us)
-    bool rows = !(which && std::strcmp(which, "tiles") == 0) && G <= nwg &&
-                (n_layers > 1 || ceil_div(dims[1], 16) <= nwg / G) &&
+    bool rows = t_opt.mlp_kernel != TC_MLP_TILES && G <= nwg &&
+                (n_layers > 1 || ceil_div(dims[1], 16) <= nwg / G || t_opt.mlp_kernel == TC_MLP_ROWS) &&
                 mr_flag_words(n_layers, G, nwg) <= (int64_t)(MLP_MAX_LAYERS - 1) * MLP_BAR_WORDS;
     for (int l = 0; l < n_layers && rows; l++)
       rows = (dims[l] == 128 || dims[l] == 256 || dims[l] == 512 || dims[l] == 1024) &&
@@ -626,7 +680,7 @@ tc_status mlp_run(const float* I, int64_t batch, int32_t n_layers, const int64_t
       a.batch = (int)batch; a.n_layers = n_layers; a.groups = (int)G;
       a.sync = reinterpret_cast<unsigned*>(ws);
       a.token = next_token();
-      a.spin_limit = (unsigned)std::max<long>(1, env_long("TC355_MLP_SPIN_LIMIT", 4000000));
+      a.spin_limit = (unsigned)std::max<int64_t>(1, std::min<int64_t>(t_opt.mlp_spin_limit, 0xffffffffll));
       static std::atomic<int> lds_ok{0};  // more than the default 64 KiB of dynamic LDS
       if (!lds_ok.load(std::memory_order_acquire)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_rows_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -635,7 +689,7 @@ tc_status mlp_run(const float* I, int64_t batch, int32_t n_layers, const int64_t
         lds_ok.store(1, std::memory_order_release);
       }
       mlp_rows_kernel<<<dim3((unsigned)nwg), dim3(MR_THREADS), MR_LDS_BYTES, s>>>(a);
-      return launch_status();
+      return took("mlp:rows", launch_status());
     }
   }
   if (fused && cus > 0) {
@@ -650,7 +704,7 @@ tc_status mlp_run(const float* I, int64_t batch, int32_t n_layers, const int64_t
     a.batch = (int)batch; a.n_layers = n_layers;
     a.sync = reinterpret_cast<unsigned*>(ws);
     a.token = next_token();
-    a.spin_limit = (unsigned)std::max<long>(1, env_long("TC355_MLP_SPIN_LIMIT", 4000000));
+    a.spin_limit = (unsigned)std::max<int64_t>(1, std::min<int64_t>(t_opt.mlp_spin_limit, 0xffffffffll));
     const unsigned nwg = (unsigned)std::min<int64_t>(std::min(2 * cus, MLP_FANIN * MLP_GROUPS), max_jobs);  // teams of four wavefronts, all resident: two per compute unit
     static std::atomic<int> lds_ok{0};  // the kernel stages more than the default 64 KiB of LDS
     if (!lds_ok.load(std::memory_order_acquire)) {
@@ -661,7 +715,7 @@ tc_status mlp_run(const float* I, int64_t batch, int32_t n_layers, const int64_t
     }
     // nwg teams of four wavefronts; MLP_TEAMS of them share a workgroup
     mlp_fused_kernel<<<dim3((nwg + MLP_TEAMS - 1) / MLP_TEAMS), dim3(MLP_TEAMS * WG_THREADS), MLP_TEAMS * MLP_LDS_BYTES, s>>>(a);
-    return launch_status();
+    return took("mlp:tiles", launch_status());
   }
 
   // Otherwise one launch per layer through the shape-generic contraction.
@@ -677,7 +731,7 @@ tc_status mlp_run(const float* I, int64_t batch, int32_t n_layers, const int64_t
     if (st != TC_OK) return st;
     in = act[l];
   }
-  return TC_OK;
+  return took("mlp:per_layer", TC_OK);
 }
 
 }  // namespace
@@ -714,8 +768,8 @@ tc_status tc_group_conv(const float* I, const float* W1, const float* bias, floa
   if (inf != TC_OK) return inf;
   if (O == I || O == W1 || (bias && O == bias)) return TC_ERR_ALIAS;
   if (misaligned(I) || misaligned(W1) || misaligned(O) || (bias && misaligned(bias))) return TC_ERR_ALIGN;
-  if (C * H * W >= kMaxElems || F * OH * OW >= kMaxElems || C * KH * KW >= kMaxElems ||
-      G * F * C * KH * KW >= kMaxElems || G >= kMaxElems / 16 || F >= kMaxElems / 16)
+  if (N >= kMaxElems || prod_reaches({C, H, W}, kMaxElems) || prod_reaches({F, OH, OW}, kMaxElems) || prod_reaches({C, KH, KW}, kMaxElems) ||
+      prod_reaches({G, F, C, KH, KW}, kMaxElems) || G >= kMaxElems / 16 || F >= kMaxElems / 16)
     return TC_ERR_UNSUPPORTED;
   if (N == 0) return TC_OK;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -725,21 +779,27 @@ tc_status tc_group_conv(const float* I, const float* W1, const float* bias, floa
   a.N = (int)N; a.G = (int)G; a.C = (int)C; a.F = (int)F; a.H = (int)H; a.W = (int)W;
   a.KH = (int)KH; a.KW = (int)KW; a.OH = (int)OH; a.OW = (int)OW;
   tc_status st = TC_OK;
-  // TC355_GCONV_ARITH: unset or "i8" = the int8 path with 10 digit products where it applies; "i8x13" = the same
-  // with 13 (for operands that are both heavy-tailed, 16 % slower); "f64" = the fp64 matrix path for every shape
-  const char* arith = std::getenv("TC355_GCONV_ARITH");
-  const bool f64_only = arith && arith[0] == 'f';
-  const bool thirteen = arith && std::strcmp(arith, "i8x13") == 0;
-  if (!f64_only && !thirteen && try_gconv_i8<58, 8, 3>(a, s, &st)) return st;
-  if (!f64_only && !thirteen && try_gconv_i8_small<14, 14>(a, s, &st)) return st;  // the paper's (32,32,16,16,14,14)
-  if (!f64_only && !thirteen && try_gconv_i8_c32<7, 7>(a, s, &st)) return st;      // the paper's (32,32,32,32,7,7)
-  if (thirteen && try_gconv_i8<58, 8, 2>(a, s, &st)) return st;
-  if (try_gconv_band<16, 3, 3, 58, 8, 2>(a, s, &st)) return st;
-  if (try_gconv_band<16, 3, 3, 14, 12, 2>(a, s, &st)) return st;  // the paper's (32,32,16,16,14,14): the whole image is one band
-  if (try_gconv_quad<4, 4, 3, 3, 56, 16, 4>(a, s, &st)) return st;    // the paper's (32,32,4,4,56,56)
-  if (try_gconv_quad<8, 8, 3, 3, 28, 26, 3>(a, s, &st)) return st;    // the paper's (32,32,8,8,28,28): one band
-  if (try_gconv_tiny<32, 32, 3, 3, 7, 7>(a, s, &st)) return st;       // the paper's (32,32,32,32,7,7)
-  if (try_gconv_lds<16, 16, 3, 3, 7>(a, s, &st)) return st;
+  // Option TC_OPT_INT8: AUTO = the int8 path where it applies, with the thirteenth to tenth digit products added for
+  // heavy-tailed blocks; TEN / THIRTEEN = the same with 10 / 13 products throughout; OFF = the fp64 path for every shape.
+  const int64_t i8 = t_opt.int8;
+  const int force13 = i8 == TC_INT8_THIRTEEN ? 1 : (i8 == TC_INT8_TEN ? -1 : 0);
+  if (i8 != TC_INT8_OFF) {
+    if (try_gconv_i8<58, 8, 3>(a, force13, s, &st)) return took("gconv:i8", st);
+    if (i8 == TC_INT8_TEN) {
+      if (try_gconv_i8_small<14, 14, 3>(a, s, &st)) return took("gconv:i8_small", st);  // the paper's (32,32,16,16,14,14)
+      if (try_gconv_i8_c32<7, 7, 3>(a, s, &st)) return took("gconv:i8_c32", st);        // the paper's (32,32,32,32,7,7)
+    } else {
+      if (try_gconv_i8_small<14, 14, 2>(a, s, &st)) return took("gconv:i8_small", st);
+      if (try_gconv_i8_c32<7, 7, 2>(a, s, &st)) return took("gconv:i8_c32", st);
+    }
+  }
+  if (try_gconv_band<16, 3, 3, 58, 8, 2>(a, s, &st)) return took("gconv:band", st);
+  if (try_gconv_band<16, 3, 3, 14, 12, 2>(a, s, &st)) return took("gconv:band", st);  // the paper's (32,32,16,16,14,14): the whole image is one band
+  if (try_gconv_quad<4, 4, 3, 3, 56, 16, 4>(a, s, &st)) return took("gconv:quad", st);    // the paper's (32,32,4,4,56,56)
+  if (try_gconv_quad<8, 8, 3, 3, 28, 26, 3>(a, s, &st)) return took("gconv:quad", st);    // the paper's (32,32,8,8,28,28): one band
+  if (try_gconv_tiny<32, 32, 3, 3, 7, 7>(a, s, &st)) return took("gconv:tiny", st);       // the paper's (32,32,32,32,7,7)
+  if (try_gconv_lds<16, 16, 3, 3, 7>(a, s, &st)) return took("gconv:lds", st);
+  t_path = "gconv:wave";
   // generic kernel: a wavefront takes 16 filters x a strip of 16*TP pixels; small images take a narrower strip
   const int64_t tiles_p = ceil_div(OH * OW, 16);
   const int tp = tiles_p >= 4 ? 4 : (tiles_p >= 2 ? 2 : 1);
@@ -761,7 +821,8 @@ tc_status tc_kron(const float* W1, const float* W2, const float* X, float* Y, in
   if (B < 0 || I <= 0 || K <= 0 || J <= 0 || L <= 0) return TC_ERR_SHAPE;
   if (Y == W1 || Y == W2 || Y == X) return TC_ERR_ALIAS;
   if (misaligned(W1) || misaligned(W2) || misaligned(X) || misaligned(Y)) return TC_ERR_ALIGN;
-  if (I * K >= kMaxElems || J * L >= kMaxElems || K * L >= kMaxElems || I * J >= kMaxElems)
+  if (B >= kMaxElems || prod_reaches({I, K}, kMaxElems) || prod_reaches({J, L}, kMaxElems) || prod_reaches({K, L}, kMaxElems) ||
+      prod_reaches({I, J}, kMaxElems))
     return TC_ERR_UNSUPPORTED;
   if (B == 0) return TC_OK;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -777,7 +838,7 @@ tc_status tc_kron(const float* W1, const float* W2, const float* X, float* Y, in
     const int64_t fgrid = B * f.iblocks;
     if (fgrid <= kMaxGrid) {
       kron_lds_kernel<64, 64, 64><<<dim3((unsigned)fgrid), dim3(WG_THREADS), 0, s>>>(f);
-      return launch_status();
+      return took("kron:lds", launch_status());
     }
   }
   constexpr int TJ = 4;
@@ -787,7 +848,7 @@ tc_status tc_kron(const float* W1, const float* W2, const float* X, float* Y, in
   const int64_t grid = ceil_div(a.jobs, WAVES_PER_WG);
   if (grid > kMaxGrid) return TC_ERR_UNSUPPORTED;
   kron_wave_kernel<TJ><<<dim3((unsigned)grid), dim3(WG_THREADS), 0, s>>>(a);
-  return launch_status();
+  return took("kron:wave", launch_status());
 }
 
 tc_status tc_sconv2d_infer(int64_t H, int64_t W, int64_t KH, int64_t KW, int64_t sh, int64_t sw, int64_t* OH,
@@ -809,10 +870,11 @@ tc_status tc_sconv2d(const float* I, const float* Wt, const float* bias, float* 
   if (inf != TC_OK) return inf;
   if (O == I || O == Wt || (bias && O == bias)) return TC_ERR_ALIAS;
   if (misaligned(I) || misaligned(Wt) || misaligned(O) || (bias && misaligned(bias))) return TC_ERR_ALIGN;
-  const int64_t K = C * KH * KW;
-  if (C * H * W >= kMaxElems || N * C * H * W >= kMaxElems || K >= kMaxElems || F * K >= kMaxElems ||
-      N * OH * OW >= kMaxElems || F * OH * OW >= kMaxElems || sh >= kMaxElems || sw >= kMaxElems)
+  const int64_t N1 = std::max<int64_t>(N, 1);
+  if (prod_reaches({N1, C, H, W}, kMaxElems) || prod_reaches({F, C, KH, KW}, kMaxElems) ||
+      prod_reaches({N1, OH, OW}, kMaxElems) || prod_reaches({F, OH, OW}, kMaxElems) || sh >= kMaxElems || sw >= kMaxElems)
     return TC_ERR_UNSUPPORTED;
+  const int64_t K = C * KH * KW;
   if (N == 0) return TC_OK;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
@@ -851,9 +913,9 @@ tc_status tc_lut(int32_t n_tables, const float* const* LUT, const int32_t* const
       if (static_cast<const void*>(O[t]) == LUT[m] || static_cast<const void*>(O[t]) == Idx[m]) return TC_ERR_ALIAS;
       if (m != t && O[t] == O[m]) return TC_ERR_ALIAS;
     }
-    if (L[t] >= kMaxElems || B * L[t] >= kMaxElems || E[t] > (int64_t)INT32_MAX + 1) return TC_ERR_UNSUPPORTED;
+    if (prod_reaches({std::max<int64_t>(B, 1), L[t]}, kMaxElems) || E[t] > (int64_t)INT32_MAX + 1) return TC_ERR_UNSUPPORTED;
   }
-  if (D >= kMaxElems || B * D >= kMaxElems) return TC_ERR_UNSUPPORTED;
+  if (prod_reaches({std::max<int64_t>(B, 1), D}, kMaxElems)) return TC_ERR_UNSUPPORTED;
   if (B == 0) return TC_OK;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
 

@@ -95,38 +95,4 @@ __device__ __forceinline__ Vec<T, V> load_vec(const T* p) {
   return r;
 }
 
-// Optional in-kernel timeline (development aid, compiled in only with -DTC355_TRACE_ENABLE):
-// thread 0 of every workgroup appends (tag, 100 MHz timestamp) pairs to a caller buffer.
-#ifdef TC355_TRACE_ENABLE
-#define TC355_TRACE_FIELD unsigned long long* trace;
-#define TC355_TRACE(p_, tag_)                                                                  \
-  do {                                                                                         \
-    if ((p_) && threadIdx.x == 0) {                                                            \
-      unsigned long long* t_ = (p_) + (size_t)blockIdx.x * 256;                                \
-      const unsigned long long n_ = t_[0];                                                     \
-      if (n_ < 126) { t_[1 + 2 * n_] = (tag_); t_[2 + 2 * n_] = __builtin_amdgcn_s_memrealtime(); t_[0] = n_ + 1; } \
-    }                                                                                          \
-  } while (0)
-// Variant that keeps the entry count in a register (no global load, so it does not
-// wait for outstanding memory traffic): declare once, log, and flush the count at the end.
-#define TC355_TRACE_DECL unsigned long long trace_n_ = 0;
-#define TC355_TRACE_R(p_, tag_)                                                                \
-  do {                                                                                         \
-    if ((p_) && threadIdx.x == 0 && trace_n_ < 126) {                                          \
-      unsigned long long* t_ = (p_) + (size_t)blockIdx.x * 256;                                \
-      t_[1 + 2 * trace_n_] = (tag_); t_[2 + 2 * trace_n_] = __builtin_amdgcn_s_memrealtime(); trace_n_++; \
-    }                                                                                          \
-  } while (0)
-#define TC355_TRACE_FLUSH(p_) do { if ((p_) && threadIdx.x == 0) (p_)[(size_t)blockIdx.x * 256] = trace_n_; } while (0)
-// continue a log that another function of the same kernel has flushed
-#define TC355_TRACE_RESUME(p_) unsigned long long trace_n_ = ((p_) && threadIdx.x == 0) ? (p_)[(size_t)blockIdx.x * 256] : 0;
-#else
-#define TC355_TRACE_FIELD
-#define TC355_TRACE(p_, tag_) do { } while (0)
-#define TC355_TRACE_DECL
-#define TC355_TRACE_R(p_, tag_) do { } while (0)
-#define TC355_TRACE_FLUSH(p_) do { } while (0)
-#define TC355_TRACE_RESUME(p_)
-#endif
-
 }  // namespace tc355

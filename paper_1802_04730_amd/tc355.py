@@ -22,8 +22,12 @@ TC_OK = 0
 STATUS_NAMES = {0: "TC_OK", 1: "TC_ERR_NULL", 2: "TC_ERR_SHAPE", 3: "TC_ERR_ALIAS", 4: "TC_ERR_ALIGN",
                 5: "TC_ERR_WORKSPACE", 6: "TC_ERR_LAUNCH", 7: "TC_ERR_UNSUPPORTED", 8: "TC_ERR_SCRATCH_LIMIT"}
 TC_MLP_STATIC_SCRATCH_BYTES = 8 << 20
+# tc355_set_option keys and values (include/tc355.h)
+TC_OPT_INT8, TC_OPT_MLP_KERNEL, TC_OPT_MLP_SPIN_LIMIT = 0, 1, 2
+TC_INT8_AUTO, TC_INT8_OFF, TC_INT8_TEN, TC_INT8_THIRTEEN = 0, 1, 2, 3
+TC_MLP_AUTO, TC_MLP_ROWS, TC_MLP_TILES, TC_MLP_PER_LAYER = 0, 1, 2, 3
 
-EXPORTS = ["tc_status_string", "tc355_version", "tc_tbmm", "tc_mlp_fcrelu", "tc_mlp_fcrelu_workspace_bytes",
+EXPORTS = ["tc_status_string", "tc355_version", "tc355_set_option", "tc355_get_option", "tc355_last_path", "tc_tbmm", "tc_mlp_fcrelu", "tc_mlp_fcrelu_workspace_bytes",
            "tc_mlp_fcrelu_static",
            "tc_group_conv", "tc_group_conv_infer", "tc_kron", "tc_sconv2d", "tc_sconv2d_infer", "tc_lut"]
 
@@ -47,6 +51,11 @@ def lib() -> ctypes.CDLL:
     L.tc_status_string.argtypes = [ctypes.c_int]
     L.tc_status_string.restype = ctypes.c_char_p
     L.tc355_version.restype = ctypes.c_int
+    L.tc355_set_option.argtypes = [ctypes.c_int, i64]
+    L.tc355_set_option.restype = ctypes.c_int
+    L.tc355_get_option.argtypes = [ctypes.c_int]
+    L.tc355_get_option.restype = i64
+    L.tc355_last_path.restype = ctypes.c_char_p
     L.tc_tbmm.argtypes = [vp, vp, vp, i64, i64, i64, i64, vp]
     L.tc_tbmm.restype = ctypes.c_int
     L.tc_mlp_fcrelu.argtypes = [vp, i64, i32, ctypes.POINTER(i64), ctypes.POINTER(vp), ctypes.POINTER(vp),
@@ -80,6 +89,37 @@ def status_string(status: int) -> str:
 
 def tc355_version() -> int:
     return int(lib().tc355_version())
+
+
+def set_option(key: int, value: int) -> int:
+    """Set an option of the calling host thread (tc355_set_option); returns the previous value."""
+    old = int(lib().tc355_get_option(int(key)))
+    _check(lib().tc355_set_option(int(key), int(value)), "tc355_set_option")
+    return old
+
+
+def get_option(key: int) -> int:
+    return int(lib().tc355_get_option(int(key)))
+
+
+def last_path() -> str:
+    """Kernel family chosen by this thread's most recent entry-point call, e.g. "tbmm:lds" (tc355_last_path)."""
+    return lib().tc355_last_path().decode()
+
+
+class option:
+    """Context manager: an option of the calling thread for the duration of a block."""
+
+    def __init__(self, key: int, value: int):
+        self.key, self.value = key, value
+
+    def __enter__(self):
+        self.old = set_option(self.key, self.value)
+        return self
+
+    def __exit__(self, *exc):
+        set_option(self.key, self.old)
+        return False
 
 
 def _ptr(t, name: str) -> int:

@@ -84,6 +84,28 @@ def test_kron_and_gconv_validation(L):
     assert L.tc_group_conv(A, B_, None, C_, 0, 1, 1, 1, 5, 5, 3, 3, None) == 0
 
 
+def test_extents_whose_products_overflow_int64_are_unsupported_not_undefined(L):
+    """Every extent product is formed without overflow: 2^32 x 2^32 = 2^64 must read as "too large", not as 0."""
+    big = 1 << 32
+    assert L.tc_group_conv(A, B_, None, C_, 1, 1, 1, 1, big, big, 3, 3, None) == 7
+    assert L.tc_group_conv(A, B_, None, C_, 1, big, big, 1, 5, 5, 3, 3, None) == 7
+    assert L.tc_group_conv(A, B_, None, C_, 1 << 62, 1, 1, 1, 5, 5, 3, 3, None) == 7
+    assert L.tc_sconv2d(A, B_, None, C_, big, big, 1, 5, 5, 3, 3, 2, 2, None) == 7
+    assert L.tc_sconv2d(A, B_, None, C_, 1, 1, 1, big, big, 3, 3, 1, 1, None) == 7
+    assert L.tc_tbmm(A, B_, C_, 1, big, big, 1, None) == 7
+    assert L.tc_tbmm(A, B_, C_, 1 << 62, 2, 3, 4, None) == 7
+    assert L.tc_kron(A, B_, C_, 0x40000, 1, big, big, 2, 2, None) == 7
+    assert L.tc_kron(A, B_, C_, 0x40000, 1 << 62, 2, 2, 2, 2, None) == 7
+    i64, vp = ctypes.c_int64, ctypes.c_void_p
+    T, I, O = (vp * 1)(0x50000), (vp * 1)(0x70000), (vp * 1)(0x90000)
+    assert L.tc_lut(1, T, I, O, (i64 * 1)(1000), (i64 * 1)(big), 64, big, None) == 7
+    assert L.tc_lut(1, T, I, O, (i64 * 1)(1000), (i64 * 1)(50), big, big, None) == 7
+    dims = (i64 * 2)(big, big)
+    Wp, bp, Op = (vp * 1)(0x50000), (vp * 1)(0x60000), (vp * 1)(0x90000)
+    assert L.tc_mlp_fcrelu(A, 1, 1, dims, Wp, bp, Op, None, 0, None) == 7
+    assert L.tc_mlp_fcrelu(A, big, 1, (i64 * 2)(big, 4), Wp, bp, Op, None, 0, None) == 7
+
+
 def test_sconv2d_validation_and_infer(L):
     oh, ow = ctypes.c_int64(), ctypes.c_int64()
     assert L.tc_sconv2d_infer(56, 56, 3, 3, 2, 2, ctypes.byref(oh), ctypes.byref(ow)) == 0
