@@ -71,6 +71,9 @@ def parse_args():
                          "input and the whole step back to back for SECONDS each and report the launch time next to "
                          "the board's power, power limit and shader clock (amdgpu sysfs sensors, read-only): one "
                          "JSON line per leg")
+    ap.add_argument("--counter-probe", action="store_true",
+                    help="for rocprofv3 --pmc: tbmm, MLP and kron on 40 cold buffer sets, tbmm at 64x batch, and a "
+                         "calibration copy; no timing")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="only launch the grouped convolution, the largest transposed matmul and a plain 512 MiB device copy a few times (for "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs; the copy calibrates the counters)")
@@ -162,8 +165,56 @@ def main():
     }
     step_flops = sum(v[1] for v in ops.values())
 
+    COLD_SETS = 40
+
+    def cold_calls(name):
+        """One launch on each of COLD_SETS copies of the operator's tensors (more than 256 MB in all)."""
+        if name == "tbmm":
+            sets = [(X.clone(), Y.clone(), torch.empty_like(Z)) for _ in range(COLD_SETS)]
+            return sets, [(lambda a=a: tc355.tc_tbmm(*a)) for a in sets]
+        if name == "mlp":
+            sets = [(I.clone(), [w.clone() for w in Ws], [b.clone() for b in bs], [torch.empty_like(o) for o in O],
+                     torch.empty_like(ws)) for _ in range(COLD_SETS)]
+            return sets, [(lambda a=a: tc355.tc_mlp_fcrelu(*a)) for a in sets]
+        if name == "kron":
+            sets = [(K1.clone(), K2.clone(), Xk.clone(), torch.empty_like(Yk)) for _ in range(COLD_SETS)]
+            return sets, [(lambda a=a: tc355.tc_kron(*a)) for a in sets]
+        return None, None  # gconv: one set is 426 MB already
+
     if args.scaling:
         scaling_study(torch, tc355, inputs)
+        return
+
+    if args.counter_probe:
+        # for `rocprofv3 --pmc ... -- python3 bench.py --counter-probe`: every small operator of the step once on each
+        # of COLD_SETS buffer sets that no launch has touched since they were written (inputs come from HBM), five
+        # times over, the batched matmul at 64 times the benchmark batch, and a plain copy of known size (calibration)
+        t_pre = time.perf_counter()
+        while (time.perf_counter() - t_pre) < 0.15:   # settle the clock
+            for name in ("tbmm", "mlp", "kron"):
+                ops[name][0]()
+            torch.cuda.synchronize()
+        src = torch.ones(128 * 1024 * 1024, dtype=torch.float32, device="cuda")  # 512 MiB read + 512 MiB written
+        dst = torch.empty_like(src)
+        X64, Y64 = X.repeat(64, 1, 1), Y.repeat(64, 1, 1)
+        Z64 = torch.empty((64 * 500, 26, 72), device="cuda")
+        out = {"counter_probe": True, "copy_bytes_each_way": src.numel() * 4, "cold_sets": COLD_SETS, "rounds": 5,
+               "algorithmic_bytes": {k: ops[k][2] for k in ("tbmm", "mlp", "kron")},
+               "tbmm_x64_algorithmic_bytes": 64 * ops["tbmm"][2]}
+        for name in ("tbmm", "mlp", "kron"):
+            sets, calls = cold_calls(name)
+            for _ in range(5):
+                dst.copy_(src)               # 1 GiB through the caches: nothing of the sets is left in them
+                for c in calls:
+                    c()
+            torch.cuda.synchronize()
+            out[name + "_path"] = tc355.last_path()
+            del sets, calls
+        for _ in range(5):
+            dst.copy_(src)
+            tc355.tc_tbmm(X64, Y64, Z64)
+        torch.cuda.synchronize()
+        print(json.dumps(out), flush=True)
         return
 
     if args.traffic_probe:
@@ -221,24 +272,10 @@ def main():
         return {"us": round(float(x.mean()), 3), "p0": round(float(x.min()), 3), "p50": round(float(np.median(x)), 3),
                 "p90": round(float(np.percentile(x, 90)), 3)}
 
-    COLD_SETS, WARM_LAUNCHES = 40, 20
+    WARM_LAUNCHES = 20
     # the smallest launch the library makes (one 1 x 1 x 1 product), replayed the same way: the launch floor
     x1, y1, z1 = (torch.zeros((1, 1, 1), device="cuda") for _ in range(3))
     floor = replay_samples(capture([lambda: tc355.tc_tbmm(x1, y1, z1)] * WARM_LAUNCHES), WARM_LAUNCHES, args.op_samples)
-
-    def cold_calls(name):
-        """One launch on each of COLD_SETS copies of the operator's tensors (more than 256 MB in all)."""
-        if name == "tbmm":
-            sets = [(X.clone(), Y.clone(), torch.empty_like(Z)) for _ in range(COLD_SETS)]
-            return sets, [(lambda a=a: tc355.tc_tbmm(*a)) for a in sets]
-        if name == "mlp":
-            sets = [(I.clone(), [w.clone() for w in Ws], [b.clone() for b in bs], [torch.empty_like(o) for o in O],
-                     torch.empty_like(ws)) for _ in range(COLD_SETS)]
-            return sets, [(lambda a=a: tc355.tc_mlp_fcrelu(*a)) for a in sets]
-        if name == "kron":
-            sets = [(K1.clone(), K2.clone(), Xk.clone(), torch.empty_like(Yk)) for _ in range(COLD_SETS)]
-            return sets, [(lambda a=a: tc355.tc_kron(*a)) for a in sets]
-        return None, None  # gconv: one set is 426 MB already
 
     per_op = {}
     for name, (fn, flops, nbytes) in ops.items():
