@@ -11,9 +11,13 @@
 // weights.  A lane's B operand for (pixel tile, j) is the 16-byte half record of its own output pixel shifted by the
 // tap, so the image needs no im2col: it sits in LDS as [4 digit planes][pixel][32 channels] bytes.
 //
-// Work split as in gconv_i8_small.hpp: a workgroup takes four images of one group at a time, one per wavefront; the
-// filter bank (2 filter tiles x 5 instructions x 4 digits of A operands: too many for the register file) is sliced
-// once per group into LDS records that all four wavefronts read; everything else is private to a wavefront.
+// Work split: a workgroup of four wavefronts takes four images of one group at a time, one per wavefront; the filter
+// bank (2 filter tiles x 5 instructions x 4 digits of A operands: too many for the register file) is sliced once per
+// group into LDS records that all wavefronts read; everything else is private to a wavefront.  A launch at the
+// paper's shape is one wave of workgroups, so the bank setup is on its critical path and is kept short: eight
+// neighbouring lanes take one filter row, each 4 channels x 9 taps of it (36 consecutive floats: nine 16-byte loads,
+// issued before the image is sliced), share the row's maximum through cross-lane moves, and write their digits
+// straight into the records: no fp32 copy in LDS, no LDS reads, one barrier.
 #pragma once
 #include "gconv_i8.hpp"
 
@@ -29,6 +33,7 @@ struct GconvI8C32Args {
 
 template <int H, int W>
 struct GconvI8C32Geom {
+  static constexpr int NW = WAVES_PER_WG, NT = WG_THREADS;
   static constexpr int C = 32, F = 32, KH = 3, KW = 3, TAPS = KH * KW;
   static constexpr int OH = H - KH + 1, OW = W - KW + 1;
   static constexpr int NPX = H * W, NOUT = OH * OW;
@@ -40,10 +45,11 @@ struct GconvI8C32Geom {
   static constexpr int NUNIT = NPX * (C / 4);               // staging units: one pixel x 4 channels
   static constexpr int ROUNDS = (NUNIT + WAVE - 1) / WAVE;
   static constexpr int AREC = FT * NJ * 4 * WAVE * 16;      // A operand records: [ft][j][digit][lane] x 16 bytes
-  static constexpr int WROW = C * TAPS + 1;                 // padded fp32 filter row (odd: conflict-free column reads)
-  static constexpr int SCRATCH = 16 * WROW * 4;             // one filter tile of fp32 weights, staged in the image area
-  static constexpr int LDS_BYTES = WAVES_PER_WG * IMG + AREC;
-  static_assert(SCRATCH <= WAVES_PER_WG * IMG, "the weight scratch borrows the image area");
+  static constexpr int LDS_BYTES = NW * IMG + AREC + F * 4;  // + the filter rows' maxima
+  static constexpr int TPR = NT / F;                        // threads that share a filter row: 8
+  static constexpr int EPT = C * TAPS / TPR;                // elements of the row per such thread: 4 channels x 9 taps
+  static_assert(TPR == 8 && EPT == 4 * TAPS && EPT % 4 == 0, "bank setup: a thread takes 4 channels of one filter row");
+  static_assert(FT * 4 * 16 * 2 == NT && 2 * TAPS + 2 == 4 * NJ, "one padding record per thread");
   static_assert(3 * PLANE + NPX * C < 65536, "LDS immediates out of range");
 };
 
@@ -53,8 +59,9 @@ template <int H, int W, int MIND = 2>
 __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_c32_kernel(GconvI8C32Args p) {
   static_assert(MIND == 2 || MIND == 3, "13 or 10 digit products");
   using Gm = GconvI8C32Geom<H, W>;
+  constexpr int NW = Gm::NW;
   constexpr int C = Gm::C, F = Gm::F, KW = Gm::KW, TAPS = Gm::TAPS, OW = Gm::OW, NPX = Gm::NPX, NOUT = Gm::NOUT,
-                PT = Gm::PT, FT = Gm::FT, NJ = Gm::NJ, PLANE = Gm::PLANE, ROUNDS = Gm::ROUNDS, WROW = Gm::WROW;
+                PT = Gm::PT, FT = Gm::FT, NJ = Gm::NJ, PLANE = Gm::PLANE, ROUNDS = Gm::ROUNDS;
   extern __shared__ __attribute__((aligned(16))) char gc_lds[];
 
   const int tid = threadIdx.x;
@@ -62,11 +69,11 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_c32_kernel(GconvI8C32A
   const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
   const int r16 = lane & 15, q = lane >> 4;
   char* img = gc_lds + wave * Gm::IMG;                       // this wavefront's digit planes
-  float* wl = reinterpret_cast<float*>(gc_lds);              // weight scratch (only during the bank setup)
-  char* arec = gc_lds + WAVES_PER_WG * Gm::IMG;
+  char* arec = gc_lds + NW * Gm::IMG;
+  unsigned* rowmax = reinterpret_cast<unsigned*>(arec + Gm::AREC);  // largest magnitude of every filter row
 
-  // this workgroup's run of iterations [u, u1); iteration = (group g, images 4i .. 4i+3), group-major
-  const int per_group = p.N / WAVES_PER_WG;
+  // this workgroup's run of iterations [u, u1); iteration = (group g, images NW i .. NW i + NW - 1), group-major
+  const int per_group = p.N / NW;
   const unsigned iters = (unsigned)(p.G * per_group);
   unsigned u = iters * blockIdx.x / gridDim.x;
   const unsigned u1 = iters * (blockIdx.x + 1) / gridDim.x;
@@ -105,58 +112,20 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_c32_kernel(GconvI8C32A
       for (int c = 0; c < 4; c++) pre[r][c] = src[(4 * cg + c) * NPX + px];
     }
   };
-  fetch((int)(u / per_group), (int)(u % per_group) * WAVES_PER_WG + wave);
+  fetch((int)(u / per_group), (int)(u % per_group) * NW + wave);
 
   double fa[FT][4];  // 2^24 / scale of filter row 16 ft + 4q + v (NaN if the row holds Inf/NaN)
   float bz[FT][4];   // bias of that row
   int g_bank = -1;
   for (; u < u1; u++) {
-    const int g = (int)(u / per_group), n = (int)(u % per_group) * WAVES_PER_WG + wave;
-    // ---- filter bank -> A operand records in LDS, one filter tile at a time through the (idle) image area:
-    // record (ft, j, k) of a lane at arec + (((ft*NJ + j)*4 + k)*64 + lane)*16; wavefront w slices bytes 4w .. 4w+3
-    if (g != g_bank) {  // uniform over the workgroup
-      g_bank = g;
-#pragma unroll 1
-      for (int ft = 0; ft < FT; ft++) {
-        __syncthreads();  // every wavefront is done with its image (and with the scratch of the last filter tile)
-        const float* wg = p.W1 + ((int64_t)g * F + 16 * ft) * (C * TAPS);
-        for (int i = tid; i < 16 * C * TAPS; i += WG_THREADS) wl[i + i / (C * TAPS)] = wg[i];
-        __syncthreads();
-        const float* wrow = wl + r16 * WROW;  // filter 16 ft + r16: [channel][tap]
-        unsigned m = 0;
+    const int g = (int)(u / per_group), n = (int)(u % per_group) * NW + wave;
+    // ---- a new group: this thread's share of the filter bank, 4 channels x 9 taps of filter row tid / 8
+    const bool new_bank = g != g_bank;  // uniform over the workgroup
+    f4 wv[Gm::EPT / 4];
+    if (new_bank) {
+      const f4* src = reinterpret_cast<const f4*>(p.W1 + ((int64_t)g * F + tid / Gm::TPR) * (C * TAPS) + (tid % Gm::TPR) * Gm::EPT);
 #pragma unroll
-        for (int j = 0; j < NJ; j++)
-#pragma unroll
-          for (int c = 0; c < 16; c++)
-            if (realj[j]) m = max(m, __float_as_uint(wrow[(16 * halfj[j] + c) * TAPS + tapj[j]]) & 0x7fffffffu);
-        m = max(m, (unsigned)__shfl_xor((int)m, 16));
-        m = max(m, (unsigned)__shfl_xor((int)m, 32));
-        const double sa = i8_scale(m);  // m = max|w| over the filter row
-#pragma unroll
-        for (int j = 0; j < NJ; j++) {
-          int d[4], y[4];
-#pragma unroll
-          for (int c = 0; c < 4; c++)
-            d[c] = i8_fixed<0x00808080>(wrow[(16 * halfj[j] + 4 * wave + c) * TAPS + tapj[j]], sa) ^ 0x00808080;
-          i8_transpose4(d, y);
-#pragma unroll
-          for (int k = 0; k < 4; k++)
-            *reinterpret_cast<int*>(arec + (((ft * NJ + j) * 4 + k) * WAVE + lane) * 16 + 4 * wave) = realj[j] ? y[k] : 0;
-        }
-#pragma unroll
-        for (int v = 0; v < 4; v++) {
-          const unsigned mv = (unsigned)__shfl((int)m, 4 * q + v);  // lane 4q+v holds filter row 4q+v of this tile
-          if (ft == 0) {
-            fa[0][v] = 16777216.0 * i8_inverse_scale(mv);
-            bz[0][v] = p.bias ? p.bias[g * F + 4 * q + v] : 0.f;
-          } else {
-            fa[FT - 1][v] = 16777216.0 * i8_inverse_scale(mv);
-            bz[FT - 1][v] = p.bias ? p.bias[g * F + 16 * (FT - 1) + 4 * q + v] : 0.f;
-          }
-        }
-      }
-      static_assert(FT == 2, "the scales of the two filter tiles are kept in named registers above");
-      __syncthreads();  // records complete; the image area is free again
+      for (int r = 0; r < Gm::EPT / 4; r++) wv[r] = src[r];
     }
 
     // ---- largest magnitude of the image block (this wavefront only)
@@ -189,10 +158,54 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_c32_kernel(GconvI8C32A
         }
       }
     }
+    // ---- filter bank -> A operand records in LDS: record (ft, j, k) of lane (r16, q) at
+    // arec + (((ft*NJ + j)*4 + k)*64 + lane)*16 holds digit k of filter 16 ft + r16, tap and channel half of slot
+    // group 4 j + q, 16 channels.  This thread has filter row 16 ft + r16' = tid / 8 and channels 4 part ..
+    if (new_bank) {
+      g_bank = g;
+      __syncthreads();  // every wavefront is done with the records of the last group
+      const int row = tid / Gm::TPR, part = tid % Gm::TPR;
+      const float* w = reinterpret_cast<const float*>(wv);  // [channel c of 4][tap]
+      unsigned m = 0;
+#pragma unroll
+      for (int i = 0; i < Gm::EPT; i++) m = max(m, __float_as_uint(w[i]) & 0x7fffffffu);
+      int mv = (int)m;  // sign cleared: signed and unsigned order agree
+      mv = max(mv, __builtin_amdgcn_update_dpp(mv, mv, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+      mv = max(mv, __builtin_amdgcn_update_dpp(mv, mv, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+      mv = max(mv, __builtin_amdgcn_update_dpp(mv, mv, 0x141, 0xF, 0xF, false));  // row_half_mirror: the row's 8 lanes
+      if (part == 0) rowmax[row] = (unsigned)mv;
+      const double sa = i8_scale((unsigned)mv);
+      char* rec = arec + ((row >> 4) * NJ * 4 * WAVE + (row & 15)) * 16 + 4 * (part & 3);
+      const int half = part >> 2;
+#pragma unroll
+      for (int t = 0; t < TAPS; t++) {
+        int d[4], y[4];
+#pragma unroll
+        for (int c = 0; c < 4; c++) d[c] = i8_fixed<0x00808080>(w[c * TAPS + t], sa) ^ 0x00808080;
+        i8_transpose4(d, y);
+        // slot group 2 t + half = 4 j + q: only q depends on the thread
+        const int j = (2 * t) / 4, q0 = (2 * t) % 4;
+#pragma unroll
+        for (int k = 0; k < 4; k++)
+          *reinterpret_cast<int*>(rec + ((j * 4 + k) * WAVE + 16 * (q0 + half)) * 16) = y[k];
+      }
+      {  // the two slot groups past the 18 real ones (instruction NJ - 1, q = 2 and 3) hold zero weights
+        const int ft = tid >> 7, k = (tid >> 5) & 3, qq = 2 + ((tid >> 4) & 1);
+        *reinterpret_cast<i4*>(arec + (((ft * NJ + NJ - 1) * 4 + k) * WAVE + 16 * qq + (tid & 15)) * 16) = i4{0, 0, 0, 0};
+      }
+      __syncthreads();  // records and row maxima complete
+#pragma unroll
+      for (int ft = 0; ft < FT; ft++)
+#pragma unroll
+        for (int v = 0; v < 4; v++) {
+          fa[ft][v] = 16777216.0 * i8_inverse_scale(rowmax[16 * ft + 4 * q + v]);
+          bz[ft][v] = p.bias ? p.bias[g * F + 16 * ft + 4 * q + v] : 0.f;
+        }
+    }
     // the next image of this wavefront, fetched while this one is contracted
     if (u + 1 < u1) {
       const unsigned un = u + 1;
-      fetch((int)(un / per_group), (int)(un % per_group) * WAVES_PER_WG + wave);
+      fetch((int)(un / per_group), (int)(un % per_group) * NW + wave);
     }
     const double invb = i8_inverse_scale(m);
 

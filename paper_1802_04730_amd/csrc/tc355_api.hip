@@ -787,7 +787,7 @@ tc_status tc_group_conv(const float* I, const float* W1, const float* bias, floa
     if (try_gconv_i8<58, 8, 3>(a, force13, s, &st)) return took("gconv:i8", st);
     if (i8 == TC_INT8_TEN) {
       if (try_gconv_i8_small<14, 14, 3>(a, s, &st)) return took("gconv:i8_small", st);  // the paper's (32,32,16,16,14,14)
-      if (try_gconv_i8_c32<7, 7, 3>(a, s, &st)) return took("gconv:i8_c32", st);        // the paper's (32,32,32,32,7,7)
+      if (try_gconv_i8_c32<7, 7, 3>(a, s, &st)) return took("gconv:i8_c32", st);     // the paper's (32,32,32,32,7,7)
     } else {
       if (try_gconv_i8_small<14, 14, 2>(a, s, &st)) return took("gconv:i8_small", st);
       if (try_gconv_i8_c32<7, 7, 2>(a, s, &st)) return took("gconv:i8_c32", st);

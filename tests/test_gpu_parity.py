@@ -667,7 +667,19 @@ def test_tmm_largest_paper_shape_sampled(tc, oracle_threads):
     pick = np.sort(rng.choice(16384, size=96, replace=False))
     pick[:4] = [0, 63, 64, 16383]
     ref = oracle.tbmm(X, np.ascontiguousarray(Y[:, pick]))
+    assert tc.last_path() == "tbmm:i8"
     check(Z[:, :, torch.from_numpy(pick).cuda()], ref, "tmm 128x4096x16384, 96 sampled columns", TIGHT_I8)
+    # every workgroup's output: the whole result against the whole result of the fp64 kernels (which the sampled
+    # columns pin to the oracle as well)
+    Z64 = torch.full((1, 128, 16384), float("nan"), device="cuda")
+    with tc.option(tc.TC_OPT_INT8, tc.TC_INT8_OFF):
+        tc.tc_tbmm(dev(X), dev(Y), Z64)
+        assert tc.last_path() != "tbmm:i8"
+    check(Z64[:, :, torch.from_numpy(pick).cuda()], ref, "tmm 128x4096x16384 on the fp64 path, 96 sampled columns")
+    torch.cuda.synchronize()
+    err = parity_error(Z.cpu().numpy().astype(np.float64), Z64.cpu().numpy().astype(np.float64))
+    print("tmm 128x4096x16384: int8 path against fp64 path, whole output: %.3e" % err, flush=True)
+    assert err <= TIGHT_I8
 
 
 @pytest.mark.parametrize("shape", [
@@ -686,8 +698,21 @@ def test_gconv_paper_table_shapes_full_size_sampled(tc, oracle_threads, shape):
     assert not torch.isnan(O).any()
     pick = np.array([0, 13, 14, 31])
     ref = oracle.group_conv(np.ascontiguousarray(I[pick]), W1, bias)
+    path = tc.last_path()
     check(O[torch.from_numpy(pick).cuda()], ref, "gconv %s, images %s" % (shape, pick.tolist()),
           tight_for_last_call(tc))
+    # every workgroup's output: where the default is an int8 kernel, its whole result against the whole result of
+    # the fp64 kernel (which the sampled images pin to the oracle as well)
+    if ":i8" in path:
+        O64 = torch.full(O.shape, float("nan"), device="cuda")
+        with tc.option(tc.TC_OPT_INT8, tc.TC_INT8_OFF):
+            tc.tc_group_conv(dev(I), dev(W1), dev(bias), O64)
+            assert ":i8" not in tc.last_path()
+        check(O64[torch.from_numpy(pick).cuda()], ref, "gconv %s on the fp64 path, images %s" % (shape, pick.tolist()))
+        torch.cuda.synchronize()
+        err = parity_error(O.cpu().numpy().astype(np.float64), O64.cpu().numpy().astype(np.float64))
+        print("gconv %s: %s against the fp64 kernel, whole output: %.3e" % (shape, path, err), flush=True)
+        assert err <= TIGHT_I8
 
 
 def test_kron_and_gconv_stay_inside_their_outputs(tc, oracle_threads):
