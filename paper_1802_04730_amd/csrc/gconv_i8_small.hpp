@@ -11,6 +11,10 @@
 // numbered row-major and cut into tiles of 16 (144 = 9 tiles for 14 x 14: none is padded); a lane's B operand for
 // (tile, kh) is the 16-byte record of pixel (h + kh, w + kw) of its own output pixel, so every (tile, kh) costs four
 // LDS reads for 10 MFMAs.  The next image is fetched into registers while the current one is contracted.
+// A launch at the paper's shape is one wave of workgroups, so the filter-bank setup is on its critical path and is kept
+// short: 16 neighbouring lanes take one filter row, each one channel's 9 taps (loaded before the image is sliced),
+// share the row's maximum through cross-lane moves and write their digit bytes straight into the records: no fp32
+// copy in LDS, one barrier.
 #pragma once
 #include "gconv_i8.hpp"
 
@@ -34,7 +38,7 @@ struct GconvI8SmallGeom {
   static constexpr int IMG = 4 * PLANE;                      // bytes of one wavefront's image
   static constexpr int NUNIT = NPX;                          // staging units of 4 channels x 4 pixels: (NPX / 4) * 4
   static constexpr int ROUNDS = (NUNIT + WAVE - 1) / WAVE;   // units per lane
-  static constexpr int BANK = 16384 + KH * 4 * WAVE * 16;    // filter-bank scratch: padded fp32 rows, then digit records
+  static constexpr int BANK = KH * 4 * WAVE * 16 + F * 4;    // the filter bank's digit records, then the filter rows' maxima
   static constexpr int LDS_BYTES = WAVES_PER_WG * IMG + BANK;
   static_assert(NPX % 4 == 0, "a channel plane is a whole number of 16-byte pieces");
   static_assert(3 * PLANE + ((H - 1) * W + W) * 16 < 65536, "LDS immediates out of range");
@@ -48,8 +52,8 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_small_kernel(GconvI8Sm
   using Gm = GconvI8SmallGeom<H, W>;
   constexpr int C = Gm::C, F = Gm::F, KH = Gm::KH, KW = Gm::KW, OW = Gm::OW, NPX = Gm::NPX, NOUT = Gm::NOUT,
                 TILES = Gm::TILES, PLANE = Gm::PLANE, ROUNDS = Gm::ROUNDS;
-  constexpr int WN = F * C * KH * KW, WPT = WN / WG_THREADS;
-  static_assert(WN % WG_THREADS == 0, "whole filter-bank floats per thread");
+  constexpr int WN = F * C * KH * KW, WPT = KH * KW;
+  static_assert(F * C == WG_THREADS, "bank setup: one (filter row, channel) per thread");
   extern __shared__ __attribute__((aligned(16))) char gs_lds[];
 
   const int tid = threadIdx.x;
@@ -58,8 +62,8 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_small_kernel(GconvI8Sm
   const int r16 = lane & 15, q = lane >> 4;
   const int kwq = q < KW ? q : KW - 1;  // slot group 3 is padding: it re-reads kw = 2 against zero weights
   char* img = gs_lds + wave * Gm::IMG;                       // this wavefront's digit planes
-  float* wl = reinterpret_cast<float*>(gs_lds + WAVES_PER_WG * Gm::IMG);
-  char* arec = reinterpret_cast<char*>(wl) + 16384;
+  char* arec = gs_lds + WAVES_PER_WG * Gm::IMG;
+  unsigned* rowmax = reinterpret_cast<unsigned*>(arec + KH * 4 * WAVE * 16);  // largest magnitude of every filter row
 
   // this workgroup's run of iterations [u, u1); iteration = (group g, images 4j .. 4j+3), group-major
   const int per_group = p.N / WAVES_PER_WG;
@@ -98,53 +102,13 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_small_kernel(GconvI8Sm
   int g_bank = -1;
   for (; u < u1; u++) {
     const int g = (int)(u / per_group), n = (int)(u % per_group) * WAVES_PER_WG + wave;
-    // ---- filter bank -> A operands (as in gconv_i8.hpp: wavefront w slices channels 4w .. 4w+3, records exchanged
-    // through LDS: record (kh, k) of a lane at arec + ((kh*4 + k)*64 + lane)*16, dword w)
-    if (g != g_bank) {  // uniform over the workgroup
-      g_bank = g;
-      const float* wg = p.W1 + (int64_t)g * WN;
-      float wpre[WPT];
+    // ---- a new group: this thread's share of the filter bank, the 9 taps of channel tid % 16 of filter row tid / 16
+    const bool new_bank = g != g_bank;  // uniform over the workgroup
+    float wv[WPT];
+    if (new_bank) {
+      const float* src = p.W1 + (int64_t)g * WN + tid * WPT;
 #pragma unroll
-      for (int j = 0; j < WPT; j++) wpre[j] = wg[tid + j * WG_THREADS];
-      __syncthreads();  // a slower wavefront may still be reading the records of the last bank
-      constexpr int WROW = C * KH * KW + 1;  // odd row distance: the 16 rows of a read fall into 16 banks
-      static_assert(F * WROW * 4 <= 16384, "padded filter bank must end before the digit records");
-#pragma unroll
-      for (int j = 0; j < WPT; j++) {
-        const int i = tid + j * WG_THREADS, f = i / (C * KH * KW);
-        wl[i + f] = wpre[j];
-      }
-      __syncthreads();
-      const float* wp = wl + r16 * WROW + kwq;
-      unsigned m = 0;
-#pragma unroll
-      for (int kh = 0; kh < KH; kh++)
-#pragma unroll
-        for (int c = 0; c < C; c++) m = max(m, __float_as_uint(wp[c * (KH * KW) + kh * KW]) & 0x7fffffffu);
-      m = max(m, (unsigned)__shfl_xor((int)m, 16));
-      m = max(m, (unsigned)__shfl_xor((int)m, 32));
-      const double sa = i8_scale(m);  // m = max|w| over the filter row
-#pragma unroll
-      for (int kh = 0; kh < KH; kh++) {
-        int d[4], y[4];
-#pragma unroll
-        for (int c = 0; c < 4; c++)
-          d[c] = i8_fixed<0x00808080>(wp[(4 * wave + c) * (KH * KW) + kh * KW], sa) ^ 0x00808080;  // byte k = digit k
-        i8_transpose4(d, y);
-#pragma unroll
-        for (int k = 0; k < 4; k++)
-          *reinterpret_cast<int*>(arec + ((kh * 4 + k) * WAVE + lane) * 16 + 4 * wave) = q < KW ? y[k] : 0;
-      }
-      __syncthreads();
-#pragma unroll
-      for (int kh = 0; kh < KH; kh++)
-#pragma unroll
-        for (int k = 0; k < 4; k++) a[kh][k] = *reinterpret_cast<const i4*>(arec + ((kh * 4 + k) * WAVE + lane) * 16);
-#pragma unroll
-      for (int v = 0; v < 4; v++) {
-        fa[v] = 16777216.0 * i8_inverse_scale((unsigned)__shfl((int)m, 4 * q + v));  // lane 4q+v holds filter row 4q+v
-        bz[v] = p.bias ? p.bias[g * F + 4 * q + v] : 0.f;
-      }
+      for (int j = 0; j < WPT; j++) wv[j] = src[j];
     }
 
     // ---- largest magnitude of the image block (this wavefront only)
@@ -180,6 +144,42 @@ __global__ __launch_bounds__(WG_THREADS, 2) void gconv_i8_small_kernel(GconvI8Sm
               *reinterpret_cast<int*>(img + k * PLANE + 16 * (4 * px4 + e) + 4 * cg) = k < 3 ? y[k] ^ (int)0x80808080 : y[k];
           }
         }
+      }
+    }
+    // ---- filter bank -> A operands: record (kh, k) of lane (r16, q) at arec + ((kh*4 + k)*64 + lane)*16 holds digit k
+    // of W1[g][r16][channel = byte][kh][kw = q]; q = 3 is padding and holds zeros
+    if (new_bank) {
+      g_bank = g;
+      __syncthreads();  // a slower wavefront may still be reading the records of the last bank
+      const int row = tid >> 4, ch = tid & 15;
+      unsigned mw = 0;
+#pragma unroll
+      for (int j = 0; j < WPT; j++) mw = max(mw, __float_as_uint(wv[j]) & 0x7fffffffu);
+      int mv = (int)mw;  // sign cleared: signed and unsigned order agree
+      mv = max(mv, __builtin_amdgcn_update_dpp(mv, mv, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+      mv = max(mv, __builtin_amdgcn_update_dpp(mv, mv, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+      mv = max(mv, __builtin_amdgcn_update_dpp(mv, mv, 0x141, 0xF, 0xF, false));  // row_half_mirror
+      mv = max(mv, __builtin_amdgcn_update_dpp(mv, mv, 0x140, 0xF, 0xF, false));  // row_mirror: the row's 16 lanes
+      if (ch == 0) rowmax[row] = (unsigned)mv;
+      const double sa = i8_scale((unsigned)mv);  // mv = max|w| over the filter row
+#pragma unroll
+      for (int t = 0; t < WPT; t++) {
+        const int d = i8_fixed<0x00808080>(wv[t], sa) ^ 0x00808080;  // byte k = digit k
+#pragma unroll
+        for (int k = 0; k < 4; k++)
+          arec[(((t / KW) * 4 + k) * WAVE + 16 * (t % KW) + row) * 16 + ch] = (char)(d >> (8 * k));
+      }
+      if (tid < KH * 4 * 16)  // the padding records
+        *reinterpret_cast<i4*>(arec + ((tid >> 4) * WAVE + 16 * KW + (tid & 15)) * 16) = i4{0, 0, 0, 0};
+      __syncthreads();
+#pragma unroll
+      for (int kh = 0; kh < KH; kh++)
+#pragma unroll
+        for (int k = 0; k < 4; k++) a[kh][k] = *reinterpret_cast<const i4*>(arec + ((kh * 4 + k) * WAVE + lane) * 16);
+#pragma unroll
+      for (int v = 0; v < 4; v++) {
+        fa[v] = 16777216.0 * i8_inverse_scale(rowmax[4 * q + v]);
+        bz[v] = p.bias ? p.bias[g * F + 4 * q + v] : 0.f;
       }
     }
     // the next image of this wavefront, fetched while this one is contracted
