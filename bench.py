@@ -523,11 +523,20 @@ def scaling_study(torch, tc355, inputs):
         launches = 10 if reps >= 100 else 4
         return float(replay_samples(capture([fn] * launches), launches, 30).mean())
 
+    def copy_us(nbytes):
+        """A plain device-to-device copy that moves nbytes in all (half read, half written), timed the same way."""
+        src = torch.ones(max(1, nbytes // 8), dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        return timed(lambda: dst.copy_(src), 100 if nbytes < (1 << 28) else 30)
+
     def report(op, scale, us, flops, nbytes):
         t_mfma, t_hbm = flops / (PEAK_F64_MFMA_TFLOPS * 1e12), nbytes / (PEAK_HBM_GBS * 1e9)
-        print(json.dumps({"op": op, "batch_scale": scale, "us": round(us, 2), "gflops": round(flops / us * 1e-3, 1),
-                          "gbs": round(nbytes / us * 1e-3, 1), "bound": "mfma" if t_mfma >= t_hbm else "hbm",
-                          "frac": round(max(t_mfma, t_hbm) * 1e6 / us, 4)}), flush=True)
+        line = {"op": op, "batch_scale": scale, "us": round(us, 2), "gflops": round(flops / us * 1e-3, 1),
+                "gbs": round(nbytes / us * 1e-3, 1), "bound": "mfma" if t_mfma >= t_hbm else "hbm",
+                "frac": round(max(t_mfma, t_hbm) * 1e6 / us, 4)}
+        if t_hbm > t_mfma:  # what the runtime's copy kernel needs for the same number of bytes
+            line["copy_same_bytes_us"] = round(copy_us(nbytes), 2)
+        print(json.dumps(line), flush=True)
 
     for scale in (1, 8, 64):
         B = 500 * scale

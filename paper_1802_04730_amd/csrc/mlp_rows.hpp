@@ -75,8 +75,8 @@ constexpr int MR_SLICE_BYTES = 16 * 128 * 4;                  // a wavefront's s
 constexpr int MR_AREA_BYTES = MR_WAVES * MR_SLICE_BYTES;       // one 16-row tile of up to 1024 fp32: 64 KiB
 constexpr int MR_PART_BYTES = MR_WAVES * MR_MAXT * WAVE * 32;  // the partial tiles
 constexpr int MR_LDS_BYTES = MR_MAXT * MR_AREA_BYTES + MR_PART_BYTES;  // 160 KiB: one workgroup per compute unit
-// flags live behind the header of the sync area: one byte per 4 output columns of a row tile,
-// [boundary][group][column / 4], with room for MR_MAXT tiles per workgroup (rounded up to whole words)
+// flags live behind the header of the sync area: one 32-bit word per 4 output columns of a row tile,
+// [boundary][group][column / 4], with room for MR_MAXT tiles per workgroup
 constexpr int MR_FLAG_WORD0 = MLP_SYNC_WORDS;
 // words of flags that a chain needs (the host checks that they fit the sync area)
 inline int64_t mr_flag_words(int n_layers, int64_t groups, int64_t nwg) {
