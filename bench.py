@@ -310,7 +310,7 @@ def main():
     Xt = torch.randn((1, 128, 4096), device="cuda")
     Yt = torch.randn((1, 16384, 4096), device="cuda")
     Zt = torch.empty((1, 128, 16384), device="cuda")
-    def timed(fn, launches=10):
+    def timed(fn, launches=20):
         """Mean GPU time per launch, microseconds: `launches` launches captured in a HIP graph, replayed 20 times."""
         return float(replay_samples(capture([fn] * launches), launches, 20).mean())
 
