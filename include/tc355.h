@@ -130,6 +130,27 @@ tc_status tc_tbmm(const float *X, const float *Y, float *Z, int64_t B,
                   int64_t N, int64_t M, int64_t K, void *hip_stream);
 
 /*
+ * tc_tbmm with an optional workspace (same comprehension, Section 7, listings
+ * tbmm / tmm; same results to the stated accuracy).  The shape class that runs
+ * on the int8 matrix core (see tc_tbmm) spends a third of its vector work on
+ * slicing X into 8-bit digits again in every workgroup that reads it; with a
+ * workspace X is sliced once, by a kernel of its own launched first on the
+ * same stream, and the contraction reads the digits.
+ *   workspace        device scratch of at least tc_tbmm_workspace_bytes(...)
+ *                    bytes, 16-byte aligned, distinct from X, Y and Z; contents
+ *                    on entry are irrelevant, contents on return unspecified;
+ *                    calls that share a workspace must be ordered on one stream.
+ *                    NULL, or fewer bytes than needed, is not an error: the call
+ *                    then does exactly what tc_tbmm does.
+ * tc_tbmm_workspace_bytes returns 0 for shapes that would not use a workspace
+ * (and on bad input); for those tc_tbmm_ws ignores the argument.
+ */
+size_t tc_tbmm_workspace_bytes(int64_t B, int64_t N, int64_t M, int64_t K);
+tc_status tc_tbmm_ws(const float *X, const float *Y, float *Z, int64_t B,
+                     int64_t N, int64_t M, int64_t K, void *workspace,
+                     size_t workspace_bytes, void *hip_stream);
+
+/*
  * Chain of n_layers fully connected + bias + ReLU layers, evaluated by one
  * call (Section 3, listing fcrelu; appendix "Production Models", listings
  * MLP1 (n_layers = 1) and MLP3 (n_layers = 3)).  For layer l = 0..n_layers-1

@@ -16,10 +16,15 @@
 // additions; the result is rounded to fp32 once.
 //
 // One workgroup of 8 wavefronts = 128 rows of X against 64 rows of Y.
-// Both operands are sliced by the workgroup that uses them (no workspace): X is
-// sliced again by every workgroup, and slicing plus the per-block scaling of
-// the sums is about 440 vector-ALU instructions per wavefront and block beside
-// its 80 MFMAs.  On this chip the vector ALU and the matrix core of a SIMD do
+// Without a workspace both operands are sliced by the workgroup that uses them:
+// X is sliced again by every workgroup, and slicing plus the per-block scaling
+// of the sums is about 475 vector-ALU instructions per wavefront and block
+// beside its 104 MFMAs (13 digit products).  With a workspace (PRE = true) X is
+// sliced ONCE by gemm_i8_slice_x_kernel, which runs the X half of the slicing
+// code and writes the digit records and the rows' inverse scales to global
+// memory in exactly the order in which this kernel's threads pick them up (one
+// 16-byte load per record, 8 KiB of consecutive addresses per instruction of
+// the workgroup): 184 of the vector instructions per wavefront and block go.  On this chip the vector ALU and the matrix core of a SIMD do
 // not work at the same time (the time of this kernel is the sum of its two
 // halves whatever their order or interleaving), so the kernel is bound by that
 // sum; blocks of 128 instead of 64 halve the per-block scaling work.
@@ -52,7 +57,14 @@ struct GemmI8Args {
   const float* Y;  // [B][M][K]
   float* Z;        // [B][N][M]
   int M, K;
+  // X sliced beforehand (PRE = true): per block of 128 rows and block of 128 k, 8 record groups (MFMA step s, digit
+  // plane k) of 512 records of 16 bytes, record t being what thread t of the contracting workgroup stages; then
+  // the 128 inverse scales of the block (fp64)
+  const i4* Xd;        // [B * N / 128][K / 128][2][4][512]
+  const double* Xinv;  // [B * N / 128][K / 128][128]
 };
+// bytes of pre-sliced X per block of 128 rows x 128 k
+constexpr int64_t GI8_XD_BYTES = 2 * 4 * 512 * 16, GI8_XINV_BYTES = 128 * 8;
 
 constexpr int GI8_TN = 128, GI8_TM = 64, GI8_KB = 128, GI8_THREADS = 512;
 constexpr int GI8_STEPS = GI8_KB / 64;                  // MFMA steps (64 reduction slots each) per block
@@ -77,7 +89,68 @@ __device__ __forceinline__ void gi8_scales(unsigned mbits, double& scale, double
 
 // MIND: the lowest digit diagonal k + l that is kept: 2 (13 products: what the library uses unless told that 10
 // will do) or 3 (10 products).
-template <int MIND = 2>
+// The digits of four elements, transposed: y[k] = digit k of the four (the offset that makes the digits signed is
+// removed after the transposition: three instructions instead of four).
+__device__ __forceinline__ void gi8_digits4(const f4& v, double scale, int (&y)[4]) {
+  int d[4];
+  d[0] = i8_fixed<0x00808080>(v.x, scale);
+  d[1] = i8_fixed<0x00808080>(v.y, scale);
+  d[2] = i8_fixed<0x00808080>(v.z, scale);
+  d[3] = i8_fixed<0x00808080>(v.w, scale);
+  i8_transpose4(d, y);
+  y[0] ^= 0x80808080; y[1] ^= 0x80808080; y[2] ^= 0x80808080;
+}
+// Largest magnitude without clearing sign bits: as signed integers the non-negative floats order by magnitude
+// and lie above every negative one; as unsigned integers the negative ones order by magnitude and lie above
+// every non-negative one.  One signed and one unsigned three-way maximum per two elements, merged at the end.
+__device__ __forceinline__ void gi8_absmax4(const f4& v, int& smax, unsigned& umax) {
+  const int s0 = __float_as_int(v.x), s1 = __float_as_int(v.y), s2 = __float_as_int(v.z), s3 = __float_as_int(v.w);
+  smax = i8_max3(i8_max3(s0, s1, s2), s3, smax);
+  umax = i8_max3(i8_max3((unsigned)s0, (unsigned)s1, (unsigned)s2), (unsigned)s3, umax);
+}
+__device__ __forceinline__ int gi8_magnitude(int smax, unsigned umax) { return max(max(smax, 0), (int)(umax & 0x7fffffffu)); }
+
+// X sliced once: one workgroup per (block of 128 k, block of 128 rows), thread t = (row t / 4, chunk t % 4) exactly
+// as in the contracting kernel, which later reads record t of every group with one 16-byte load.
+__global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_slice_x_kernel(const float* X, int K, i4* Xd, double* Xinv) {
+  const int tid = threadIdx.x, blk = blockIdx.x, nb = K / GI8_KB;
+  const int64_t rb = blockIdx.y;
+  const int xrow = tid >> 2, cx = tid & 3;
+  const float* xs = X + (rb * GI8_TN + xrow) * (int64_t)K + (int64_t)blk * GI8_KB + 4 * cx;
+  f4 rx[GI8_STEPS][4];
+#pragma unroll
+  for (int s = 0; s < GI8_STEPS; s++)
+#pragma unroll
+    for (int j = 0; j < 4; j++) rx[s][j] = *reinterpret_cast<const f4*>(xs + 64 * s + 16 * j);
+  int sm = 0;
+  unsigned um = 0;
+#pragma unroll
+  for (int s = 0; s < GI8_STEPS; s++)
+#pragma unroll
+    for (int j = 0; j < 4; j++) gi8_absmax4(rx[s][j], sm, um);
+  int v = gi8_magnitude(sm, um);
+  v = max(v, __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false));  // quad_perm [1,0,3,2]
+  v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false));  // quad_perm [2,3,0,1]
+  double scale, inverse;
+  gi8_scales((unsigned)v, scale, inverse);
+  i4* dst = Xd + (rb * nb + blk) * (int64_t)(GI8_STEPS * 4 * GI8_THREADS) + tid;
+#pragma unroll
+  for (int s = 0; s < GI8_STEPS; s++) {
+    int y[4][4];
+#pragma unroll
+    for (int j = 0; j < 4; j++) gi8_digits4(rx[s][j], scale, y[j]);
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+      i4 rec;
+      rec.x = y[0][k]; rec.y = y[1][k]; rec.z = y[2][k]; rec.w = y[3][k];
+      dst[(s * 4 + k) * GI8_THREADS] = rec;
+    }
+  }
+  if (cx == 0) Xinv[(rb * nb + blk) * GI8_TN + xrow] = inverse;
+}
+
+// PRE: X arrives sliced (Xd, Xinv) instead of as fp32.
+template <int MIND = 2, bool PRE = false>
 __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
   static_assert(MIND == 2 || MIND == 3, "13 or 10 digit products");
   extern __shared__ __attribute__((aligned(16))) char gi8g_lds[];
@@ -102,46 +175,47 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
   const float* xsrc = X + (int64_t)xrow * K + 4 * cx;
   const float* ysrc = Y + (int64_t)yrow * K + 32 * hy + 4 * cyc;
   f4 rx[GI8_STEPS][4], ry[GI8_STEPS][2];
+  i4 xd[GI8_STEPS][4];  // PRE: this thread's digit records of the block
+  double xinv = 0.0;    // PRE: inverse scale of row xrow in the block
+  const int64_t rb = b * gridDim.z + blockIdx.z;  // block of 128 rows of X
   auto fetch = [&](int blk) {
-    const float* xs = xsrc + blk * GI8_KB;
     const float* ys = ysrc + blk * GI8_KB;
+    if constexpr (PRE) {
+      const i4* xr = p.Xd + (rb * nb + blk) * (int64_t)(GI8_STEPS * 4 * GI8_THREADS) + tid;
 #pragma unroll
-    for (int s = 0; s < GI8_STEPS; s++) {
+      for (int s = 0; s < GI8_STEPS; s++)
 #pragma unroll
-      for (int j = 0; j < 4; j++) rx[s][j] = *reinterpret_cast<const f4*>(xs + 64 * s + 16 * j);
+        for (int k = 0; k < 4; k++) xd[s][k] = xr[(s * 4 + k) * GI8_THREADS];
+      xinv = p.Xinv[(rb * nb + blk) * GI8_TN + xrow];
+    } else {
+      const float* xs = xsrc + blk * GI8_KB;
+#pragma unroll
+      for (int s = 0; s < GI8_STEPS; s++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) rx[s][j] = *reinterpret_cast<const f4*>(xs + 64 * s + 16 * j);
+    }
+#pragma unroll
+    for (int s = 0; s < GI8_STEPS; s++)
 #pragma unroll
       for (int j = 0; j < 2; j++) ry[s][j] = *reinterpret_cast<const f4*>(ys + 64 * s + 16 * j);
-    }
-  };
-  // Largest magnitude without clearing sign bits: as signed integers the non-negative floats order by magnitude
-  // and lie above every negative one; as unsigned integers the negative ones order by magnitude and lie above
-  // every non-negative one.  One signed and one unsigned three-way maximum per two elements, merged at the end.
-  auto absmax4 = [](const f4& v, int& smax, unsigned& umax) {
-    const int s0 = __float_as_int(v.x), s1 = __float_as_int(v.y), s2 = __float_as_int(v.z), s3 = __float_as_int(v.w);
-    smax = i8_max3(i8_max3(s0, s1, s2), s3, smax);
-    umax = i8_max3(i8_max3((unsigned)s0, (unsigned)s1, (unsigned)s2), (unsigned)s3, umax);
-  };
-  auto magnitude = [](int smax, unsigned umax) { return max(max(smax, 0), (int)(umax & 0x7fffffffu)); };
-  // digits of four elements, transposed: y[k] = digit k of the four (the offset that makes the digits signed
-  // is removed after the transposition: three instructions instead of four)
-  auto digits4 = [](const f4& v, double scale, int (&y)[4]) {
-    int d[4];
-    d[0] = i8_fixed<0x00808080>(v.x, scale);
-    d[1] = i8_fixed<0x00808080>(v.y, scale);
-    d[2] = i8_fixed<0x00808080>(v.z, scale);
-    d[3] = i8_fixed<0x00808080>(v.w, scale);
-    i8_transpose4(d, y);
-    y[0] ^= 0x80808080; y[1] ^= 0x80808080; y[2] ^= 0x80808080;
   };
   auto slice = [&]() {
-    {  // X: 16 elements per step, row shared by the 4 lanes of a quad
+    if constexpr (PRE) {  // X: the records as they came
+#pragma unroll
+      for (int s = 0; s < GI8_STEPS; s++) {
+        char* dst = gi8g_lds + xrow * GI8_RS + 16 * (4 * s + cx);
+#pragma unroll
+        for (int k = 0; k < 4; k++) *reinterpret_cast<i4*>(dst + k * GI8_PLANE) = xd[s][k];
+      }
+      invs[xrow] = xinv;
+    } else {  // X: 16 elements per step, row shared by the 4 lanes of a quad
       int sm = 0;
       unsigned um = 0;
 #pragma unroll
       for (int s = 0; s < GI8_STEPS; s++)
 #pragma unroll
-        for (int j = 0; j < 4; j++) absmax4(rx[s][j], sm, um);
-      int v = magnitude(sm, um);
+        for (int j = 0; j < 4; j++) gi8_absmax4(rx[s][j], sm, um);
+      int v = gi8_magnitude(sm, um);
       v = max(v, __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false));  // quad_perm [1,0,3,2]
       v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false));  // quad_perm [2,3,0,1]
       double scale, inverse;
@@ -150,7 +224,7 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
       for (int s = 0; s < GI8_STEPS; s++) {
         int y[4][4];
 #pragma unroll
-        for (int j = 0; j < 4; j++) digits4(rx[s][j], scale, y[j]);
+        for (int j = 0; j < 4; j++) gi8_digits4(rx[s][j], scale, y[j]);
         char* dst = gi8g_lds + xrow * GI8_RS + 16 * (4 * s + cx);
 #pragma unroll
         for (int k = 0; k < 4; k++) {
@@ -166,10 +240,10 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
       unsigned um = 0;
 #pragma unroll
       for (int s = 0; s < GI8_STEPS; s++) {
-        absmax4(ry[s][0], sm, um);
-        absmax4(ry[s][1], sm, um);
+        gi8_absmax4(ry[s][0], sm, um);
+        gi8_absmax4(ry[s][1], sm, um);
       }
-      int v = magnitude(sm, um);
+      int v = gi8_magnitude(sm, um);
       v = max(v, __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
       v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
       v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x141, 0xF, 0xF, false));  // row_half_mirror: the other quad
@@ -179,7 +253,7 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
       for (int s = 0; s < GI8_STEPS; s++) {
         int y[2][4];
 #pragma unroll
-        for (int j = 0; j < 2; j++) digits4(ry[s][j], scale, y[j]);
+        for (int j = 0; j < 2; j++) gi8_digits4(ry[s][j], scale, y[j]);
         char* dst = gi8g_lds + (GI8_TN + yrow) * GI8_RS + 16 * (4 * s + cyc) + 8 * hy;
 #pragma unroll
         for (int k = 0; k < 4; k++) {

@@ -511,8 +511,32 @@ int64_t tc355_get_option(tc_option key) {
 
 const char* tc355_last_path(void) { return t_path; }
 
-tc_status tc_tbmm(const float* X, const float* Y, float* Z, int64_t B, int64_t N, int64_t M, int64_t K,
-                  void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// Does (B, N, M, K) belong to the shape class of the int8 transposed-matmul kernel (blocks of 128 rows of X against
+// many rows of Y, long reduction)?
+bool tbmm_i8_shape(int64_t B, int64_t N, int64_t M, int64_t K) {
+  return N % GI8_TN == 0 && K % GI8_KB == 0 && K >= 2 * GI8_KB && M % GI8_TM == 0 && B <= 65535 && N / GI8_TN <= 65535 &&
+         (M / GI8_TM) * (N / GI8_TN) * B >= 128;
+}
+
+// Does slicing X once, in a kernel of its own, pay?  The extra launch costs 2-3 us; what it saves grows with the number
+// of workgroups that would each slice X (M / 64) and with the length of the reduction.  Measured: 138 -> 128 us at
+// (B,N,M,K) = (1,128,16384,4096), 19.8 -> 22.3 us at (2,256,4096,512).
+bool tbmm_presliced_pays(int64_t B, int64_t N, int64_t M, int64_t K) {
+  return M / GI8_TM >= 128 && K / GI8_KB >= 16 && B * (N / GI8_TN) <= 65535;
+}
+
+// bytes of X sliced once for the int8 kernel: digit records, then inverse scales
+size_t tbmm_ws_bytes(int64_t B, int64_t N, int64_t K) {
+  const int64_t blocks = B * (N / GI8_TN) * (K / GI8_KB);
+  return (size_t)(blocks * (GI8_XD_BYTES + GI8_XINV_BYTES));
+}
+
+tc_status tbmm_run(const float* X, const float* Y, float* Z, int64_t B, int64_t N, int64_t M, int64_t K, void* workspace,
+                   size_t workspace_bytes, void* hip_stream) {
   if (!X || !Y || !Z) return TC_ERR_NULL;
   if (B < 0 || N <= 0 || M <= 0 || K <= 0) return TC_ERR_SHAPE;
   if (Z == X || Z == Y) return TC_ERR_ALIAS;
@@ -523,27 +547,36 @@ tc_status tc_tbmm(const float* X, const float* Y, float* Z, int64_t B, int64_t N
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
   // The paper's largest tmm shape class (blocks of 128 rows against many, long reduction) on the int8 matrix core;
-  // TC355_TBMM_ARITH=f64 keeps it on the fp64 kernels.
-  if (N % GI8_TN == 0 && K % GI8_KB == 0 && K >= 2 * GI8_KB && M % GI8_TM == 0 && B <= 65535 &&
-      N / GI8_TN <= 65535 && (M / GI8_TM) * (N / GI8_TN) * B >= 128) {
-    if (t_opt.int8 != TC_INT8_OFF) {
-      static std::atomic<int> lds_ok{0};  // more than the default 64 KiB of dynamic LDS
-      if (!lds_ok.load(std::memory_order_acquire)) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                GI8_LDS_BYTES) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel<3>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                GI8_LDS_BYTES) != hipSuccess)
-          return TC_ERR_LAUNCH;
-        lds_ok.store(1, std::memory_order_release);
-      }
-      GemmI8Args g{};
-      g.X = X; g.Y = Y; g.Z = Z; g.M = (int)M; g.K = (int)K;
-      const dim3 grid((unsigned)(M / GI8_TM), (unsigned)B, (unsigned)(N / GI8_TN));
-      // 13 digit products unless the caller has said that 10 will do (TC_INT8_TEN)
-      if (t_opt.int8 == TC_INT8_TEN) gemm_i8_kernel<3><<<grid, dim3(GI8_THREADS), GI8_LDS_BYTES, s>>>(g);
-      else gemm_i8_kernel<2><<<grid, dim3(GI8_THREADS), GI8_LDS_BYTES, s>>>(g);
-      return took("tbmm:i8", launch_status());
+  // option TC_INT8_OFF keeps it on the fp64 kernels.
+  if (tbmm_i8_shape(B, N, M, K) && t_opt.int8 != TC_INT8_OFF) {
+    static std::atomic<int> lds_ok{0};  // more than the default 64 KiB of dynamic LDS
+    if (!lds_ok.load(std::memory_order_acquire)) {
+      const void* kernels[4] = {reinterpret_cast<const void*>(gemm_i8_kernel<2, false>), reinterpret_cast<const void*>(gemm_i8_kernel<3, false>),
+                                reinterpret_cast<const void*>(gemm_i8_kernel<2, true>), reinterpret_cast<const void*>(gemm_i8_kernel<3, true>)};
+      for (const void* k : kernels)
+        if (hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, GI8_LDS_BYTES) != hipSuccess) return TC_ERR_LAUNCH;
+      lds_ok.store(1, std::memory_order_release);
     }
+    GemmI8Args g{};
+    g.X = X; g.Y = Y; g.Z = Z; g.M = (int)M; g.K = (int)K;
+    const dim3 grid((unsigned)(M / GI8_TM), (unsigned)B, (unsigned)(N / GI8_TN));
+    const bool ten = t_opt.int8 == TC_INT8_TEN;  // 13 digit products unless the caller has said that 10 will do
+    // With a workspace X is sliced once, by a kernel of its own, instead of by every workgroup that reads it.
+    if (workspace && tbmm_presliced_pays(B, N, M, K) && workspace_bytes >= tbmm_ws_bytes(B, N, K)) {
+      const int64_t rblocks = B * (N / GI8_TN), nb = K / GI8_KB;
+      i4* xd = static_cast<i4*>(workspace);
+      double* xinv = reinterpret_cast<double*>(static_cast<char*>(workspace) + rblocks * nb * GI8_XD_BYTES);
+      gemm_i8_slice_x_kernel<<<dim3((unsigned)nb, (unsigned)rblocks), dim3(GI8_THREADS), 0, s>>>(X, (int)K, xd, xinv);
+      const tc_status st = launch_status();
+      if (st != TC_OK) return st;
+      g.Xd = xd; g.Xinv = xinv;
+      if (ten) gemm_i8_kernel<3, true><<<grid, dim3(GI8_THREADS), GI8_LDS_BYTES, s>>>(g);
+      else gemm_i8_kernel<2, true><<<grid, dim3(GI8_THREADS), GI8_LDS_BYTES, s>>>(g);
+      return took("tbmm:i8_presliced", launch_status());
+    }
+    if (ten) gemm_i8_kernel<3, false><<<grid, dim3(GI8_THREADS), GI8_LDS_BYTES, s>>>(g);
+    else gemm_i8_kernel<2, false><<<grid, dim3(GI8_THREADS), GI8_LDS_BYTES, s>>>(g);
+    return took("tbmm:i8", launch_status());
   }
 
   {
@@ -557,6 +590,28 @@ tc_status tc_tbmm(const float* X, const float* Y, float* Z, int64_t B, int64_t N
   a.N = (int)N; a.M = (int)M; a.K = (int)K;
   const int tm = pick_strip(M, B * ceil_div(N, 16) * ceil_div(M, 16));
   return launch_gemm<float, EPI_NONE>(a, B, tm, s);  // records tbmm:tile, tbmm:splitk or tbmm:wave
+}
+
+}  // namespace
+
+extern "C" {
+
+tc_status tc_tbmm(const float* X, const float* Y, float* Z, int64_t B, int64_t N, int64_t M, int64_t K,
+                  void* hip_stream) {
+  return tbmm_run(X, Y, Z, B, N, M, K, nullptr, 0, hip_stream);
+}
+
+size_t tc_tbmm_workspace_bytes(int64_t B, int64_t N, int64_t M, int64_t K) {
+  if (B <= 0 || N <= 0 || M <= 0 || K <= 0 || B >= kMaxElems || prod_reaches({N, K}, kMaxElems)) return 0;
+  if (!tbmm_i8_shape(B, N, M, K) || !tbmm_presliced_pays(B, N, M, K)) return 0;
+  return tbmm_ws_bytes(B, N, K);
+}
+
+tc_status tc_tbmm_ws(const float* X, const float* Y, float* Z, int64_t B, int64_t N, int64_t M, int64_t K,
+                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (workspace && misaligned(workspace)) return TC_ERR_ALIGN;
+  if (workspace && (workspace == X || workspace == Y || workspace == Z)) return TC_ERR_ALIAS;
+  return tbmm_run(X, Y, Z, B, N, M, K, workspace, workspace_bytes, hip_stream);
 }
 
 size_t tc_mlp_fcrelu_workspace_bytes(int64_t batch, int32_t n_layers, const int64_t* dims) {

@@ -27,7 +27,7 @@ TC_OPT_INT8, TC_OPT_MLP_KERNEL, TC_OPT_MLP_SPIN_LIMIT = 0, 1, 2
 TC_INT8_AUTO, TC_INT8_OFF, TC_INT8_TEN, TC_INT8_THIRTEEN = 0, 1, 2, 3
 TC_MLP_AUTO, TC_MLP_ROWS, TC_MLP_TILES, TC_MLP_PER_LAYER = 0, 1, 2, 3
 
-EXPORTS = ["tc_status_string", "tc355_version", "tc355_set_option", "tc355_get_option", "tc355_last_path", "tc_tbmm", "tc_mlp_fcrelu", "tc_mlp_fcrelu_workspace_bytes",
+EXPORTS = ["tc_status_string", "tc355_version", "tc355_set_option", "tc355_get_option", "tc355_last_path", "tc_tbmm", "tc_tbmm_ws", "tc_tbmm_workspace_bytes", "tc_mlp_fcrelu", "tc_mlp_fcrelu_workspace_bytes",
            "tc_mlp_fcrelu_static",
            "tc_group_conv", "tc_group_conv_infer", "tc_kron", "tc_sconv2d", "tc_sconv2d_infer", "tc_lut"]
 
@@ -58,6 +58,10 @@ def lib() -> ctypes.CDLL:
     L.tc355_last_path.restype = ctypes.c_char_p
     L.tc_tbmm.argtypes = [vp, vp, vp, i64, i64, i64, i64, vp]
     L.tc_tbmm.restype = ctypes.c_int
+    L.tc_tbmm_ws.argtypes = [vp, vp, vp, i64, i64, i64, i64, vp, ctypes.c_size_t, vp]
+    L.tc_tbmm_ws.restype = ctypes.c_int
+    L.tc_tbmm_workspace_bytes.argtypes = [i64, i64, i64, i64]
+    L.tc_tbmm_workspace_bytes.restype = ctypes.c_size_t
     L.tc_mlp_fcrelu.argtypes = [vp, i64, i32, ctypes.POINTER(i64), ctypes.POINTER(vp), ctypes.POINTER(vp),
                                 ctypes.POINTER(vp), vp, ctypes.c_size_t, vp]
     L.tc_mlp_fcrelu.restype = ctypes.c_int
@@ -152,6 +156,22 @@ def tc_tbmm(X, Y, Z, stream=None) -> None:
     if (B, K) != (B2, K2) or tuple(Z.shape) != (B, N, M):
         raise ValueError("tc_tbmm: shapes X %s Y %s Z %s do not fit" % (tuple(X.shape), tuple(Y.shape), tuple(Z.shape)))
     _check(lib().tc_tbmm(_ptr(X, "X"), _ptr(Y, "Y"), _ptr(Z, "Z"), B, N, M, K, _stream(stream)), "tc_tbmm")
+
+
+def tc_tbmm_workspace_bytes(B: int, N: int, M: int, K: int) -> int:
+    return int(lib().tc_tbmm_workspace_bytes(int(B), int(N), int(M), int(K)))
+
+
+def tc_tbmm_ws(X, Y, Z, workspace, stream=None) -> None:
+    """tc_tbmm with a workspace (a uint8 tensor of at least tc_tbmm_workspace_bytes bytes, or None)."""
+    B, N, K = X.shape
+    B2, M, K2 = Y.shape
+    if (B, K) != (B2, K2) or tuple(Z.shape) != (B, N, M):
+        raise ValueError("tc_tbmm_ws: shapes X %s Y %s Z %s do not fit" % (tuple(X.shape), tuple(Y.shape), tuple(Z.shape)))
+    wp = ctypes.c_void_p(workspace.data_ptr()) if workspace is not None else None
+    wn = int(workspace.numel() * workspace.element_size()) if workspace is not None else 0
+    _check(lib().tc_tbmm_ws(_ptr(X, "X"), _ptr(Y, "Y"), _ptr(Z, "Z"), B, N, M, K, wp, ctypes.c_size_t(wn), _stream(stream)),
+           "tc_tbmm_ws")
 
 
 def tc_mlp_fcrelu_workspace_bytes(batch: int, dims) -> int:

@@ -70,6 +70,23 @@ def test_tbmm_validation(L):
     assert L.tc_tbmm(A, B_, C_, 0, 2, 3, 4, None) == 0  # empty batch: nothing to do
 
 
+def test_tbmm_ws_validation_and_workspace_size(L):
+    W_ = 0x80000
+    assert L.tc_tbmm_ws(None, B_, C_, 1, 2, 3, 4, W_, 1 << 20, None) == 1
+    assert L.tc_tbmm_ws(A, B_, C_, 1, 0, 3, 4, W_, 1 << 20, None) == 2
+    assert L.tc_tbmm_ws(A, B_, A, 1, 2, 3, 4, W_, 1 << 20, None) == 3
+    assert L.tc_tbmm_ws(A, B_, C_, 1, 2, 3, 4, W_ + 4, 1 << 20, None) == 4     # misaligned workspace
+    assert L.tc_tbmm_ws(A, B_, C_, 1, 2, 3, 4, C_, 1 << 20, None) == 3         # the workspace is the output
+    assert L.tc_tbmm_ws(A, B_, C_, 0, 2, 3, 4, None, 0, None) == 0             # no workspace, empty batch
+    # the paper's largest transposed matmul (Section 7): 32 reduction blocks x one block of 128 rows of X,
+    # 64 KiB of digit records and 1 KiB of inverse scales each
+    assert L.tc_tbmm_workspace_bytes(1, 128, 16384, 4096) == 32 * (65536 + 1024)
+    assert L.tc_tbmm_workspace_bytes(3, 256, 16384, 2048) == 3 * 2 * 16 * (65536 + 1024)
+    for shape in ((500, 26, 72, 26), (1, 128, 1024, 1024), (1, 128, 256, 32), (0, 128, 16384, 4096), (1, -128, 16384, 4096),
+                  (1, 1 << 40, 1 << 40, 4096)):
+        assert L.tc_tbmm_workspace_bytes(*shape) == 0
+
+
 def test_kron_and_gconv_validation(L):
     assert L.tc_kron(A, B_, C_, None, 1, 2, 2, 2, 2, None) == 1
     assert L.tc_kron(A, B_, C_, 0x40000, 1, 2, 0, 2, 2, None) == 2

@@ -655,6 +655,47 @@ def test_mlp_large_batch_sampled(tc, oracle_threads, mlp_option, fused):
         check(O[l][sel], ref[l], "mlp batch 8192 (fused=%s), layer %d, sampled rows" % (fused, l))
 
 
+def test_tbmm_ws_slices_x_once_and_agrees_bit_for_bit(tc, oracle_threads):
+    """tc_tbmm_ws: with a workspace the int8 transposed matmul reads X's digits from it (same digits, same sums: the
+    result is bit-identical to tc_tbmm's); without one, with too small a one, or for a shape that has no use for it,
+    it is tc_tbmm.  A reduced instance of the paper's largest tmm (Section 7), compared with the oracle in full."""
+    B, N, M, K = 1, 128, 8192, 2048
+    X, Y = inputs.make_tbmm(B, N, M, K, seed=41)
+    ref = oracle.tbmm(X, Y)
+    Xd, Yd = dev(X), dev(Y)
+    need = tc.tc_tbmm_workspace_bytes(B, N, M, K)
+    assert need == (K // 128) * (N // 128) * (65536 + 1024)
+    Z0 = torch.full((B, N, M), float("nan"), device="cuda")
+    tc.tc_tbmm(Xd, Yd, Z0)
+    assert tc.last_path() == "tbmm:i8"
+    check(Z0, ref, "tmm 128x2048x8192, X sliced by every workgroup", TIGHT_I8)
+    ws = torch.randint(0, 255, (need + 64,), dtype=torch.uint8, device="cuda")   # garbage, and a guard band behind it
+    ws[need:] = 77
+    for _ in range(2):
+        Z1 = torch.full((B, N, M), float("nan"), device="cuda")
+        tc.tc_tbmm_ws(Xd, Yd, Z1, ws[:need])
+        assert tc.last_path() == "tbmm:i8_presliced"
+        assert torch.equal(Z0, Z1)
+    assert bool((ws[need:] == 77).all()), "the workspace is not overrun"
+    for w in (None, ws[:need - 16]):
+        Z2 = torch.full((B, N, M), float("nan"), device="cuda")
+        tc.tc_tbmm_ws(Xd, Yd, Z2, w)
+        assert tc.last_path() == "tbmm:i8" and torch.equal(Z0, Z2)
+    with tc.option(tc.TC_OPT_INT8, tc.TC_INT8_TEN):
+        Z3 = torch.full((B, N, M), float("nan"), device="cuda")
+        Z4 = torch.full((B, N, M), float("nan"), device="cuda")
+        tc.tc_tbmm(Xd, Yd, Z3)
+        tc.tc_tbmm_ws(Xd, Yd, Z4, ws[:need])
+        assert tc.last_path() == "tbmm:i8_presliced" and torch.equal(Z3, Z4) and not torch.equal(Z3, Z0)
+    # a shape with no use for a workspace: the argument is ignored
+    assert tc.tc_tbmm_workspace_bytes(500, 26, 72, 26) == 0 and tc.tc_tbmm_workspace_bytes(2, 256, 4096, 512) == 0
+    Xs, Ys = inputs.make_tbmm(8, 26, 72, 26, seed=1)
+    Zs = torch.full((8, 26, 72), float("nan"), device="cuda")
+    tc.tc_tbmm_ws(dev(Xs), dev(Ys), Zs, ws[:need])
+    assert tc.last_path() == "tbmm:lds"
+    check(Zs, oracle.tbmm(Xs, Ys), "tc_tbmm_ws on configuration 1")
+
+
 def test_tmm_largest_paper_shape_sampled(tc, oracle_threads):
     """Section 7, tmm (M,K,N) = (128,4096,16384) through tc_tbmm with B = 1: full size on the GPU, sampled columns in the oracle."""
     rng = np.random.default_rng(77)
@@ -680,6 +721,11 @@ def test_tmm_largest_paper_shape_sampled(tc, oracle_threads):
     err = parity_error(Z.cpu().numpy().astype(np.float64), Z64.cpu().numpy().astype(np.float64))
     print("tmm 128x4096x16384: int8 path against fp64 path, whole output: %.3e" % err, flush=True)
     assert err <= TIGHT_I8
+    # with X sliced once into a workspace: the same digits and sums, bit for bit
+    ws = torch.empty(tc.tc_tbmm_workspace_bytes(1, 128, 16384, 4096), dtype=torch.uint8, device="cuda")
+    Zw = torch.full((1, 128, 16384), float("nan"), device="cuda")
+    tc.tc_tbmm_ws(dev(X), dev(Y), Zw, ws)
+    assert tc.last_path() == "tbmm:i8_presliced" and torch.equal(Z, Zw)
 
 
 @pytest.mark.parametrize("shape", [
