@@ -157,12 +157,16 @@ __device__ __forceinline__ f4 mr_read(const char* slice, const MrPlace& c, int l
 // `slice1`) and double for the workspace copy of the previous layer (read in place).  The first tile's weights are
 // on their way into `slice0`; the second tile's into `slice1` (layer 0: requested here, once the input has been
 // read out of it).  `part`: the LDS area for the partial tiles; the caller separates layers by a barrier.
-template <typename TA>
-__device__ __forceinline__ void mr_layer(const MlpRowsArgs& p, const MrPlace& c, int l, const TA* __restrict__ Ain,
-                                         char* slice0, char* slice1, d4* part, unsigned* flags_out,
-                                         const unsigned long long* tokp, bool& token_seen) {
-  const int K = p.dims[l], M = p.dims[l + 1];
-  const int CT = (M + 15) >> 4, ks = K >> 3, nj = ks >> 4, lp = mr_log2_pieces(K);
+// NJ = K / 128 (1, 2, 4 or 8) is a template parameter: with the trip counts known the compiler can count the
+// outstanding loads (behind a branch on a run-time count it waits for all of them before the first use of any).
+template <typename TA, int NJ>
+__device__ __forceinline__ void mr_layer_n(const MlpRowsArgs& p, const MrPlace& c, int l, const TA* __restrict__ Ain,
+                                           char* slice0, char* slice1, d4* part, unsigned* flags_out,
+                                           const unsigned long long* tokp, bool& token_seen) {
+  constexpr int K = 128 * NJ, ks = K >> 3, nj = NJ, lp = NJ == 1 ? 2 : NJ == 2 ? 3 : NJ == 4 ? 4 : 5;
+  static_assert(NJ == 1 || NJ == 2 || NJ == 4 || NJ == 8, "reduction extents 128, 256, 512, 1024");
+  const int M = p.dims[l + 1];
+  const int CT = (M + 15) >> 4;
   if (c.rank >= CT) return;  // uniform: no tile in this layer
   const bool two = c.rank + c.gsize < CT;  // uniform: a second tile
   const int rows = min(16, p.batch - 16 * c.g);  // rows of this row tile inside the batch
@@ -274,6 +278,18 @@ __device__ __forceinline__ void mr_layer(const MlpRowsArgs& p, const MrPlace& c,
         __hip_atomic_store(flags_out + 4 * (c.rank + fin_t * c.gsize) + (c.wave & 3), 1u, __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
     }
+  }
+}
+
+template <typename TA>
+__device__ __forceinline__ void mr_layer(const MlpRowsArgs& p, const MrPlace& c, int l, const TA* __restrict__ Ain,
+                                         char* slice0, char* slice1, d4* part, unsigned* flags_out,
+                                         const unsigned long long* tokp, bool& token_seen) {
+  switch (p.dims[l] >> 7) {  // uniform
+    case 1: mr_layer_n<TA, 1>(p, c, l, Ain, slice0, slice1, part, flags_out, tokp, token_seen); break;
+    case 2: mr_layer_n<TA, 2>(p, c, l, Ain, slice0, slice1, part, flags_out, tokp, token_seen); break;
+    case 4: mr_layer_n<TA, 4>(p, c, l, Ain, slice0, slice1, part, flags_out, tokp, token_seen); break;
+    default: mr_layer_n<TA, 8>(p, c, l, Ain, slice0, slice1, part, flags_out, tokp, token_seen); break;
   }
 }
 
