@@ -371,7 +371,7 @@ __global__ __launch_bounds__(MR_THREADS, 1) void mlp_rows_kernel(MlpRowsArgs p) 
         }
         if (!ok && c.lane == 0) __hip_atomic_store(p.sync + MLP_SYNC_ERROR, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
-      token_seen = true;  // (for the other wavefronts: by the barrier below)
+      if (c.rank < ((p.dims[l + 1] + 15) >> 4)) token_seen = true;  // (for the other wavefronts: by the barrier below)
       __syncthreads();
       mr_layer<double>(p, c, l, p.act[l - 1], slice0, slice1, part, fout, tokp, token_seen);
     }
@@ -387,7 +387,20 @@ __global__ __launch_bounds__(MR_THREADS, 1) void mlp_rows_kernel(MlpRowsArgs p) 
 
   // The last workgroup out withdraws the token: a replay of a captured HIP graph launches this kernel again with
   // the SAME token, and must again wait for workgroup 0 to zero the flags.
+  // Nobody counts itself out before it has seen the token: workgroup 0 zeroes the counter before it publishes the
+  // token, and a workgroup with nothing to do would otherwise get here first and have its count wiped (the token
+  // would then survive the launch, and a replay would trust flags that workgroup 0 is about to zero).
   if (chained && tid == 0) {
+    if (!token_seen) {
+      unsigned spins = 0;
+      while (__hip_atomic_load(tokp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != p.token) {
+        __builtin_amdgcn_s_sleep(8);
+        if (++spins >= p.spin_limit) {
+          __hip_atomic_store(p.sync + MLP_SYNC_ERROR, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          break;
+        }
+      }
+    }
     const unsigned old = __hip_atomic_fetch_add(p.sync + MLP_SYNC_EXIT, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (old == (unsigned)nwg - 1) __hip_atomic_store(tokp, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }

@@ -575,6 +575,34 @@ def test_outputs_need_no_zeroing_and_calls_repeat(tc, oracle_threads):
 
 
 # ---------------------------------------------------------------- HIP graph capture
+def test_mlp_replays_when_most_workgroups_have_nothing_to_do(tc, oracle_threads):
+    """Batch 16 through widths of 128: 8 of the row-tile kernel's 256 workgroups have a tile, the others leave at
+    once.  None of them may count itself out before workgroup 0 has zeroed the exit counter, or the call's token
+    outlives the launch and a replay (same token) trusts flags that are about to be zeroed.  Twenty replays of a graph
+    of several launches, into a workspace that starts as garbage; every replay checked; the error word stays clear."""
+    batch, dims = 16, (128, 128, 128, 128)
+    I, Ws, bs = inputs.make_mlp(batch, dims, seed=61, w_std=0.1)
+    ref = oracle.mlp_fcrelu(I, Ws, bs)
+    Id, Wd, bd = dev(I), [dev(w) for w in Ws], [dev(b) for b in bs]
+    O = [torch.empty((batch, d), device="cuda") for d in dims[1:]]
+    ws = torch.randint(0, 255, (tc.tc_mlp_fcrelu_workspace_bytes(batch, dims),), dtype=torch.uint8, device="cuda")
+    tc.tc_mlp_fcrelu(Id, Wd, bd, O, ws)
+    assert tc.last_path() == "mlp:rows"
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(4):
+            tc.tc_mlp_fcrelu(Id, Wd, bd, O, ws)
+    for rep in range(20):
+        for o in O:
+            o.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        assert int(ws[:256].view(torch.int32)[33]) == 0, "a bounded wait gave up in replay %d" % rep
+        for l in range(3):
+            assert parity_error(O[l].cpu().numpy().astype(np.float64), ref[l]) <= TIGHT, (rep, l)
+
+
 def test_all_entry_points_replay_from_a_hip_graph(tc, oracle_threads):
     # The library enqueues kernels only (no memset, no allocation), so a step can be captured once and
     # replayed.  Replays are interleaved with eager work and synchronisations, and every replay is
