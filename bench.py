@@ -302,6 +302,9 @@ def main():
             "frac": round(roof_us / cold_us, 4),       # against inputs that come from HBM
             "frac_warm": round(roof_us / us, 4),       # inputs in the Infinity Cache
             "frac_vs_f32_mfma_or_hbm": round(max(flops / (PEAK_F32_MFMA_TFLOPS * 1e12), t_hbm) * 1e6 / cold_us, 4),
+            # (roofline time + the time of the smallest launch the library makes) / cold time: what the kernel itself
+            # leaves on the table once the launch, which no kernel can shorten, is granted
+            "frac_launch_floor_aware": round((roof_us + float(floor.mean())) / cold_us, 4),
         }
     launch_floor = pcts(floor)
 
