@@ -724,6 +724,37 @@ def test_tbmm_ws_slices_x_once_and_agrees_bit_for_bit(tc, oracle_threads):
     check(Zs, oracle.tbmm(Xs, Ys), "tc_tbmm_ws on configuration 1")
 
 
+def test_tbmm_ws_with_several_blocks_of_rows_and_batches(tc, oracle_threads):
+    """The pre-sliced path with B = 2 and N = 256: four blocks of 128 rows of X, each with its own digit records and
+    inverse scales in the workspace.  Bit-identical to tc_tbmm; sampled columns against the oracle."""
+    B, N, M, K = 2, 256, 8192, 2048
+    rng = np.random.default_rng(52)
+    X = rng.standard_normal((B, N, K)).astype(np.float32)
+    Y = rng.standard_normal((B, M, K)).astype(np.float32)
+    X[1, 130] *= 1e6      # rows of very different scale in different blocks
+    X[0, 7, 256:384] = 0  # an all-zero (row, k block)
+    Xd, Yd = dev(X), dev(Y)
+    need = tc.tc_tbmm_workspace_bytes(B, N, M, K)
+    assert need == 2 * 2 * 16 * (65536 + 1024)
+    ws = torch.randint(0, 255, (need,), dtype=torch.uint8, device="cuda")
+    Z0 = torch.full((B, N, M), float("nan"), device="cuda")
+    Z1 = torch.full((B, N, M), float("nan"), device="cuda")
+    tc.tc_tbmm(Xd, Yd, Z0)
+    assert tc.last_path() == "tbmm:i8"
+    tc.tc_tbmm_ws(Xd, Yd, Z1, ws)
+    assert tc.last_path() == "tbmm:i8_presliced"
+    assert torch.equal(Z0, Z1)
+    pick = np.sort(rng.choice(M, size=48, replace=False))
+    pick[:3] = [0, 63, 64]
+    pick[-1] = M - 1
+    ref = oracle.tbmm(X, np.ascontiguousarray(Y[:, pick]))
+    got = Z1[:, :, torch.from_numpy(pick).cuda()].cpu().numpy().astype(np.float64)
+    # row 130 of batch 1 is 10^6 times the others: every row on its own scale
+    worst = max(parity_error(got[b, n], ref[b, n]) for b in range(B) for n in range(N))
+    print("tbmm_ws (2,256,8192,2048), 48 sampled columns, worst row: %.3e" % worst, flush=True)
+    assert worst <= TIGHT_I8
+
+
 def test_tmm_largest_paper_shape_sampled(tc, oracle_threads):
     """Section 7, tmm (M,K,N) = (128,4096,16384) through tc_tbmm with B = 1: full size on the GPU, sampled columns in the oracle."""
     rng = np.random.default_rng(77)
