@@ -4,23 +4,30 @@
 //
 //   O_l(b,n) = max(0, bias_l(n) + sum_m In_l(b,m) * W_l(n,m)),   In_{l+1} = O_l
 //
-// Row b of O_{l+1} needs row b of O_l and nothing else of it.  So the batch is
-// cut into tiles of 16 rows and a GROUP of workgroups takes one row tile through
-// ALL layers: only the workgroups of a group ever exchange activations, and only
-// they wait for each other between layers.  Workgroup w belongs to group
-// w % groups; with 8 row tiles on an 8-XCD chip, whose dispatcher deals
-// workgroups to the XCDs in turn (measured: workgroup w runs on XCD w % 8), a
-// group is one XCD: the activations never leave that XCD's L2 and a wait
-// involves 32 workgroups instead of 256.  (Nothing depends on that placement
-// for correctness: data is exchanged with agent-scope write-through stores,
-// agent-scope loads and flags, wherever the workgroups run.)  The price: every
-// group reads every weight once, 8 x 6.8 MB for the benchmark instead of 1 x --
-// but weights depend on no activation, so they are requested a whole wait ahead.
+// The launch is one workgroup per compute unit, all resident, and a layer's
+// 16 x 16 output tiles (row tile = 16 rows of the batch, column tile = 16
+// output features) are dealt out so that the WEIGHTS cross the chip's fabric
+// once.  The chip is 8 XCDs, each with its own L2 behind a port of about
+// 1 TB/s, and the dispatcher deals workgroups to them in turn (measured:
+// workgroup w runs on XCD w % 8).  Workgroup w therefore belongs to share
+// x = w % 8, and share x owns the column tiles x, x + 8, x + 16, .. of EVERY
+// layer, for all row tiles: an XCD pulls one eighth of every weight matrix
+// (0.9 MB of the benchmark's 7.3 MB) instead of all of it.  (With one row tile
+// per XCD, each XCD pulled every weight; at the port's rate that was 3 us of
+// the first layer alone: the same kernel made to fetch only 8 distinct weight
+// tiles per XCD, wrong results and all, ran 2.9 us faster.)  What crosses XCDs instead is the
+// activations, 1 MB per layer boundary and XCD, served from the producers'
+// write-through stores.  (Nothing depends on the placement for correctness:
+// all exchange is by agent-scope stores, loads and flags.)
 //
-// One workgroup = 8 wavefronts on one compute unit.  In layer l it owns the
-// column tiles rank, rank + gsize (at most 2) of its row tile; its 8 wavefronts
-// split the reduction into 8 contiguous slices of K/8 elements.  Operands reach
-// the matrix core like this:
+// Inside a share the R = gridDim / 8 workgroups take (column tile, row tile)
+// jobs: one job each while there are at most R of them (later layers of the
+// benchmark), else one column tile with a PAIR of row tiles -- one weight tile
+// against two sets of activations, one after the other (first layer).  The
+// host checks that a layer never has more than R pairs per share.
+//
+// One workgroup = 8 wavefronts that split the reduction into 8 contiguous
+// slices of K/8 elements.  Operands reach the matrix core like this:
 //  - weights (and the caller's fp32 input): a wavefront brings its slice of a
 //    16-row tile from global memory STRAIGHT INTO LDS (global_load_lds, 16 bytes
 //    per lane, 1 KiB of whole row pieces per instruction: no registers, no LDS
@@ -30,7 +37,10 @@
 //    the image is conflict-free for the reads: piece p of row r sits in slot
 //    p ^ (r mod pieces) of the row.  A lane then reads row r16, pieces 4j + q,
 //    whose elements e = 0..3 feed MFMA step (j, e).  A slice is private to its
-//    wavefront, so no wavefront waits for another inside a layer;
+//    wavefront, so no wavefront waits for another inside a layer.  The weight
+//    tile is read out of LDS into registers once and serves both row tiles of
+//    a pair; the second row tile's input follows the first one's through the
+//    same LDS slice;
 //  - activations between layers: the workspace copy is the library's own, so it
 //    is WRITTEN in the layout the next layer reads: [row tile][feature][row]
 //    doubles.  A lane's operand for step (j, e) is one 8-byte load, and the 16
@@ -38,28 +48,29 @@
 //    dependent path.  These loads are agent-scope loads (they never take a stale
 //    line from a cache), so the wait needs no cache invalidation: an invalidation
 //    by all workgroups at once was measured at 1.7 us per layer boundary.
-// The weights of layer l+1 are requested as soon as layer l has issued its
-// stores and travel during the group's wait.  The 8 partial tiles are combined
-// through LDS in a fixed order, bias first (the listing's first statement);
-// clamp in fp64; O_l leaves as fp32 (if the caller wants it) and as fp64 into
-// the workspace.  No activation is rounded before it is consumed.
+// The weight tile of layer l+1 is requested as soon as layer l has issued its
+// stores and flags and travels during the hand-over.
+// The 8 partial tiles are combined through LDS in a fixed order, bias first
+// (the listing's first statement); clamp in fp64; O_l leaves as fp32 (if the
+// caller wants it) and as fp64 into the workspace.  No activation is rounded
+// before it is consumed.
 //
 // Hand-over between layers, without any read-modify-write and without a
 // producer-side workgroup barrier: the wavefront that has written 4 columns of
 // a tile of O_l (16 rows, into the workspace) waits for its own stores to be
-// acknowledged and then sets the flag word of those 4 columns; in the next
-// layer one wavefront per workgroup polls the K/4 flag words of its row tile
-// (at most 256: two 8-byte loads per lane, in flight together) while the
-// others wait at the workgroup barrier.  Flags only ever go from 0 to 1: workgroup 0 zeroes them
-// and then publishes the call's 64-bit token; nobody writes or trusts a flag
-// before it has seen that token (requested while the first layer's operands
-// arrive, checked before the first flag is written or read); the last
+// acknowledged and then sets the flag word of those 4 columns of that row
+// tile; in the next layer one wavefront per workgroup polls the K/4 flag words
+// of each row tile it consumes (two 8-byte loads per lane, in flight together)
+// while the others wait at the workgroup barrier.  Flags only ever go from 0
+// to 1: workgroup 0 zeroes them and then publishes the call's 64-bit token;
+// nobody writes or trusts a flag before it has seen that token; the last
 // workgroup out withdraws it, so a replayed HIP graph (same token) starts
 // clean.  Every spin is bounded: on expiry the error word is raised and the
 // wavefront goes on, so the grid always drains.
 //
 // Requirements (checked by the host): every reduction extent one of 128, 256,
-// 512, 1024; at most 2 column tiles per workgroup in every layer.
+// 512, 1024; gridDim a multiple of 8; at most gridDim / 8 pairs per share in
+// every layer; the flag words fit the sync area.
 #pragma once
 #include "mlp_fused.hpp"
 #include "tc355_device.hpp"
@@ -68,20 +79,17 @@ namespace tc355 {
 
 constexpr int MR_WAVES = 8;
 constexpr int MR_THREADS = MR_WAVES * WAVE;
-constexpr int MR_MAXT = 2;    // column tiles per workgroup and layer
-constexpr int MR_MAXJ = 8;    // 16-element pieces of a wavefront's reduction slice (K / 8 / 16)
+constexpr int MR_SHARES = 8;  // shares of the column tiles (= XCDs of the chip)
+constexpr int MR_MAXT = 2;    // row tiles per workgroup and layer
+constexpr int MR_MAXJ = 8;    // 16-element groups of a wavefront's reduction slice (K / 8 / 16)
 constexpr int MR_MAX_WG = 256;
 constexpr int MR_SLICE_BYTES = 16 * 128 * 4;                  // a wavefront's slice of a tile: 16 rows x (1024 / 8) fp32
 constexpr int MR_AREA_BYTES = MR_WAVES * MR_SLICE_BYTES;       // one 16-row tile of up to 1024 fp32: 64 KiB
 constexpr int MR_PART_BYTES = MR_WAVES * MR_MAXT * WAVE * 32;  // the partial tiles
-constexpr int MR_LDS_BYTES = MR_MAXT * MR_AREA_BYTES + MR_PART_BYTES;  // 160 KiB: one workgroup per compute unit
+constexpr int MR_LDS_BYTES = 2 * MR_AREA_BYTES + MR_PART_BYTES;  // 160 KiB: one workgroup per compute unit
 // flags live behind the header of the sync area: one 32-bit word per 4 output columns of a row tile,
-// [boundary][group][column / 4], with room for MR_MAXT tiles per workgroup
+// [boundary][row tile][column / 4], `fstride` words per (boundary, row tile)
 constexpr int MR_FLAG_WORD0 = MLP_SYNC_WORDS;
-// words of flags that a chain needs (the host checks that they fit the sync area)
-inline int64_t mr_flag_words(int n_layers, int64_t groups, int64_t nwg) {
-  return (int64_t)(n_layers - 1) * groups * 4 * MR_MAXT * ((nwg + groups - 1) / groups);
-}
 
 struct MlpRowsArgs {
   const float* I;
@@ -94,14 +102,45 @@ struct MlpRowsArgs {
   int dims[MLP_MAX_LAYERS + 1];
   int batch;
   int n_layers;
-  int groups;  // number of 16-row tiles of the batch
+  int groups;   // number of 16-row tiles of the batch
+  int fstride;  // flag words per (boundary, row tile): 4 x the most column tiles of any layer but the last
   unsigned spin_limit;
 };
 
+// Host and device: how a layer with CT column tiles and RT row tiles is dealt out inside a share of R workgroups.
+// Single jobs while they fit, else pairs of row tiles; `fits` is false if even the pairs do not.
+struct MrDeal {
+  int per_ct;  // workgroups per column tile of the share (= row tiles, or pairs of them)
+  int nrt;     // row tiles per workgroup: 1 or 2
+  bool fits;
+};
+__host__ __device__ inline MrDeal mr_deal(int CT, int RT, int R) {
+  const int max_nct = (CT + MR_SHARES - 1) / MR_SHARES, RP = (RT + 1) / 2;
+  MrDeal d;
+  if (max_nct * RT <= R) { d.per_ct = RT; d.nrt = 1; d.fits = true; }
+  else { d.per_ct = RP; d.nrt = 2; d.fits = max_nct * RP <= R; }
+  return d;
+}
+
 struct MrPlace {
   int lane, wave, r16, q;
-  int g, rank, gsize;  // group (= row tile), this workgroup's number in it, workgroups in it
+  int share, rank, R;  // share of the column tiles (w % 8), this workgroup's number in it, workgroups in it
 };
+
+// This workgroup's job in a layer: column tile ct, row tiles rt0 .. rt0 + nrt - 1 (nrt = 0: none).
+struct MrJob {
+  int ct, rt0, nrt;
+};
+__device__ __forceinline__ MrJob mr_job(const MrPlace& c, int M, int RT) {
+  const int CT = (M + 15) >> 4;
+  const MrDeal d = mr_deal(CT, RT, c.R);
+  const int i = c.rank / d.per_ct, u = c.rank - i * d.per_ct;
+  MrJob j;
+  j.ct = c.share + MR_SHARES * i;
+  j.rt0 = d.nrt * u;
+  j.nrt = j.ct < CT ? max(0, min(d.nrt, RT - j.rt0)) : 0;
+  return j;
+}
 
 // Index (in doubles) of activation (row r of the tile, feature n) in the workspace copy of a layer of width M.
 __device__ __forceinline__ size_t mr_act_index(int rt, int M, int r, int n) { return ((size_t)rt * M + n) * 16 + r; }
@@ -153,97 +192,122 @@ __device__ __forceinline__ f4 mr_read(const char* slice, const MrPlace& c, int l
   return *reinterpret_cast<const f4*>(slice + 16 * slot);
 }
 
-// One layer's share of this workgroup.  TA is float for the caller's input (its slice is already on its way into
-// `slice1`) and double for the workspace copy of the previous layer (read in place).  The first tile's weights are
-// on their way into `slice0`; the second tile's into `slice1` (layer 0: requested here, once the input has been
-// read out of it).  `part`: the LDS area for the partial tiles; the caller separates layers by a barrier.
-// NJ = K / 128 (1, 2, 4 or 8) is a template parameter: with the trip counts known the compiler can count the
-// outstanding loads (behind a branch on a run-time count it waits for all of them before the first use of any).
+// Workgroup 0 of a chained call: this call's flags start at zero; then the token says so.
+__device__ __forceinline__ void mr_publish_token(const MlpRowsArgs& p, unsigned long long* tokp) {
+  const int tid = threadIdx.x;
+  unsigned* fw = p.sync + MR_FLAG_WORD0;
+  const int nwords = (p.n_layers - 1) * p.groups * p.fstride;
+  for (int i = tid; i < nwords; i += MR_THREADS) __hip_atomic_store(fw + i, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (tid == 0) {
+    __hip_atomic_store(p.sync + MLP_SYNC_EXIT, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p.sync + MLP_SYNC_ERROR, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  // every wavefront's zeroes are acknowledged (a plain wait for everything: the operand requests count too) ...
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();  // ... before the token goes out.  (Relaxed: the zeroes are write-through stores that have been
+  // acknowledged; a release here would write back this XCD's whole L2.)
+  if (tid == 0) __hip_atomic_store(tokp, p.token, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// One layer's share of this workgroup: job `jb` (nrt >= 1).  TA is float for the caller's input and double for the
+// workspace copy of the previous layer.  `slice`: this wavefront's LDS slice of the layer's weight tile, already
+// requested; `ain`: its LDS slice for the input rows (layer 0 only).  `part`: the LDS area for the partial tiles; the
+// caller separates layers by a barrier.  NJ = K / 128 is a template parameter: with the trip counts known the
+// compiler can count the outstanding loads (behind a branch on a run-time count it waits for all of them before the
+// first use of any).
 template <typename TA, int NJ>
-__device__ __forceinline__ void mr_layer_n(const MlpRowsArgs& p, const MrPlace& c, int l, const TA* __restrict__ Ain,
-                                           char* slice0, char* slice1, d4* part, unsigned* flags_out,
-                                           const unsigned long long* tokp, bool& token_seen) {
-  constexpr int K = 128 * NJ, ks = K >> 3, nj = NJ, lp = NJ == 1 ? 2 : NJ == 2 ? 3 : NJ == 4 ? 4 : 5;
+__device__ __forceinline__ void mr_layer_n(const MlpRowsArgs& p, const MrPlace& c, int l, const MrJob jb,
+                                           const TA* __restrict__ Ain, char* slice, char* ain, d4* part,
+                                           unsigned long long* tokp, bool& token_seen) {
+  constexpr int K = 128 * NJ, ks = K >> 3;
   static_assert(NJ == 1 || NJ == 2 || NJ == 4 || NJ == 8, "reduction extents 128, 256, 512, 1024");
   const int M = p.dims[l + 1];
-  const int CT = (M + 15) >> 4;
-  if (c.rank >= CT) return;  // uniform: no tile in this layer
-  const bool two = c.rank + c.gsize < CT;  // uniform: a second tile
-  const int rows = min(16, p.batch - 16 * c.g);  // rows of this row tile inside the batch
+  const bool two = jb.nrt == 2;  // uniform
+  const bool chain = l + 1 < p.n_layers;
 
-  // ---- activations of this wavefront's slice as MFMA A operands: a[j].e[e] = In[row r16][slice + 16j + 4q + e]
-  unsigned long long tok_early = 0;
-  Vec<TA, 4> a[MR_MAXJ];
-  if constexpr (sizeof(TA) == 4) {
-    mr_wait_vm(0);  // the input slice (and the first tile's weights) have landed in LDS
-    // by now workgroup 0 has long published the token: requested here, looked at after the contraction
-    if (p.n_layers > 1) tok_early = __hip_atomic_load(tokp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-    for (int j = 0; j < MR_MAXJ; j++) {
-      if (j < nj) {
-        const f4 t = mr_read(slice1, c, lp, j);
-        a[j].e[0] = t[0]; a[j].e[1] = t[1]; a[j].e[2] = t[2]; a[j].e[3] = t[3];
-      }
-    }
-  } else {
-    const double* src = Ain + mr_act_index(c.g, K, min(c.r16, rows - 1), c.wave * ks + 4 * c.q);
-#pragma unroll
-    for (int j = 0; j < MR_MAXJ; j++) {
-      if (j < nj) {
-#pragma unroll
-        for (int e = 0; e < 4; e++)
-          a[j].e[e] = __hip_atomic_load(src + (size_t)(16 * j + e) * 16, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-    }
-    mr_wait_vm(4 * nj);  // everything older than these 4 nj loads is done: the weights have landed in LDS
-  }
-  // the bias of this thread's output element (used after the contraction; requested now)
+  // the bias of this thread's output element (used after the contraction; requested first, lands first).
+  // Threads 0..255 finish row tile rt0, threads 256..511 row tile rt0 + 1; thread i of a tile owns the element at
+  // position i of the tile's 2 KiB block in the workspace layout, so those stores are contiguous.
   const int fin_t = c.wave >> 2, fin_i = (c.wave & 3) * WAVE + c.lane;
-  const int fin_r = fin_i & 15, fin_c = fin_i >> 4;  // row and column inside the tile: the workspace block's order
-  const int fin_col = 16 * (c.rank + fin_t * c.gsize) + fin_c;
+  const int fin_r = fin_i & 15, fin_c = fin_i >> 4;
+  const int fin_col = 16 * jb.ct + fin_c;
   const float bias_v = p.bias[l][min(fin_col, M - 1)];
 
-  // ---- first tile: its weights into registers, then (layer 0) the second tile's weights are requested into the
-  // slice that held the input, and travel while the first tile is contracted
-  f4 b[MR_MAXJ];
-#pragma unroll
-  for (int j = 0; j < MR_MAXJ; j++)
-    if (j < nj) b[j] = mr_read(slice0, c, lp, j);
-  if constexpr (sizeof(TA) == 4) {
-    if (two) {
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the input has been read out of slice1
-      mr_fetch(p.W[l], K, 16 * (c.rank + c.gsize), M - 1, c, slice1);
-    }
-  }
+  unsigned long long tok_early = 0;
   d4 acc0 = d4_zero(), acc1 = d4_zero();
+  constexpr int lp = NJ == 1 ? 2 : NJ == 2 ? 3 : NJ == 4 ? 4 : 5;
+  f4 b[NJ];  // this layer's weight tile, read out of LDS once and used for both row tiles
+  if constexpr (sizeof(TA) == 4) {
+    // ---- layer 0: the kernel's first instructions requested the input slice of row tile rt0 (into `ain`) and the
+    // weight tile (into `slice`).  With a second row tile, its input slice is requested into `ain` as soon as the
+    // first one has been read out of it, and travels while the first tile is contracted.
+    mr_wait_vm(0);
+    // by now workgroup 0 has long published the token: requested here, looked at after the contraction
+    if (chain) tok_early = __hip_atomic_load(tokp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    f4 a[NJ];
 #pragma unroll
-  for (int j = 0; j < MR_MAXJ; j++) {
-    if (j < nj) {
+    for (int j = 0; j < NJ; j++) a[j] = mr_read(ain, c, lp, j);
 #pragma unroll
-      for (int e = 0; e < 4; e++) acc0 = mfma_f64((double)a[j].e[e], (double)b[j][e], acc0);
+    for (int j = 0; j < NJ; j++) b[j] = mr_read(slice, c, lp, j);
+    if (two) {
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the first input slice has been read out
+      mr_fetch(Ain, K, 16 * (jb.rt0 + 1), p.batch - 1, c, ain);
+    }
+#pragma unroll
+    for (int j = 0; j < NJ; j++)
+#pragma unroll
+      for (int e = 0; e < 4; e++) acc0 = mfma_f64((double)a[j][e], (double)b[j][e], acc0);
+    if (two) {
+      mr_wait_vm(0);  // the second row tile's input, requested above, has landed
+#pragma unroll
+      for (int j = 0; j < NJ; j++) a[j] = mr_read(ain, c, lp, j);
+#pragma unroll
+      for (int j = 0; j < NJ; j++)
+#pragma unroll
+        for (int e = 0; e < 4; e++) acc1 = mfma_f64((double)a[j][e], (double)b[j][e], acc1);
+    }
+  } else {
+    // ---- later layers: the activations of this wavefront's slice come from the workspace copy, already in MFMA
+    // layout (a[j][e] = In[row r16][slice + 16 j + 4 q + e], agent-scope loads: never a stale line from a cache); the
+    // weight tile was requested a hand-over ago
+    double a[NJ][4];
+    {
+      const int rows0 = min(16, p.batch - 16 * jb.rt0);
+      const double* s0 = Ain + mr_act_index(jb.rt0, K, min(c.r16, rows0 - 1), c.wave * ks + 4 * c.q);
+#pragma unroll
+      for (int j = 0; j < NJ; j++)
+#pragma unroll
+        for (int e = 0; e < 4; e++)
+          a[j][e] = __hip_atomic_load(s0 + (size_t)(16 * j + e) * 16, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    mr_wait_vm(4 * NJ);  // everything older than these 4 nj loads is done: the weights have landed in LDS
+#pragma unroll
+    for (int j = 0; j < NJ; j++) b[j] = mr_read(slice, c, lp, j);
+#pragma unroll
+    for (int j = 0; j < NJ; j++)
+#pragma unroll
+      for (int e = 0; e < 4; e++) acc0 = mfma_f64(a[j][e], (double)b[j][e], acc0);
+    if (two) {
+      const int rows1 = min(16, p.batch - 16 * (jb.rt0 + 1));
+      const double* s1 = Ain + mr_act_index(jb.rt0 + 1, K, min(c.r16, rows1 - 1), c.wave * ks + 4 * c.q);
+#pragma unroll
+      for (int j = 0; j < NJ; j++)
+#pragma unroll
+        for (int e = 0; e < 4; e++)
+          a[j][e] = __hip_atomic_load(s1 + (size_t)(16 * j + e) * 16, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+      for (int j = 0; j < NJ; j++)
+#pragma unroll
+        for (int e = 0; e < 4; e++) acc1 = mfma_f64(a[j][e], (double)b[j][e], acc1);
     }
   }
   part[(c.wave * MR_MAXT + 0) * WAVE + c.lane] = acc0;
-  if (two) {
-    if constexpr (sizeof(TA) == 4) mr_wait_vm(0);  // the second tile's weights, requested above, have landed
-#pragma unroll
-    for (int j = 0; j < MR_MAXJ; j++)
-      if (j < nj) b[j] = mr_read(slice1, c, lp, j);
-#pragma unroll
-    for (int j = 0; j < MR_MAXJ; j++) {
-      if (j < nj) {
-#pragma unroll
-        for (int e = 0; e < 4; e++) acc1 = mfma_f64((double)a[j].e[e], (double)b[j][e], acc1);
-      }
-    }
-    part[(c.wave * MR_MAXT + 1) * WAVE + c.lane] = acc1;
-  }
+  if (two) part[(c.wave * MR_MAXT + 1) * WAVE + c.lane] = acc1;
   __syncthreads();
 
-  // ---- finish: threads 0..255 take tile 0, threads 256..511 tile 1.  Thread i of a tile owns the element that sits
-  // at position i of the tile's 2 KiB block in the workspace layout, so those stores are contiguous.
-  const bool fin = fin_t == 0 || two;  // uniform per wavefront
-  double x = (double)bias_v;  // bias first (the listing's first statement), then a fixed order
+  // ---- finish
+  const bool fin = fin_t < jb.nrt;  // uniform per wavefront
+  double x = (double)bias_v;        // bias first (the listing's first statement), then a fixed order
   if (fin) {
     const int dl = fin_c + 16 * (fin_r & 3), dv = fin_r >> 2;  // where the MFMA result layout keeps it: lane, element
 #pragma unroll
@@ -252,12 +316,12 @@ __device__ __forceinline__ void mr_layer_n(const MlpRowsArgs& p, const MrPlace& 
   }
   __syncthreads();  // the partial tiles have been read: the next layer may overwrite them
   if (fin) {
-    const int row = 16 * c.g + fin_r;
+    const int rt = jb.rt0 + fin_t, row = 16 * rt + fin_r;
     if (row < p.batch && fin_col < M) {
-      if (l + 1 < p.n_layers) act_store(p.act[l] + mr_act_index(c.g, M, fin_r, fin_col), x);
+      if (chain) act_store(p.act[l] + mr_act_index(rt, M, fin_r, fin_col), x);
       if (p.O[l]) p.O[l][(size_t)row * M + fin_col] = (float)x;
     }
-    if (l + 1 < p.n_layers) {
+    if (chain) {
       // This wavefront has just written columns 4u .. 4u+3 (u = wave % 4) of its tile, all 16 rows.  Once its stores
       // are acknowledged (neither a fence of workgroup scope nor a workgroup barrier waits for outstanding global
       // stores on this target), their flag goes out.
@@ -274,22 +338,22 @@ __device__ __forceinline__ void mr_layer_n(const MlpRowsArgs& p, const MrPlace& 
         }
         token_seen = true;
       }
+      unsigned* flags_out = p.sync + MR_FLAG_WORD0 + ((size_t)l * p.groups + rt) * p.fstride;
       if (c.lane == 0)
-        __hip_atomic_store(flags_out + 4 * (c.rank + fin_t * c.gsize) + (c.wave & 3), 1u, __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(flags_out + 4 * jb.ct + (c.wave & 3), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
 }
 
 template <typename TA>
-__device__ __forceinline__ void mr_layer(const MlpRowsArgs& p, const MrPlace& c, int l, const TA* __restrict__ Ain,
-                                         char* slice0, char* slice1, d4* part, unsigned* flags_out,
-                                         const unsigned long long* tokp, bool& token_seen) {
+__device__ __forceinline__ void mr_layer(const MlpRowsArgs& p, const MrPlace& c, int l, const MrJob jb,
+                                         const TA* __restrict__ Ain, char* slice, char* ain, d4* part,
+                                         unsigned long long* tokp, bool& token_seen) {
   switch (p.dims[l] >> 7) {  // uniform
-    case 1: mr_layer_n<TA, 1>(p, c, l, Ain, slice0, slice1, part, flags_out, tokp, token_seen); break;
-    case 2: mr_layer_n<TA, 2>(p, c, l, Ain, slice0, slice1, part, flags_out, tokp, token_seen); break;
-    case 4: mr_layer_n<TA, 4>(p, c, l, Ain, slice0, slice1, part, flags_out, tokp, token_seen); break;
-    default: mr_layer_n<TA, 8>(p, c, l, Ain, slice0, slice1, part, flags_out, tokp, token_seen); break;
+    case 1: mr_layer_n<TA, 1>(p, c, l, jb, Ain, slice, ain, part, tokp, token_seen); break;
+    case 2: mr_layer_n<TA, 2>(p, c, l, jb, Ain, slice, ain, part, tokp, token_seen); break;
+    case 4: mr_layer_n<TA, 4>(p, c, l, jb, Ain, slice, ain, part, tokp, token_seen); break;
+    default: mr_layer_n<TA, 8>(p, c, l, jb, Ain, slice, ain, part, tokp, token_seen); break;
   }
 }
 
@@ -301,95 +365,81 @@ __global__ __launch_bounds__(MR_THREADS, 1) void mlp_rows_kernel(MlpRowsArgs p) 
   c.wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
   c.r16 = c.lane & 15;
   c.q = c.lane >> 4;
-  char* slice0 = mr_smem + c.wave * MR_SLICE_BYTES;
-  char* slice1 = mr_smem + MR_AREA_BYTES + c.wave * MR_SLICE_BYTES;
-  d4* part = reinterpret_cast<d4*>(mr_smem + MR_MAXT * MR_AREA_BYTES);
-  const int nwg = (int)gridDim.x, G = p.groups;
-  const int w = (int)blockIdx.x;
-  c.g = w % G;
-  c.rank = w / G;
-  c.gsize = (nwg - c.g + G - 1) / G;
-  const int fstride = 4 * MR_MAXT * ((nwg + G - 1) / G);  // flag words reserved per group and boundary
-  unsigned* flags = p.sync + MR_FLAG_WORD0;
+  const int nwg = (int)gridDim.x, w = (int)blockIdx.x, RT = p.groups;
+  c.share = w % MR_SHARES;
+  c.rank = w / MR_SHARES;
+  c.R = nwg / MR_SHARES;
+  d4* part = reinterpret_cast<d4*>(mr_smem + 2 * MR_AREA_BYTES);
   unsigned long long* tokp = reinterpret_cast<unsigned long long*>(p.sync + MLP_SYNC_TOKEN);
   const bool chained = p.n_layers > 1;
-
-  // the input and the first tile of the first layer's weights are requested before anything else
-  if (c.rank < ((p.dims[1] + 15) >> 4)) {  // uniform
-    mr_fetch(p.I, p.dims[0], 16 * c.g, p.batch - 1, c, slice1);
-    mr_fetch(p.W[0], p.dims[0], 16 * c.rank, p.dims[1] - 1, c, slice0);
-  }
-
-  if (chained && w == 0) {
-    // this call's flags start at zero; then the token says so
-    unsigned* fw = p.sync + MR_FLAG_WORD0;
-    const int nwords = (p.n_layers - 1) * G * fstride;
-    for (int i = tid; i < nwords; i += MR_THREADS) __hip_atomic_store(fw + i, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (tid == 0) {
-      __hip_atomic_store(p.sync + MLP_SYNC_EXIT, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(p.sync + MLP_SYNC_ERROR, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    // every wavefront's zeroes are acknowledged (a plain wait for everything: the requests above count too) ...
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();  // ... before the token goes out.  (Relaxed: the zeroes are write-through stores that have been
-    // acknowledged; a release here would write back this XCD's whole L2.)
-    if (tid == 0) __hip_atomic_store(tokp, p.token, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
   bool token_seen = !chained;  // per wavefront: has it seen this call's token?
 
-  // A layer's weights are requested as soon as the layer before it has issued its stores and flags: they travel
-  // while the next layer's wavefronts wait for their activations.
+  char* slice0 = mr_smem + c.wave * MR_SLICE_BYTES;                  // this wavefront's slice of the weight tile
+  char* slice1 = mr_smem + MR_AREA_BYTES + c.wave * MR_SLICE_BYTES;  // layer 0: its slice of the input row tile(s)
+
+  MrJob jb = mr_job(c, p.dims[1], RT);
+  // the input rows and the weight tile of the first layer's job are requested before anything else
+  if (jb.nrt > 0) {  // uniform
+    mr_fetch(p.I, p.dims[0], 16 * jb.rt0, p.batch - 1, c, slice1);
+    mr_fetch(p.W[0], p.dims[0], 16 * jb.ct, p.dims[1] - 1, c, slice0);
+  }
+  if (chained && w == 0) mr_publish_token(p, tokp);  // (workgroup 0 always has a job in layer 0: it waits for its requests here)
+
   for (int l = 0; l < p.n_layers; l++) {
-    unsigned* fout = flags + ((size_t)l * G + c.g) * fstride;  // boundary l: what layer l writes
-    if (l == 0) {
-      mr_layer<float>(p, c, 0, p.I, slice0, slice1, part, fout, tokp, token_seen);
+    MrJob jn{0, 0, 0};
+    if (l + 1 < p.n_layers) jn = mr_job(c, p.dims[l + 2], RT);
+    if (jb.nrt == 0) {
+      // no job in this layer
+    } else if (l == 0) {
+      mr_layer<float>(p, c, 0, jb, p.I, slice0, slice1, part, tokp, token_seen);
     } else {
-      // Layer l reads row tile g of O_{l-1}: all of it is there once the K/4 flag bytes of boundary l-1 are set.
-      // One wavefront polls them (4 per lane: one load), the others wait at the workgroup barrier: eight polling
-      // wavefronts per workgroup were measured slower (their loads delay the flags they wait for).
-      if (c.wave == 0 && c.rank < ((p.dims[l + 1] + 15) >> 4)) {
+      // Layer l reads row tiles rt0 .. of O_{l-1}: a row tile is all there once the K/4 flag words of boundary l-1
+      // are set.  One wavefront polls them (two 8-byte loads per lane and row tile, in flight together), the others
+      // wait at the workgroup barrier: eight polling wavefronts per workgroup were measured slower.
+      if (c.wave == 0) {
         unsigned spins = 0;
         bool ok = true;
-        if (!token_seen) {  // a workgroup without a tile in the first layer comes here first
+        if (!token_seen) {  // a workgroup without a job in the first layer comes here first
           while (__hip_atomic_load(tokp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != p.token) {
             __builtin_amdgcn_s_sleep(2);
             if (++spins >= p.spin_limit) { ok = false; break; }
           }
         }
-        // K/4 flag words (32 .. 256): a lane takes up to four of them, as two 8-byte loads that travel together
-        const unsigned long long* fin = reinterpret_cast<const unsigned long long*>(flags + ((size_t)(l - 1) * G + c.g) * fstride);
-        const int npairs = p.dims[l] >> 3;
-        const unsigned long long* f0 = fin + min(c.lane, npairs - 1);
-        const unsigned long long* f1 = fin + min(c.lane + WAVE, npairs - 1);
+        const int npairs = p.dims[l] >> 3;  // K/4 flag words (32 .. 256), two to a load
+        const unsigned long long* fin0 =
+            reinterpret_cast<const unsigned long long*>(p.sync + MR_FLAG_WORD0 + ((size_t)(l - 1) * RT + jb.rt0) * p.fstride);
+        const unsigned long long* fin1 =
+            reinterpret_cast<const unsigned long long*>(p.sync + MR_FLAG_WORD0 + ((size_t)(l - 1) * RT + jb.rt0 + jb.nrt - 1) * p.fstride);
+        const int i0 = min(c.lane, npairs - 1), i1 = min(c.lane + WAVE, npairs - 1);
         const unsigned long long want = 0x0000000100000001ull;
-        for (;;) {
-          const unsigned long long v0 = __hip_atomic_load(f0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          const unsigned long long v1 = __hip_atomic_load(f1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          if (__builtin_amdgcn_ballot_w64(v0 != want || v1 != want) == 0) break;
+        while (ok) {
+          const unsigned long long v0 = __hip_atomic_load(fin0 + i0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          const unsigned long long v1 = __hip_atomic_load(fin0 + i1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          const unsigned long long v2 = __hip_atomic_load(fin1 + i0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          const unsigned long long v3 = __hip_atomic_load(fin1 + i1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if (__builtin_amdgcn_ballot_w64(v0 != want || v1 != want || v2 != want || v3 != want) == 0) break;
           __builtin_amdgcn_s_sleep(1);
-          if (++spins >= p.spin_limit) { ok = false; break; }
+          if (++spins >= p.spin_limit) ok = false;
         }
         if (!ok && c.lane == 0) __hip_atomic_store(p.sync + MLP_SYNC_ERROR, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
-      if (c.rank < ((p.dims[l + 1] + 15) >> 4)) token_seen = true;  // (for the other wavefronts: by the barrier below)
+      token_seen = true;  // (for the other wavefronts: by the barrier below)
       __syncthreads();
-      mr_layer<double>(p, c, l, p.act[l - 1], slice0, slice1, part, fout, tokp, token_seen);
+      mr_layer<double>(p, c, l, jb, p.act[l - 1], slice0, slice1, part, tokp, token_seen);
     }
-    if (l + 1 < p.n_layers) {
-      const int Kn = p.dims[l + 1], Mn = p.dims[l + 2];
-      const int CTn = (Mn + 15) >> 4;
-      // this wavefront has read everything it needs out of its slices (the contraction consumed it)
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      if (c.rank < CTn) mr_fetch(p.W[l + 1], Kn, 16 * c.rank, Mn - 1, c, slice0);
-      if (c.rank + c.gsize < CTn) mr_fetch(p.W[l + 1], Kn, 16 * (c.rank + c.gsize), Mn - 1, c, slice1);
+    // The next layer's weight tile is requested as soon as this layer has issued its stores and flags: it travels
+    // while the next layer's wavefronts wait for their activations.
+    if (jn.nrt > 0) {
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wavefront has read everything out of its slice
+      mr_fetch(p.W[l + 1], p.dims[l + 1], 16 * jn.ct, p.dims[l + 2] - 1, c, slice0);
     }
+    jb = jn;
   }
 
   // The last workgroup out withdraws the token: a replay of a captured HIP graph launches this kernel again with
-  // the SAME token, and must again wait for workgroup 0 to zero the flags.
-  // Nobody counts itself out before it has seen the token: workgroup 0 zeroes the counter before it publishes the
-  // token, and a workgroup with nothing to do would otherwise get here first and have its count wiped (the token
-  // would then survive the launch, and a replay would trust flags that workgroup 0 is about to zero).
+  // the SAME token, and must again wait for workgroup 0 to zero the flags.  Nobody counts itself out before it has
+  // seen the token: workgroup 0 zeroes the counter before it publishes the token, and a workgroup with nothing to do
+  // would otherwise get here first and have its count wiped.
   if (chained && tid == 0) {
     if (!token_seen) {
       unsigned spins = 0;

@@ -711,20 +711,20 @@ tc_status mlp_run(const float* I, int64_t batch, int32_t n_layers, const int64_t
     if (min_blocks >= 256) fused = false;
   }
   const int cus = device_cus();
-  // Small batches with reductions of at most 1024: one group of workgroups per 16-row tile of the batch carries the
-  // tile through all layers (mlp_rows.hpp).  Option TC_OPT_MLP_KERNEL = TC_MLP_TILES keeps the tile-stream kernel below.
-  if (fused && cus > 0) {
+  // Small batches with reductions of at most 1024: one workgroup per compute unit, every XCD's workgroups own an eighth
+  // of the column tiles of every layer (mlp_rows.hpp).  Option TC_OPT_MLP_KERNEL = TC_MLP_TILES keeps the tile-stream
+  // kernel below.
+  if (fused && cus >= MR_SHARES) {
     const int64_t G = ceil_div(batch, 16);
-    const int64_t nwg = std::min<int64_t>(cus, MR_MAX_WG);
-    // (a single layer with two tiles per workgroup has nothing to hand over and nothing to hide its second tile's
-    // weights behind: the tile-stream kernel, which pipelines its loads, is faster there: 9.1 against 10.4 us at
-    // 128 x 1024 -> 1024; with one tile per workgroup this kernel is: 6.8 against 8.6 us)
-    bool rows = t_opt.mlp_kernel != TC_MLP_TILES && G <= nwg &&
-                (n_layers > 1 || ceil_div(dims[1], 16) <= nwg / G || t_opt.mlp_kernel == TC_MLP_ROWS) &&
-                mr_flag_words(n_layers, G, nwg) <= (int64_t)(MLP_MAX_LAYERS - 1) * MLP_BAR_WORDS;
+    const int64_t nwg = std::min<int64_t>(cus, MR_MAX_WG) / MR_SHARES * MR_SHARES;
+    int64_t max_ct = 1;  // most column tiles of any layer whose output is handed on
+    for (int l = 0; l + 1 < n_layers; l++) max_ct = std::max(max_ct, ceil_div(dims[l + 1], 16));
+    const int64_t fstride = 4 * max_ct;
+    bool rows = t_opt.mlp_kernel != TC_MLP_TILES && G <= 64 &&
+                (int64_t)(n_layers - 1) * G * fstride <= (int64_t)(MLP_MAX_LAYERS - 1) * MLP_BAR_WORDS;
     for (int l = 0; l < n_layers && rows; l++)
       rows = (dims[l] == 128 || dims[l] == 256 || dims[l] == 512 || dims[l] == 1024) &&
-             ceil_div(dims[l + 1], 16) <= MR_MAXT * (nwg / G);
+             mr_deal((int)ceil_div(dims[l + 1], 16), (int)G, (int)(nwg / MR_SHARES)).fits;
     if (rows) {
       MlpRowsArgs a{};
       a.I = I;
@@ -732,7 +732,7 @@ tc_status mlp_run(const float* I, int64_t batch, int32_t n_layers, const int64_t
         a.W[l] = W[l]; a.bias[l] = bias[l]; a.O[l] = O[l]; a.act[l] = act[l];
       }
       for (int l = 0; l <= n_layers; l++) a.dims[l] = (int)dims[l];
-      a.batch = (int)batch; a.n_layers = n_layers; a.groups = (int)G;
+      a.batch = (int)batch; a.n_layers = n_layers; a.groups = (int)G; a.fstride = (int)fstride;
       a.sync = reinterpret_cast<unsigned*>(ws);
       a.token = next_token();
       a.spin_limit = (unsigned)std::max<int64_t>(1, std::min<int64_t>(t_opt.mlp_spin_limit, 0xffffffffll));
