@@ -40,7 +40,10 @@
 //    wavefront, so no wavefront waits for another inside a layer.  The weight
 //    tile is read out of LDS into registers once and serves both row tiles of
 //    a pair; the second row tile's input follows the first one's through the
-//    same LDS slice;
+//    same LDS slice.  The first layer's operands cannot be requested ahead, so
+//    there the slice travels in sub-slices of 32 reduction elements (whole
+//    128-byte lines of 8 rows per instruction) and is contracted sub-slice by
+//    sub-slice as it lands;
 //  - activations between layers: the workspace copy is the library's own, so it
 //    is WRITTEN in the layout the next layer reads: [row tile][feature][row]
 //    doubles.  A lane's operand for step (j, e) is one 8-byte load, and the 16
@@ -49,7 +52,9 @@
 //    line from a cache), so the wait needs no cache invalidation: an invalidation
 //    by all workgroups at once was measured at 1.7 us per layer boundary.
 // The weight tile of layer l+1 is requested as soon as layer l has issued its
-// stores and flags and travels during the hand-over.
+// stores and flags and travels during the hand-over; the wavefronts that do not
+// poll turn it into fp64 operands while they wait (on this chip a conversion
+// occupies the same pipe as the fp64 MFMA: 16 clocks against the MFMA's 64).
 // The 8 partial tiles are combined through LDS in a fixed order, bias first
 // (the listing's first statement); clamp in fp64; O_l leaves as fp32 (if the
 // caller wants it) and as fp64 into the workspace.  No activation is rounded
@@ -169,6 +174,43 @@ __device__ __forceinline__ void mr_fetch(const float* mat, int K, int row0, int 
   }
 }
 
+// The same for the first layer, whose operands nobody could request ahead: the slice is cut into sub-slices of 32
+// reduction elements (16 rows x 128 bytes, whole cache lines; 2 instructions of 8 rows each), so that the contraction
+// starts on sub-slice 0 while the others travel.  Sub-slice g sits at slice + 2048 g (K = 128: one instruction, as
+// above); within it, piece p of row r is in slot p ^ (r mod 8) of the row.
+__device__ __forceinline__ void mr_fetch_sub(const float* mat, int K, int row0, int last_row, const MrPlace& c, char* slice, int g) {
+  typedef __attribute__((address_space(1))) const void* gptr;
+  typedef __attribute__((address_space(3))) void* lptr;
+  const int lps = min(mr_log2_pieces(K), 3), pieces = 1 << lps, ks = K >> 3;
+  const int xs = c.lane & (pieces - 1), rl = c.lane >> lps, rpi = WAVE >> lps, ni = 16 / rpi;
+  const float* src0 = mat + (size_t)c.wave * ks + 4 * pieces * g;
+#pragma unroll
+  for (int n = 0; n < 2; n++) {
+    if (n < ni) {  // uniform
+      const int row = n * rpi + rl;
+      const int piece = xs ^ (row & (pieces - 1));
+      const float* src = src0 + (size_t)min(row0 + row, last_row) * K + 4 * piece;
+      __builtin_amdgcn_global_load_lds((gptr)src, (lptr)(slice + (g * ni + n) * 1024), 16, 0, 0);
+    }
+  }
+}
+__device__ __forceinline__ int mr_subslices(int K) { return max(1, K >> 8); }
+
+// Pieces 4j + q of row r16 of a slice fetched in sub-slices (NJ = K / 128).
+template <int NJ>
+__device__ __forceinline__ f4 mr_read_sub(const char* slice, const MrPlace& c, int j) {
+  int slot;
+  if constexpr (NJ == 1) slot = (c.r16 << 2) + (c.q ^ (c.r16 & 3));
+  else slot = ((j >> 1) << 7) + (c.r16 << 3) + ((4 * (j & 1) + c.q) ^ (c.r16 & 7));
+  return *reinterpret_cast<const f4*>(slice + 16 * slot);
+}
+
+template <int N>
+__device__ __forceinline__ void mr_wait_vm_c() {
+  static_assert(N >= 0 && N < 64, "the counter has 6 bits");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 // Wait until at most n of this wavefront's vector-memory operations are outstanding (the counter retires in order).
 // The compiler does not order LDS reads after the global_load_lds requests that fill the LDS, so every such
 // dependency is stated with this.
@@ -238,29 +280,41 @@ __device__ __forceinline__ void mr_layer_n(const MlpRowsArgs& p, const MrPlace& 
   constexpr int lp = NJ == 1 ? 2 : NJ == 2 ? 3 : NJ == 4 ? 4 : 5;
   f4 b[NJ];  // this layer's weight tile, read out of LDS once and used for both row tiles
   if constexpr (sizeof(TA) == 4) {
-    // ---- layer 0: the kernel's first instructions requested the input slice of row tile rt0 (into `ain`) and the
-    // weight tile (into `slice`).  With a second row tile, its input slice is requested into `ain` as soon as the
+    // ---- layer 0: the kernel's first instructions requested, sub-slice by sub-slice, the input rows of row tile rt0
+    // (into `ain`) and the weight tile (into `slice`); the only younger request is the bias.  Sub-slice g is
+    // contracted as soon as it has landed.  With a second row tile, its input is requested into `ain` as soon as the
     // first one has been read out of it, and travels while the first tile is contracted.
-    mr_wait_vm(0);
-    // by now workgroup 0 has long published the token: requested here, looked at after the contraction
-    if (chain) tok_early = __hip_atomic_load(tokp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    constexpr int NS = NJ <= 2 ? 1 : NJ / 2, JS = NJ / NS, NI = NJ == 1 ? 1 : 2;  // sub-slices, their j's, instructions each
     f4 a[NJ];
 #pragma unroll
-    for (int j = 0; j < NJ; j++) a[j] = mr_read(ain, c, lp, j);
+    for (int g = 0; g < NS; g++) {
+      if (g == 0) mr_wait_vm_c<2 * NI * (NS - 1) + 1>();
+      else if (g == 1) mr_wait_vm_c<(NS > 1 ? 2 * NI * (NS - 2) : 0) + 1>();
+      else if (g == 2) mr_wait_vm_c<(NS > 2 ? 2 * NI * (NS - 3) : 0) + 1>();
+      else mr_wait_vm_c<1>();
 #pragma unroll
-    for (int j = 0; j < NJ; j++) b[j] = mr_read(slice, c, lp, j);
-    if (two) {
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the first input slice has been read out
-      mr_fetch(Ain, K, 16 * (jb.rt0 + 1), p.batch - 1, c, ain);
+      for (int j = g * JS; j < (g + 1) * JS; j++) {
+        a[j] = mr_read_sub<NJ>(ain, c, j);
+        b[j] = mr_read_sub<NJ>(slice, c, j);
+      }
+      if (g == NS - 1) {
+        // by now workgroup 0 has long published the token: requested here, looked at after the contraction
+        if (chain) tok_early = __hip_atomic_load(tokp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (two) {
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the first input slice has been read out
+#pragma unroll
+          for (int h = 0; h < NS; h++) mr_fetch_sub(Ain, K, 16 * (jb.rt0 + 1), p.batch - 1, c, ain, h);
+        }
+      }
+#pragma unroll
+      for (int j = g * JS; j < (g + 1) * JS; j++)
+#pragma unroll
+        for (int e = 0; e < 4; e++) acc0 = mfma_f64((double)a[j][e], (double)b[j][e], acc0);
     }
-#pragma unroll
-    for (int j = 0; j < NJ; j++)
-#pragma unroll
-      for (int e = 0; e < 4; e++) acc0 = mfma_f64((double)a[j][e], (double)b[j][e], acc0);
     if (two) {
       mr_wait_vm(0);  // the second row tile's input, requested above, has landed
 #pragma unroll
-      for (int j = 0; j < NJ; j++) a[j] = mr_read(ain, c, lp, j);
+      for (int j = 0; j < NJ; j++) a[j] = mr_read_sub<NJ>(ain, c, j);
 #pragma unroll
       for (int j = 0; j < NJ; j++)
 #pragma unroll
@@ -270,6 +324,20 @@ __device__ __forceinline__ void mr_layer_n(const MlpRowsArgs& p, const MrPlace& 
     // ---- later layers: the activations of this wavefront's slice come from the workspace copy, already in MFMA
     // layout (a[j][e] = In[row r16][slice + 16 j + 4 q + e], agent-scope loads: never a stale line from a cache); the
     // weight tile was requested a hand-over ago
+    // Wavefront 0 is still polling the flags of the row tile(s); the others turn their weight slice into fp64
+    // operands meanwhile (a conversion takes the matrix pipe's time: 16 clocks against the MFMA's 64) and meet it at
+    // the barrier.
+    double bd[NJ][4];
+    if (c.wave != 0) {  // uniform per wavefront
+      mr_wait_vm(0);    // the weights have landed in LDS
+#pragma unroll
+      for (int j = 0; j < NJ; j++) {
+        b[j] = mr_read(slice, c, lp, j);
+#pragma unroll
+        for (int e = 0; e < 4; e++) bd[j][e] = (double)b[j][e];
+      }
+    }
+    __syncthreads();  // wavefront 0 has seen the flags (and, if nobody had yet, the token)
     double a[NJ][4];
     {
       const int rows0 = min(16, p.batch - 16 * jb.rt0);
@@ -280,13 +348,19 @@ __device__ __forceinline__ void mr_layer_n(const MlpRowsArgs& p, const MrPlace& 
         for (int e = 0; e < 4; e++)
           a[j][e] = __hip_atomic_load(s0 + (size_t)(16 * j + e) * 16, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    mr_wait_vm(4 * NJ);  // everything older than these 4 nj loads is done: the weights have landed in LDS
+    if (c.wave == 0) {
+      mr_wait_vm(4 * NJ);  // everything older than these 4 nj loads is done: the weights have landed in LDS
 #pragma unroll
-    for (int j = 0; j < NJ; j++) b[j] = mr_read(slice, c, lp, j);
+      for (int j = 0; j < NJ; j++) {
+        b[j] = mr_read(slice, c, lp, j);
+#pragma unroll
+        for (int e = 0; e < 4; e++) bd[j][e] = (double)b[j][e];
+      }
+    }
 #pragma unroll
     for (int j = 0; j < NJ; j++)
 #pragma unroll
-      for (int e = 0; e < 4; e++) acc0 = mfma_f64(a[j][e], (double)b[j][e], acc0);
+      for (int e = 0; e < 4; e++) acc0 = mfma_f64(a[j][e], bd[j][e], acc0);
     if (two) {
       const int rows1 = min(16, p.batch - 16 * (jb.rt0 + 1));
       const double* s1 = Ain + mr_act_index(jb.rt0 + 1, K, min(c.r16, rows1 - 1), c.wave * ks + 4 * c.q);
@@ -298,7 +372,7 @@ __device__ __forceinline__ void mr_layer_n(const MlpRowsArgs& p, const MrPlace& 
 #pragma unroll
       for (int j = 0; j < NJ; j++)
 #pragma unroll
-        for (int e = 0; e < 4; e++) acc1 = mfma_f64(a[j][e], (double)b[j][e], acc1);
+        for (int e = 0; e < 4; e++) acc1 = mfma_f64(a[j][e], bd[j][e], acc1);
     }
   }
   part[(c.wave * MR_MAXT + 0) * WAVE + c.lane] = acc0;
@@ -380,8 +454,14 @@ __global__ __launch_bounds__(MR_THREADS, 1) void mlp_rows_kernel(MlpRowsArgs p) 
   MrJob jb = mr_job(c, p.dims[1], RT);
   // the input rows and the weight tile of the first layer's job are requested before anything else
   if (jb.nrt > 0) {  // uniform
-    mr_fetch(p.I, p.dims[0], 16 * jb.rt0, p.batch - 1, c, slice1);
-    mr_fetch(p.W[0], p.dims[0], 16 * jb.ct, p.dims[1] - 1, c, slice0);
+    const int ns = mr_subslices(p.dims[0]);
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+      if (g < ns) {  // uniform
+        mr_fetch_sub(p.I, p.dims[0], 16 * jb.rt0, p.batch - 1, c, slice1, g);
+        mr_fetch_sub(p.W[0], p.dims[0], 16 * jb.ct, p.dims[1] - 1, c, slice0, g);
+      }
+    }
   }
   if (chained && w == 0) mr_publish_token(p, tokp);  // (workgroup 0 always has a job in layer 0: it waits for its requests here)
 
@@ -423,8 +503,7 @@ __global__ __launch_bounds__(MR_THREADS, 1) void mlp_rows_kernel(MlpRowsArgs p) 
         }
         if (!ok && c.lane == 0) __hip_atomic_store(p.sync + MLP_SYNC_ERROR, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
-      token_seen = true;  // (for the other wavefronts: by the barrier below)
-      __syncthreads();
+      token_seen = true;  // (for the other wavefronts: by the barrier at which the layer meets wavefront 0)
       mr_layer<double>(p, c, l, jb, p.act[l - 1], slice0, slice1, part, tokp, token_seen);
     }
     // The next layer's weight tile is requested as soon as this layer has issued its stores and flags: it travels
