@@ -384,8 +384,9 @@ __device__ __forceinline__ void mr_layer_n(const MlpRowsArgs& p, const MrPlace& 
   double x = (double)bias_v;        // bias first (the listing's first statement), then a fixed order
   if (fin) {
     const int dl = fin_c + 16 * (fin_r & 3), dv = fin_r >> 2;  // where the MFMA result layout keeps it: lane, element
+    const double* pd = reinterpret_cast<const double*>(part) + 4 * (fin_t * WAVE + dl) + dv;  // one 8-byte read each
 #pragma unroll
-    for (int u = 0; u < MR_WAVES; u++) x += part[(u * MR_MAXT + fin_t) * WAVE + dl][dv];
+    for (int u = 0; u < MR_WAVES; u++) x += pd[4 * u * MR_MAXT * WAVE];
     x = relu64(x);
   }
   __syncthreads();  // the partial tiles have been read: the next layer may overwrite them
