@@ -191,12 +191,16 @@ MLP_SHAPES = [
     (128, (1024, 1000)),            # odd output extent 1000 (the C3 weight of Section 7)
     (48, (256, 336, 80)),           # 63 and 15 tiles: an odd number of four-wavefront teams, the last workgroup half empty
     (2048, (64, 128, 64)),          # 1024 and 512 tiles on 512 teams: two tiles per team, then one
-    # the row-tile kernel (reductions of 128, 256, 512 or 1024, small batch):
-    (100, (512, 256, 1000)),        # 7 row tiles, the last with 4 rows; ragged last column tile; two tiles per workgroup
-    (16, (128, 128, 128)),          # one row tile: every workgroup in one group, most without a tile
-    (200, (1024, 512, 40)),         # 13 row tiles: groups of 19 and 20 workgroups
+    # the row kernel (reductions of 128, 256, 512 or 1024, at most two tiles per workgroup and layer); the 32 workgroups
+    # of an XCD take single (column tile, row tile) jobs of their eighth of the columns, or pairs of row tiles:
+    (100, (512, 256, 1000)),        # 7 row tiles, the last with 4 rows: 14 single jobs, then pairs with a lone last row tile and a ragged last column tile
+    (16, (128, 128, 128)),          # one row tile: one job per XCD, most workgroups without any
+    (200, (1024, 512, 40)),         # 13 row tiles: 28 pairs per XCD (the last one half empty), then 13 jobs in 3 XCDs only
     (64, (1024, 512)),              # a single layer with one tile per workgroup
     (128, (256, 1024, 128, 512, 256, 128)),  # five layers
+    (128, (1024, 1024, 1024)),      # pairs of row tiles in a later layer too (activations of two row tiles against one weight tile)
+    (512, (128, 128, 128)),         # 32 row tiles: every workgroup of an XCD on the same column tile
+    (1024, (128, 128)),             # 64 row tiles, the most the kernel takes: pairs
 ]
 
 
@@ -209,6 +213,19 @@ def test_mlp(tc, shape, oracle_threads):
     for l in range(len(Ws)):
         check(O[l], ref[l], "mlp %s layer %d" % (shape, l))
         assert float(O[l].min()) >= 0.0
+
+
+def test_mlp_shapes_that_the_row_kernel_takes(tc):
+    # which kernel a chain runs on is decided by the host from the shape alone (batch <= 1024, reductions of 128, 256,
+    # 512 or 1024, at most two tiles per workgroup in every layer)
+    cases = [((128, (1024, 1024, 512, 256)), "mlp:rows"), ((128, (1024, 1024, 1024)), "mlp:rows"),
+             ((1024, (128, 128)), "mlp:rows"), ((128, (1024, 1000)), "mlp:rows"), ((100, (512, 256, 1000)), "mlp:rows"),
+             ((1024, (128, 256)), "mlp:tiles"),    # 2 column tiles per XCD x 32 pairs of row tiles: more than 32 workgroups
+             ((256, (1024, 1024)), "mlp:tiles"), ((2048, (128, 128)), "mlp:tiles"), ((128, (384, 128)), "mlp:tiles")]
+    for (batch, dims), path in cases:
+        I, Ws, bs = inputs.make_mlp(batch, dims, seed=5)
+        run_mlp(tc, I, Ws, bs)
+        assert tc.last_path() == path, (batch, dims, tc.last_path())
 
 
 def test_mlp_tile_stream_kernel_by_option(tc, oracle_threads, mlp_option):
