@@ -420,18 +420,28 @@ __device__ __forceinline__ void mr_layer_n(const MlpRowsArgs& p, const MrPlace& 
   }
 }
 
-template <typename TA>
+// WIDE: every reduction extent of the chain is 512 or 1024 (the host says so): the kernel then carries only those two
+// layer bodies.  Every instruction of this kernel runs once or a few times per launch, so what it costs to fetch the
+// code shows: the benchmark chain runs 0.15 us faster on the smaller kernel.
+template <typename TA, bool WIDE>
 __device__ __forceinline__ void mr_layer(const MlpRowsArgs& p, const MrPlace& c, int l, const MrJob jb,
                                          const TA* __restrict__ Ain, char* slice, char* ain, d4* part,
                                          unsigned long long* tokp, bool& token_seen) {
-  switch (p.dims[l] >> 7) {  // uniform
-    case 1: mr_layer_n<TA, 1>(p, c, l, jb, Ain, slice, ain, part, tokp, token_seen); break;
-    case 2: mr_layer_n<TA, 2>(p, c, l, jb, Ain, slice, ain, part, tokp, token_seen); break;
-    case 4: mr_layer_n<TA, 4>(p, c, l, jb, Ain, slice, ain, part, tokp, token_seen); break;
-    default: mr_layer_n<TA, 8>(p, c, l, jb, Ain, slice, ain, part, tokp, token_seen); break;
+  const int nj = p.dims[l] >> 7;  // uniform
+  if constexpr (WIDE) {
+    if (nj == 4) mr_layer_n<TA, 4>(p, c, l, jb, Ain, slice, ain, part, tokp, token_seen);
+    else mr_layer_n<TA, 8>(p, c, l, jb, Ain, slice, ain, part, tokp, token_seen);
+  } else {
+    switch (nj) {
+      case 1: mr_layer_n<TA, 1>(p, c, l, jb, Ain, slice, ain, part, tokp, token_seen); break;
+      case 2: mr_layer_n<TA, 2>(p, c, l, jb, Ain, slice, ain, part, tokp, token_seen); break;
+      case 4: mr_layer_n<TA, 4>(p, c, l, jb, Ain, slice, ain, part, tokp, token_seen); break;
+      default: mr_layer_n<TA, 8>(p, c, l, jb, Ain, slice, ain, part, tokp, token_seen); break;
+    }
   }
 }
 
+template <bool WIDE>
 __global__ __launch_bounds__(MR_THREADS, 1) void mlp_rows_kernel(MlpRowsArgs p) {
   extern __shared__ __attribute__((aligned(32))) char mr_smem[];
   const int tid = threadIdx.x;
@@ -472,7 +482,7 @@ __global__ __launch_bounds__(MR_THREADS, 1) void mlp_rows_kernel(MlpRowsArgs p) 
     if (jb.nrt == 0) {
       // no job in this layer
     } else if (l == 0) {
-      mr_layer<float>(p, c, 0, jb, p.I, slice0, slice1, part, tokp, token_seen);
+      mr_layer<float, WIDE>(p, c, 0, jb, p.I, slice0, slice1, part, tokp, token_seen);
     } else {
       // Layer l reads row tiles rt0 .. of O_{l-1}: a row tile is all there once the K/4 flag words of boundary l-1
       // are set.  One wavefront polls them (two 8-byte loads per lane and row tile, in flight together), the others
@@ -505,7 +515,7 @@ __global__ __launch_bounds__(MR_THREADS, 1) void mlp_rows_kernel(MlpRowsArgs p) 
         if (!ok && c.lane == 0) __hip_atomic_store(p.sync + MLP_SYNC_ERROR, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
       token_seen = true;  // (for the other wavefronts: by the barrier at which the layer meets wavefront 0)
-      mr_layer<double>(p, c, l, jb, p.act[l - 1], slice0, slice1, part, tokp, token_seen);
+      mr_layer<double, WIDE>(p, c, l, jb, p.act[l - 1], slice0, slice1, part, tokp, token_seen);
     }
     // The next layer's weight tile is requested as soon as this layer has issued its stores and flags: it travels
     // while the next layer's wavefronts wait for their activations.

@@ -738,12 +738,17 @@ tc_status mlp_run(const float* I, int64_t batch, int32_t n_layers, const int64_t
       a.spin_limit = (unsigned)std::max<int64_t>(1, std::min<int64_t>(t_opt.mlp_spin_limit, 0xffffffffll));
       static std::atomic<int> lds_ok{0};  // more than the default 64 KiB of dynamic LDS
       if (!lds_ok.load(std::memory_order_acquire)) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_rows_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_rows_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                MR_LDS_BYTES) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_rows_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 MR_LDS_BYTES) != hipSuccess)
           return TC_ERR_LAUNCH;
         lds_ok.store(1, std::memory_order_release);
       }
-      mlp_rows_kernel<<<dim3((unsigned)nwg), dim3(MR_THREADS), MR_LDS_BYTES, s>>>(a);
+      bool wide = true;  // every reduction extent 512 or 1024: the kernel that carries only those layer bodies
+      for (int l = 0; l < n_layers; l++) wide = wide && dims[l] >= 512;
+      if (wide) mlp_rows_kernel<true><<<dim3((unsigned)nwg), dim3(MR_THREADS), MR_LDS_BYTES, s>>>(a);
+      else mlp_rows_kernel<false><<<dim3((unsigned)nwg), dim3(MR_THREADS), MR_LDS_BYTES, s>>>(a);
       return took("mlp:rows", launch_status());
     }
   }
