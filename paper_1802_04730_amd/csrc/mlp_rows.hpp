@@ -15,9 +15,9 @@
 // (0.9 MB of the benchmark's 7.3 MB) instead of all of it.  (With one row tile
 // per XCD, each XCD pulled every weight; at the port's rate that was 3 us of
 // the first layer alone: the same kernel made to fetch only 8 distinct weight
-// tiles per XCD, wrong results and all, ran 2.9 us faster.)  What crosses XCDs instead is the
-// activations, 1 MB per layer boundary and XCD, served from the producers'
-// write-through stores.  (Nothing depends on the placement for correctness:
+// tiles per XCD, wrong results and all, ran 2.9 us faster.)  What crosses XCDs
+// instead is the activations, 1 MB per layer boundary and XCD, served from the
+// producers' write-through stores.  (Nothing depends on the placement for correctness:
 // all exchange is by agent-scope stores, loads and flags.)
 //
 // Inside a share the R = gridDim / 8 workgroups take (column tile, row tile)
@@ -52,9 +52,12 @@
 //    line from a cache), so the wait needs no cache invalidation: an invalidation
 //    by all workgroups at once was measured at 1.7 us per layer boundary.
 // The weight tile of layer l+1 is requested as soon as layer l has issued its
-// stores and flags and travels during the hand-over; the wavefronts that do not
-// poll turn it into fp64 operands while they wait (on this chip a conversion
-// occupies the same pipe as the fp64 MFMA: 16 clocks against the MFMA's 64).
+// stores and flags (a tile of 32 KB or more: once all wavefronts of the
+// workgroup have, so that its requests do not delay their stores'
+// acknowledgements) and travels during the hand-over; the wavefronts that do not
+// poll turn it into fp64 operands while they wait (on this chip nothing
+// overlaps an fp64 MFMA on its SIMD: a conversion costs 8-10 of the MFMA's 64
+// clocks wherever it stands).
 // The 8 partial tiles are combined through LDS in a fixed order, bias first
 // (the listing's first statement); clamp in fp64; O_l leaves as fp32 (if the
 // caller wants it) and as fp64 into the workspace.  No activation is rounded
@@ -66,7 +69,7 @@
 // acknowledged and then sets the flag word of those 4 columns of that row
 // tile; in the next layer one wavefront per workgroup polls the K/4 flag words
 // of each row tile it consumes (two 8-byte loads per lane, in flight together)
-// while the others wait at the workgroup barrier.  Flags only ever go from 0
+// while the others meet it at the workgroup barrier.  Flags only ever go from 0
 // to 1: workgroup 0 zeroes them and then publishes the call's 64-bit token;
 // nobody writes or trusts a flag before it has seen that token; the last
 // workgroup out withdraws it, so a replayed HIP graph (same token) starts
@@ -325,7 +328,7 @@ __device__ __forceinline__ void mr_layer_n(const MlpRowsArgs& p, const MrPlace& 
     // layout (a[j][e] = In[row r16][slice + 16 j + 4 q + e], agent-scope loads: never a stale line from a cache); the
     // weight tile was requested a hand-over ago
     // Wavefront 0 is still polling the flags of the row tile(s); the others turn their weight slice into fp64
-    // operands meanwhile (a conversion takes the matrix pipe's time: 16 clocks against the MFMA's 64) and meet it at
+    // operands meanwhile (a conversion takes the matrix pipe's time: 8-10 clocks against the MFMA's 64) and meet it at
     // the barrier.
     double bd[NJ][4];
     if (c.wave != 0) {  // uniform per wavefront
