@@ -228,6 +228,25 @@ def test_mlp_shapes_that_the_row_kernel_takes(tc):
         assert tc.last_path() == path, (batch, dims, tc.last_path())
 
 
+def test_mlp_seeded_random_chains_in_the_row_kernels_range(tc, oracle_threads):
+    # a seeded draw of chains whose reductions are all 128, 256, 512 or 1024: whatever deal of tiles the host picks
+    # (single jobs, pairs of row tiles, or the tile-stream kernel when neither fits), every layer must agree with the
+    # oracle; ragged batches and ragged last widths included
+    rng = np.random.default_rng(20273)  # a draw with 9 chains for the row kernel (4 with pairs in later layers) and 3 for the other
+    took = set()
+    for case in range(12):
+        n = int(rng.integers(1, 5))
+        dims = [int(rng.choice([128, 256, 512, 1024])) for _ in range(n)] + [int(rng.integers(1, 1100))]
+        batch = int(rng.choice([1, 16, 17, 50, 96, 128, 130, 200, 256, 512]))
+        I, Ws, bs = inputs.make_mlp(batch, dims, seed=100 + case, w_std=1.0 / np.sqrt(max(dims[:-1])))
+        ref = oracle.mlp_fcrelu(I, Ws, bs)
+        O = run_mlp(tc, I, Ws, bs)
+        took.add(tc.last_path())
+        for l in range(n):
+            check(O[l], ref[l], "mlp case %d batch %d dims %s layer %d (%s)" % (case, batch, dims, l, tc.last_path()))
+    assert took == {"mlp:rows", "mlp:tiles"}
+
+
 def test_mlp_tile_stream_kernel_by_option(tc, oracle_threads, mlp_option):
     # TC_OPT_MLP_KERNEL = TC_MLP_TILES: the benchmark chain on the persistent tile-stream kernel (what shapes outside
     # the row-tile kernel's range take), with a workspace full of garbage
