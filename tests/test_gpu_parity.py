@@ -249,7 +249,7 @@ def test_mlp_seeded_random_chains_in_the_row_kernels_range(tc, oracle_threads):
 
 def test_mlp_tile_stream_kernel_by_option(tc, oracle_threads, mlp_option):
     # TC_OPT_MLP_KERNEL = TC_MLP_TILES: the benchmark chain on the persistent tile-stream kernel (what shapes outside
-    # the row-tile kernel's range take), with a workspace full of garbage
+    # the row kernel's range take), with a workspace full of garbage
     mlp_option(tc.TC_OPT_MLP_KERNEL, tc.TC_MLP_TILES)
     batch, dims = 128, (1024, 1024, 512, 256)
     I, Ws, bs = inputs.make_mlp(batch, dims, seed=inputs.SEED_BASE + 3)
@@ -612,7 +612,7 @@ def test_outputs_need_no_zeroing_and_calls_repeat(tc, oracle_threads):
 
 # ---------------------------------------------------------------- HIP graph capture
 def test_mlp_replays_when_most_workgroups_have_nothing_to_do(tc, oracle_threads):
-    """Batch 16 through widths of 128: 8 of the row-tile kernel's 256 workgroups have a tile, the others leave at
+    """Batch 16 through widths of 128: 8 of the row kernel's 256 workgroups have a tile, the others leave at
     once.  None of them may count itself out before workgroup 0 has zeroed the exit counter, or the call's token
     outlives the launch and a replay (same token) trusts flags that are about to be zeroed.  Twenty replays of a graph
     of several launches, into a workspace that starts as garbage; every replay checked; the error word stays clear."""
