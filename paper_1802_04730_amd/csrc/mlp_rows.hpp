@@ -447,6 +447,10 @@ __device__ __forceinline__ void mr_layer(const MlpRowsArgs& p, const MrPlace& c,
 template <bool WIDE>
 __global__ __launch_bounds__(MR_THREADS, 1) void mlp_rows_kernel(MlpRowsArgs p) {
   extern __shared__ __attribute__((aligned(32))) char mr_smem[];
+  // Everything that the first requests need is read from the argument block in one go: read where it is first
+  // used, it is two dependent trips to memory before the first request goes out.
+  asm volatile("" ::"s"(p.I), "s"(p.W[0]), "s"(p.dims[0]), "s"(p.dims[1]), "s"(p.batch), "s"(p.groups), "s"(p.n_layers),
+               "s"(p.sync));
   const int tid = threadIdx.x;
   MrPlace c;
   c.lane = tid & (WAVE - 1);
