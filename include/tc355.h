@@ -78,8 +78,11 @@ int tc355_version(void);
  *   TC_OPT_MLP_KERNEL      TC_MLP_AUTO (default), TC_MLP_ROWS, TC_MLP_TILES (one
  *                          persistent kernel of either kind where it applies),
  *                          TC_MLP_PER_LAYER (one launch per layer)
- *   TC_OPT_MLP_SPIN_LIMIT  polls after which a wait inside a fused MLP kernel gives
- *                          up (default 4000000; >= 1)
+ *   TC_OPT_MLP_SPIN_LIMIT  polls that a wait inside a fused MLP kernel may make before
+ *                          it gives up (default 4000000; >= 0).  0: every wait for
+ *                          another workgroup's results gives up without looking, so
+ *                          the call is certain to end with the error word raised
+ *                          (what the tests of that path use)
  * tc355_set_option returns TC_ERR_SHAPE for an unknown key or a value out of
  * range.  tc355_get_option returns the current value (-1 for an unknown key).
  */

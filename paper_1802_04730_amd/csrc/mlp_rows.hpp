@@ -511,13 +511,17 @@ __global__ __launch_bounds__(MR_THREADS, 1) void mlp_rows_kernel(MlpRowsArgs p) 
         const int i0 = min(c.lane, npairs - 1), i1 = min(c.lane + WAVE, npairs - 1);
         const unsigned long long want = 0x0000000100000001ull;
         while (ok) {
+          if (spins >= p.spin_limit) {  // (a limit of 0: gives up without looking)
+            ok = false;
+            break;
+          }
           const unsigned long long v0 = __hip_atomic_load(fin0 + i0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           const unsigned long long v1 = __hip_atomic_load(fin0 + i1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           const unsigned long long v2 = __hip_atomic_load(fin1 + i0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           const unsigned long long v3 = __hip_atomic_load(fin1 + i1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           if (__builtin_amdgcn_ballot_w64(v0 != want || v1 != want || v2 != want || v3 != want) == 0) break;
           __builtin_amdgcn_s_sleep(1);
-          if (++spins >= p.spin_limit) ok = false;
+          ++spins;
         }
         if (!ok && c.lane == 0) __hip_atomic_store(p.sync + MLP_SYNC_ERROR, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }

@@ -493,7 +493,7 @@ tc_status tc355_set_option(tc_option key, int64_t value) {
       t_opt.mlp_kernel = value;
       return TC_OK;
     case TC_OPT_MLP_SPIN_LIMIT:
-      if (value < 1) return TC_ERR_SHAPE;
+      if (value < 0) return TC_ERR_SHAPE;
       t_opt.mlp_spin_limit = value;
       return TC_OK;
   }
@@ -735,7 +735,7 @@ tc_status mlp_run(const float* I, int64_t batch, int32_t n_layers, const int64_t
       a.batch = (int)batch; a.n_layers = n_layers; a.groups = (int)G; a.fstride = (int)fstride;
       a.sync = reinterpret_cast<unsigned*>(ws);
       a.token = next_token();
-      a.spin_limit = (unsigned)std::max<int64_t>(1, std::min<int64_t>(t_opt.mlp_spin_limit, 0xffffffffll));
+      a.spin_limit = (unsigned)std::max<int64_t>(0, std::min<int64_t>(t_opt.mlp_spin_limit, 0xffffffffll));
       static std::atomic<int> lds_ok{0};  // more than the default 64 KiB of dynamic LDS
       if (!lds_ok.load(std::memory_order_acquire)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_rows_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize,

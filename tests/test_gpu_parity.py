@@ -278,15 +278,16 @@ def test_mlp_per_layer_launch_path(tc, oracle_threads, mlp_option):
 
 @pytest.mark.parametrize("kernel", ["rows", "tiles"])
 def test_mlp_bounded_wait_gives_up_and_recovers(tc, oracle_threads, mlp_option, kernel):
-    # A spin limit of 1 makes the device-wide wait give up at once: the kernel must still
-    # drain, flag the workspace, and the next ordinary call must be correct again.
+    # A spin limit of 0 makes every wait for another workgroup give up without looking (with a limit of 1 the row
+    # kernel's first poll often finds all flags set already: its workgroups reach their polls in step).  The kernel
+    # must still drain, flag the workspace, and the next ordinary call must be correct again.
     batch, dims = 128, (1024, 1024, 512, 256)
     I, Ws, bs = inputs.make_mlp(batch, dims, seed=inputs.SEED_BASE + 3)
     Id, Wd, bd = dev(I), [dev(w) for w in Ws], [dev(b) for b in bs]
     O = [torch.empty((batch, d), device="cuda") for d in dims[1:]]
     ws = torch.zeros(tc.tc_mlp_fcrelu_workspace_bytes(batch, dims), dtype=torch.uint8, device="cuda")
     mlp_option(tc.TC_OPT_MLP_KERNEL, tc.TC_MLP_ROWS if kernel == "rows" else tc.TC_MLP_TILES)
-    old = tc.set_option(tc.TC_OPT_MLP_SPIN_LIMIT, 1)
+    old = tc.set_option(tc.TC_OPT_MLP_SPIN_LIMIT, 0)
     try:
         tc.tc_mlp_fcrelu(Id, Wd, bd, O, ws)
         assert tc.last_path() == "mlp:" + kernel
