@@ -78,7 +78,9 @@ __global__ __launch_bounds__(WG_THREADS, 3) void sconv_tile_kernel(SconvArgs p) 
   for (int i = 0; i < A_LD; i++) aoff[i] = min(f0 + a_row0 + i * (WG_THREADS / A_UPR), F - 1) * K + a_k;
 
   // ---- gathered pixels: this thread's pixel, and its taps b_k0 + KSTEP*j of every chunk
-  const int b_p = tid & (SC_BP - 1), b_k0 = tid / SC_BP;
+  // (with 64 pixels per block a wavefront's lanes share their taps: the tap counters below and the offsets made from
+  // them then live in scalar registers and cost the vector ALU nothing)
+  const int b_p = tid & (SC_BP - 1), b_k0 = SC_BP == WAVE ? wave : tid / SC_BP;
   int pixbase;
   {
     const int px = min(p0 + b_p, P - 1);  // clamped: a ragged tile re-reads the last pixel and does not store it
@@ -106,12 +108,19 @@ __global__ __launch_bounds__(WG_THREADS, 3) void sconv_tile_kernel(SconvArgs p) 
   auto fetch = [&](Regs& r) {
     const int k0 = min(fck, nck - 1) * SC_KC;
     const bool whole = k0 + SC_KC <= K;  // uniform
+    if (whole) {  // every chunk but perhaps the last: no per-lane choice at all
 #pragma unroll
-    for (int i = 0; i < A_LD; i++) r.a[i] = load_vec<float, AV>(p.Wt + aoff[i] + ((whole || k0 + a_k < K) ? k0 : -a_k));
+      for (int i = 0; i < A_LD; i++) r.a[i] = load_vec<float, AV>(p.Wt + aoff[i] + k0);
 #pragma unroll
-    for (int j = 0; j < SC_TAPS; j++) {
-      const bool in = whole || k0 + b_k0 + KSTEP * j < K;
-      r.b[j] = p.I[pixbase + (in ? (tc[j] * H + tkh[j]) * W + tkw[j] : 0)];  // a tap past K reads a valid element, staged as 0
+      for (int j = 0; j < SC_TAPS; j++) r.b[j] = p.I[pixbase + ((tc[j] * H + tkh[j]) * W + tkw[j])];
+    } else {
+#pragma unroll
+      for (int i = 0; i < A_LD; i++) r.a[i] = load_vec<float, AV>(p.Wt + aoff[i] + (k0 + a_k < K ? k0 : -a_k));
+#pragma unroll
+      for (int j = 0; j < SC_TAPS; j++) {
+        const bool in = k0 + b_k0 + KSTEP * j < K;
+        r.b[j] = p.I[pixbase + (in ? (tc[j] * H + tkh[j]) * W + tkw[j] : 0)];  // a tap past K reads a valid element, staged as 0
+      }
     }
     if (fck + 1 < nck) {
 #pragma unroll
@@ -130,7 +139,24 @@ __global__ __launch_bounds__(WG_THREADS, 3) void sconv_tile_kernel(SconvArgs p) 
     const bool whole = k0 + SC_KC <= K;
     double* As = buf + a_row0 * SC_RSA + a_k;
     double* Bs = buf + SC_BF * SC_RSA + b_k0 * SC_RSB + b_p;
-    const bool ain = whole || k0 + a_k < K;
+    if (whole) {  // (uniform)
+#pragma unroll
+      for (int i = 0; i < A_LD; i++) {
+        if constexpr (AV == 4) {
+#pragma unroll
+          for (int e = 0; e < 4; e += 2) {
+            dbl2 v = {(double)r.a[i].e[e], (double)r.a[i].e[e + 1]};
+            *reinterpret_cast<dbl2*>(As + i * (WG_THREADS / A_UPR) * SC_RSA + e) = v;
+          }
+        } else {
+          As[i * (WG_THREADS / A_UPR) * SC_RSA] = (double)r.a[i].e[0];
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < SC_TAPS; j++) Bs[KSTEP * j * SC_RSB] = (double)r.b[j];
+      return;
+    }
+    const bool ain = k0 + a_k < K;
 #pragma unroll
     for (int i = 0; i < A_LD; i++) {
       if constexpr (AV == 4) {
@@ -145,7 +171,7 @@ __global__ __launch_bounds__(WG_THREADS, 3) void sconv_tile_kernel(SconvArgs p) 
     }
 #pragma unroll
     for (int j = 0; j < SC_TAPS; j++) {
-      const bool in = whole || k0 + b_k0 + KSTEP * j < K;
+      const bool in = k0 + b_k0 + KSTEP * j < K;
       Bs[KSTEP * j * SC_RSB] = in ? (double)r.b[j] : 0.0;
     }
   };
