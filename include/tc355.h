@@ -95,9 +95,9 @@ int64_t tc355_get_option(tc_option key);
 /*
  * Which kernel family the calling thread's most recent entry-point call chose,
  * as a static string "op:family" (for example "tbmm:lds", "tbmm:i8",
- * "mlp:rows", "gconv:i8", "gconv:band"; "" before the first call).  A debugging
- * and testing aid: tests pick the tolerance of the arithmetic that actually
- * ran instead of re-deriving the dispatch.
+ * "mlp:rows", "gconv:i8", "gconv:band", "sconv:tile", "lut:sum"; "" before the
+ * first call).  A debugging and testing aid: tests pick the tolerance of the
+ * arithmetic that actually ran instead of re-deriving the dispatch.
  */
 const char *tc355_last_path(void);
 

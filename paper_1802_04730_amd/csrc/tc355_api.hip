@@ -956,7 +956,7 @@ tc_status tc_sconv2d(const float* I, const float* Wt, const float* bias, float* 
     if (K % 4 == 0) sconv_tile_kernel<4, 32><<<gd, bd, SconvGeom<32>::LDS_BYTES, s>>>(a);
     else sconv_tile_kernel<1, 32><<<gd, bd, SconvGeom<32>::LDS_BYTES, s>>>(a);
   }
-  return launch_status();
+  return took("sconv:tile", launch_status());
 }
 
 tc_status tc_lut(int32_t n_tables, const float* const* LUT, const int32_t* const* Idx, float* const* O,
@@ -994,7 +994,7 @@ tc_status tc_lut(int32_t n_tables, const float* const* LUT, const int32_t* const
   if (grid > kMaxGrid) return TC_ERR_UNSUPPORTED;
   if (v == 4) lut_sum_kernel<4><<<dim3((unsigned)grid), dim3(WG_THREADS), 0, s>>>(a);
   else lut_sum_kernel<1><<<dim3((unsigned)grid), dim3(WG_THREADS), 0, s>>>(a);
-  return launch_status();
+  return took("lut:sum", launch_status());
 }
 
 }  // extern "C"

@@ -57,6 +57,7 @@ def test_sconv2d(tc, shape, oracle_threads):
     ref = oracle.sconv2d(I, Wt, bias, sh, sw)
     O = torch.full(ref.shape, float("nan"), device="cuda")
     tc.tc_sconv2d(dev(I), dev(Wt), dev(bias), O, sh, sw)
+    assert tc.last_path() == "sconv:tile"  # (every entry point names its kernel family, not only the step's)
     check(O, ref, "sconv2d %s" % (shape,))
 
 
@@ -117,6 +118,7 @@ def test_lut_one_table(tc, shape, oracle_threads):
     ref = oracle.lut(LUT, Idx)
     O = torch.full((B, D), float("nan"), device="cuda")
     tc.tc_lut([dev(LUT)], [dev(Idx)], [O])
+    assert tc.last_path() == "lut:sum"
     check(O, ref, "lut %s" % (shape,))
 
 
