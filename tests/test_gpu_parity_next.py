@@ -209,3 +209,74 @@ def test_sconv2d_and_lut_replay_from_a_hip_graph(tc, oracle_threads):
         check(O1, ref_1, "graph replay %d lut 1" % rep)
         check(O2, ref_2, "graph replay %d lut 2" % rep)
         del scratch
+
+
+# ---------------------------------------------------------------- every entry point, seeded random shapes
+def test_seeded_random_shapes_through_every_entry_point(tc, oracle_threads):
+    """A seeded draw of shapes for all six entry points (ragged extents, shapes on both sides of every dispatch rule),
+    each checked element by element against the oracle, with a guard band around every output.  The bound is the one
+    of the arithmetic that ran (tc355_last_path): a quarter of the bar on the int8 paths, one fp32 rounding elsewhere."""
+    rng = np.random.default_rng(413)
+    ri = lambda a, b: int(rng.integers(a, b + 1))
+    pick = lambda xs: xs[int(rng.integers(0, len(xs)))]
+    f32 = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+    GUARD = 64
+
+    def guarded(shape):
+        n = int(np.prod(shape))
+        buf = torch.full((n + 2 * GUARD,), 777.0, device="cuda")
+        return buf, buf[GUARD:GUARD + n].view(shape)
+
+    def verify(buf, out, ref, what):
+        tight = PARITY_BAR / 4 if ":i8" in tc.last_path() else TIGHT
+        check(out, ref, "%s on %s" % (what, tc.last_path()), tight=tight)
+        n = out.numel()
+        assert bool((buf[:GUARD] == 777.0).all()) and bool((buf[GUARD + n:] == 777.0).all()), what + ": wrote outside its output"
+
+    paths = set()
+    for it in range(10):
+        # transposed batched matmul: small per-batch matrices, mid-sized ones, long reductions
+        B, N, M, K = [(ri(1, 300), ri(1, 40), ri(1, 90), pick([4, 12, 26, 28, 64, 100])), (ri(1, 3), ri(1, 150), ri(1, 200), ri(1, 200)),
+                      (1, 128, 64 * ri(1, 12), 128 * ri(1, 4))][it % 3]
+        X, Y = f32(rng.standard_normal((B, N, K))), f32(rng.standard_normal((B, M, K)))
+        buf, Z = guarded((B, N, M))
+        tc.tc_tbmm(dev(X), dev(Y), Z)
+        paths.add(tc.last_path())
+        verify(buf, Z, oracle.tbmm(X, Y), "tbmm %s" % ((B, N, M, K),))
+        # Kronecker layer: the LDS kernel's factors of 64 with a ragged I, and anything else
+        Bk, Ik, Kk, Jk, Lk = (ri(1, 40), ri(1, 130), 64, 64, 64) if it % 2 == 0 else (ri(1, 12), ri(1, 40), ri(1, 40), ri(1, 40), ri(1, 40))
+        W1, W2, Xk = f32(rng.standard_normal((Ik, Kk)) / 8), f32(rng.standard_normal((Jk, Lk)) / 8), f32(rng.standard_normal((Bk, Kk, Lk)))
+        buf, Yk = guarded((Bk, Ik, Jk))
+        tc.tc_kron(dev(W1), dev(W2), dev(Xk), Yk)
+        paths.add(tc.last_path())
+        verify(buf, Yk, oracle.kron(W1, W2, Xk), "kron %s" % ((Bk, Ik, Kk, Jk, Lk),))
+        # grouped convolution: the three int8 geometries, the small-channel ones, anything else
+        gk = it % 5
+        if gk == 0: shp = (ri(1, 2), ri(1, 3), 16, 16, 8 * ri(1, 4) + 2, 58, 3, 3)
+        elif gk == 1: shp = (4, ri(1, 3), 16, 16, 14, 14, 3, 3)
+        elif gk == 2: shp = (4, ri(1, 3), 32, 32, 7, 7, 3, 3)
+        elif gk == 3: shp = (ri(1, 3), ri(1, 3)) + pick([(4, 4, 56, 56), (8, 8, 28, 28)]) + (3, 3)
+        else: shp = (ri(1, 3), ri(1, 4), ri(1, 20), ri(1, 20), ri(3, 24), ri(3, 24), ri(1, 3), ri(1, 3))
+        N_, G, C, F, H, W, KH, KW = shp
+        I, Wg, bg = inputs.make_gconv(N_, G, C, F, H, W, KH, KW, seed=1000 + it)
+        buf, Og = guarded((N_, G, F, H - KH + 1, W - KW + 1))
+        tc.tc_group_conv(dev(I), dev(Wg), dev(bg), Og)
+        paths.add(tc.last_path())
+        verify(buf, Og, oracle.group_conv(I, Wg, bg), "gconv %s" % (shp,))
+        # strided convolution
+        shp = (ri(1, 3), ri(1, 30), ri(1, 100), ri(5, 30), ri(5, 30), ri(1, 4), ri(1, 4), ri(1, 3), ri(1, 3))
+        N_, C, F, H, W, KH, KW, sh, sw = shp
+        Is, Wt, bs_ = inputs.make_sconv2d(N_, C, F, H, W, KH, KW, seed=2000 + it)
+        ref = oracle.sconv2d(Is, Wt, bs_, sh, sw)
+        buf, Os = guarded(ref.shape)
+        tc.tc_sconv2d(dev(Is), dev(Wt), dev(bs_), Os, sh, sw)
+        verify(buf, Os, ref, "sconv2d %s" % (shp,))
+        # lookup-table sums, up to four tables in one launch
+        nt, Bl, D = ri(1, 4), ri(1, 150), pick([4, 16, 33, 64, 100])
+        tabs = [inputs.make_lut(ri(1, 4000), D, Bl, ri(1, 50), seed=3000 + 10 * it + t) for t in range(nt)]
+        Ol = [torch.full((Bl, D), float("nan"), device="cuda") for _ in range(nt)]
+        tc.tc_lut([dev(t[0]) for t in tabs], [dev(t[1]) for t in tabs], Ol)
+        for t in range(nt):
+            check(Ol[t], oracle.lut(*tabs[t]), "lut draw %d table %d" % (it, t))
+    assert {"tbmm:lds", "tbmm:wave", "kron:lds", "kron:wave", "gconv:i8", "gconv:i8_small", "gconv:i8_c32", "gconv:quad",
+            "gconv:wave"} <= paths, paths
