@@ -181,6 +181,12 @@ tc_status tc_tbmm_ws(const float *X, const float *Y, float *Z, int64_t B,
  *            at once; outputs are then unspecified) and 0 otherwise.
  * When every reduction extent dims[l] is a multiple of 4 the whole chain runs
  * as one persistent kernel; otherwise one kernel per layer is launched.
+ * The persistent kernel's workgroups wait for one another, so it wants the
+ * device to itself while it runs: kernels running at the same time on other
+ * streams delay it (two chains on two streams were measured at 2.6 times the
+ * time per call of one after the other, with correct results), and if its
+ * workgroups cannot all become resident its waits give up (the error word
+ * above).  TC_OPT_MLP_KERNEL = TC_MLP_PER_LAYER has no such waits.
  * The host arrays are read before the call returns.  1 <= n_layers <= 8.
  * The clamp maps NaN and -0 to +0, like fmaxf(x, 0).
  */
