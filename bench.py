@@ -272,16 +272,21 @@ def main():
         return {"us": round(float(x.mean()), 3), "p0": round(float(x.min()), 3), "p50": round(float(np.median(x)), 3),
                 "p90": round(float(np.percentile(x, 90)), 3)}
 
-    WARM_LAUNCHES = 20
+    # A replay of a graph costs about 10 us of its own between two graphs (measured: the 1 x 1 x 1 product below takes
+    # 2.18 / 1.82 / 1.69 / 1.63 us per launch with 20 / 50 / 100 / 200 launches per graph), so the graphs of the short
+    # operators hold 200 launches; the convolution's (95 us per launch) 20.
+    WARM_LAUNCHES, WARM_LAUNCHES_GCONV, COLD_ROUNDS = 200, 20, 5
     # the smallest launch the library makes (one 1 x 1 x 1 product), replayed the same way: the launch floor
     x1, y1, z1 = (torch.zeros((1, 1, 1), device="cuda") for _ in range(3))
     floor = replay_samples(capture([lambda: tc355.tc_tbmm(x1, y1, z1)] * WARM_LAUNCHES), WARM_LAUNCHES, args.op_samples)
 
     per_op = {}
     for name, (fn, flops, nbytes) in ops.items():
-        warm = replay_samples(capture([fn] * WARM_LAUNCHES), WARM_LAUNCHES, args.op_samples)
+        nl = WARM_LAUNCHES_GCONV if name == "gconv" else WARM_LAUNCHES
+        warm = replay_samples(capture([fn] * nl), nl, args.op_samples if name == "gconv" else max(20, args.op_samples // 4))
         sets, calls = cold_calls(name)
-        cold = replay_samples(capture(calls), COLD_SETS, max(20, args.op_samples // 4)) if calls else warm
+        # every buffer set COLD_ROUNDS times per graph: between two launches on one set lie the 39 others (> 256 MB)
+        cold = replay_samples(capture(calls * COLD_ROUNDS), COLD_SETS * COLD_ROUNDS, max(20, args.op_samples // 4)) if calls else warm
         del sets, calls
         if name == "gconv":  # int8 matrix pipe on operand slices
             arith, t_mfma = "i8x4", GCONV_I8_PRODUCTS * flops / (PEAK_I8_MFMA_TOPS * 1e12)
@@ -313,7 +318,7 @@ def main():
     Xt = torch.randn((1, 128, 4096), device="cuda")
     Yt = torch.randn((1, 16384, 4096), device="cuda")
     Zt = torch.empty((1, 128, 16384), device="cuda")
-    def timed(fn, launches=20):
+    def timed(fn, launches=100):
         """Mean GPU time per launch, microseconds: `launches` launches captured in a HIP graph, replayed 20 times."""
         return float(replay_samples(capture([fn] * launches), launches, 20).mean())
 
@@ -445,9 +450,9 @@ def main():
                                "gconv N=32 G=32 C=F=16 58x58 3x3; kron B=256 64^4",
                    "flops_per_step": step_flops},
         "ops": per_op,
-        "ops_protocol": "HIP-graph replays; warm = %d launches on one buffer set per sample, cold = one launch on each of %d "
-                        "rotating buffer sets per sample (gconv: one 426 MB set); us = mean, p0/p50/p90 over the samples; "
-                        "frac = roofline_us / cold us" % (WARM_LAUNCHES, COLD_SETS),
+        "ops_protocol": "HIP-graph replays; warm = %d launches on one buffer set per sample (gconv: %d), cold = %d launches on "
+                        "each of %d rotating buffer sets per sample (gconv: one 426 MB set); us = mean, p0/p50/p90 over the "
+                        "samples; frac = roofline_us / cold us" % (WARM_LAUNCHES, WARM_LAUNCHES_GCONV, COLD_ROUNDS, COLD_SETS),
         "launch_floor_us": launch_floor,
         "ops_beyond_step": extra,
         "roofline": roofline,
@@ -528,7 +533,7 @@ def sustained_study(torch, tc355, ops, Ig, gconv_tensors, seconds):
 def scaling_study(torch, tc355, inputs):
     """Batch-scaled versions of the three latency-bound operators (supplementary, not the headline metric)."""
     def timed(fn, reps):
-        launches = 10 if reps >= 100 else 4
+        launches = reps if reps >= 100 else 4  # (a replay costs ~10 us of its own: many launches per graph where they are short)
         return float(replay_samples(capture([fn] * launches), launches, 30).mean())
 
     def copy_us(nbytes):
