@@ -1,0 +1,277 @@
+// Strided convolution (Section 3, listing sconv2d) on the int8 matrix core, for a multiple of 128 filters and a
+// reduction C * KH * KW that is a multiple of 4:
+//
+//   O(n,f,h,w) = B(f) + sum_{c,kh,kw} I(n,c, sh*h + kh, sw*w + kw) * W(f,c,kh,kw)
+//
+// As a contraction this is the transposed matmul of gemm_i8.hpp: the rows of "X" are the filters (their
+// C * KH * KW taps are contiguous in W), the rows of "Y" are the N * OH * OW output pixels of the whole batch, whose
+// taps are gathered from I, and the reduction runs over the taps in W's order.  The arithmetic is that kernel's: in
+// every block of 128 taps each filter and each pixel is scaled so that its largest magnitude maps to 0x7F7F7F7E,
+// rounded to a 32-bit integer and cut into four signed 8-bit digits; the digit products with k + l >= MIND are
+// summed exactly in int32 (v_mfma_i32_16x16x64_i8), scaled back and added over the blocks in fp64; one rounding to
+// fp32.  The last block of a reduction that is not a multiple of 128 is filled with zeros.
+//
+// One workgroup of 8 wavefronts = 128 filters against 16 * NT consecutive pixels (NT = 1 .. 4, chosen by the host
+// so that one round of workgroups covers the image batch where it can).
+// Staging: the filter half is gemm_i8.hpp's X half (a thread owns 32 taps of one filter, row maximum across its
+// quad).  The pixel half: a thread owns one group of 4 consecutive taps of the block (group g = tid / 16: 32 groups)
+// for NT pixels (16 i + tid % 16), so a load instruction of a wavefront covers 16 consecutive pixels for each of 4
+// groups; the byte offsets of the block's taps relative to a pixel's first input element come from a table in LDS
+// (built once per workgroup: one division per tap there instead of one per gathered element).  A pixel's 128 taps are
+// spread over 32 threads in all 8 wavefronts, so its maximum is formed by LDS atomics (ds_max_u32) one block ahead:
+// the gathers of block t + 1 are issued before block t is contracted, their maxima are posted after it, and the
+// barrier that ends block t publishes them.
+// Contraction: wavefront w holds the operands of filter tile w (16 filters) in registers and runs them against the
+// NT pixel tiles; MFMA rows = pixels, columns = filters, so a lane ends up with 4 consecutive pixels of one filter.
+//
+// A filter or a pixel whose taps hold Inf or NaN gives NaN in every output of that filter (pixel).
+#pragma once
+#include "gemm_i8.hpp"
+
+namespace tc355 {
+
+struct SconvI8Args {
+  const float* I;     // [N][C][H][W], fewer than 2^30 elements
+  const float* Wt;    // [F][C][KH][KW]
+  const float* bias;  // [F] or nullptr
+  float* O;           // [N][F][OH][OW]
+  int C, F, H, W, sh, sw, OH, OW;
+  int K;              // C * KH * KW
+  int P;              // N * OH * OW
+};
+
+constexpr int SI8_TF = 128, SI8_KB = 128, SI8_THREADS = 512, SI8_WAVES = SI8_THREADS / WAVE;
+constexpr int SI8_STEPS = SI8_KB / 64;
+constexpr int SI8_RS = SI8_KB + 32;  // row stride of a digit plane: see GI8_RS
+constexpr int SI8_MAX_NT = 4;        // pixel tiles per workgroup: five and six do not fit the 256 registers of a wavefront
+
+template <int NT>
+struct SconvI8Geom {
+  static constexpr int TP = 16 * NT;                 // pixels per workgroup
+  static constexpr int ROWS = SI8_TF + TP;           // rows staged per block: filters, then pixels
+  static constexpr int PLANE = ROWS * SI8_RS;
+  static constexpr int INVS = 4 * PLANE;             // ROWS inverse scales (fp64)
+  static constexpr int RMAX = INVS + ROWS * 8;       // [2][TP] largest magnitudes of the pixels' blocks
+  static constexpr int TABLE = RMAX + 2 * TP * 4;    // [blocks * 128] byte offsets of the taps, -1 past the end
+  static constexpr int64_t lds_bytes(int64_t blocks) { return TABLE + blocks * SI8_KB * 4; }
+  static_assert(INVS % 16 == 0 && RMAX % 16 == 0 && TABLE % 16 == 0, "16-byte LDS accesses");
+};
+
+template <int KH, int KW, int NT, int MIND>
+__global__ __launch_bounds__(SI8_THREADS, 1) void sconv_i8_kernel(SconvI8Args p) {
+  static_assert(MIND == 2 || MIND == 3, "13 or 10 digit products");
+  static_assert(NT >= 1 && NT <= SI8_MAX_NT, "16 to 64 pixels per workgroup");
+  using Gm = SconvI8Geom<NT>;
+  constexpr int TP = Gm::TP, PLANE = Gm::PLANE;
+  extern __shared__ __attribute__((aligned(16))) char si8_lds[];
+  const int tid = threadIdx.x;
+  const int lane = tid & (WAVE - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
+  const int r16 = lane & 15, q = lane >> 4;
+  const int K = p.K, nb = (K + SI8_KB - 1) / SI8_KB;
+  const int f0 = blockIdx.y * SI8_TF;
+  const int p0 = blockIdx.x * TP;
+  const int OHW = p.OH * p.OW;
+  double* invs = reinterpret_cast<double*>(si8_lds + Gm::INVS);
+  unsigned* rmax = reinterpret_cast<unsigned*>(si8_lds + Gm::RMAX);
+  int* table = reinterpret_cast<int*>(si8_lds + Gm::TABLE);
+
+  // ---- the taps' byte offsets from a pixel's first input element, in W's order (c, kh, kw)
+  {
+    const int HW = p.H * p.W;
+    for (int k = tid; k < nb * SI8_KB; k += SI8_THREADS) {
+      const int c = k / (KH * KW), t = k - c * (KH * KW), kh = t / KW, kw = t - kh * KW;
+      table[k] = k < K ? 4 * (c * HW + kh * p.W + kw) : -1;
+    }
+    if (tid < 2 * TP) rmax[tid] = 0u;
+  }
+
+  // ---- staging role, filters: 16 slots per MFMA step of filter tid / 4 (chunk cx of the step); slot 16 c + 4 j + e
+  // of step s holds tap 64 s + 16 j + 4 c + e of the block
+  const int xrow = tid >> 2, cx = tid & 3;
+  const float* xsrc = p.Wt + (int64_t)(f0 + xrow) * K + 4 * cx;
+  f4 rx[SI8_STEPS][4];
+  // ---- staging role, pixels: taps 64 s + 16 j + 4 c .. + 3 of the block (group g = (s, j, c)) of pixels 16 i + pl
+  const int g = tid >> 4, pl = tid & 15;
+  const int kg = 64 * (g >> 4) + 16 * ((g >> 2) & 3) + 4 * (g & 3);              // first tap of the group in its block
+  const int ycol = 16 * (4 * (g >> 4) + (g & 3)) + 4 * ((g >> 2) & 3);           // its 4 bytes in a digit-plane row
+  unsigned ybase[NT];  // byte offset of the pixel's first input element
+#pragma unroll
+  for (int i = 0; i < NT; i++) {
+    const int pi = min(p0 + 16 * i + pl, p.P - 1);  // pixels past the end repeat the last one (never stored)
+    const int img = pi / OHW, rem = pi - img * OHW, oh = rem / p.OW, ow = rem - oh * p.OW;
+    ybase[i] = 4u * (unsigned)((img * p.C * p.H + oh * p.sh) * p.W + ow * p.sw);
+  }
+  f4 ry[NT];
+
+  auto fetch = [&](int blk) {
+    const float* xs = xsrc + blk * SI8_KB;
+    if (blk * SI8_KB + SI8_KB <= K) {
+#pragma unroll
+      for (int s = 0; s < SI8_STEPS; s++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) rx[s][j] = *reinterpret_cast<const f4*>(xs + 64 * s + 16 * j);
+    } else {
+#pragma unroll
+      for (int s = 0; s < SI8_STEPS; s++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+          const bool in = blk * SI8_KB + 64 * s + 16 * j + 4 * cx < K;  // K is a multiple of 4: whole pieces
+          rx[s][j] = in ? *reinterpret_cast<const f4*>(xs + 64 * s + 16 * j) : f4{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+    const i4 off = *reinterpret_cast<const i4*>(table + blk * SI8_KB + kg);
+    const char* src = reinterpret_cast<const char*>(p.I);
+#pragma unroll
+    for (int i = 0; i < NT; i++)
+#pragma unroll
+      for (int e = 0; e < 4; e++)
+        ry[i][e] = off[e] >= 0 ? *reinterpret_cast<const float*>(src + (ybase[i] + (unsigned)off[e])) : 0.f;
+  };
+  // largest magnitudes of the fetched pixel taps, posted for the block that is staged next (buffer `buf`)
+  auto post_max = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < NT; i++) {
+      int sm = 0;
+      unsigned um = 0;
+      gi8_absmax4(ry[i], sm, um);
+      __hip_atomic_fetch_max(&rmax[buf * TP + 16 * i + pl], (unsigned)gi8_magnitude(sm, um), __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+  };
+  auto slice = [&](int buf) {
+    {  // filters: 16 elements per step, row shared by the 4 lanes of a quad
+      int sm = 0;
+      unsigned um = 0;
+#pragma unroll
+      for (int s = 0; s < SI8_STEPS; s++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) gi8_absmax4(rx[s][j], sm, um);
+      int v = gi8_magnitude(sm, um);
+      v = max(v, __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false));  // quad_perm [1,0,3,2]
+      v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false));  // quad_perm [2,3,0,1]
+      double scale, inverse;
+      gi8_scales((unsigned)v, scale, inverse);
+#pragma unroll
+      for (int s = 0; s < SI8_STEPS; s++) {
+        int y[4][4];
+#pragma unroll
+        for (int j = 0; j < 4; j++) gi8_digits4(rx[s][j], scale, y[j]);
+        char* dst = si8_lds + xrow * SI8_RS + 16 * (4 * s + cx);
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+          i4 rec;
+          rec.x = y[0][k]; rec.y = y[1][k]; rec.z = y[2][k]; rec.w = y[3][k];
+          *reinterpret_cast<i4*>(dst + k * PLANE) = rec;
+        }
+      }
+      invs[xrow] = inverse;  // the four lanes of the row write the same value
+    }
+#pragma unroll
+    for (int i = 0; i < NT; i++) {  // pixels: 4 elements, row shared by 32 threads
+      const int row = 16 * i + pl;
+      double scale, inverse;
+      gi8_scales(rmax[buf * TP + row], scale, inverse);
+      int y[4];
+      gi8_digits4(ry[i], scale, y);
+      char* dst = si8_lds + (SI8_TF + row) * SI8_RS + ycol;
+#pragma unroll
+      for (int k = 0; k < 4; k++) *reinterpret_cast<int*>(dst + k * PLANE) = y[k];
+      if (g == 0) invs[SI8_TF + row] = inverse * 16777216.0;  // 2^24: the weight of the lowest kept diagonal
+    }
+    if (tid < TP) rmax[(buf ^ 1) * TP + tid] = 0u;  // last read one block ago; next written after the coming barrier
+  };
+
+  // ---- contraction role: filter tile `wave` against the NT pixel tiles
+  double acc[NT][4];
+#pragma unroll
+  for (int i = 0; i < NT; i++)
+#pragma unroll
+    for (int v = 0; v < 4; v++) acc[i][v] = 0.0;
+  // one_step: the block holds at most 64 taps (the end of a reduction), its second MFMA step would multiply zeros
+  auto contract = [&](bool one_step) {
+    i4 xa[SI8_STEPS][4];
+#pragma unroll
+    for (int s = 0; s < SI8_STEPS; s++) {
+      const char* xb = si8_lds + (16 * wave + r16) * SI8_RS + 16 * (4 * s + q);
+#pragma unroll
+      for (int l = 0; l < 4; l++) xa[s][l] = *reinterpret_cast<const i4*>(xb + l * PLANE);
+    }
+    const double fx = invs[16 * wave + r16];
+    // order: no two consecutive products on one diagonal
+    constexpr int ND = 7 - MIND, NP = MIND == 3 ? 10 : 13;
+    constexpr int PK[13] = {3, 2, 3, 3, 2, 1, 2, 1, 0, 3, 2, 1, 0};  // the last three: the diagonal k + l = 2
+    constexpr int PL[13] = {0, 1, 1, 2, 2, 2, 3, 3, 3, 3, 0, 1, 2};
+    i4 d[ND];  // d[i]: diagonal k + l = MIND + i
+    auto mma = [&](int i, i4 (&dd)[ND]) {
+#pragma unroll
+      for (int j = 0; j < ND; j++) dd[j] = i4{0, 0, 0, 0};
+#pragma unroll
+      for (int s = 0; s < SI8_STEPS; s++) {
+        if (s == 1 && one_step) break;
+        const char* yb = si8_lds + (SI8_TF + 16 * i + r16) * SI8_RS + 16 * (4 * s + q);
+        i4 ya[4];
+#pragma unroll
+        for (int k = 0; k < 4; k++) ya[k] = *reinterpret_cast<const i4*>(yb + k * PLANE);
+#pragma unroll
+        for (int pr = 0; pr < NP; pr++)
+          dd[PK[pr] + PL[pr] - MIND] = mfma_i8(ya[PK[pr]], xa[s][PL[pr]], dd[PK[pr] + PL[pr] - MIND]);
+      }
+    };
+    auto epilogue = [&](int i, const i4 (&dd)[ND]) {
+#pragma unroll
+      for (int v = 0; v < 4; v++) {
+        // 128 terms of at most 2^14 per digit pair: 2^21 x 256 + 2 x 2^21 and 3 x 2^21 x 256 + 4 x 2^21, below 2^31
+        const int hi = dd[ND - 1][v] * 256 + dd[ND - 2][v], lo = dd[ND - 3][v] * 256 + dd[ND - 4][v];
+        double rr = __builtin_fma((double)hi, 65536.0, (double)lo);
+        if constexpr (MIND == 2) rr = __builtin_fma((double)dd[0][v], 0.00390625, rr);
+        acc[i][v] = __builtin_fma(rr, invs[SI8_TF + 16 * i + 4 * q + v] * fx, acc[i][v]);
+      }
+    };
+#pragma unroll
+    for (int i = 0; i < NT; i++) {
+      __builtin_amdgcn_sched_barrier(0);  // one tile's operands at a time: hoisted reads of all tiles do not fit the registers
+      mma(i, d);
+      epilogue(i, d);
+    }
+  };
+
+  __syncthreads();  // the table
+  fetch(0);
+  post_max(0);
+  __syncthreads();
+  for (int t = 0; t < nb; t++) {
+    slice(t & 1);
+    __builtin_amdgcn_sched_barrier(0);  // the next block's loads only once this block's registers are free
+    if (t + 1 < nb) fetch(t + 1);
+    __syncthreads();
+    contract(K - t * SI8_KB <= 64);
+    if (t + 1 < nb) post_max((t + 1) & 1);
+    __syncthreads();
+  }
+
+  // ---- outputs: staged in the digit planes' LDS (free now) as [filter][pixel], then written as runs of consecutive
+  // pixels of one filter (a lane's own 4 pixels of 16 filters per instruction would be 64 separate 4-byte writes)
+  constexpr int OS = TP + 1;  // row stride in floats: odd, so the 16 filters of a wavefront's write fall into 16 banks
+  float* ostage = reinterpret_cast<float*>(si8_lds);
+  int* pxoff = reinterpret_cast<int*>(si8_lds + SI8_TF * OS * 4);  // [TP] offset of (image, pixel) in O for filter 0, -1 past the end
+  static_assert(SI8_TF * OS * 4 + TP * 4 <= Gm::INVS, "the output stage fits the digit planes");
+  {
+    const double bz = p.bias ? (double)p.bias[f0 + 16 * wave + r16] : 0.0;
+#pragma unroll
+    for (int i = 0; i < NT; i++)
+#pragma unroll
+      for (int v = 0; v < 4; v++) ostage[(16 * wave + r16) * OS + 16 * i + 4 * q + v] = (float)(acc[i][v] + bz);
+    if (tid < TP) {
+      const int pi = p0 + tid, img = pi / OHW, rem = pi - img * OHW;
+      pxoff[tid] = pi < p.P ? img * p.F * OHW + rem : -1;
+    }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < SI8_TF * TP; idx += SI8_THREADS) {
+    const int fl = idx / TP, px = idx - fl * TP, po = pxoff[px];
+    if (po >= 0) store_stream(p.O + (int64_t)po + (int64_t)(f0 + fl) * OHW, ostage[fl * OS + px]);
+  }
+}
+
+}  // namespace tc355

@@ -31,6 +31,7 @@
 #include "mlp_fused.hpp"
 #include "mlp_rows.hpp"
 #include "sconv_tile.hpp"
+#include "sconv_i8.hpp"
 #include "tbmm_lds.hpp"
 
 using namespace tc355;
@@ -794,6 +795,62 @@ tc_status mlp_run(const float* I, int64_t batch, int32_t n_layers, const int64_t
   return took("mlp:per_layer", TC_OK);
 }
 
+// Strided convolution on the int8 matrix core (sconv_i8.hpp): 128 filters against 16 * NT pixels per workgroup.
+template <int NT>
+tc_status launch_sconv_i8(const SconvI8Args& a, int64_t blocks, dim3 grid, bool ten, hipStream_t s) {
+  constexpr int kLdsMax = 160 * 1024;
+  static std::atomic<int> lds_ok{0};  // more than the default 64 KiB of dynamic LDS
+  if (!lds_ok.load(std::memory_order_acquire)) {
+    const void* kernels[2] = {reinterpret_cast<const void*>(sconv_i8_kernel<3, 3, NT, 2>),
+                              reinterpret_cast<const void*>(sconv_i8_kernel<3, 3, NT, 3>)};
+    for (const void* k : kernels)
+      if (hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsMax) != hipSuccess) return TC_ERR_LAUNCH;
+    lds_ok.store(1, std::memory_order_release);
+  }
+  const size_t lds = (size_t)SconvI8Geom<NT>::lds_bytes(blocks);
+  if (ten) sconv_i8_kernel<3, 3, NT, 3><<<grid, dim3(SI8_THREADS), lds, s>>>(a);
+  else sconv_i8_kernel<3, 3, NT, 2><<<grid, dim3(SI8_THREADS), lds, s>>>(a);
+  return launch_status();
+}
+
+int64_t sconv_i8_lds_bytes(int nt, int64_t blocks) {
+  switch (nt) {
+    case 1: return SconvI8Geom<1>::lds_bytes(blocks);
+    case 2: return SconvI8Geom<2>::lds_bytes(blocks);
+    case 3: return SconvI8Geom<3>::lds_bytes(blocks);
+    default: return SconvI8Geom<4>::lds_bytes(blocks);
+  }
+}
+
+// Takes the call if the shape is one the int8 kernel is built for: 3 x 3 filters, a multiple of 128 of them, a
+// reduction of at least 256 taps (two blocks), operands that 32-bit offsets reach.  Measured faster than the fp64
+// kernel from a single 8 x 8 image up.
+bool try_sconv_i8(const SconvI8Args& a, int64_t N, int KH, int KW, hipStream_t s, tc_status* st) {
+  if (t_opt.int8 == TC_INT8_OFF) return false;
+  if (KH != 3 || KW != 3 || a.F % SI8_TF != 0 || a.K % 4 != 0 || a.K < 256) return false;
+  if (prod_reaches({N, a.C, a.H, a.W}, (int64_t)1 << 30)) return false;                 // 32-bit byte offsets into I
+  if (prod_reaches({N, a.F, a.OH, a.OW}, (int64_t)1 << 31)) return false;               // 32-bit element offsets into O
+  const int64_t blocks = ceil_div(a.K, SI8_KB), units = ceil_div(a.P, 16), fblocks = a.F / SI8_TF;
+  // pixel tiles per workgroup: as few rounds of workgroups as the largest tile allows, then the smallest tile
+  // that still makes that number of rounds
+  const int64_t per_round = std::max<int64_t>(1, device_cus() / fblocks);
+  const int64_t rounds = ceil_div(units, SI8_MAX_NT * per_round);
+  int nt = (int)std::min<int64_t>(SI8_MAX_NT, std::max<int64_t>(1, ceil_div(units, rounds * per_round)));
+  while (nt > 1 && sconv_i8_lds_bytes(nt, blocks) > 160 * 1024) nt--;
+  if (sconv_i8_lds_bytes(nt, blocks) > 160 * 1024) return false;
+  const int64_t gx = ceil_div(units, nt);
+  if (gx > kMaxGrid || fblocks > 65535) return false;
+  const dim3 grid((unsigned)gx, (unsigned)fblocks);
+  const bool ten = t_opt.int8 == TC_INT8_TEN;  // 13 digit products unless the caller has said that 10 will do
+  switch (nt) {
+    case 1: *st = launch_sconv_i8<1>(a, blocks, grid, ten, s); break;
+    case 2: *st = launch_sconv_i8<2>(a, blocks, grid, ten, s); break;
+    case 3: *st = launch_sconv_i8<3>(a, blocks, grid, ten, s); break;
+    default: *st = launch_sconv_i8<4>(a, blocks, grid, ten, s); break;
+  }
+  return true;
+}
+
 }  // namespace
 
 extern "C" {
@@ -937,6 +994,15 @@ tc_status tc_sconv2d(const float* I, const float* Wt, const float* bias, float* 
   const int64_t K = C * KH * KW;
   if (N == 0) return TC_OK;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+  {
+    SconvI8Args e{};
+    e.I = I; e.Wt = Wt; e.bias = bias; e.O = O;
+    e.C = (int)C; e.F = (int)F; e.H = (int)H; e.W = (int)W; e.sh = (int)sh; e.sw = (int)sw; e.OH = (int)OH; e.OW = (int)OW;
+    e.K = (int)K; e.P = (int)(N * OH * OW);
+    tc_status st = TC_OK;
+    if (try_sconv_i8(e, N, (int)KH, (int)KW, s, &st)) return took("sconv:i8", st);
+  }
 
   SconvArgs a{};
   a.I = I; a.Wt = Wt; a.bias = bias; a.O = O;

@@ -1,6 +1,8 @@
 """GPU parity of the strided convolution and the lookup-table sums (through the C ABI) against the float64 oracle.
 
-Same bar and same tight bound as the other fp64 kernels: one fp32 rounding of the exact result.
+Same bar and same tight bound as the other fp64 kernels: one fp32 rounding of the exact result.  Strided
+convolutions with 3 x 3 filters, a multiple of 128 of them and at least 256 taps run on the int8 matrix core
+(tc355_last_path says "sconv:i8"); their bound is the int8 scheme's (tests/test_i8_scheme.py derives the budget).
 """
 import numpy as np
 import pytest
@@ -13,6 +15,7 @@ from paper_1802_04730_amd.metric import PARITY_BAR, parity_error
 pytestmark = pytest.mark.gpu
 
 TIGHT = 2.5e-7
+TIGHT_I8 = 4e-6
 
 
 @pytest.fixture(scope="module")
@@ -45,7 +48,8 @@ SCONV_SHAPES = [
     (2, 8, 8, 15, 15, 1, 1, 2, 2),       # 1 x 1 filter: pure subsampling plus channel mixing, one short chunk
     (1, 3, 4, 12, 12, 7, 7, 2, 2),       # 7 x 7 stride 2 (the first layer of residual networks), reduction 147
     (1, 1, 1, 3, 3, 3, 3, 5, 5),         # a single output element
-    (4, 64, 128, 20, 20, 3, 3, 2, 2),    # many chunks (reduction 576), 64 x 64 blocks all full in the filter dimension
+    (4, 64, 96, 20, 20, 3, 3, 2, 2),     # many chunks (reduction 576), 64 x 64 blocks, the second filter block half full
+    (2, 28, 128, 20, 20, 3, 3, 1, 1),    # 128 filters but only 252 taps: below the int8 kernel's two blocks
     (2, 6, 10, 9, 40, 2, 5, 1, 4),       # wide stride along w only
 ]
 
@@ -59,6 +63,97 @@ def test_sconv2d(tc, shape, oracle_threads):
     tc.tc_sconv2d(dev(I), dev(Wt), dev(bias), O, sh, sw)
     assert tc.last_path() == "sconv:tile"  # (every entry point names its kernel family, not only the step's)
     check(O, ref, "sconv2d %s" % (shape,))
+
+
+# Shapes of the int8 kernel: 128 filters x 16 NT pixels per workgroup, NT chosen from the number of pixel tiles per
+# compute unit; reduction in blocks of 128 taps.  (N, C, F, H, W, sh, sw), 3 x 3 filters.
+SCONV_I8_SHAPES = [
+    (2, 64, 128, 31, 29, 2, 2),     # reduction 576: four blocks and a half one (a single MFMA step); 420 pixels: NT = 1, ragged
+    (3, 32, 128, 20, 23, 1, 1),     # reduction 288: two blocks and 32 taps; 1134 pixels
+    (1, 128, 256, 17, 17, 2, 2),    # two blocks of filters; reduction 1152: nine whole blocks; 64 pixels
+    (2, 36, 128, 40, 41, 3, 2),     # reduction 324 (not a multiple of 16); strides 3 and 2
+    (3, 32, 256, 34, 34, 1, 1),     # 3072 pixels for 128 compute units per filter block: NT = 2
+    (5, 32, 256, 34, 35, 1, 1),     # 5280 pixels: NT = 3, the last workgroup ragged
+    (7, 32, 256, 34, 34, 1, 1),     # 7168 pixels: NT = 4
+    (1, 32, 128, 3, 3, 1, 1),       # one output pixel per filter
+]
+
+
+@pytest.mark.parametrize("shape", SCONV_I8_SHAPES)
+def test_sconv2d_int8_kernel(tc, shape, oracle_threads):
+    N, C, F, H, W, sh, sw = shape
+    I, Wt, bias = inputs.make_sconv2d(N, C, F, H, W, 3, 3, seed=inputs.SEED_BASE + 60 + C)
+    ref = oracle.sconv2d(I, Wt, bias, sh, sw)
+    n = ref.size
+    buf = torch.full((n + 512,), 7.0, device="cuda")
+    O = buf[256:256 + n].view(ref.shape)
+    tc.tc_sconv2d(dev(I), dev(Wt), dev(bias), O, sh, sw)
+    assert tc.last_path() == "sconv:i8"
+    check(O, ref, "sconv2d int8 %s" % (shape,), TIGHT_I8)
+    assert torch.all(buf[:256] == 7.0) and torch.all(buf[256 + n:] == 7.0)
+    # without a bias; the fp64 kernel by option; ten digit products by option
+    ref0 = oracle.sconv2d(I, Wt, None, sh, sw)
+    O0 = torch.full(ref.shape, float("nan"), device="cuda")
+    tc.tc_sconv2d(dev(I), dev(Wt), None, O0, sh, sw)
+    check(O0, ref0, "sconv2d int8 %s, no bias" % (shape,), TIGHT_I8)
+    with tc.option(tc.TC_OPT_INT8, tc.TC_INT8_OFF):
+        tc.tc_sconv2d(dev(I), dev(Wt), dev(bias), O0, sh, sw)
+        assert tc.last_path() == "sconv:tile"
+    check(O0, ref, "sconv2d %s, fp64 kernel by option" % (shape,))
+    with tc.option(tc.TC_OPT_INT8, tc.TC_INT8_TEN):
+        tc.tc_sconv2d(dev(I), dev(Wt), dev(bias), O0, sh, sw)
+        assert tc.last_path() == "sconv:i8"
+    check(O0, ref, "sconv2d int8 %s, 10 products" % (shape,), TIGHT_I8)
+
+
+@pytest.mark.parametrize("kind", ["lognormal", "student3", "sparse"])
+def test_sconv2d_int8_heavy_tailed_operands_stay_a_quarter_of_the_bar(tc, oracle_threads, kind):
+    """A few large elements in every block of taps of the filters AND of the pixels: the default (13 digit products)
+    keeps a quarter of the bar over four seeds."""
+    for seed in range(4):
+        I, Wt, bias = inputs.make_sconv2d(2, 64, 128, 25, 27, 3, 3, seed=70 + seed)
+        rng = np.random.default_rng(9 + seed)
+        if kind == "lognormal":
+            mag = lambda a: np.exp(rng.normal(size=a.shape) * 1.5)
+        elif kind == "student3":
+            mag = lambda a: np.abs(rng.standard_t(3, size=a.shape))
+        else:
+            mag = lambda a: np.where(rng.random(a.shape) < 0.01, 300.0, 1.0)
+        I, Wt = (I * mag(I)).astype(np.float32), (Wt * mag(Wt)).astype(np.float32)
+        ref = oracle.sconv2d(I, Wt, bias, 2, 1)
+        O = torch.full(ref.shape, float("nan"), device="cuda")
+        tc.tc_sconv2d(dev(I), dev(Wt), dev(bias), O, 2, 1)
+        assert tc.last_path() == "sconv:i8"
+        torch.cuda.synchronize()
+        err = parity_error(O.cpu().numpy().astype(np.float64), ref)
+        print("sconv2d int8, %s magnitudes, seed %d: parity error %.3e" % (kind, seed, err), flush=True)
+        assert err <= PARITY_BAR / 4
+
+
+def test_sconv2d_int8_nan_stays_in_the_outputs_that_read_it(tc, oracle_threads):
+    """A NaN in one input element: exactly the outputs whose windows hold it are NaN (all filters), the others keep
+    their values.  A NaN in one filter: all outputs of that filter, and no other."""
+    N, C, F, H, W = 2, 32, 128, 15, 17
+    I, Wt, bias = inputs.make_sconv2d(N, C, F, H, W, 3, 3, seed=81)
+    ref = oracle.sconv2d(I, Wt, bias, 2, 2)
+    In = I.copy()
+    In[1, 5, 6, 8] = np.nan                       # rows 6 = 2*2 + 2 = 2*3 + 0, columns 8 = 2*3 + 2 = 2*4 + 0
+    O = torch.full(ref.shape, 0.0, device="cuda")
+    tc.tc_sconv2d(dev(In), dev(Wt), dev(bias), O, 2, 2)
+    assert tc.last_path() == "sconv:i8"
+    got = O.cpu().numpy().astype(np.float64)
+    hit = np.zeros(ref.shape, dtype=bool)
+    hit[1, :, 2:4, 3:5] = True
+    assert np.isnan(got[hit]).all() and not np.isnan(got[~hit]).any()
+    assert parity_error(np.where(hit, ref, got), ref) <= TIGHT_I8
+    Wn = Wt.copy()
+    Wn[77, 3, 1, 2] = np.nan
+    tc.tc_sconv2d(dev(I), dev(Wn), dev(bias), O, 2, 2)
+    got = O.cpu().numpy().astype(np.float64)
+    hit = np.zeros(ref.shape, dtype=bool)
+    hit[:, 77] = True
+    assert np.isnan(got[hit]).all() and not np.isnan(got[~hit]).any()
+    assert parity_error(np.where(hit, ref, got), ref) <= TIGHT_I8
 
 
 def test_sconv2d_without_bias_and_unit_strides_match_group_conv(tc, oracle_threads):
@@ -80,10 +175,19 @@ def test_sconv2d_resnext_like_full_size_sampled(tc, oracle_threads):
     I, Wt, bias = inputs.make_sconv2d(N, C, F, H, W, 3, 3)
     O = torch.full((N, F, 27, 27), float("nan"), device="cuda")
     tc.tc_sconv2d(dev(I), dev(Wt), dev(bias), O, 2, 2)
+    assert tc.last_path() == "sconv:i8"
     torch.cuda.synchronize()
     assert not torch.isnan(O).any()
     for n in (0, 31):
-        check(O[n:n + 1], oracle.sconv2d(I[n:n + 1], Wt, bias, 2, 2), "sconv2d full size, image %d" % n)
+        check(O[n:n + 1], oracle.sconv2d(I[n:n + 1], Wt, bias, 2, 2), "sconv2d full size, image %d" % n, TIGHT_I8)
+    # every workgroup's output: the whole result against the fp64 kernel's, which the same two images pin to the oracle
+    O64 = torch.full((N, F, 27, 27), float("nan"), device="cuda")
+    with tc.option(tc.TC_OPT_INT8, tc.TC_INT8_OFF):
+        tc.tc_sconv2d(dev(I), dev(Wt), dev(bias), O64, 2, 2)
+        assert tc.last_path() == "sconv:tile"
+    for n in (0, 31):
+        check(O64[n:n + 1], oracle.sconv2d(I[n:n + 1], Wt, bias, 2, 2), "sconv2d full size, fp64 kernel, image %d" % n)
+    check(O, O64.cpu().numpy().astype(np.float64), "sconv2d full size, int8 against fp64 kernel, all images", TIGHT_I8)
 
 
 def test_sconv2d_stays_inside_its_output(tc, oracle_threads):
@@ -189,8 +293,14 @@ def test_sconv2d_and_lut_replay_from_a_hip_graph(tc, oracle_threads):
     Os = torch.empty(ref_s.shape, device="cuda")
     O1, O2 = torch.empty((32, 64), device="cuda"), torch.empty((32, 64), device="cuda")
 
+    I8, W8, b8 = inputs.make_sconv2d(2, 32, 128, 14, 15, 3, 3, seed=34)  # the int8 kernel
+    ref_8 = oracle.sconv2d(I8, W8, b8, 1, 2)
+    I8d, W8d, b8d = dev(I8), dev(W8), dev(b8)
+    O8 = torch.empty(ref_8.shape, device="cuda")
+
     def step():
         tc.tc_sconv2d(Id, Wd, bd, Os, 2, 2)
+        tc.tc_sconv2d(I8d, W8d, b8d, O8, 1, 2)
         tc.tc_lut(T, J, [O1, O2])
 
     step()
@@ -199,13 +309,14 @@ def test_sconv2d_and_lut_replay_from_a_hip_graph(tc, oracle_threads):
     with torch.cuda.graph(g):
         step()
     for rep in range(3):
-        for t in (Os, O1, O2):
+        for t in (Os, O8, O1, O2):
             t.fill_(float("nan"))
         torch.cuda.synchronize()
         g.replay()
         scratch = torch.randn(1 << 20, device="cuda").sum()  # eager work between replays
         torch.cuda.synchronize()
         check(Os, ref_s, "graph replay %d sconv2d" % rep)
+        check(O8, ref_8, "graph replay %d sconv2d, int8 kernel" % rep, TIGHT_I8)
         check(O1, ref_1, "graph replay %d lut 1" % rep)
         check(O2, ref_2, "graph replay %d lut 2" % rep)
         del scratch
@@ -264,12 +375,14 @@ def test_seeded_random_shapes_through_every_entry_point(tc, oracle_threads):
         paths.add(tc.last_path())
         verify(buf, Og, oracle.group_conv(I, Wg, bg), "gconv %s" % (shp,))
         # strided convolution
-        shp = (ri(1, 3), ri(1, 30), ri(1, 100), ri(5, 30), ri(5, 30), ri(1, 4), ri(1, 4), ri(1, 3), ri(1, 3))
+        if it % 2 == 0: shp = (ri(1, 3), ri(1, 30), ri(1, 100), ri(5, 30), ri(5, 30), ri(1, 4), ri(1, 4), ri(1, 3), ri(1, 3))
+        else: shp = (ri(1, 3), 4 * ri(8, 24), 128 * ri(1, 2), ri(5, 30), ri(5, 30), 3, 3, ri(1, 3), ri(1, 3))  # the int8 kernel's range
         N_, C, F, H, W, KH, KW, sh, sw = shp
         Is, Wt, bs_ = inputs.make_sconv2d(N_, C, F, H, W, KH, KW, seed=2000 + it)
         ref = oracle.sconv2d(Is, Wt, bs_, sh, sw)
         buf, Os = guarded(ref.shape)
         tc.tc_sconv2d(dev(Is), dev(Wt), dev(bs_), Os, sh, sw)
+        paths.add(tc.last_path())
         verify(buf, Os, ref, "sconv2d %s" % (shp,))
         # lookup-table sums, up to four tables in one launch
         nt, Bl, D = ri(1, 4), ri(1, 150), pick([4, 16, 33, 64, 100])
@@ -279,4 +392,4 @@ def test_seeded_random_shapes_through_every_entry_point(tc, oracle_threads):
         for t in range(nt):
             check(Ol[t], oracle.lut(*tabs[t]), "lut draw %d table %d" % (it, t))
     assert {"tbmm:lds", "tbmm:wave", "kron:lds", "kron:wave", "gconv:i8", "gconv:i8_small", "gconv:i8_c32", "gconv:quad",
-            "gconv:wave"} <= paths, paths
+            "gconv:wave", "sconv:tile", "sconv:i8"} <= paths, paths
