@@ -75,7 +75,7 @@ def parse_args():
                     help="for rocprofv3 --pmc: tbmm, MLP and kron on 40 cold buffer sets, tbmm at 64x batch, and a "
                          "calibration copy; no timing")
     ap.add_argument("--traffic-probe", action="store_true",
-                    help="only launch the grouped convolution, the largest transposed matmul and a plain 512 MiB device copy a few times (for "
+                    help="only launch the grouped convolution, the largest transposed matmul, the strided convolution and a plain 512 MiB device copy a few times (for "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs; the copy calibrates the counters)")
     return ap.parse_args()
 
@@ -224,14 +224,21 @@ def main():
         Xp = torch.rand((1, 128, 4096), device="cuda") * 2 - 1
         Yp = torch.rand((1, 16384, 4096), device="cuda") * 2 - 1
         Zp = torch.empty((1, 128, 16384), device="cuda")
+        # and the strided convolution (Section 3, listing sconv2d) at the size that the full run times
+        Isp = torch.randn((32, 64, 56, 56), device="cuda")
+        Wsp = torch.randn((128, 64, 3, 3), device="cuda") * 0.05
+        bsp = torch.randn((128,), device="cuda") * 0.05
+        Osp = torch.empty((32, 128, 27, 27), device="cuda")
         for _ in range(5):
             ops["gconv"][0]()
             dst.copy_(src)
             tc355.tc_tbmm(Xp, Yp, Zp)
+            tc355.tc_sconv2d(Isp, Wsp, bsp, Osp, 2, 2)
         torch.cuda.synchronize()
         print(json.dumps({"traffic_probe": True, "copy_bytes_each_way": src.numel() * 4,
                           "gconv_algorithmic_bytes": ops["gconv"][2],
-                          "tmm_algorithmic_bytes": 4 * (128 * 4096 + 16384 * 4096 + 128 * 16384)}), flush=True)
+                          "tmm_algorithmic_bytes": 4 * (128 * 4096 + 16384 * 4096 + 128 * 16384),
+                          "sconv2d_algorithmic_bytes": inputs.bytes_sconv2d(32, 64, 128, 56, 56, 3, 3, 2, 2)}), flush=True)
         return
 
     if args.sustain > 0:
@@ -368,9 +375,12 @@ def main():
     Ws_ = torch.randn((128, 64, 3, 3), device="cuda") * 0.05
     bs_ = torch.randn((128,), device="cuda") * 0.05
     Os_ = torch.empty((32, 128, 27, 27), device="cuda")
-    extra["sconv2d_32x64x128x56x56_3x3_s2"] = entry(timed(lambda: tc355.tc_sconv2d(Is_, Ws_, bs_, Os_, 2, 2)),
-                                                    inputs.flops_sconv2d(32, 64, 128, 56, 56, 3, 3, 2, 2),
-                                                    inputs.bytes_sconv2d(32, 64, 128, 56, 56, 3, 3, 2, 2))
+    sc_flops, sc_bytes = inputs.flops_sconv2d(32, 64, 128, 56, 56, 3, 3, 2, 2), inputs.bytes_sconv2d(32, 64, 128, 56, 56, 3, 3, 2, 2)
+    # (128 filters of 576 taps: the int8 kernel with 13 digit products; then the fp64 kernel)
+    extra["sconv2d_32x64x128x56x56_3x3_s2"] = entry_i8(timed(lambda: tc355.tc_sconv2d(Is_, Ws_, bs_, Os_, 2, 2)), sc_flops, sc_bytes)
+    extra["sconv2d_32x64x128x56x56_3x3_s2"]["path"] = tc355.last_path()
+    with tc355.option(tc355.TC_OPT_INT8, tc355.TC_INT8_OFF):
+        extra["sconv2d_32x64x128x56x56_3x3_s2_fp64_path"] = entry(timed(lambda: tc355.tc_sconv2d(Is_, Ws_, bs_, Os_, 2, 2)), sc_flops, sc_bytes)
     # lookup-table sums at the paper's size (Section 7, production models: (E,D,L) = (10^7,64,50), batch 128);
     # fresh random indices every call, so that no gathered row is still in a cache from the call before
     E_, D_, B_, L_ = 10**7, 64, 128, 50

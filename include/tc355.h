@@ -68,7 +68,7 @@ int tc355_version(void);
  * thread makes afterwards and race with nothing).  Meant for tests, benchmarks
  * and for callers that know their data; the defaults are safe for any input.
  *   TC_OPT_INT8            arithmetic of the shapes that have an int8 matrix-core
- *                          path (see tc_group_conv, tc_tbmm):
+ *                          path (see tc_group_conv, tc_tbmm, tc_sconv2d):
  *       TC_INT8_AUTO       (default) sliced int8 arithmetic; blocks whose operands
  *                          are heavy-tailed get 13 instead of 10 digit products
  *       TC_INT8_OFF        the fp64 path for every shape
@@ -95,8 +95,8 @@ int64_t tc355_get_option(tc_option key);
 /*
  * Which kernel family the calling thread's most recent entry-point call chose,
  * as a static string "op:family" (for example "tbmm:lds", "tbmm:i8",
- * "mlp:rows", "gconv:i8", "gconv:band", "sconv:tile", "lut:sum"; "" before the
- * first call).  A debugging and testing aid: tests pick the tolerance of the
+ * "mlp:rows", "gconv:i8", "gconv:band", "sconv:i8", "sconv:tile", "lut:sum"; ""
+ * before the first call).  A debugging and testing aid: tests pick the tolerance of the
  * arithmetic that actually ran instead of re-deriving the dispatch.
  */
 const char *tc355_last_path(void);
@@ -299,8 +299,21 @@ tc_status tc_kron(const float *W1, const float *W2, const float *X, float *Y,
  * I: [N,C,H,W]   Wt: [F,C,KH,KW]   bias: [F] or NULL (the first statement
  * then assigns 0)   O: [N,F,OH,OW] with OH = (H-KH)/sh + 1, OW = (W-KW)/sw + 1
  * (integer division; see tc_sconv2d_infer).  sh, sw >= 1; sh = sw = 1 is the
- * plain convolution.  H < KH or W < KW gives TC_ERR_SHAPE.  Arithmetic: fp64,
- * one rounding per output.
+ * plain convolution.  H < KH or W < KW gives TC_ERR_SHAPE.  Arithmetic: fp64
+ * products and sums, one rounding per output -- except for F a multiple of 128
+ * with C*KH*KW a multiple of 4 and at least 256 (I below 2^30 elements, O below
+ * 2^31), which run on the int8 matrix core by the scheme of
+ * tc_tbmm: the reduction index (c,kh,kw), in W's order, is cut into blocks of
+ * 128 (the last one filled with zeros); in every block each filter and each
+ * output pixel's taps are scaled to 0x7F7F7F7E by their own largest magnitude,
+ * rounded to a 32-bit integer and cut into four signed 8-bit digits; the 13
+ * digit products of weight 256^2 and above are summed exactly in int32, scaled
+ * back and added over the blocks in fp64; bias added in fp64, one rounding to
+ * fp32.  Error bound and measured errors as for tc_tbmm (C*KH*KW for K);
+ * TC_OPT_INT8 = TC_INT8_TEN drops the lowest diagonal (10 products),
+ * TC_INT8_OFF keeps the fp64 kernel.  On the int8 path a NaN or an Inf among
+ * an output's own taps, or anywhere in its filter, gives NaN (the exact sum
+ * would give an Inf where every infinite product has the same sign).
  */
 tc_status tc_sconv2d(const float *I, const float *Wt, const float *bias,
                      float *O, int64_t N, int64_t C, int64_t F, int64_t H,

@@ -1,5 +1,5 @@
 // Strided convolution (Section 3, listing sconv2d) on the int8 matrix core, for a multiple of 128 filters and a
-// reduction C * KH * KW that is a multiple of 4:
+// reduction C * KH * KW that is a multiple of 4 (any filter size and strides):
 //
 //   O(n,f,h,w) = B(f) + sum_{c,kh,kw} I(n,c, sh*h + kh, sw*w + kw) * W(f,c,kh,kw)
 //
@@ -35,7 +35,7 @@ struct SconvI8Args {
   const float* Wt;    // [F][C][KH][KW]
   const float* bias;  // [F] or nullptr
   float* O;           // [N][F][OH][OW]
-  int C, F, H, W, sh, sw, OH, OW;
+  int C, F, H, W, KH, KW, sh, sw, OH, OW;
   int K;              // C * KH * KW
   int P;              // N * OH * OW
 };
@@ -52,12 +52,12 @@ struct SconvI8Geom {
   static constexpr int PLANE = ROWS * SI8_RS;
   static constexpr int INVS = 4 * PLANE;             // ROWS inverse scales (fp64)
   static constexpr int RMAX = INVS + ROWS * 8;       // [2][TP] largest magnitudes of the pixels' blocks
-  static constexpr int TABLE = RMAX + 2 * TP * 4;    // [blocks * 128] byte offsets of the taps, -1 past the end
+  static constexpr int TABLE = RMAX + 2 * TP * 4;    // [blocks * 128] byte offsets of the taps, 0 past the end
   static constexpr int64_t lds_bytes(int64_t blocks) { return TABLE + blocks * SI8_KB * 4; }
   static_assert(INVS % 16 == 0 && RMAX % 16 == 0 && TABLE % 16 == 0, "16-byte LDS accesses");
 };
 
-template <int KH, int KW, int NT, int MIND>
+template <int NT, int MIND>
 __global__ __launch_bounds__(SI8_THREADS, 1) void sconv_i8_kernel(SconvI8Args p) {
   static_assert(MIND == 2 || MIND == 3, "13 or 10 digit products");
   static_assert(NT >= 1 && NT <= SI8_MAX_NT, "16 to 64 pixels per workgroup");
@@ -74,14 +74,14 @@ __global__ __launch_bounds__(SI8_THREADS, 1) void sconv_i8_kernel(SconvI8Args p)
   const int OHW = p.OH * p.OW;
   double* invs = reinterpret_cast<double*>(si8_lds + Gm::INVS);
   unsigned* rmax = reinterpret_cast<unsigned*>(si8_lds + Gm::RMAX);
-  int* table = reinterpret_cast<int*>(si8_lds + Gm::TABLE);
+  unsigned* table = reinterpret_cast<unsigned*>(si8_lds + Gm::TABLE);
 
   // ---- the taps' byte offsets from a pixel's first input element, in W's order (c, kh, kw)
   {
-    const int HW = p.H * p.W;
+    const int HW = p.H * p.W, KW = p.KW, KHW = p.KH * p.KW;
     for (int k = tid; k < nb * SI8_KB; k += SI8_THREADS) {
-      const int c = k / (KH * KW), t = k - c * (KH * KW), kh = t / KW, kw = t - kh * KW;
-      table[k] = k < K ? 4 * (c * HW + kh * p.W + kw) : -1;
+      const int c = k / KHW, t = k - c * KHW, kh = t / KW, kw = t - kh * KW;
+      table[k] = k < K ? 4u * (unsigned)(c * HW + kh * p.W + kw) : 0u;  // past the end: any element of I; the value is dropped
     }
     if (tid < 2 * TP) rmax[tid] = 0u;
   }
@@ -125,8 +125,13 @@ __global__ __launch_bounds__(SI8_THREADS, 1) void sconv_i8_kernel(SconvI8Args p)
 #pragma unroll
     for (int i = 0; i < NT; i++)
 #pragma unroll
-      for (int e = 0; e < 4; e++)
-        ry[i][e] = off[e] >= 0 ? *reinterpret_cast<const float*>(src + (ybase[i] + (unsigned)off[e])) : 0.f;
+      for (int e = 0; e < 4; e++) ry[i][e] = *reinterpret_cast<const float*>(src + (ybase[i] + (unsigned)off[e]));
+    if (blk * SI8_KB + SI8_KB > K) {  // the end of the reduction: taps past it count as zeros
+#pragma unroll
+      for (int i = 0; i < NT; i++)
+#pragma unroll
+        for (int e = 0; e < 4; e++) ry[i][e] = blk * SI8_KB + kg + e < K ? ry[i][e] : 0.f;
+    }
   };
   // largest magnitudes of the fetched pixel taps, posted for the block that is staged next (buffer `buf`)
   auto post_max = [&](int buf) {
@@ -205,17 +210,19 @@ __global__ __launch_bounds__(SI8_THREADS, 1) void sconv_i8_kernel(SconvI8Args p)
     i4 d[ND];  // d[i]: diagonal k + l = MIND + i
     auto mma = [&](int i, i4 (&dd)[ND]) {
 #pragma unroll
-      for (int j = 0; j < ND; j++) dd[j] = i4{0, 0, 0, 0};
-#pragma unroll
       for (int s = 0; s < SI8_STEPS; s++) {
         if (s == 1 && one_step) break;
         const char* yb = si8_lds + (SI8_TF + 16 * i + r16) * SI8_RS + 16 * (4 * s + q);
         i4 ya[4];
 #pragma unroll
         for (int k = 0; k < 4; k++) ya[k] = *reinterpret_cast<const i4*>(yb + k * PLANE);
+        bool begun[ND] = {};  // (compile-time after unrolling) the first product of a diagonal starts from a literal zero
 #pragma unroll
-        for (int pr = 0; pr < NP; pr++)
-          dd[PK[pr] + PL[pr] - MIND] = mfma_i8(ya[PK[pr]], xa[s][PL[pr]], dd[PK[pr] + PL[pr] - MIND]);
+        for (int pr = 0; pr < NP; pr++) {
+          const int dg = PK[pr] + PL[pr] - MIND;
+          dd[dg] = mfma_i8(ya[PK[pr]], xa[s][PL[pr]], s == 0 && !begun[dg] ? i4{0, 0, 0, 0} : dd[dg]);
+          begun[dg] = true;
+        }
       }
     };
     auto epilogue = [&](int i, const i4 (&dd)[ND]) {

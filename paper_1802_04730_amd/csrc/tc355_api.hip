@@ -801,15 +801,15 @@ tc_status launch_sconv_i8(const SconvI8Args& a, int64_t blocks, dim3 grid, bool 
   constexpr int kLdsMax = 160 * 1024;
   static std::atomic<int> lds_ok{0};  // more than the default 64 KiB of dynamic LDS
   if (!lds_ok.load(std::memory_order_acquire)) {
-    const void* kernels[2] = {reinterpret_cast<const void*>(sconv_i8_kernel<3, 3, NT, 2>),
-                              reinterpret_cast<const void*>(sconv_i8_kernel<3, 3, NT, 3>)};
+    const void* kernels[2] = {reinterpret_cast<const void*>(sconv_i8_kernel<NT, 2>),
+                              reinterpret_cast<const void*>(sconv_i8_kernel<NT, 3>)};
     for (const void* k : kernels)
       if (hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsMax) != hipSuccess) return TC_ERR_LAUNCH;
     lds_ok.store(1, std::memory_order_release);
   }
   const size_t lds = (size_t)SconvI8Geom<NT>::lds_bytes(blocks);
-  if (ten) sconv_i8_kernel<3, 3, NT, 3><<<grid, dim3(SI8_THREADS), lds, s>>>(a);
-  else sconv_i8_kernel<3, 3, NT, 2><<<grid, dim3(SI8_THREADS), lds, s>>>(a);
+  if (ten) sconv_i8_kernel<NT, 3><<<grid, dim3(SI8_THREADS), lds, s>>>(a);
+  else sconv_i8_kernel<NT, 2><<<grid, dim3(SI8_THREADS), lds, s>>>(a);
   return launch_status();
 }
 
@@ -822,12 +822,12 @@ int64_t sconv_i8_lds_bytes(int nt, int64_t blocks) {
   }
 }
 
-// Takes the call if the shape is one the int8 kernel is built for: 3 x 3 filters, a multiple of 128 of them, a
-// reduction of at least 256 taps (two blocks), operands that 32-bit offsets reach.  Measured faster than the fp64
+// Takes the call if the shape is one the int8 kernel is built for: a multiple of 128 filters, a reduction C * KH * KW
+// that is a multiple of 4 and at least 256 taps (two blocks), operands that 32-bit offsets reach.  Measured faster than the fp64
 // kernel from a single 8 x 8 image up.
-bool try_sconv_i8(const SconvI8Args& a, int64_t N, int KH, int KW, hipStream_t s, tc_status* st) {
+bool try_sconv_i8(const SconvI8Args& a, int64_t N, hipStream_t s, tc_status* st) {
   if (t_opt.int8 == TC_INT8_OFF) return false;
-  if (KH != 3 || KW != 3 || a.F % SI8_TF != 0 || a.K % 4 != 0 || a.K < 256) return false;
+  if (a.F % SI8_TF != 0 || a.K % 4 != 0 || a.K < 256) return false;
   if (prod_reaches({N, a.C, a.H, a.W}, (int64_t)1 << 30)) return false;                 // 32-bit byte offsets into I
   if (prod_reaches({N, a.F, a.OH, a.OW}, (int64_t)1 << 31)) return false;               // 32-bit element offsets into O
   const int64_t blocks = ceil_div(a.K, SI8_KB), units = ceil_div(a.P, 16), fblocks = a.F / SI8_TF;
@@ -998,10 +998,11 @@ tc_status tc_sconv2d(const float* I, const float* Wt, const float* bias, float* 
   {
     SconvI8Args e{};
     e.I = I; e.Wt = Wt; e.bias = bias; e.O = O;
-    e.C = (int)C; e.F = (int)F; e.H = (int)H; e.W = (int)W; e.sh = (int)sh; e.sw = (int)sw; e.OH = (int)OH; e.OW = (int)OW;
+    e.C = (int)C; e.F = (int)F; e.H = (int)H; e.W = (int)W; e.KH = (int)KH; e.KW = (int)KW; e.sh = (int)sh; e.sw = (int)sw;
+    e.OH = (int)OH; e.OW = (int)OW;
     e.K = (int)K; e.P = (int)(N * OH * OW);
     tc_status st = TC_OK;
-    if (try_sconv_i8(e, N, (int)KH, (int)KW, s, &st)) return took("sconv:i8", st);
+    if (try_sconv_i8(e, N, s, &st)) return took("sconv:i8", st);
   }
 
   SconvArgs a{};

@@ -1,7 +1,7 @@
 """GPU parity of the strided convolution and the lookup-table sums (through the C ABI) against the float64 oracle.
 
 Same bar and same tight bound as the other fp64 kernels: one fp32 rounding of the exact result.  Strided
-convolutions with 3 x 3 filters, a multiple of 128 of them and at least 256 taps run on the int8 matrix core
+convolutions with a multiple of 128 filters and at least 256 taps (a multiple of 4) run on the int8 matrix core
 (tc355_last_path says "sconv:i8"); their bound is the int8 scheme's (tests/test_i8_scheme.py derives the budget).
 """
 import numpy as np
@@ -66,23 +66,26 @@ def test_sconv2d(tc, shape, oracle_threads):
 
 
 # Shapes of the int8 kernel: 128 filters x 16 NT pixels per workgroup, NT chosen from the number of pixel tiles per
-# compute unit; reduction in blocks of 128 taps.  (N, C, F, H, W, sh, sw), 3 x 3 filters.
+# compute unit; reduction in blocks of 128 taps.  (N, C, F, H, W, KH, KW, sh, sw)
 SCONV_I8_SHAPES = [
-    (2, 64, 128, 31, 29, 2, 2),     # reduction 576: four blocks and a half one (a single MFMA step); 420 pixels: NT = 1, ragged
-    (3, 32, 128, 20, 23, 1, 1),     # reduction 288: two blocks and 32 taps; 1134 pixels
-    (1, 128, 256, 17, 17, 2, 2),    # two blocks of filters; reduction 1152: nine whole blocks; 64 pixels
-    (2, 36, 128, 40, 41, 3, 2),     # reduction 324 (not a multiple of 16); strides 3 and 2
-    (3, 32, 256, 34, 34, 1, 1),     # 3072 pixels for 128 compute units per filter block: NT = 2
-    (5, 32, 256, 34, 35, 1, 1),     # 5280 pixels: NT = 3, the last workgroup ragged
-    (7, 32, 256, 34, 34, 1, 1),     # 7168 pixels: NT = 4
-    (1, 32, 128, 3, 3, 1, 1),       # one output pixel per filter
+    (2, 64, 128, 31, 29, 3, 3, 2, 2),     # reduction 576: four blocks and a half one (a single MFMA step); 420 pixels: NT = 1, ragged
+    (3, 32, 128, 20, 23, 3, 3, 1, 1),     # reduction 288: two blocks and 32 taps; 1134 pixels
+    (1, 128, 256, 17, 17, 3, 3, 2, 2),    # two blocks of filters; reduction 1152: nine whole blocks; 64 pixels
+    (2, 36, 128, 40, 41, 3, 3, 3, 2),     # reduction 324 (not a multiple of 16); strides 3 and 2
+    (3, 32, 256, 34, 34, 3, 3, 1, 1),     # 3072 pixels for 128 compute units per filter block: NT = 2
+    (5, 32, 256, 34, 35, 3, 3, 1, 1),     # 5280 pixels: NT = 3, the last workgroup ragged
+    (7, 32, 256, 34, 34, 3, 3, 1, 1),     # 7168 pixels: NT = 4
+    (1, 32, 128, 3, 3, 3, 3, 1, 1),       # one output pixel per filter
+    (2, 256, 128, 9, 11, 1, 1, 2, 1),     # 1 x 1 filters: channel mixing and subsampling, two whole blocks
+    (1, 12, 128, 21, 20, 7, 7, 2, 2),     # 7 x 7 stride 2: reduction 588
+    (2, 20, 128, 14, 19, 5, 3, 1, 2),     # 5 x 3 filters: reduction 300
 ]
 
 
 @pytest.mark.parametrize("shape", SCONV_I8_SHAPES)
 def test_sconv2d_int8_kernel(tc, shape, oracle_threads):
-    N, C, F, H, W, sh, sw = shape
-    I, Wt, bias = inputs.make_sconv2d(N, C, F, H, W, 3, 3, seed=inputs.SEED_BASE + 60 + C)
+    N, C, F, H, W, KH, KW, sh, sw = shape
+    I, Wt, bias = inputs.make_sconv2d(N, C, F, H, W, KH, KW, seed=inputs.SEED_BASE + 60 + C)
     ref = oracle.sconv2d(I, Wt, bias, sh, sw)
     n = ref.size
     buf = torch.full((n + 512,), 7.0, device="cuda")
@@ -376,7 +379,7 @@ def test_seeded_random_shapes_through_every_entry_point(tc, oracle_threads):
         verify(buf, Og, oracle.group_conv(I, Wg, bg), "gconv %s" % (shp,))
         # strided convolution
         if it % 2 == 0: shp = (ri(1, 3), ri(1, 30), ri(1, 100), ri(5, 30), ri(5, 30), ri(1, 4), ri(1, 4), ri(1, 3), ri(1, 3))
-        else: shp = (ri(1, 3), 4 * ri(8, 24), 128 * ri(1, 2), ri(5, 30), ri(5, 30), 3, 3, ri(1, 3), ri(1, 3))  # the int8 kernel's range
+        else: shp = (ri(1, 3), 4 * ri(8, 24), 128 * ri(1, 2), ri(5, 30), ri(5, 30), ri(3, 4), ri(3, 4), ri(1, 3), ri(1, 3))  # the int8 kernel's range
         N_, C, F, H, W, KH, KW, sh, sw = shp
         Is, Wt, bs_ = inputs.make_sconv2d(N_, C, F, H, W, KH, KW, seed=2000 + it)
         ref = oracle.sconv2d(Is, Wt, bs_, sh, sw)

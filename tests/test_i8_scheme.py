@@ -277,3 +277,24 @@ def test_transposed_matmul_heavy_tailed_operands():
     assert PARITY_BAR / 4 < worst <= PARITY_BAR, worst
     diag = 2
     assert max(case(seed, 2.0, 2.0) for seed in (0, 3, 4, 5)) <= PARITY_BAR / 10
+
+
+def test_strided_convolution_as_a_transposed_matmul_over_gathered_taps():
+    """The int8 strided convolution is the transposed matmul's scheme with the filters as one operand and every
+    output pixel's taps, gathered in the filters' own order (c, kh, kw), as the other; a reduction that is no
+    multiple of 128 ends in a partial block (zeros scale nothing).  Emulated by gathering the taps in numpy and
+    running the blocks of 128; 13 digit products, the kernel's default."""
+    N, C, F, H, W, sh, sw = 2, 36, 16, 13, 15, 2, 1           # 324 taps: two blocks and 68 taps
+    I, Wt, bias = inputs.make_sconv2d(N, C, F, H, W, 3, 3, seed=91)
+    ref = oracle.sconv2d(I, Wt, bias, sh, sw)
+    OH, OW = ref.shape[2:]
+    taps = np.empty((N, OH, OW, C, 3, 3), dtype=np.float32)
+    for h in range(OH):
+        for w in range(OW):
+            taps[:, h, w] = I[:, :, sh * h:sh * h + 3, sw * w:sw * w + 3]
+    got = emulate_tmm(Wt.reshape(F, -1), taps.reshape(N * OH * OW, -1), min_diagonal=2)       # [F, pixels], rounded to fp32
+    # (the kernel adds the bias in fp64 before its one rounding; here it is added to the rounded sum, which costs at
+    # most one more rounding of the bound below)
+    got = (got + bias[:, None].astype(np.float64)).reshape(F, N, OH, OW).transpose(1, 0, 2, 3)
+    err = parity_error(got, ref)
+    assert err <= 1e-6, err
