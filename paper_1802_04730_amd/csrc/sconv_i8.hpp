@@ -104,37 +104,35 @@ __global__ __launch_bounds__(SI8_THREADS, 1) void sconv_i8_kernel(SconvI8Args p)
   }
   f4 ry[NT];
 
-  auto fetch = [&](int blk) {
-    const float* xs = xsrc + blk * SI8_KB;
+  auto fetch_x = [&](int blk, int s) {  // step s (64 taps) of the block
+    const float* xs = xsrc + blk * SI8_KB + 64 * s;
     if (blk * SI8_KB + SI8_KB <= K) {
 #pragma unroll
-      for (int s = 0; s < SI8_STEPS; s++)
-#pragma unroll
-        for (int j = 0; j < 4; j++) rx[s][j] = *reinterpret_cast<const f4*>(xs + 64 * s + 16 * j);
+      for (int j = 0; j < 4; j++) rx[s][j] = *reinterpret_cast<const f4*>(xs + 16 * j);
     } else {
 #pragma unroll
-      for (int s = 0; s < SI8_STEPS; s++)
-#pragma unroll
-        for (int j = 0; j < 4; j++) {
-          const bool in = blk * SI8_KB + 64 * s + 16 * j + 4 * cx < K;  // K is a multiple of 4: whole pieces
-          rx[s][j] = in ? *reinterpret_cast<const f4*>(xs + 64 * s + 16 * j) : f4{0.f, 0.f, 0.f, 0.f};
-        }
+      for (int j = 0; j < 4; j++) {
+        const bool in = blk * SI8_KB + 64 * s + 16 * j + 4 * cx < K;  // K is a multiple of 4: whole pieces
+        rx[s][j] = in ? *reinterpret_cast<const f4*>(xs + 16 * j) : f4{0.f, 0.f, 0.f, 0.f};
+      }
     }
+  };
+  auto fetch_y = [&](int blk) {
     const i4 off = *reinterpret_cast<const i4*>(table + blk * SI8_KB + kg);
     const char* src = reinterpret_cast<const char*>(p.I);
 #pragma unroll
     for (int i = 0; i < NT; i++)
 #pragma unroll
       for (int e = 0; e < 4; e++) ry[i][e] = *reinterpret_cast<const float*>(src + (ybase[i] + (unsigned)off[e]));
+  };
+  // largest magnitudes of the fetched pixel taps, posted for the block that is staged next (buffer `buf`)
+  auto post_max = [&](int buf, int blk) {
     if (blk * SI8_KB + SI8_KB > K) {  // the end of the reduction: taps past it count as zeros
 #pragma unroll
       for (int i = 0; i < NT; i++)
 #pragma unroll
         for (int e = 0; e < 4; e++) ry[i][e] = blk * SI8_KB + kg + e < K ? ry[i][e] : 0.f;
     }
-  };
-  // largest magnitudes of the fetched pixel taps, posted for the block that is staged next (buffer `buf`)
-  auto post_max = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < NT; i++) {
       int sm = 0;
@@ -144,34 +142,34 @@ __global__ __launch_bounds__(SI8_THREADS, 1) void sconv_i8_kernel(SconvI8Args p)
                              __HIP_MEMORY_SCOPE_WORKGROUP);
     }
   };
-  auto slice = [&](int buf) {
-    {  // filters: 16 elements per step, row shared by the 4 lanes of a quad
-      int sm = 0;
-      unsigned um = 0;
+  double xscale;  // of this thread's filter in the block being staged
+  auto scale_x = [&]() {  // filters: row shared by the 4 lanes of a quad
+    int sm = 0;
+    unsigned um = 0;
 #pragma unroll
-      for (int s = 0; s < SI8_STEPS; s++)
+    for (int s = 0; s < SI8_STEPS; s++)
 #pragma unroll
-        for (int j = 0; j < 4; j++) gi8_absmax4(rx[s][j], sm, um);
-      int v = gi8_magnitude(sm, um);
-      v = max(v, __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false));  // quad_perm [1,0,3,2]
-      v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false));  // quad_perm [2,3,0,1]
-      double scale, inverse;
-      gi8_scales((unsigned)v, scale, inverse);
+      for (int j = 0; j < 4; j++) gi8_absmax4(rx[s][j], sm, um);
+    int v = gi8_magnitude(sm, um);
+    v = max(v, __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false));  // quad_perm [1,0,3,2]
+    v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false));  // quad_perm [2,3,0,1]
+    double inverse;
+    gi8_scales((unsigned)v, xscale, inverse);
+    invs[xrow] = inverse;  // the four lanes of the row write the same value
+  };
+  auto slice_x = [&](int s) {  // 16 elements of step s
+    int y[4][4];
 #pragma unroll
-      for (int s = 0; s < SI8_STEPS; s++) {
-        int y[4][4];
+    for (int j = 0; j < 4; j++) gi8_digits4(rx[s][j], xscale, y[j]);
+    char* dst = si8_lds + xrow * SI8_RS + 16 * (4 * s + cx);
 #pragma unroll
-        for (int j = 0; j < 4; j++) gi8_digits4(rx[s][j], scale, y[j]);
-        char* dst = si8_lds + xrow * SI8_RS + 16 * (4 * s + cx);
-#pragma unroll
-        for (int k = 0; k < 4; k++) {
-          i4 rec;
-          rec.x = y[0][k]; rec.y = y[1][k]; rec.z = y[2][k]; rec.w = y[3][k];
-          *reinterpret_cast<i4*>(dst + k * PLANE) = rec;
-        }
-      }
-      invs[xrow] = inverse;  // the four lanes of the row write the same value
+    for (int k = 0; k < 4; k++) {
+      i4 rec;
+      rec.x = y[0][k]; rec.y = y[1][k]; rec.z = y[2][k]; rec.w = y[3][k];
+      *reinterpret_cast<i4*>(dst + k * PLANE) = rec;
     }
+  };
+  auto slice_y = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < NT; i++) {  // pixels: 4 elements, row shared by 32 threads
       const int row = 16 * i + pl;
@@ -244,16 +242,28 @@ __global__ __launch_bounds__(SI8_THREADS, 1) void sconv_i8_kernel(SconvI8Args p)
   };
 
   __syncthreads();  // the table
-  fetch(0);
-  post_max(0);
+  fetch_x(0, 0);
+  fetch_x(0, 1);
+  fetch_y(0);
+  post_max(0, 0);
   __syncthreads();
   for (int t = 0; t < nb; t++) {
-    slice(t & 1);
-    __builtin_amdgcn_sched_barrier(0);  // the next block's loads only once this block's registers are free
-    if (t + 1 < nb) fetch(t + 1);
+    // the next block's loads as soon as this block's registers are free: the gathers' address work (8 clocks per
+    // instruction and compute unit) runs under the filters' slicing
+    slice_y(t & 1);
+    __builtin_amdgcn_sched_barrier(0);
+    if (t + 1 < nb) fetch_y(t + 1);
+    scale_x();
+    slice_x(0);
+    slice_x(1);
+    __builtin_amdgcn_sched_barrier(0);
+    if (t + 1 < nb) {  // (a step's loads right after that step's slicing measured 1-2 % slower)
+      fetch_x(t + 1, 0);
+      fetch_x(t + 1, 1);
+    }
     __syncthreads();
     contract(K - t * SI8_KB <= 64);
-    if (t + 1 < nb) post_max((t + 1) & 1);
+    if (t + 1 < nb) post_max((t + 1) & 1, t + 1);
     __syncthreads();
   }
 
