@@ -300,7 +300,7 @@ tc_status tc_kron(const float *W1, const float *W2, const float *X, float *Y,
  * then assigns 0)   O: [N,F,OH,OW] with OH = (H-KH)/sh + 1, OW = (W-KW)/sw + 1
  * (integer division; see tc_sconv2d_infer).  sh, sw >= 1; sh = sw = 1 is the
  * plain convolution.  H < KH or W < KW gives TC_ERR_SHAPE.  Arithmetic: fp64
- * products and sums, one rounding per output -- except for F a multiple of 128
+ * products and sums, one rounding per output -- except for F a multiple of 64
  * with C*KH*KW a multiple of 4 and at least 256 (I below 2^30 elements, O below
  * 2^31), which run on the int8 matrix core by the scheme of
  * tc_tbmm: the reduction index (c,kh,kw), in W's order, is cut into blocks of

@@ -795,58 +795,68 @@ tc_status mlp_run(const float* I, int64_t batch, int32_t n_layers, const int64_t
   return took("mlp:per_layer", TC_OK);
 }
 
-// Strided convolution on the int8 matrix core (sconv_i8.hpp): 128 filters against 16 * NT pixels per workgroup.
-template <int NT>
+// Strided convolution on the int8 matrix core (sconv_i8.hpp): TF filters against 16 * NT pixels per workgroup.
+template <int TF, int NT>
 tc_status launch_sconv_i8(const SconvI8Args& a, int64_t blocks, dim3 grid, bool ten, hipStream_t s) {
   constexpr int kLdsMax = 160 * 1024;
   static std::atomic<int> lds_ok{0};  // more than the default 64 KiB of dynamic LDS
   if (!lds_ok.load(std::memory_order_acquire)) {
-    const void* kernels[2] = {reinterpret_cast<const void*>(sconv_i8_kernel<NT, 2>),
-                              reinterpret_cast<const void*>(sconv_i8_kernel<NT, 3>)};
+    const void* kernels[2] = {reinterpret_cast<const void*>(sconv_i8_kernel<TF, NT, 2>),
+                              reinterpret_cast<const void*>(sconv_i8_kernel<TF, NT, 3>)};
     for (const void* k : kernels)
       if (hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsMax) != hipSuccess) return TC_ERR_LAUNCH;
     lds_ok.store(1, std::memory_order_release);
   }
-  const size_t lds = (size_t)SconvI8Geom<NT>::lds_bytes(blocks);
-  if (ten) sconv_i8_kernel<NT, 3><<<grid, dim3(SI8_THREADS), lds, s>>>(a);
-  else sconv_i8_kernel<NT, 2><<<grid, dim3(SI8_THREADS), lds, s>>>(a);
+  const size_t lds = (size_t)SconvI8Geom<TF, NT>::lds_bytes(blocks);
+  if (lds > (size_t)kLdsMax) return TC_ERR_LAUNCH;  // (the caller has checked)
+  if (ten) sconv_i8_kernel<TF, NT, 3><<<grid, dim3(SI8_THREADS), lds, s>>>(a);
+  else sconv_i8_kernel<TF, NT, 2><<<grid, dim3(SI8_THREADS), lds, s>>>(a);
   return launch_status();
 }
 
-int64_t sconv_i8_lds_bytes(int nt, int64_t blocks) {
-  switch (nt) {
-    case 1: return SconvI8Geom<1>::lds_bytes(blocks);
-    case 2: return SconvI8Geom<2>::lds_bytes(blocks);
-    case 3: return SconvI8Geom<3>::lds_bytes(blocks);
-    default: return SconvI8Geom<4>::lds_bytes(blocks);
-  }
+// LDS bytes of the kernel for tf filters and nt pixel tiles per workgroup (the geometry depends on tf + 16 nt only)
+int64_t sconv_i8_lds_bytes(int tf, int nt, int64_t blocks) {
+  const int64_t rows = tf + 16 * nt;
+  return 4 * rows * SI8_RS + rows * 8 + 2 * 16 * nt * 4 + blocks * SI8_KB * 4;
 }
 
-// Takes the call if the shape is one the int8 kernel is built for: a multiple of 128 filters, a reduction C * KH * KW
-// that is a multiple of 4 and at least 256 taps (two blocks), operands that 32-bit offsets reach.  Measured faster than the fp64
-// kernel from a single 8 x 8 image up.
+// Takes the call if the shape is one the int8 kernel is built for: a multiple of 64 filters, a reduction C * KH * KW
+// that is a multiple of 4 and at least 256 taps (two blocks), operands that 32-bit offsets reach.  Measured faster
+// than the fp64 kernel from a single 8 x 8 image up.
 bool try_sconv_i8(const SconvI8Args& a, int64_t N, hipStream_t s, tc_status* st) {
   if (t_opt.int8 == TC_INT8_OFF) return false;
-  if (a.F % SI8_TF != 0 || a.K % 4 != 0 || a.K < 256) return false;
+  if (a.F % 64 != 0 || a.K % 4 != 0 || a.K < 256) return false;
   if (prod_reaches({N, a.C, a.H, a.W}, (int64_t)1 << 30)) return false;                 // 32-bit byte offsets into I
   if (prod_reaches({N, a.F, a.OH, a.OW}, (int64_t)1 << 31)) return false;               // 32-bit element offsets into O
-  const int64_t blocks = ceil_div(a.K, SI8_KB), units = ceil_div(a.P, 16), fblocks = a.F / SI8_TF;
+  // 128 filters per workgroup and 1 .. 4 pixel tiles, or (a multiple of 64 filters only) 64 filters and 2, 4, 6, 8
+  const int tf = a.F % 128 == 0 ? 128 : 64, nt_step = tf == 128 ? 1 : 2, nt_max = 4 * nt_step;
+  const int64_t blocks = ceil_div(a.K, SI8_KB), units = ceil_div(a.P, 16), fblocks = a.F / tf;
   // pixel tiles per workgroup: as few rounds of workgroups as the largest tile allows, then the smallest tile
   // that still makes that number of rounds
   const int64_t per_round = std::max<int64_t>(1, device_cus() / fblocks);
-  const int64_t rounds = ceil_div(units, SI8_MAX_NT * per_round);
-  int nt = (int)std::min<int64_t>(SI8_MAX_NT, std::max<int64_t>(1, ceil_div(units, rounds * per_round)));
-  while (nt > 1 && sconv_i8_lds_bytes(nt, blocks) > 160 * 1024) nt--;
-  if (sconv_i8_lds_bytes(nt, blocks) > 160 * 1024) return false;
+  const int64_t rounds = ceil_div(units, nt_max * per_round);
+  int nt = (int)ceil_div(ceil_div(units, rounds * per_round), nt_step) * nt_step;
+  nt = std::min(nt_max, std::max(nt_step, nt));
+  while (nt > nt_step && sconv_i8_lds_bytes(tf, nt, blocks) > 160 * 1024) nt -= nt_step;
+  if (sconv_i8_lds_bytes(tf, nt, blocks) > 160 * 1024) return false;
   const int64_t gx = ceil_div(units, nt);
   if (gx > kMaxGrid || fblocks > 65535) return false;
   const dim3 grid((unsigned)gx, (unsigned)fblocks);
   const bool ten = t_opt.int8 == TC_INT8_TEN;  // 13 digit products unless the caller has said that 10 will do
-  switch (nt) {
-    case 1: *st = launch_sconv_i8<1>(a, blocks, grid, ten, s); break;
-    case 2: *st = launch_sconv_i8<2>(a, blocks, grid, ten, s); break;
-    case 3: *st = launch_sconv_i8<3>(a, blocks, grid, ten, s); break;
-    default: *st = launch_sconv_i8<4>(a, blocks, grid, ten, s); break;
+  if (tf == 128) {
+    switch (nt) {
+      case 1: *st = launch_sconv_i8<128, 1>(a, blocks, grid, ten, s); break;
+      case 2: *st = launch_sconv_i8<128, 2>(a, blocks, grid, ten, s); break;
+      case 3: *st = launch_sconv_i8<128, 3>(a, blocks, grid, ten, s); break;
+      default: *st = launch_sconv_i8<128, 4>(a, blocks, grid, ten, s); break;
+    }
+  } else {
+    switch (nt) {
+      case 2: *st = launch_sconv_i8<64, 2>(a, blocks, grid, ten, s); break;
+      case 4: *st = launch_sconv_i8<64, 4>(a, blocks, grid, ten, s); break;
+      case 6: *st = launch_sconv_i8<64, 6>(a, blocks, grid, ten, s); break;
+      default: *st = launch_sconv_i8<64, 8>(a, blocks, grid, ten, s); break;
+    }
   }
   return true;
 }

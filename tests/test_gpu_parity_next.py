@@ -1,7 +1,7 @@
 """GPU parity of the strided convolution and the lookup-table sums (through the C ABI) against the float64 oracle.
 
 Same bar and same tight bound as the other fp64 kernels: one fp32 rounding of the exact result.  Strided
-convolutions with a multiple of 128 filters and at least 256 taps (a multiple of 4) run on the int8 matrix core
+convolutions with a multiple of 64 filters and at least 256 taps (a multiple of 4) run on the int8 matrix core
 (tc355_last_path says "sconv:i8"); their bound is the int8 scheme's (tests/test_i8_scheme.py derives the budget).
 """
 import numpy as np
@@ -65,8 +65,8 @@ def test_sconv2d(tc, shape, oracle_threads):
     check(O, ref, "sconv2d %s" % (shape,))
 
 
-# Shapes of the int8 kernel: 128 filters x 16 NT pixels per workgroup, NT chosen from the number of pixel tiles per
-# compute unit; reduction in blocks of 128 taps.  (N, C, F, H, W, KH, KW, sh, sw)
+# Shapes of the int8 kernel: 128 (or 64) filters x 16 NT pixels per workgroup, NT chosen from the number of pixel tiles
+# per compute unit; reduction in blocks of 128 taps.  (N, C, F, H, W, KH, KW, sh, sw)
 SCONV_I8_SHAPES = [
     (2, 64, 128, 31, 29, 3, 3, 2, 2),     # reduction 576: four blocks and a half one (a single MFMA step); 420 pixels: NT = 1, ragged
     (3, 32, 128, 20, 23, 3, 3, 1, 1),     # reduction 288: two blocks and 32 taps; 1134 pixels
@@ -79,6 +79,11 @@ SCONV_I8_SHAPES = [
     (2, 256, 128, 9, 11, 1, 1, 2, 1),     # 1 x 1 filters: channel mixing and subsampling, two whole blocks
     (1, 12, 128, 21, 20, 7, 7, 2, 2),     # 7 x 7 stride 2: reduction 588
     (2, 20, 128, 14, 19, 5, 3, 1, 2),     # 5 x 3 filters: reduction 300
+    (2, 64, 64, 20, 21, 3, 3, 1, 1),      # 64 filters: workgroups of 64 filters x 32 pixels (NT = 2), four and a half blocks
+    (8, 32, 64, 40, 40, 3, 3, 1, 1),      # 64 filters, 11552 pixels: NT = 4
+    (6, 32, 192, 34, 34, 3, 3, 1, 1),     # 192 filters = three blocks of 64, 85 compute units each: NT = 6
+    (20, 32, 64, 40, 40, 3, 3, 1, 1),     # 64 filters, 28880 pixels: NT = 8, the last workgroup ragged
+    (1, 72, 320, 9, 9, 2, 2, 1, 2),       # 320 filters = five blocks of 64; 2 x 2 filters
 ]
 
 
@@ -379,7 +384,7 @@ def test_seeded_random_shapes_through_every_entry_point(tc, oracle_threads):
         verify(buf, Og, oracle.group_conv(I, Wg, bg), "gconv %s" % (shp,))
         # strided convolution
         if it % 2 == 0: shp = (ri(1, 3), ri(1, 30), ri(1, 100), ri(5, 30), ri(5, 30), ri(1, 4), ri(1, 4), ri(1, 3), ri(1, 3))
-        else: shp = (ri(1, 3), 4 * ri(8, 24), 128 * ri(1, 2), ri(5, 30), ri(5, 30), ri(3, 4), ri(3, 4), ri(1, 3), ri(1, 3))  # the int8 kernel's range
+        else: shp = (ri(1, 3), 4 * ri(8, 24), 64 * ri(1, 4), ri(5, 30), ri(5, 30), ri(3, 4), ri(3, 4), ri(1, 3), ri(1, 3))  # the int8 kernel's range
         N_, C, F, H, W, KH, KW, sh, sw = shp
         Is, Wt, bs_ = inputs.make_sconv2d(N_, C, F, H, W, KH, KW, seed=2000 + it)
         ref = oracle.sconv2d(Is, Wt, bs_, sh, sw)
