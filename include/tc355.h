@@ -301,8 +301,8 @@ tc_status tc_kron(const float *W1, const float *W2, const float *X, float *Y,
  * (integer division; see tc_sconv2d_infer).  sh, sw >= 1; sh = sw = 1 is the
  * plain convolution.  H < KH or W < KW gives TC_ERR_SHAPE.  Arithmetic: fp64
  * products and sums, one rounding per output -- except for F a multiple of 64
- * with C*KH*KW a multiple of 4 and at least 256 (I below 2^30 elements, O below
- * 2^31), which run on the int8 matrix core by the scheme of
+ * with C*KH*KW a multiple of 4, at least 256 and at most about 17,000 (I below
+ * 2^30 elements, O below 2^31), which run on the int8 matrix core by the scheme of
  * tc_tbmm: the reduction index (c,kh,kw), in W's order, is cut into blocks of
  * 128 (the last one filled with zeros); in every block each filter and each
  * output pixel's taps are scaled to 0x7F7F7F7E by their own largest magnitude,

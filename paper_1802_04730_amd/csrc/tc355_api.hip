@@ -821,8 +821,9 @@ int64_t sconv_i8_lds_bytes(int tf, int nt, int64_t blocks) {
 }
 
 // Takes the call if the shape is one the int8 kernel is built for: a multiple of 64 filters, a reduction C * KH * KW
-// that is a multiple of 4 and at least 256 taps (two blocks), operands that 32-bit offsets reach.  Measured faster
-// than the fp64 kernel from a single 8 x 8 image up.
+// that is a multiple of 4 and at least 256 taps (two blocks), operands that 32-bit offsets reach, a table of tap
+// offsets that fits LDS beside the digit planes (about 17,000 taps).  Measured faster than the fp64 kernel from a
+// single 8 x 8 image up.
 bool try_sconv_i8(const SconvI8Args& a, int64_t N, hipStream_t s, tc_status* st) {
   if (t_opt.int8 == TC_INT8_OFF) return false;
   if (a.F % 64 != 0 || a.K % 4 != 0 || a.K < 256) return false;
