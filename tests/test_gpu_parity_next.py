@@ -50,6 +50,7 @@ SCONV_SHAPES = [
     (1, 1, 1, 3, 3, 3, 3, 5, 5),         # a single output element
     (4, 64, 96, 20, 20, 3, 3, 2, 2),     # many chunks (reduction 576), 64 x 64 blocks, the second filter block half full
     (2, 28, 128, 20, 20, 3, 3, 1, 1),    # 128 filters but only 252 taps: below the int8 kernel's two blocks
+    (1, 2048, 128, 4, 3, 3, 3, 1, 1),    # 18432 taps: the int8 kernel's table of tap offsets would not fit LDS
     (2, 6, 10, 9, 40, 2, 5, 1, 4),       # wide stride along w only
 ]
 
@@ -84,6 +85,7 @@ SCONV_I8_SHAPES = [
     (6, 32, 192, 34, 34, 3, 3, 1, 1),     # 192 filters = three blocks of 64, 85 compute units each: NT = 6
     (20, 32, 64, 40, 40, 3, 3, 1, 1),     # 64 filters, 28880 pixels: NT = 8, the last workgroup ragged
     (1, 72, 320, 9, 9, 2, 2, 1, 2),       # 320 filters = five blocks of 64; 2 x 2 filters
+    (1, 1900, 128, 3, 4, 3, 3, 1, 1),     # 17100 taps: 134 blocks, the longest reduction the kernel takes at 128 filters
 ]
 
 
