@@ -95,7 +95,8 @@ int64_t tc355_get_option(tc_option key);
 /*
  * Which kernel family the calling thread's most recent entry-point call chose,
  * as a static string "op:family" (for example "tbmm:lds", "tbmm:i8",
- * "mlp:rows", "gconv:i8", "gconv:band", "sconv:i8", "sconv:tile", "lut:sum"; ""
+ * "mlp:rows", "gconv:i8", "gconv:i8_taps", "gconv:band", "sconv:i8", "sconv:tile",
+ * "lut:sum"; ""
  * before the first call).  A debugging and testing aid: tests pick the tolerance of the
  * arithmetic that actually ran instead of re-deriving the dispatch.
  */
@@ -265,6 +266,12 @@ tc_status tc_mlp_fcrelu_static(const float *I, int64_t batch, int32_t n_layers,
  * measured with log-normal magnitudes of sigma 1.5 and 1), TC_INT8_THIRTEEN
  * always does, TC_INT8_OFF takes the fp64 path.  A band that holds Inf or NaN
  * gives NaN in all outputs that read the band.
+ * Groups with F a multiple of 64 and C*KH*KW a multiple of 4 and at least 256
+ * (G = 1 with such extents is the plain convolution of Section 3) run on the
+ * int8 kernel of tc_sconv2d with stride 1, one group after the other in one
+ * launch: its arithmetic (blocks of 128 taps, a scale per filter and per
+ * output pixel in every block, 13 digit products; TC_INT8_TEN: 10), its
+ * limits and its Inf/NaN behaviour are described there.
  */
 tc_status tc_group_conv(const float *I, const float *W1, const float *bias,
                         float *O, int64_t N, int64_t G, int64_t C, int64_t F,

@@ -26,6 +26,9 @@
 // pixel tiles (all NT of them at 128 filters; at 64 filters the tiles i with i % 2 = w / 4); MFMA rows = pixels,
 // columns = filters, so a lane ends up with 4 consecutive pixels of one filter.
 //
+// Groups (the grouped convolution of Section 7 with stride 1): blockIdx.z is the group; a group's channels, filters
+// and outputs are contiguous slices of I, Wt, bias and O, so only base offsets change.
+//
 // A filter or a pixel whose taps hold Inf or NaN gives NaN in every output of that filter (pixel).
 #pragma once
 #include "gemm_i8.hpp"
@@ -33,11 +36,12 @@
 namespace tc355 {
 
 struct SconvI8Args {
-  const float* I;     // [N][C][H][W], fewer than 2^30 elements
+  const float* I;     // [N][C][H][W] (G = 1), fewer than 2^30 elements
   const float* Wt;    // [F][C][KH][KW]
   const float* bias;  // [F] or nullptr
   float* O;           // [N][F][OH][OW]
   int C, F, H, W, KH, KW, sh, sw, OH, OW;
+  int G;              // groups (blockIdx.z): I is [N][G][C][H][W], Wt [G][F][C][KH][KW], bias [G * F], O [N][G][F][OH][OW]
   int K;              // C * KH * KW
   int P;              // N * OH * OW
 };
@@ -81,6 +85,7 @@ __global__ __launch_bounds__(SI8_THREADS, 1) void sconv_i8_kernel(SconvI8Args p)
   const int f0 = blockIdx.y * TF;
   const int p0 = blockIdx.x * TP;
   const int OHW = p.OH * p.OW;
+  const int G = p.G, grp = blockIdx.z;
   double* invs = reinterpret_cast<double*>(si8_lds + Gm::INVS);
   unsigned* rmax = reinterpret_cast<unsigned*>(si8_lds + Gm::RMAX);
   unsigned* table = reinterpret_cast<unsigned*>(si8_lds + Gm::TABLE);
@@ -99,7 +104,7 @@ __global__ __launch_bounds__(SI8_THREADS, 1) void sconv_i8_kernel(SconvI8Args p)
   // of step s holds tap 64 s + 16 j + 4 c + e of the block.  With 128 filters a thread stages both steps, with 64
   // the step xs0 only.
   const int xrow = tid / TPR, cx = tid & 3, xs0 = XS == 2 ? 0 : (tid >> 2) & 1;
-  const float* xsrc = p.Wt + (int64_t)(f0 + xrow) * K + 4 * cx;
+  const float* xsrc = p.Wt + ((int64_t)grp * p.F + f0 + xrow) * K + 4 * cx;
   f4 rx[XS][4];
   // ---- staging role, pixels: taps 64 s + 16 j + 4 c .. + 3 of the block (group g = (s, j, c)) of pixels 16 i + pl
   const int g = tid >> 4, pl = tid & 15;
@@ -110,7 +115,7 @@ __global__ __launch_bounds__(SI8_THREADS, 1) void sconv_i8_kernel(SconvI8Args p)
   for (int i = 0; i < NT; i++) {
     const int pi = min(p0 + 16 * i + pl, p.P - 1);  // pixels past the end repeat the last one (never stored)
     const int img = pi / OHW, rem = pi - img * OHW, oh = rem / p.OW, ow = rem - oh * p.OW;
-    ybase[i] = 4u * (unsigned)((img * p.C * p.H + oh * p.sh) * p.W + ow * p.sw);
+    ybase[i] = 4u * (unsigned)(((img * G + grp) * p.C * p.H + oh * p.sh) * p.W + ow * p.sw);
   }
   f4 ry[NT];
 
@@ -287,14 +292,14 @@ __global__ __launch_bounds__(SI8_THREADS, 1) void sconv_i8_kernel(SconvI8Args p)
   int* pxoff = reinterpret_cast<int*>(si8_lds + TF * OS * 4);  // [TP] offset of (image, pixel) in O for filter 0, -1 past the end
   static_assert(TF * OS * 4 + TP * 4 <= Gm::INVS, "the output stage fits the digit planes");
   {
-    const double bz = p.bias ? (double)p.bias[f0 + 16 * ft + r16] : 0.0;
+    const double bz = p.bias ? (double)p.bias[grp * p.F + f0 + 16 * ft + r16] : 0.0;
 #pragma unroll
     for (int i = 0; i < NTW; i++)
 #pragma unroll
       for (int v = 0; v < 4; v++) ostage[(16 * ft + r16) * OS + 16 * (pg + PG * i) + 4 * q + v] = (float)(acc[i][v] + bz);
     if (tid < TP) {
       const int pi = p0 + tid, img = pi / OHW, rem = pi - img * OHW;
-      pxoff[tid] = pi < p.P ? img * p.F * OHW + rem : -1;
+      pxoff[tid] = pi < p.P ? (img * G + grp) * p.F * OHW + rem : -1;
     }
   }
   __syncthreads();

@@ -795,6 +795,24 @@ tc_status mlp_run(const float* I, int64_t batch, int32_t n_layers, const int64_t
   return took("mlp:per_layer", TC_OK);
 }
 
+// Strided convolution on the fp64 matrix core (sconv_tile.hpp): blocks of 64 filters x 64 or 32 pixels.
+tc_status launch_sconv_tile(SconvArgs a, hipStream_t s) {
+  a.tiles_f = (int)ceil_div(a.F, SC_BF);
+  // 64-pixel blocks when there are at least two of them per compute unit, else 32-pixel blocks (twice as many)
+  const bool wide = (int64_t)a.tiles_f * ceil_div(a.P, 64) >= 2 * (int64_t)std::max(1, device_cus());
+  const int64_t grid = (int64_t)a.tiles_f * ceil_div(a.P, wide ? 64 : 32);
+  if (grid > kMaxGrid) return TC_ERR_UNSUPPORTED;
+  const dim3 gd((unsigned)grid), bd(WG_THREADS);
+  if (wide) {
+    if (a.K % 4 == 0) sconv_tile_kernel<4, 64><<<gd, bd, SconvGeom<64>::LDS_BYTES, s>>>(a);
+    else sconv_tile_kernel<1, 64><<<gd, bd, SconvGeom<64>::LDS_BYTES, s>>>(a);
+  } else {
+    if (a.K % 4 == 0) sconv_tile_kernel<4, 32><<<gd, bd, SconvGeom<32>::LDS_BYTES, s>>>(a);
+    else sconv_tile_kernel<1, 32><<<gd, bd, SconvGeom<32>::LDS_BYTES, s>>>(a);
+  }
+  return launch_status();
+}
+
 // Strided convolution on the int8 matrix core (sconv_i8.hpp): TF filters against 16 * NT pixels per workgroup.
 template <int TF, int NT>
 tc_status launch_sconv_i8(const SconvI8Args& a, int64_t blocks, dim3 grid, bool ten, hipStream_t s) {
@@ -824,17 +842,18 @@ int64_t sconv_i8_lds_bytes(int tf, int nt, int64_t blocks) {
 // that is a multiple of 4 and at least 256 taps (two blocks), operands that 32-bit offsets reach, a table of tap
 // offsets that fits LDS beside the digit planes (about 17,000 taps).  Measured faster than the fp64 kernel from a
 // single 8 x 8 image up.
-bool try_sconv_i8(const SconvI8Args& a, int64_t N, hipStream_t s, tc_status* st) {
+bool try_sconv_i8(const SconvI8Args& a, int64_t N, hipStream_t s, tc_status* st) {  // a.G groups of a.C channels and a.F filters
   if (t_opt.int8 == TC_INT8_OFF) return false;
   if (a.F % 64 != 0 || a.K % 4 != 0 || a.K < 256) return false;
-  if (prod_reaches({N, a.C, a.H, a.W}, (int64_t)1 << 30)) return false;                 // 32-bit byte offsets into I
-  if (prod_reaches({N, a.F, a.OH, a.OW}, (int64_t)1 << 31)) return false;               // 32-bit element offsets into O
+  if (prod_reaches({N, a.G, a.C, a.H, a.W}, (int64_t)1 << 30)) return false;            // 32-bit byte offsets into I
+  if (prod_reaches({N, a.G, a.F, a.OH, a.OW}, (int64_t)1 << 31)) return false;          // 32-bit element offsets into O
+  if (a.G > 65535) return false;
   // 128 filters per workgroup and 1 .. 4 pixel tiles, or (a multiple of 64 filters only) 64 filters and 2, 4, 6, 8
   const int tf = a.F % 128 == 0 ? 128 : 64, nt_step = tf == 128 ? 1 : 2, nt_max = 4 * nt_step;
   const int64_t blocks = ceil_div(a.K, SI8_KB), units = ceil_div(a.P, 16), fblocks = a.F / tf;
   // pixel tiles per workgroup: as few rounds of workgroups as the largest tile allows, then the smallest tile
   // that still makes that number of rounds
-  const int64_t per_round = std::max<int64_t>(1, device_cus() / fblocks);
+  const int64_t per_round = std::max<int64_t>(1, device_cus() / (fblocks * a.G));
   const int64_t rounds = ceil_div(units, nt_max * per_round);
   int nt = (int)ceil_div(ceil_div(units, rounds * per_round), nt_step) * nt_step;
   nt = std::min(nt_max, std::max(nt_step, nt));
@@ -842,7 +861,7 @@ bool try_sconv_i8(const SconvI8Args& a, int64_t N, hipStream_t s, tc_status* st)
   if (sconv_i8_lds_bytes(tf, nt, blocks) > 160 * 1024) return false;
   const int64_t gx = ceil_div(units, nt);
   if (gx > kMaxGrid || fblocks > 65535) return false;
-  const dim3 grid((unsigned)gx, (unsigned)fblocks);
+  const dim3 grid((unsigned)gx, (unsigned)fblocks, (unsigned)a.G);
   const bool ten = t_opt.int8 == TC_INT8_TEN;  // 13 digit products unless the caller has said that 10 will do
   if (tf == 128) {
     switch (nt) {
@@ -920,6 +939,15 @@ tc_status tc_group_conv(const float* I, const float* W1, const float* bias, floa
       if (try_gconv_i8_small<14, 14, 2>(a, s, &st)) return took("gconv:i8_small", st);
       if (try_gconv_i8_c32<7, 7, 2>(a, s, &st)) return took("gconv:i8_c32", st);
     }
+    // groups with a multiple of 64 filters and at least 256 taps (G = 1: the plain convolution of Section 3): the
+    // strided convolution's int8 kernel with stride 1, one grid plane per group
+    if (C * KH * KW < kMaxElems && N * OH * OW < kMaxElems) {
+      SconvI8Args e{};
+      e.I = I; e.Wt = W1; e.bias = bias; e.O = O;
+      e.C = (int)C; e.F = (int)F; e.H = (int)H; e.W = (int)W; e.KH = (int)KH; e.KW = (int)KW; e.sh = 1; e.sw = 1;
+      e.OH = (int)OH; e.OW = (int)OW; e.K = (int)(C * KH * KW); e.P = (int)(N * OH * OW); e.G = (int)G;
+      if (try_sconv_i8(e, N, s, &st)) return took("gconv:i8_taps", st);
+    }
   }
   if (try_gconv_band<16, 3, 3, 58, 8, 2>(a, s, &st)) return took("gconv:band", st);
   if (try_gconv_band<16, 3, 3, 14, 12, 2>(a, s, &st)) return took("gconv:band", st);  // the paper's (32,32,16,16,14,14): the whole image is one band
@@ -927,6 +955,16 @@ tc_status tc_group_conv(const float* I, const float* W1, const float* bias, floa
   if (try_gconv_quad<8, 8, 3, 3, 28, 26, 3>(a, s, &st)) return took("gconv:quad", st);    // the paper's (32,32,8,8,28,28): one band
   if (try_gconv_tiny<32, 32, 3, 3, 7, 7>(a, s, &st)) return took("gconv:tiny", st);       // the paper's (32,32,32,32,7,7)
   if (try_gconv_lds<16, 16, 3, 3, 7>(a, s, &st)) return took("gconv:lds", st);
+  // G = 1 is the plain convolution of Section 3: the strided convolution's fp64 kernel (implicit contraction over
+  // all pixels of the batch in blocks of 64 x 64) where there are at least 64 filters and 64 taps to fill its blocks
+  if (G == 1 && F >= 64 && C * KH * KW >= 64 && !prod_reaches({N, C, H, W}, kMaxElems) && !prod_reaches({N, F, OH, OW}, kMaxElems) &&
+      !prod_reaches({N, OH, OW}, kMaxElems)) {
+    SconvArgs e{};
+    e.I = I; e.Wt = W1; e.bias = bias; e.O = O;
+    e.N = (int)N; e.C = (int)C; e.F = (int)F; e.H = (int)H; e.W = (int)W; e.KH = (int)KH; e.KW = (int)KW;
+    e.sh = 1; e.sw = 1; e.OH = (int)OH; e.OW = (int)OW; e.K = (int)(C * KH * KW); e.P = (int)(N * OH * OW);
+    return took("gconv:tile", launch_sconv_tile(e, s));
+  }
   t_path = "gconv:wave";
   // generic kernel: a wavefront takes 16 filters x a strip of 16*TP pixels; small images take a narrower strip
   const int64_t tiles_p = ceil_div(OH * OW, 16);
@@ -1011,7 +1049,7 @@ tc_status tc_sconv2d(const float* I, const float* Wt, const float* bias, float* 
     e.I = I; e.Wt = Wt; e.bias = bias; e.O = O;
     e.C = (int)C; e.F = (int)F; e.H = (int)H; e.W = (int)W; e.KH = (int)KH; e.KW = (int)KW; e.sh = (int)sh; e.sw = (int)sw;
     e.OH = (int)OH; e.OW = (int)OW;
-    e.K = (int)K; e.P = (int)(N * OH * OW);
+    e.K = (int)K; e.P = (int)(N * OH * OW); e.G = 1;
     tc_status st = TC_OK;
     if (try_sconv_i8(e, N, s, &st)) return took("sconv:i8", st);
   }
@@ -1021,20 +1059,7 @@ tc_status tc_sconv2d(const float* I, const float* Wt, const float* bias, float* 
   a.N = (int)N; a.C = (int)C; a.F = (int)F; a.H = (int)H; a.W = (int)W; a.KH = (int)KH; a.KW = (int)KW;
   a.sh = (int)sh; a.sw = (int)sw; a.OH = (int)OH; a.OW = (int)OW;
   a.K = (int)K; a.P = (int)(N * OH * OW);
-  a.tiles_f = (int)ceil_div(F, SC_BF);
-  // 64-pixel blocks when there are at least two of them per compute unit, else 32-pixel blocks (twice as many)
-  const bool wide = (int64_t)a.tiles_f * ceil_div(a.P, 64) >= 2 * (int64_t)std::max(1, device_cus());
-  const int64_t grid = (int64_t)a.tiles_f * ceil_div(a.P, wide ? 64 : 32);
-  if (grid > kMaxGrid) return TC_ERR_UNSUPPORTED;
-  const dim3 gd((unsigned)grid), bd(WG_THREADS);
-  if (wide) {
-    if (K % 4 == 0) sconv_tile_kernel<4, 64><<<gd, bd, SconvGeom<64>::LDS_BYTES, s>>>(a);
-    else sconv_tile_kernel<1, 64><<<gd, bd, SconvGeom<64>::LDS_BYTES, s>>>(a);
-  } else {
-    if (K % 4 == 0) sconv_tile_kernel<4, 32><<<gd, bd, SconvGeom<32>::LDS_BYTES, s>>>(a);
-    else sconv_tile_kernel<1, 32><<<gd, bd, SconvGeom<32>::LDS_BYTES, s>>>(a);
-  }
-  return took("sconv:tile", launch_status());
+  return took("sconv:tile", launch_sconv_tile(a, s));
 }
 
 tc_status tc_lut(int32_t n_tables, const float* const* LUT, const int32_t* const* Idx, float* const* O,

@@ -362,6 +362,11 @@ GCONV_SHAPES = [
     (1, 2, 4, 4, 5, 56, 3, 3),      # 4x4x4-block kernel: one short band
     (2, 3, 8, 8, 28, 28, 3, 3),     # 4x4x4-block kernel, 8 channels (paper table shape)
     (1, 2, 8, 8, 31, 28, 3, 3),     # 4x4x4-block kernel, 8 channels: two bands, ragged tiles
+    (2, 2, 32, 64, 12, 13, 3, 3),   # big groups (64 filters, 288 taps): the int8 kernel over gathered taps, one grid plane per group
+    (1, 1, 64, 128, 20, 20, 3, 3),  # G = 1 at 64 -> 128 channels: the plain convolution of Section 3 on that kernel
+    (3, 3, 36, 64, 9, 9, 3, 3),     # three groups, 324 taps, 147 pixels
+    (2, 2, 16, 128, 10, 11, 4, 4),  # 4 x 4 filters: 256 taps exactly
+    (2, 1, 12, 70, 15, 17, 3, 3),   # G = 1 with 70 filters of 108 taps: the strided convolution's fp64 kernel (stride 1)
 ]
 
 
@@ -372,6 +377,8 @@ def test_gconv(tc, shape, oracle_threads):
     ref = oracle.group_conv(I, W1, bias)
     O = torch.full(ref.shape, float("nan"), device="cuda")
     tc.tc_group_conv(dev(I), dev(W1), dev(bias), O)
+    if F % 64 == 0 and C * KH * KW >= 256:
+        assert tc.last_path() == "gconv:i8_taps"
     check(O, ref, "gconv %s" % (shape,), tight_for_last_call(tc))
 
 
