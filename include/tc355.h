@@ -266,7 +266,7 @@ tc_status tc_mlp_fcrelu_static(const float *I, int64_t batch, int32_t n_layers,
  * measured with log-normal magnitudes of sigma 1.5 and 1), TC_INT8_THIRTEEN
  * always does, TC_INT8_OFF takes the fp64 path.  A band that holds Inf or NaN
  * gives NaN in all outputs that read the band.
- * Groups with F a multiple of 64 and C*KH*KW a multiple of 4 and at least 256
+ * Groups with F a multiple of 32 and C*KH*KW a multiple of 4 and at least 256
  * (G = 1 with such extents is the plain convolution of Section 3) run on the
  * int8 kernel of tc_sconv2d with stride 1, one group after the other in one
  * launch: its arithmetic (blocks of 128 taps, a scale per filter and per
@@ -307,7 +307,7 @@ tc_status tc_kron(const float *W1, const float *W2, const float *X, float *Y,
  * then assigns 0)   O: [N,F,OH,OW] with OH = (H-KH)/sh + 1, OW = (W-KW)/sw + 1
  * (integer division; see tc_sconv2d_infer).  sh, sw >= 1; sh = sw = 1 is the
  * plain convolution.  H < KH or W < KW gives TC_ERR_SHAPE.  Arithmetic: fp64
- * products and sums, one rounding per output -- except for F a multiple of 64
+ * products and sums, one rounding per output -- except for F a multiple of 32
  * with C*KH*KW a multiple of 4, at least 256 and at most about 17,000 (I below
  * 2^30 elements, O below 2^31), which run on the int8 matrix core by the scheme of
  * tc_tbmm: the reduction index (c,kh,kw), in W's order, is cut into blocks of

@@ -1,4 +1,4 @@
-// Strided convolution (Section 3, listing sconv2d) on the int8 matrix core, for a multiple of 64 filters and a
+// Strided convolution (Section 3, listing sconv2d) on the int8 matrix core, for a multiple of 32 filters and a
 // reduction C * KH * KW that is a multiple of 4 (any filter size and strides):
 //
 //   O(n,f,h,w) = B(f) + sum_{c,kh,kw} I(n,c, sh*h + kh, sw*w + kw) * W(f,c,kh,kw)
@@ -12,8 +12,9 @@
 // fp32.  The last block of a reduction that is not a multiple of 128 is filled with zeros.
 //
 // One workgroup of 8 wavefronts = TF filters against 16 * NT consecutive pixels: TF = 128 with NT = 1 .. 4, or, where
-// the number of filters is a multiple of 64 only, TF = 64 with NT = 2, 4, 6, 8 (the host picks NT so that one round
-// of workgroups covers the image batch where it can).
+// the number of filters is a multiple of 64 (of 32) only, TF = 64 with NT = 2, 4, 6, 8 (TF = 32 with NT = 4, 8, 12;
+// the first four wavefronts stage the filters); the host picks NT so that one round of workgroups covers the image
+// batch where it can.
 // Staging: the filter half is gemm_i8.hpp's X half (a thread owns 32 taps of one filter, row maximum across its
 // quad; with 64 filters 16 taps -- one MFMA step of a chunk -- and the maximum across 8 lanes).  The pixel half: a
 // thread owns one group of 4 consecutive taps of the block (group g = tid / 16: 32 groups) for NT pixels
@@ -23,7 +24,8 @@
 // the gathers of block t + 1 are issued before block t is contracted, their maxima are posted after it, and the
 // barrier that ends block t publishes them.
 // Contraction: wavefront w holds the operands of filter tile w % (TF / 16) in registers and runs them against its
-// pixel tiles (all NT of them at 128 filters; at 64 filters the tiles i with i % 2 = w / 4); MFMA rows = pixels,
+// pixel tiles (all NT of them at 128 filters; at 64 (32) filters the tiles i with i % 2 = w / 4 (i % 4 = w / 2));
+// MFMA rows = pixels,
 // columns = filters, so a lane ends up with 4 consecutive pixels of one filter.
 //
 // Groups (the grouped convolution of Section 7 with stride 1): blockIdx.z is the group; a group's channels, filters
@@ -54,13 +56,14 @@ constexpr int SI8_MAX_TILES_PER_WAVE = 4;
 
 template <int TF, int NT>
 struct SconvI8Geom {
-  static_assert(TF == 128 || TF == 64, "8 or 4 filter tiles");
+  static_assert(TF == 128 || TF == 64 || TF == 32, "8, 4 or 2 filter tiles");
   static constexpr int FT = TF / 16;                 // filter tiles
-  static constexpr int PG = SI8_WAVES / FT;          // groups of wavefronts that share the pixel tiles out: 1 or 2
+  static constexpr int PG = SI8_WAVES / FT;          // groups of wavefronts that share the pixel tiles out: 1, 2 or 4
   static constexpr int NTW = NT / PG;                // pixel tiles per wavefront
   static_assert(NT % PG == 0 && NTW >= 1 && NTW <= SI8_MAX_TILES_PER_WAVE, "16 to 64 pixels per wavefront");
-  static constexpr int TPR = SI8_THREADS / TF;       // threads that stage one filter's block: 4 or 8
+  static constexpr int TPR = TF == 128 ? 4 : 8;      // threads that stage one filter's block
   static constexpr int XS = 4 * SI8_STEPS / TPR;     // MFMA steps of the block that one of them stages: 2 or 1
+  static constexpr int XTHREADS = TF * TPR;          // threads with a share of the filters: all, or (32 filters) the first 256
   static constexpr int TP = 16 * NT;                 // pixels per workgroup
   static constexpr int ROWS = TF + TP;               // rows staged per block: filters, then pixels
   static constexpr int PLANE = ROWS * SI8_RS;
@@ -76,6 +79,7 @@ __global__ __launch_bounds__(SI8_THREADS, 1) void sconv_i8_kernel(SconvI8Args p)
   static_assert(MIND == 2 || MIND == 3, "13 or 10 digit products");
   using Gm = SconvI8Geom<TF, NT>;
   constexpr int TP = Gm::TP, PLANE = Gm::PLANE, FT = Gm::FT, PG = Gm::PG, NTW = Gm::NTW, TPR = Gm::TPR, XS = Gm::XS;
+  constexpr bool XALL = Gm::XTHREADS == SI8_THREADS;
   extern __shared__ __attribute__((aligned(16))) char si8_lds[];
   const int tid = threadIdx.x;
   const int lane = tid & (WAVE - 1);
@@ -104,6 +108,7 @@ __global__ __launch_bounds__(SI8_THREADS, 1) void sconv_i8_kernel(SconvI8Args p)
   // of step s holds tap 64 s + 16 j + 4 c + e of the block.  With 128 filters a thread stages both steps, with 64
   // the step xs0 only.
   const int xrow = tid / TPR, cx = tid & 3, xs0 = XS == 2 ? 0 : (tid >> 2) & 1;
+  const bool xon = XALL || wave < Gm::XTHREADS / WAVE;  // (whole wavefronts: uniform)
   const float* xsrc = p.Wt + ((int64_t)grp * p.F + f0 + xrow) * K + 4 * cx;
   f4 rx[XS][4];
   // ---- staging role, pixels: taps 64 s + 16 j + 4 c .. + 3 of the block (group g = (s, j, c)) of pixels 16 i + pl
@@ -120,6 +125,7 @@ __global__ __launch_bounds__(SI8_THREADS, 1) void sconv_i8_kernel(SconvI8Args p)
   f4 ry[NT];
 
   auto fetch_x = [&](int blk, int u) {  // this thread's u-th step (64 taps) of the block
+    if (!xon) return;
     const int st = xs0 + u;
     const float* xs = xsrc + blk * SI8_KB + 64 * st;
     if (blk * SI8_KB + SI8_KB <= K) {
@@ -160,6 +166,7 @@ __global__ __launch_bounds__(SI8_THREADS, 1) void sconv_i8_kernel(SconvI8Args p)
   };
   double xscale;  // of this thread's filter in the block being staged
   auto scale_x = [&]() {  // filters: row shared by TPR neighbouring lanes
+    if (!xon) return;
     int sm = 0;
     unsigned um = 0;
 #pragma unroll
@@ -175,6 +182,7 @@ __global__ __launch_bounds__(SI8_THREADS, 1) void sconv_i8_kernel(SconvI8Args p)
     invs[xrow] = inverse;  // the lanes of the row write the same value
   };
   auto slice_x = [&](int u) {  // 16 elements of this thread's u-th step
+    if (!xon) return;
     int y[4][4];
 #pragma unroll
     for (int j = 0; j < 4; j++) gi8_digits4(rx[u][j], xscale, y[j]);

@@ -838,18 +838,19 @@ int64_t sconv_i8_lds_bytes(int tf, int nt, int64_t blocks) {
   return 4 * rows * SI8_RS + rows * 8 + 2 * 16 * nt * 4 + blocks * SI8_KB * 4;
 }
 
-// Takes the call if the shape is one the int8 kernel is built for: a multiple of 64 filters, a reduction C * KH * KW
+// Takes the call if the shape is one the int8 kernel is built for: a multiple of 32 filters, a reduction C * KH * KW
 // that is a multiple of 4 and at least 256 taps (two blocks), operands that 32-bit offsets reach, a table of tap
 // offsets that fits LDS beside the digit planes (about 17,000 taps).  Measured faster than the fp64 kernel from a
 // single 8 x 8 image up.
 bool try_sconv_i8(const SconvI8Args& a, int64_t N, hipStream_t s, tc_status* st) {  // a.G groups of a.C channels and a.F filters
   if (t_opt.int8 == TC_INT8_OFF) return false;
-  if (a.F % 64 != 0 || a.K % 4 != 0 || a.K < 256) return false;
+  if (a.F % 32 != 0 || a.K % 4 != 0 || a.K < 256) return false;
   if (prod_reaches({N, a.G, a.C, a.H, a.W}, (int64_t)1 << 30)) return false;            // 32-bit byte offsets into I
   if (prod_reaches({N, a.G, a.F, a.OH, a.OW}, (int64_t)1 << 31)) return false;          // 32-bit element offsets into O
   if (a.G > 65535) return false;
-  // 128 filters per workgroup and 1 .. 4 pixel tiles, or (a multiple of 64 filters only) 64 filters and 2, 4, 6, 8
-  const int tf = a.F % 128 == 0 ? 128 : 64, nt_step = tf == 128 ? 1 : 2, nt_max = 4 * nt_step;
+  // 128 filters per workgroup and 1 .. 4 pixel tiles, or (a multiple of 64 filters only) 64 filters and 2, 4, 6, 8,
+  // or (a multiple of 32 only) 32 filters and 4, 8, 12
+  const int tf = a.F % 128 == 0 ? 128 : (a.F % 64 == 0 ? 64 : 32), nt_step = 128 / tf, nt_max = tf == 32 ? 12 : 4 * nt_step;
   const int64_t blocks = ceil_div(a.K, SI8_KB), units = ceil_div(a.P, 16), fblocks = a.F / tf;
   // pixel tiles per workgroup: as few rounds of workgroups as the largest tile allows, then the smallest tile
   // that still makes that number of rounds
@@ -870,12 +871,18 @@ bool try_sconv_i8(const SconvI8Args& a, int64_t N, hipStream_t s, tc_status* st)
       case 3: *st = launch_sconv_i8<128, 3>(a, blocks, grid, ten, s); break;
       default: *st = launch_sconv_i8<128, 4>(a, blocks, grid, ten, s); break;
     }
-  } else {
+  } else if (tf == 64) {
     switch (nt) {
       case 2: *st = launch_sconv_i8<64, 2>(a, blocks, grid, ten, s); break;
       case 4: *st = launch_sconv_i8<64, 4>(a, blocks, grid, ten, s); break;
       case 6: *st = launch_sconv_i8<64, 6>(a, blocks, grid, ten, s); break;
       default: *st = launch_sconv_i8<64, 8>(a, blocks, grid, ten, s); break;
+    }
+  } else {
+    switch (nt) {
+      case 4: *st = launch_sconv_i8<32, 4>(a, blocks, grid, ten, s); break;
+      case 8: *st = launch_sconv_i8<32, 8>(a, blocks, grid, ten, s); break;
+      default: *st = launch_sconv_i8<32, 12>(a, blocks, grid, ten, s); break;
     }
   }
   return true;

@@ -1,7 +1,7 @@
 """GPU parity of the strided convolution and the lookup-table sums (through the C ABI) against the float64 oracle.
 
 Same bar and same tight bound as the other fp64 kernels: one fp32 rounding of the exact result.  Strided
-convolutions with a multiple of 64 filters and at least 256 taps (a multiple of 4) run on the int8 matrix core
+convolutions with a multiple of 32 filters and at least 256 taps (a multiple of 4) run on the int8 matrix core
 (tc355_last_path says "sconv:i8"); their bound is the int8 scheme's (tests/test_i8_scheme.py derives the budget).
 """
 import numpy as np
@@ -48,7 +48,7 @@ SCONV_SHAPES = [
     (2, 8, 8, 15, 15, 1, 1, 2, 2),       # 1 x 1 filter: pure subsampling plus channel mixing, one short chunk
     (1, 3, 4, 12, 12, 7, 7, 2, 2),       # 7 x 7 stride 2 (the first layer of residual networks), reduction 147
     (1, 1, 1, 3, 3, 3, 3, 5, 5),         # a single output element
-    (4, 64, 96, 20, 20, 3, 3, 2, 2),     # many chunks (reduction 576), 64 x 64 blocks, the second filter block half full
+    (4, 64, 80, 20, 20, 3, 3, 2, 2),     # many chunks (reduction 576), 64 x 64 blocks, the second filter block a quarter full
     (2, 28, 128, 20, 20, 3, 3, 1, 1),    # 128 filters but only 252 taps: below the int8 kernel's two blocks
     (1, 2048, 128, 4, 3, 3, 3, 1, 1),    # 18432 taps: the int8 kernel's table of tap offsets would not fit LDS
     (2, 6, 10, 9, 40, 2, 5, 1, 4),       # wide stride along w only
@@ -85,6 +85,8 @@ SCONV_I8_SHAPES = [
     (6, 32, 192, 34, 34, 3, 3, 1, 1),     # 192 filters = three blocks of 64, 85 compute units each: NT = 6
     (20, 32, 64, 40, 40, 3, 3, 1, 1),     # 64 filters, 28880 pixels: NT = 8, the last workgroup ragged
     (1, 72, 320, 9, 9, 2, 2, 1, 2),       # 320 filters = five blocks of 64; 2 x 2 filters
+    (2, 32, 32, 20, 21, 3, 3, 1, 1),      # 32 filters: workgroups of 32 filters x 64 pixels, four wavefronts stage the filters
+    (6, 32, 96, 30, 30, 3, 3, 2, 1),      # 96 filters = three blocks of 32; 5880 pixels: NT = 8
     (1, 1900, 128, 3, 4, 3, 3, 1, 1),     # 17100 taps: 134 blocks, the longest reduction the kernel takes at 128 filters
 ]
 
@@ -386,7 +388,7 @@ def test_seeded_random_shapes_through_every_entry_point(tc, oracle_threads):
         verify(buf, Og, oracle.group_conv(I, Wg, bg), "gconv %s" % (shp,))
         # strided convolution
         if it % 2 == 0: shp = (ri(1, 3), ri(1, 30), ri(1, 100), ri(5, 30), ri(5, 30), ri(1, 4), ri(1, 4), ri(1, 3), ri(1, 3))
-        else: shp = (ri(1, 3), 4 * ri(8, 24), 64 * ri(1, 4), ri(5, 30), ri(5, 30), ri(3, 4), ri(3, 4), ri(1, 3), ri(1, 3))  # the int8 kernel's range
+        else: shp = (ri(1, 3), 4 * ri(8, 24), 32 * ri(1, 6), ri(5, 30), ri(5, 30), ri(3, 4), ri(3, 4), ri(1, 3), ri(1, 3))  # the int8 kernel's range
         N_, C, F, H, W, KH, KW, sh, sw = shp
         Is, Wt, bs_ = inputs.make_sconv2d(N_, C, F, H, W, KH, KW, seed=2000 + it)
         ref = oracle.sconv2d(Is, Wt, bs_, sh, sw)
