@@ -18,15 +18,15 @@
 // Staging: the filter half is gemm_i8.hpp's X half (a thread owns 32 taps of one filter, row maximum across its
 // quad; with 64 filters 16 taps -- one MFMA step of a chunk -- and the maximum across 8 lanes).  The pixel half: a
 // thread owns one group of 4 consecutive taps of the block (group g = tid / 16: 32 groups) for NT pixels
-// (16 i + tid % 16), so a load instruction of a wavefront covers 16 consecutive pixels for each of 4 groups; the byte offsets of the block's taps relative to a pixel's first input element come from a table in LDS
-// (built once per workgroup: one division per tap there instead of one per gathered element).  A pixel's 128 taps are
+// (16 i + tid % 16), so a load instruction of a wavefront covers 16 consecutive pixels for each of 4 groups; the byte
+// offsets of the block's taps relative to a pixel's first input element come from a table in LDS (built once per
+// workgroup: one division per tap there instead of one per gathered element).  A pixel's 128 taps are
 // spread over 32 threads in all 8 wavefronts, so its maximum is formed by LDS atomics (ds_max_u32) one block ahead:
 // the gathers of block t + 1 are issued before block t is contracted, their maxima are posted after it, and the
 // barrier that ends block t publishes them.
 // Contraction: wavefront w holds the operands of filter tile w % (TF / 16) in registers and runs them against its
 // pixel tiles (all NT of them at 128 filters; at 64 (32) filters the tiles i with i % 2 = w / 4 (i % 4 = w / 2));
-// MFMA rows = pixels,
-// columns = filters, so a lane ends up with 4 consecutive pixels of one filter.
+// MFMA rows = pixels, columns = filters, so a lane ends up with 4 consecutive pixels of one filter.
 //
 // Groups (the grouped convolution of Section 7 with stride 1): blockIdx.z is the group; a group's channels, filters
 // and outputs are contiguous slices of I, Wt, bias and O, so only base offsets change.
