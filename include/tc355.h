@@ -237,7 +237,7 @@ tc_status tc_mlp_fcrelu_static(const float *I, int64_t batch, int32_t n_layers,
  * TC_ERR_SHAPE.
  * Arithmetic: fp64 as everywhere, except for C = F = 16, KH = KW = 3 with
  * W = 58, H even and H - 2 a multiple of 8 (the benchmark's geometry) or with
- * H = W = 14 and N a multiple of 4 (and for C = F = 32, KH = KW = 3,
+ * H = W = 14 or 16 and N a multiple of 4 (and for C = F = 32, KH = KW = 3,
  * H = W = 7, N a multiple of 4), which run on
  * the int8 matrix core: every filter row and every band of 10 input rows
  * (for 14 x 14: every whole block of 16 input planes) is

@@ -1,6 +1,6 @@
 // Grouped convolution (Section 7, listing gconv) for FEW channels per group
 // (C and F multiples of 4, up to 8; the paper's table shapes (4,4,56,56) and
-// (8,8,28,28)), image width known at compile time:
+// (8,8,28,28), and the same with a border of one pixel: widths 58 and 30), image width known at compile time:
 //
 //   O(n,g,o,h,w) = sum_{i,kh,kw} I(n,g,i,h+kh,w+kw) * W1(g,o,i,kh,kw) + bias(g*F+o)
 //
@@ -48,7 +48,8 @@ struct GconvQuadGeom {
   static constexpr int CQ = C / 4, FQ = F / 4;
   static constexpr int NS = KH * KW * CQ;                          // reduction steps per tile
   static_assert(C % 4 == 0 && F % 4 == 0 && C <= 8 && F <= 8, "4 or 8 channels and filters per group");
-  static_assert(W % 4 == 0, "16-byte loads: every row starts 16-byte aligned");
+  static constexpr int VEC = W % 4 == 0 ? 4 : 2;                   // floats per staging load: rows start 16- or 8-byte aligned
+  static_assert(W % 2 == 0, "8-byte loads at least: every row starts 8-byte aligned");
   static_assert(PS >= LEN, "plane stride too small");
   static_assert((4 * (CQ - 1) * PS + (KH - 1) * W + KW - 1) * 8 < 65536, "LDS immediates out of range");
   static_assert(F * C * KH * KW * 4 <= LDS_BYTES, "the filter bank is parked in the band area first");
@@ -98,28 +99,31 @@ __global__ __launch_bounds__(WG_THREADS, MINW) void gconv_quad_kernel(GconvQuadA
   for (int b = 0; b < nbands; b++) {
     __syncthreads();  // the previous band (or the parked filter bank) has been read by everyone
     // ---- stage the band: rows b*ROWS .. of every channel, widened to fp64; rows past the image are skipped.
-    // W is a multiple of 4, so planes, band starts and row ends are 16-byte aligned.  All loads are issued
-    // before the first conversion (one at a time, every load would wait for the previous one's round trip).
+    // W is a multiple of 4 (of 2), so planes, band starts and row ends are 16-byte (8-byte) aligned.  All loads are
+    // issued before the first conversion (one at a time, every load would wait for the previous one's round trip).
     const int h0 = b * ROWS;
-    const int avail = min((H - h0) * W, LEN);  // floats of each plane that belong to this band (a multiple of 4)
+    const int avail = min((H - h0) * W, LEN);  // floats of each plane that belong to this band (a multiple of VEC)
     {
-      constexpr int LEN4 = LEN / 4, NLD = (C * LEN4 + WG_THREADS - 1) / WG_THREADS;
-      f4 v[NLD];
+      constexpr int VEC = Gm::VEC, LENV = LEN / VEC, NLD = (C * LENV + WG_THREADS - 1) / WG_THREADS;
+      static_assert(LEN % VEC == 0, "whole loads");
+      Vec<float, VEC> v[NLD];
 #pragma unroll
       for (int j = 0; j < NLD; j++) {
-        const int u = min(tid + j * WG_THREADS, C * LEN4 - 1);
-        const int c = u / LEN4, i = min(4 * (u - c * LEN4), avail - 4);  // clamped, never skipped per lane
-        v[j] = *reinterpret_cast<const f4*>(src + c * plane + (int64_t)h0 * W + i);
+        const int u = min(tid + j * WG_THREADS, C * LENV - 1);
+        const int c = u / LENV, i = min(VEC * (u - c * LENV), avail - VEC);  // clamped, never skipped per lane
+        v[j] = load_vec<float, VEC>(src + c * plane + (int64_t)h0 * W + i);
       }
 #pragma unroll
       for (int j = 0; j < NLD; j++) {
         const int u = tid + j * WG_THREADS;
-        const int c = u / LEN4, i = 4 * (u - c * LEN4);
-        if (u < C * LEN4 && i < avail) {
+        const int c = u / LENV, i = VEC * (u - c * LENV);
+        if (u < C * LENV && i < avail) {
           double* d = gq_band + c * PS + i;  // PS and i are even: 16-byte aligned pairs
-          const dbl2 lo = {(double)v[j][0], (double)v[j][1]}, hi = {(double)v[j][2], (double)v[j][3]};
-          *reinterpret_cast<dbl2*>(d) = lo;
-          *reinterpret_cast<dbl2*>(d + 2) = hi;
+#pragma unroll
+          for (int e = 0; e < VEC; e += 2) {
+            const dbl2 pr = {(double)v[j].e[e], (double)v[j].e[e + 1]};
+            *reinterpret_cast<dbl2*>(d + e) = pr;
+          }
         }
       }
     }

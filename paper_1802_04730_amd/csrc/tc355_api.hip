@@ -942,9 +942,11 @@ tc_status tc_group_conv(const float* I, const float* W1, const float* bias, floa
     if (i8 == TC_INT8_TEN) {
       if (try_gconv_i8_small<14, 14, 3>(a, s, &st)) return took("gconv:i8_small", st);  // the paper's (32,32,16,16,14,14)
       if (try_gconv_i8_c32<7, 7, 3>(a, s, &st)) return took("gconv:i8_c32", st);     // the paper's (32,32,32,32,7,7)
+      if (try_gconv_i8_small<16, 16, 3>(a, s, &st)) return took("gconv:i8_small", st);  // the first with a border of one pixel
     } else {
       if (try_gconv_i8_small<14, 14, 2>(a, s, &st)) return took("gconv:i8_small", st);
       if (try_gconv_i8_c32<7, 7, 2>(a, s, &st)) return took("gconv:i8_c32", st);
+      if (try_gconv_i8_small<16, 16, 2>(a, s, &st)) return took("gconv:i8_small", st);
     }
     // groups with a multiple of 64 filters and at least 256 taps (G = 1: the plain convolution of Section 3): the
     // strided convolution's int8 kernel with stride 1, one grid plane per group
@@ -960,6 +962,8 @@ tc_status tc_group_conv(const float* I, const float* W1, const float* bias, floa
   if (try_gconv_band<16, 3, 3, 14, 12, 2>(a, s, &st)) return took("gconv:band", st);  // the paper's (32,32,16,16,14,14): the whole image is one band
   if (try_gconv_quad<4, 4, 3, 3, 56, 16, 4>(a, s, &st)) return took("gconv:quad", st);    // the paper's (32,32,4,4,56,56)
   if (try_gconv_quad<8, 8, 3, 3, 28, 26, 3>(a, s, &st)) return took("gconv:quad", st);    // the paper's (32,32,8,8,28,28): one band
+  if (try_gconv_quad<4, 4, 3, 3, 58, 16, 4>(a, s, &st)) return took("gconv:quad", st);    // the same two with a border of one pixel
+  if (try_gconv_quad<8, 8, 3, 3, 30, 28, 2>(a, s, &st)) return took("gconv:quad", st);
   if (try_gconv_tiny<32, 32, 3, 3, 7, 7>(a, s, &st)) return took("gconv:tiny", st);       // the paper's (32,32,32,32,7,7)
   if (try_gconv_lds<16, 16, 3, 3, 7>(a, s, &st)) return took("gconv:lds", st);
   // G = 1 is the plain convolution of Section 3: the strided convolution's fp64 kernel (implicit contraction over

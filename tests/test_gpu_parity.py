@@ -362,6 +362,12 @@ GCONV_SHAPES = [
     (1, 2, 4, 4, 5, 56, 3, 3),      # 4x4x4-block kernel: one short band
     (2, 3, 8, 8, 28, 28, 3, 3),     # 4x4x4-block kernel, 8 channels (paper table shape)
     (1, 2, 8, 8, 31, 28, 3, 3),     # 4x4x4-block kernel, 8 channels: two bands, ragged tiles
+    (4, 3, 16, 16, 16, 16, 3, 3),   # int8 kernel for small images at 16 x 16 (the table shape with a border): 13 tiles, the last a quarter full
+    (8, 5, 16, 16, 16, 16, 3, 3),   # the same, runs that cross a group boundary
+    (2, 3, 4, 4, 58, 58, 3, 3),     # 4x4x4-block kernel at width 58 (the table shape with a border): 8-byte staging loads
+    (1, 2, 4, 4, 21, 58, 3, 3),     # the same, odd height: two bands, the second ragged
+    (2, 3, 8, 8, 30, 30, 3, 3),     # 4x4x4-block kernel, 8 channels at width 30: the whole image one band
+    (1, 2, 8, 8, 17, 30, 3, 3),     # the same, a short image
     (2, 2, 32, 64, 12, 13, 3, 3),   # big groups (64 filters, 288 taps): the int8 kernel over gathered taps, one grid plane per group
     (1, 1, 64, 128, 20, 20, 3, 3),  # G = 1 at 64 -> 128 channels: the plain convolution of Section 3 on that kernel
     (3, 3, 36, 64, 9, 9, 3, 3),     # three groups, 324 taps, 147 pixels
