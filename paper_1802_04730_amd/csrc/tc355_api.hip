@@ -963,7 +963,7 @@ tc_status tc_group_conv(const float* I, const float* W1, const float* bias, floa
   if (try_gconv_quad<4, 4, 3, 3, 56, 16, 4>(a, s, &st)) return took("gconv:quad", st);    // the paper's (32,32,4,4,56,56)
   if (try_gconv_quad<8, 8, 3, 3, 28, 26, 3>(a, s, &st)) return took("gconv:quad", st);    // the paper's (32,32,8,8,28,28): one band
   if (try_gconv_quad<4, 4, 3, 3, 58, 16, 4>(a, s, &st)) return took("gconv:quad", st);    // the same two with a border of one pixel
-  if (try_gconv_quad<8, 8, 3, 3, 30, 28, 2>(a, s, &st)) return took("gconv:quad", st);
+  if (try_gconv_quad<8, 8, 3, 3, 30, 14, 3>(a, s, &st)) return took("gconv:quad", st);
   if (try_gconv_tiny<32, 32, 3, 3, 7, 7>(a, s, &st)) return took("gconv:tiny", st);       // the paper's (32,32,32,32,7,7)
   if (try_gconv_lds<16, 16, 3, 3, 7>(a, s, &st)) return took("gconv:lds", st);
   // G = 1 is the plain convolution of Section 3: the strided convolution's fp64 kernel (implicit contraction over
