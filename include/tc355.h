@@ -111,10 +111,11 @@ const char *tc355_last_path(void);
  * The reduction index is the fastest index of both operands.  B = 1 gives the
  * transposed matmul of Section 7 (listing tmm).
  * Arithmetic: fp64 products and sums, one rounding to fp32 -- except for
- * N a multiple of 128 with K a multiple of 128 (at least 256), M a multiple
+ * N a multiple of 128 with K a multiple of 4 (at least 256), M a multiple
  * of 64 and at least 128 blocks of 128 x 64 outputs in all (the paper's (M,K,N) =
  * (128,4096,16384) is of this kind), which run on the int8 matrix core: in
- * every block of 128 reduction indices each row of X and of Y is scaled so that
+ * every block of 128 reduction indices (the last one filled with zeros where
+ * K is no multiple of 128) each row of X and of Y is scaled so that
  * its largest magnitude m maps to 0x7F7F7F7E, rounded to a 32-bit integer
  * (off by at most 2^-32 m) and cut into four signed 8-bit digits; the 13 digit
  * products of weight 256^2 and above (digit k of one operand times digit l

@@ -1,6 +1,7 @@
 // Transposed matmul (Section 7, listing tmm / tbmm) on the int8 matrix core, for
-// a multiple of 128 rows of X, a reduction that is a multiple of 128 and a
-// multiple of 64 rows of Y -- the paper's largest tmm, (M,K,N) = (128,4096,16384):
+// a multiple of 128 rows of X, a reduction that is a multiple of 4 (at least 256;
+// the last block of 128 is filled with zeros) and a multiple of 64 rows of Y --
+// the paper's largest tmm, (M,K,N) = (128,4096,16384):
 //
 //   Z(b,n,m) = sum_k X(b,n,k) * Y(b,m,k)
 //
@@ -113,7 +114,7 @@ __device__ __forceinline__ int gi8_magnitude(int smax, unsigned umax) { return m
 // X sliced once: one workgroup per (block of 128 k, block of 128 rows), thread t = (row t / 4, chunk t % 4) exactly
 // as in the contracting kernel, which later reads record t of every group with one 16-byte load.
 __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_slice_x_kernel(const float* X, int K, i4* Xd, double* Xinv) {
-  const int tid = threadIdx.x, blk = blockIdx.x, nb = K / GI8_KB;
+  const int tid = threadIdx.x, blk = blockIdx.x, nb = (K + GI8_KB - 1) / GI8_KB;
   const int64_t rb = blockIdx.y;
   const int xrow = tid >> 2, cx = tid & 3;
   const float* xs = X + (rb * GI8_TN + xrow) * (int64_t)K + (int64_t)blk * GI8_KB + 4 * cx;
@@ -121,7 +122,10 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_slice_x_kernel(const f
 #pragma unroll
   for (int s = 0; s < GI8_STEPS; s++)
 #pragma unroll
-    for (int j = 0; j < 4; j++) rx[s][j] = *reinterpret_cast<const f4*>(xs + 64 * s + 16 * j);
+    for (int j = 0; j < 4; j++) {  // K is a multiple of 4: whole pieces; past the end of the reduction: zeros
+      const bool in = blk * GI8_KB + 64 * s + 16 * j + 4 * cx < K;
+      rx[s][j] = in ? *reinterpret_cast<const f4*>(xs + 64 * s + 16 * j) : f4{0.f, 0.f, 0.f, 0.f};
+    }
   int sm = 0;
   unsigned um = 0;
 #pragma unroll
@@ -158,7 +162,7 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
   const int lane = tid & (WAVE - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
   const int r16 = lane & 15, q = lane >> 4;
-  const int M = p.M, K = p.K, nb = K / GI8_KB;
+  const int M = p.M, K = p.K, nb = (K + GI8_KB - 1) / GI8_KB;  // the last block of a K that is no multiple of 128 is filled with zeros
   const int m0 = blockIdx.x * GI8_TM;
   const int64_t b = blockIdx.y;
   const int64_t n0 = (b * gridDim.z + blockIdx.z) * GI8_TN;  // first row of this workgroup's 128 in [B * N]
@@ -180,6 +184,7 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
   const int64_t rb = b * gridDim.z + blockIdx.z;  // block of 128 rows of X
   auto fetch = [&](int blk) {
     const float* ys = ysrc + blk * GI8_KB;
+    const bool whole = blk * GI8_KB + GI8_KB <= K;  // K is a multiple of 4: 16-byte pieces are inside or outside as a whole
     if constexpr (PRE) {
       const i4* xr = p.Xd + (rb * nb + blk) * (int64_t)(GI8_STEPS * 4 * GI8_THREADS) + tid;
 #pragma unroll
@@ -189,15 +194,35 @@ __global__ __launch_bounds__(GI8_THREADS, 1) void gemm_i8_kernel(GemmI8Args p) {
       xinv = p.Xinv[(rb * nb + blk) * GI8_TN + xrow];
     } else {
       const float* xs = xsrc + blk * GI8_KB;
+      if (whole) {
+#pragma unroll
+        for (int s = 0; s < GI8_STEPS; s++)
+#pragma unroll
+          for (int j = 0; j < 4; j++) rx[s][j] = *reinterpret_cast<const f4*>(xs + 64 * s + 16 * j);
+      } else {
+#pragma unroll
+        for (int s = 0; s < GI8_STEPS; s++)
+#pragma unroll
+          for (int j = 0; j < 4; j++) {
+            const bool in = blk * GI8_KB + 64 * s + 16 * j + 4 * cx < K;
+            rx[s][j] = in ? *reinterpret_cast<const f4*>(xs + 64 * s + 16 * j) : f4{0.f, 0.f, 0.f, 0.f};
+          }
+      }
+    }
+    if (whole) {
 #pragma unroll
       for (int s = 0; s < GI8_STEPS; s++)
 #pragma unroll
-        for (int j = 0; j < 4; j++) rx[s][j] = *reinterpret_cast<const f4*>(xs + 64 * s + 16 * j);
+        for (int j = 0; j < 2; j++) ry[s][j] = *reinterpret_cast<const f4*>(ys + 64 * s + 16 * j);
+    } else {
+#pragma unroll
+      for (int s = 0; s < GI8_STEPS; s++)
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+          const bool in = blk * GI8_KB + 64 * s + 16 * j + 32 * hy + 4 * cyc < K;
+          ry[s][j] = in ? *reinterpret_cast<const f4*>(ys + 64 * s + 16 * j) : f4{0.f, 0.f, 0.f, 0.f};
+        }
     }
-#pragma unroll
-    for (int s = 0; s < GI8_STEPS; s++)
-#pragma unroll
-      for (int j = 0; j < 2; j++) ry[s][j] = *reinterpret_cast<const f4*>(ys + 64 * s + 16 * j);
   };
   auto slice = [&]() {
     if constexpr (PRE) {  // X: the records as they came

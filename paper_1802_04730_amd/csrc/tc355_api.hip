@@ -519,7 +519,7 @@ namespace {
 // Does (B, N, M, K) belong to the shape class of the int8 transposed-matmul kernel (blocks of 128 rows of X against
 // many rows of Y, long reduction)?
 bool tbmm_i8_shape(int64_t B, int64_t N, int64_t M, int64_t K) {
-  return N % GI8_TN == 0 && K % GI8_KB == 0 && K >= 2 * GI8_KB && M % GI8_TM == 0 && B <= 65535 && N / GI8_TN <= 65535 &&
+  return N % GI8_TN == 0 && K % 4 == 0 && K >= 2 * GI8_KB && M % GI8_TM == 0 && B <= 65535 && N / GI8_TN <= 65535 &&
          (M / GI8_TM) * (N / GI8_TN) * B >= 128;
 }
 
@@ -527,12 +527,12 @@ bool tbmm_i8_shape(int64_t B, int64_t N, int64_t M, int64_t K) {
 // of workgroups that would each slice X (M / 64) and with the length of the reduction.  Measured: 138 -> 128 us at
 // (B,N,M,K) = (1,128,16384,4096), 19.8 -> 22.3 us at (2,256,4096,512).
 bool tbmm_presliced_pays(int64_t B, int64_t N, int64_t M, int64_t K) {
-  return M / GI8_TM >= 128 && K / GI8_KB >= 16 && B * (N / GI8_TN) <= 65535;
+  return M / GI8_TM >= 128 && K / GI8_KB >= 16 && B * (N / GI8_TN) <= 65535 && ceil_div(K, GI8_KB) <= kMaxGrid;
 }
 
 // bytes of X sliced once for the int8 kernel: digit records, then inverse scales
 size_t tbmm_ws_bytes(int64_t B, int64_t N, int64_t K) {
-  const int64_t blocks = B * (N / GI8_TN) * (K / GI8_KB);
+  const int64_t blocks = B * (N / GI8_TN) * ceil_div(K, GI8_KB);
   return (size_t)(blocks * (GI8_XD_BYTES + GI8_XINV_BYTES));
 }
 
@@ -564,7 +564,7 @@ tc_status tbmm_run(const float* X, const float* Y, float* Z, int64_t B, int64_t 
     const bool ten = t_opt.int8 == TC_INT8_TEN;  // 13 digit products unless the caller has said that 10 will do
     // With a workspace X is sliced once, by a kernel of its own, instead of by every workgroup that reads it.
     if (workspace && tbmm_presliced_pays(B, N, M, K) && workspace_bytes >= tbmm_ws_bytes(B, N, K)) {
-      const int64_t rblocks = B * (N / GI8_TN), nb = K / GI8_KB;
+      const int64_t rblocks = B * (N / GI8_TN), nb = ceil_div(K, GI8_KB);
       i4* xd = static_cast<i4*>(workspace);
       double* xinv = reinterpret_cast<double*>(static_cast<char*>(workspace) + rblocks * nb * GI8_XD_BYTES);
       gemm_i8_slice_x_kernel<<<dim3((unsigned)nb, (unsigned)rblocks), dim3(GI8_THREADS), 0, s>>>(X, (int)K, xd, xinv);

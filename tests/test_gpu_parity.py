@@ -116,6 +116,37 @@ def test_tbmm_i8_blocks_of_any_magnitude_zero_rows_and_nonfinite_rows(tc, oracle
     assert np.array_equal(got2[0][keep], got.astype(np.float32)[0][keep])
 
 
+@pytest.mark.parametrize("shape", [(1, 128, 8192, 300), (2, 256, 4096, 1000), (1, 128, 8192, 2116)])
+def test_tbmm_int8_reduction_that_is_no_multiple_of_128(tc, shape, oracle_threads):
+    """The int8 kernel fills the last block of 128 with zeros: K = 300 (two blocks and 44), 1000 (seven and 104), 2116
+    (sixteen and 68: long enough for the workspace form, whose slicing kernel fills the same zeros)."""
+    B, N, M, K = shape
+    X, Y = inputs.make_tbmm(*shape, seed=13)
+    ref = oracle.tbmm(X, Y)
+    Xd, Yd = dev(X), dev(Y)
+    n = ref.size
+    buf = torch.full((n + 512,), 7.0, device="cuda")
+    Z = buf[256:256 + n].view(ref.shape)
+    tc.tc_tbmm(Xd, Yd, Z)
+    assert tc.last_path() == "tbmm:i8"
+    check(Z, ref, "tbmm %s, int8 path" % (shape,), TIGHT_I8)
+    assert torch.all(buf[:256] == 7.0) and torch.all(buf[256 + n:] == 7.0)
+    need = tc.tc_tbmm_workspace_bytes(*shape)
+    if need:
+        assert need == B * (N // 128) * ((K + 127) // 128) * (65536 + 1024)
+        ws = torch.randint(0, 255, (need + 64,), dtype=torch.uint8, device="cuda")
+        ws[need:] = 77
+        Zw = torch.full(ref.shape, float("nan"), device="cuda")
+        tc.tc_tbmm_ws(Xd, Yd, Zw, ws[:need])
+        assert tc.last_path() == "tbmm:i8_presliced" and torch.equal(Z, Zw)
+        assert bool((ws[need:] == 77).all()), "the workspace is not overrun"
+    with tc.option(tc.TC_OPT_INT8, tc.TC_INT8_OFF):
+        Z64 = torch.full(ref.shape, float("nan"), device="cuda")
+        tc.tc_tbmm(Xd, Yd, Z64)
+        assert ":i8" not in tc.last_path()
+    check(Z64, ref, "tbmm %s, fp64 path" % (shape,), TIGHT)
+
+
 def test_tbmm_int8_option_off_keeps_the_fp64_kernels(tc, oracle_threads):
     """TC_OPT_INT8 = TC_INT8_OFF: the same shape on the fp64 matrix core, to one fp32 rounding; TEN and the default
     (13 digit products) on the int8 matrix core."""
